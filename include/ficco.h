@@ -1,0 +1,252 @@
+/*
+ * ficco.h - C ABI of the finer-grain compute/communication overlap path on one MI355X (gfx950).
+ *
+ * The operation (paper Sec. II-B, Fig. 3(a)-(b)): a GPU holds a column share W [K,N] of a weight
+ * and needs the row-gathered activation A = [I_0; ...; I_{G-1}] (G shards of M/G rows, [M/G,K])
+ * to compute C = A * W. Serial execution gathers first and multiplies afterwards; shard-level
+ * overlap (Fig. 3(c)) multiplies shard j while shard j+1 is in flight; the finer-grain scheme
+ * (Sec. III, Sec. V-A/B) cuts every shard once more into `chunks` row pieces, moves piece s of
+ * every shard in step s, and multiplies pieces as they land. The mirror direction streams row
+ * blocks of C = A * W out to G peer buffers as they are completed (the data-movement half of
+ * GEMM -> reduce-scatter; the element-wise sum over GPUs is not part of this library).
+ *
+ * On one GPU the transfers are copy-engine (SDMA) copies issued with hipMemcpyAsync on the
+ * caller's copy stream, from pinned host memory or from a device staging buffer; the GEMM is a
+ * hand-written bf16 MFMA kernel (fp32 accumulate, one round-to-nearest-even to bf16 at the end)
+ * launched per group of landed pieces, or once as a resident kernel whose tiles wait on
+ * per-piece ready flags in device memory (Sec. VI-A uses stream write/wait for the same purpose).
+ *
+ * Conventions
+ *   - All matrices are row-major bf16 (1-8-7). "device" = hipMalloc'ed memory of the current
+ *     device; "host" = ordinary host memory; "pinned" = hipHostMalloc'ed host memory.
+ *   - Streams are hipStream_t passed as void*. Every call uses the device that is current on the
+ *     calling thread; a plan must be used on the device it was created on.
+ *   - Every function returns 0 (FICCO_OK) or a negative ficco_status; nothing throws or aborts.
+ *     On failure output arguments are left untouched.
+ *   - The caller owns every data buffer and both streams. The plan owns its flags, events,
+ *     tables, packed weight and statistics. A plan is not thread safe; runs of one plan are
+ *     ordered by the streams they are enqueued on, and at most one run of a plan may be in
+ *     flight per pair of streams.
+ *   - Result bits do not depend on schedule, chunk count, arrival order, tile shape or source
+ *     kind: every output element is accumulated over k in the same order by the same
+ *     instruction sequence.
+ */
+#ifndef FICCO_H
+#define FICCO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ficco_plan_s ficco_plan_t;   /* opaque, library-owned */
+
+typedef enum ficco_status {
+    FICCO_OK          = 0,
+    FICCO_ERR_ARG     = -1,   /* null pointer, unknown enum value, option set too late        */
+    FICCO_ERR_SHAPE   = -2,   /* shape rule violated (see ficco_plan)                         */
+    FICCO_ERR_ALLOC   = -3,   /* host or device allocation failed                             */
+    FICCO_ERR_HIP     = -4,   /* a HIP call failed; ficco_last_hip_error() has the code       */
+    FICCO_ERR_TIMEOUT = -5,   /* a resident kernel gave up waiting for a ready flag           */
+    FICCO_ERR_STATE   = -6    /* call not valid in the plan's state (e.g. stats before a run) */
+} ficco_status;
+
+/* Schedules (Sec. II-B, Sec. V-A/B). */
+typedef enum ficco_schedule {
+    FICCO_SERIAL          = 0,   /* all G shard transfers, then one GEMM (Fig. 3(b)); chunks must be 1 */
+    FICCO_SHARD           = 1,   /* one GEMM per landed shard (Fig. 3(c)); chunks must be 1            */
+    FICCO_FINE_UNFUSED    = 2,   /* G*chunks pieces, one GEMM launch per landed piece ("unfused")       */
+    FICCO_FINE_FUSED      = 3,   /* one GEMM launch per step over the G pieces of that step ("fused");
+                                    the kernel reads the pieces in place through a row-block table,
+                                    so no Gather/Scatter copies are issued                             */
+    FICCO_FINE_PERSISTENT = 4,   /* one resident kernel; every tile waits on its piece's ready flag     */
+    FICCO_AUTO            = 100  /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
+} ficco_schedule;
+
+typedef enum ficco_direction {
+    FICCO_DIR_AG_GEMM = 0,       /* transfers feed the GEMM                                   */
+    FICCO_DIR_GEMM_RS = 1        /* the GEMM feeds transfers of C row blocks to peer buffers  */
+} ficco_direction;
+
+typedef enum ficco_order {
+    FICCO_ORDER_STEP_MAJOR  = 0, /* step s moves piece s of every shard (all-to-all pattern, Sec. III-B) */
+    FICCO_ORDER_SHARD_MAJOR = 1, /* all pieces of shard 0, then shard 1, ...                              */
+    FICCO_ORDER_CUSTOM      = 2  /* set by ficco_plan_set_arrival()                                       */
+} ficco_order;
+
+typedef enum ficco_mode {
+    FICCO_MODE_PAIR        = 0,  /* the dependent pair (default)                                        */
+    FICCO_MODE_GEMM_ONLY   = 1,  /* only the plan's GEMM launches, operands resident (isolated, Sec. IV-B) */
+    FICCO_MODE_COPY_ONLY   = 2,  /* only the plan's transfers (isolated)                                 */
+    FICCO_MODE_INDEPENDENT = 3   /* both, concurrently, with no dependency between them (Sec. IV-C)      */
+} ficco_mode;
+
+/* Options for ficco_plan_set(). */
+typedef enum ficco_option {
+    FICCO_OPT_DIRECTION   = 0,   /* ficco_direction; default AG_GEMM                                    */
+    FICCO_OPT_ORDER       = 1,   /* ficco_order; default STEP_MAJOR for the FINE schedules              */
+    FICCO_OPT_MODE        = 2,   /* ficco_mode; default PAIR                                            */
+    FICCO_OPT_TIMING      = 3,   /* 0: begin/end events only (default); 1: also per-piece and per-launch
+                                    events (adds one barrier packet around every launch)                */
+    FICCO_OPT_TILE        = 4,   /* 0: choose by shape (default); else a ficco_tile value               */
+    FICCO_OPT_FLAG_WRITE  = 5,   /* resident kernel only. 0 (default): the ready flag is written by a
+                                    4-byte copy-engine copy queued behind the piece's transfer;
+                                    1: by hipStreamWriteValue32                                         */
+    FICCO_OPT_SPIN_LIMIT_US = 6, /* resident kernel: give up after this long without the awaited flag
+                                    (default 2,000,000); the run then reports FICCO_ERR_TIMEOUT        */
+    FICCO_OPT_LOCAL_SHARD = 7,   /* -1 (default): every shard arrives by transfer. j >= 0: shard j is
+                                    already in A_dev and is multiplied first without waiting
+                                    ("hetero" start, Sec. V-A); its transfers are skipped              */
+    FICCO_OPT_HOLD_FLAGS  = 8    /* test hook, resident kernel: 1 = issue the transfers but never write
+                                    the ready flags, so that the kernel's bounded wait expires         */
+} ficco_option;
+
+typedef enum ficco_tile {        /* workgroup tile (rows x columns of C); the k order is the same in all */
+    FICCO_TILE_AUTO    = 0,
+    FICCO_TILE_256x256 = 1,
+    FICCO_TILE_128x128 = 2,
+    FICCO_TILE_256x128 = 3,
+    FICCO_TILE_128x256 = 4,
+    FICCO_TILE_64x256  = 5,      /* for pieces of fewer than 128 rows */
+    FICCO_TILE_32x256  = 6       /* for pieces of fewer than 64 rows  */
+} ficco_tile;
+
+typedef struct ficco_plan_info {
+    int64_t M, K, N;
+    int32_t shards, chunks;          /* chunks = pieces per shard                                */
+    int32_t schedule, direction, order, mode;
+    int32_t n_chunks;                /* shards * chunks                                          */
+    int32_t n_groups;                /* GEMM launches per run                                    */
+    int64_t chunk_rows;              /* M / n_chunks                                             */
+    int32_t tile_m, tile_n, tile_k;  /* chosen workgroup tile                                    */
+    int32_t resident_grid;           /* workgroups of the resident kernel (0 if not used)        */
+    double  otb;                     /* static op-to-byte of one launch's GEMM (Sec. IV-B)       */
+    double  mt_bytes;                /* static memory traffic MK+NK+MN of it, in bytes (Sec. IV-C) */
+} ficco_plan_info_t;
+
+typedef struct ficco_stats {
+    double  wall_us;          /* first transfer (or first launch) start -> last operation end           */
+    double  copy_span_us;     /* first transfer start -> last transfer end (0 if no transfers)          */
+    double  gemm_span_us;     /* first GEMM launch start -> last GEMM launch end                        */
+    double  gemm_busy_us;     /* sum of per-launch kernel durations (TIMING=1), else = gemm_span_us     */
+    double  copy_busy_us;     /* sum of per-transfer durations (TIMING=1), else = copy_span_us          */
+    double  exposed_comm_us;  /* wall_us - gemm_busy_us                                                 */
+    double  eff_tflops;       /* 2*M*N*K / wall_us                                                      */
+    double  copy_gbps;        /* transferred bytes / copy_span_us                                       */
+    int64_t flops;            /* 2*M*N*K                                                                */
+    int64_t copy_bytes;       /* bytes moved by transfers in this run                                   */
+    int32_t n_copies, n_launches;
+    int32_t timed_out;        /* 1 if the resident kernel's bounded wait expired                        */
+    int32_t run_index;        /* 1 for the first run of the plan                                        */
+} ficco_stats_t;
+
+typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this plan's decomposition    */
+    double t_gemm_whole_us;         /* one GEMM over all M rows, isolated                               */
+    double t_gemm_pieces_us;        /* sum of the plan's GEMM launches, isolated, back to back          */
+    double t_gemm_pieces_cont_us;   /* the same launches while the plan's transfers run independently   */
+    double t_copy_whole_us;         /* G shard-sized transfers, isolated                                */
+    double t_copy_pieces_us;        /* the plan's transfers, isolated                                   */
+    double t_copy_pieces_cont_us;   /* the plan's transfers while the GEMM launches run independently   */
+    double gemm_dil, gemm_cil;      /* ratios: pieces/whole, contended/isolated                         */
+    double comm_dil, comm_cil;
+    double ideal_us;                /* ideal-overlap time from the whole-operator times (Sec. IV-A)     */
+} ficco_losses_t;
+
+/*
+ * Build a plan for C[M,N] = A[M,K] * W[K,N] with A arriving as `shards` row shards, each cut into
+ * `chunks` pieces (Sec. III-A). Validates and builds the arrival list and the launch groups for
+ * the current device; the tile is chosen and flags/events/tables are allocated on first use
+ * (ficco_pack_weight or ficco_run), after which most options are frozen.
+ * Shape rules (FICCO_ERR_SHAPE otherwise): M, K, N >= 1; shards >= 1; chunks >= 1;
+ * M % (shards*chunks) == 0; K % 64 == 0; N % 8 == 0; chunks == 1 for SERIAL and SHARD;
+ * shards*chunks <= 4096. With FICCO_AUTO, `chunks` is ignored and chosen by the heuristic.
+ */
+int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule,
+               ficco_plan_t **out);
+
+/* Set an option; only before the plan's first use (FICCO_ERR_STATE afterwards), except
+ * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US and FICCO_OPT_HOLD_FLAGS, which may
+ * change between runs. */
+int ficco_plan_set(ficco_plan_t *plan, int option, int64_t value);
+
+/* Replace the arrival order by a permutation of 0..n_chunks-1 (tests: reversed, shuffled).
+ * Launch groups are rebuilt over the new order. Only before the first run. */
+int ficco_plan_set_arrival(ficco_plan_t *plan, const int32_t *chunk_ids, int n);
+
+int ficco_plan_info(const ficco_plan_t *plan, ficco_plan_info_t *out);
+
+/* Arrival list: chunk_ids[p] = chunk issued p-th (chunk i = piece i%chunks of shard i/chunks,
+ * rows [i*chunk_rows, (i+1)*chunk_rows)); group_ids[p] = index of the GEMM launch that consumes
+ * it. Both host arrays of at least n_chunks entries; `cap` is their length. */
+int ficco_plan_arrival(const ficco_plan_t *plan, int32_t *chunk_ids, int32_t *group_ids, int cap);
+
+/*
+ * Pack the static weight W_dev ([K,N] row-major, device) into the plan's kernel layout
+ * ([N,K], k contiguous) on `stream`. ficco_run() does this by itself the first time it sees a
+ * W_dev pointer; call it again whenever the *contents* of W change. Not part of the timed path:
+ * the weight share is resident and static across calls (Sec. II-B).
+ */
+int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
+
+/*
+ * Enqueue one run of the plan; returns without waiting for the device.
+ *   AG_GEMM : A_src  - the G shards, contiguous ([M,K] bf16), pinned host or device memory;
+ *                      piece i is copied to the same rows of A_dev on copy_stream (may be NULL in
+ *                      FICCO_MODE_GEMM_ONLY).
+ *             A_dev  - [M,K] device; written by the transfers, read by the GEMM.
+ *             C_dev  - [M,N] device; written by the GEMM.
+ *             peer_out must be NULL.
+ *   GEMM_RS : A_src must be NULL; A_dev is read; C_dev is written by the GEMM and its row block
+ *             p (rows [p*M/G, (p+1)*M/G)) is then copied on copy_stream to peer_out[p]
+ *             ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces complete.
+ *             peer_out is a host array of `shards` pointers.
+ *   W_dev   - [K,N] device (see ficco_pack_weight).
+ * compute_stream and copy_stream must differ and have the default priority.
+ */
+int ficco_run(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
+              void *const *peer_out, void *compute_stream, void *copy_stream);
+
+/* Block until the plan's last run has completed, then report its timings (Sec. IV-A quantities
+ * are in ficco_profile_losses). FICCO_ERR_TIMEOUT (with *out filled) if the resident kernel's
+ * bounded wait expired; FICCO_ERR_STATE if the plan has not run. */
+int ficco_query_stats(ficco_plan_t *plan, ficco_stats_t *out);
+
+/* Per-piece and per-launch spans of the last run, microseconds from the run's start
+ * (FICCO_OPT_TIMING=1; FICCO_ERR_STATE otherwise). copy_* have n_chunks entries in arrival
+ * order, gemm_* have n_groups entries; any pointer may be NULL. */
+int ficco_query_spans(ficco_plan_t *plan, double *copy_begin_us, double *copy_end_us, int cap_chunks,
+                      double *gemm_begin_us, double *gemm_end_us, int cap_groups);
+
+/*
+ * Measure decomposition and contention losses for this plan's decomposition (Sec. IV-A..C):
+ * runs the isolated, decomposed and independent-concurrent modes `warmup`+`iters` times each
+ * and averages (the paper uses 10 and 5). Synchronous. AG_GEMM plans only.
+ */
+int ficco_profile_losses(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_dev,
+                         void *C_dev, void *compute_stream, void *copy_stream,
+                         int warmup, int iters, ficco_losses_t *out);
+
+/*
+ * Static schedule heuristic (Sec. V-C): from (M, K, N, shards) alone pick a schedule and a
+ * piece count. Host-only arithmetic; thresholds are constants fitted on MI355X.
+ */
+int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
+
+/* Static descriptors of an (m, N, K) bf16 GEMM: op-to-byte (Sec. IV-B) and memory traffic in
+ * bytes (Sec. IV-C). Host-only. */
+int ficco_static_descriptors(int64_t m, int64_t N, int64_t K, double *otb, double *mt_bytes);
+
+/* Ideal-overlap time (Sec. IV-A): n pieces, times scale exactly with the split. Host-only. */
+double ficco_ideal_overlap_us(double t_comm_us, double t_gemm_us, int n);
+
+void ficco_destroy(ficco_plan_t *plan);      /* waits for the plan's runs, frees what it owns */
+
+const char *ficco_strerror(int status);
+int ficco_last_hip_error(void);              /* hipError_t of the last failed HIP call on this thread */
+const char *ficco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FICCO_H */

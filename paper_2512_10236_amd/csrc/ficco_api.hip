@@ -1,0 +1,870 @@
+// C-ABI of libficco: plan construction, the transfer/launch scheduler, statistics, the
+// decomposition/contention profiler and the static schedule heuristic. See include/ficco.h for the
+// contract of every entry point.
+#include "../../include/ficco.h"
+#include "ficco_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace ficco;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                                \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) {                      \
+            g_last_hip = (int)e_;                    \
+            return FICCO_ERR_HIP;                    \
+        }                                            \
+    } while (0)
+
+struct Group {
+    int pos_begin, pos_end;      // arrival positions consumed by this launch
+};
+
+constexpr int kEpochSlots = 65536;   // pinned source words for flag writes; epoch e lives in slot e
+
+}  // namespace
+
+struct ficco_plan_s {
+    int64_t M = 0, K = 0, N = 0;
+    int G = 0, c = 0;
+    int schedule = 0, direction = FICCO_DIR_AG_GEMM, order = FICCO_ORDER_STEP_MAJOR, mode = FICCO_MODE_PAIR;
+    int timing = 0, tile_opt = 0, flag_write = 0, local_shard = -1, hold_flags = 0;
+    int64_t spin_limit_us = 2000000;
+    int device = 0;
+    int n_chunks = 0;
+    int64_t m = 0;                       // rows per chunk
+    std::vector<int32_t> arrival;        // chunk ids in issue order
+    std::vector<int32_t> group_of;       // per arrival position
+    std::vector<Group> groups;
+
+    // resources (allocated by finalize())
+    bool finalized = false;
+    int tile = 0;
+    int resident_grid = 0;
+    uint32_t *d_words = nullptr;         // flags | ticket | status
+    uint32_t *d_flags = nullptr, *d_ticket = nullptr, *d_status = nullptr;
+    int32_t *d_tables = nullptr;         // arrival | block_row0 (by arrival position)
+    int32_t *d_arrival = nullptr, *d_block_row0 = nullptr;
+    uint32_t *h_epochs = nullptr;        // pinned
+    uint16_t *d_wt = nullptr;            // packed weight [N,K]
+    const void *packed_from = nullptr;
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_copy_first = nullptr, ev_copy_last = nullptr;
+    hipEvent_t ev_gemm_first = nullptr, ev_gemm_last = nullptr;
+    std::vector<hipEvent_t> ev_dep;          // per group: transfers of the group done / launch done
+    std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
+    int wall_clock_khz = 100000;
+
+    // run state
+    uint32_t run_index = 0;
+    uint32_t ticket_total = 0;           // tickets drawn by all resident runs so far
+    bool last_had_copies = false, last_had_gemm = false, last_timing = false;
+    int64_t last_copy_bytes = 0;
+    int last_n_copies = 0, last_n_launches = 0;
+};
+
+namespace {
+
+int build_lists(ficco_plan_t *p)
+{
+    const int G = p->G, c = p->c, n = G * c;
+    p->n_chunks = n;
+    p->m = p->M / n;
+    if (p->order != FICCO_ORDER_CUSTOM) {
+        p->arrival.clear();
+        if (p->schedule == FICCO_SERIAL || p->schedule == FICCO_SHARD || p->order == FICCO_ORDER_SHARD_MAJOR) {
+            for (int i = 0; i < n; ++i) p->arrival.push_back(i);
+        } else {
+            for (int s = 0; s < c; ++s)
+                for (int j = 0; j < G; ++j) p->arrival.push_back(j * c + s);
+        }
+    }
+    // "hetero" start: the local shard's pieces come first and need no transfer
+    if (p->local_shard >= 0) {
+        std::stable_partition(p->arrival.begin(), p->arrival.end(),
+                              [&](int32_t i) { return i / c == p->local_shard; });
+    }
+    p->groups.clear();
+    p->group_of.assign(n, 0);
+    switch (p->schedule) {
+    case FICCO_SERIAL:
+    case FICCO_FINE_PERSISTENT:
+        p->groups.push_back({0, n});
+        break;
+    case FICCO_SHARD:
+    case FICCO_FINE_UNFUSED:
+        for (int q = 0; q < n; ++q) p->groups.push_back({q, q + 1});
+        break;
+    case FICCO_FINE_FUSED:
+        for (int q = 0; q < n; q += G) p->groups.push_back({q, std::min(q + G, n)});
+        break;
+    default:
+        return FICCO_ERR_ARG;
+    }
+    for (size_t g = 0; g < p->groups.size(); ++g)
+        for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q) p->group_of[q] = (int32_t)g;
+    return FICCO_OK;
+}
+
+// Rows one launch covers as equal-height blocks: contiguous runs of chunks are merged so that a
+// monolithic launch is one block of M rows and a shard-major fused step is one block too.
+struct LaunchShape { int n_blocks; int64_t rows_per_block; bool contiguous; int64_t row0; };
+
+LaunchShape launch_shape(const ficco_plan_t *p, const Group &g)
+{
+    bool contig = true;
+    for (int q = g.pos_begin + 1; q < g.pos_end; ++q)
+        if (p->arrival[q] != p->arrival[q - 1] + 1) { contig = false; break; }
+    if (contig) return {1, (int64_t)(g.pos_end - g.pos_begin) * p->m, true, (int64_t)p->arrival[g.pos_begin] * p->m};
+    return {g.pos_end - g.pos_begin, p->m, false, 0};
+}
+
+// Tile choice: estimated time = rounds of the launch over the machine x work per tile / relative
+// tile efficiency; padded (masked) rows and columns are paid in full.
+int choose_tile(const ficco_plan_t *p, int cus)
+{
+    static const struct { int id; double eff; int occ; } cand[] = {
+        {TILE_256x256, 1.00, 1}, {TILE_256x128, 0.88, 1}, {TILE_128x256, 0.88, 1},
+        {TILE_128x128, 0.72, 2}, {TILE_64x256, 0.60, 2},  {TILE_32x256, 0.40, 2},
+    };
+    double best = 1e300;
+    int best_id = TILE_128x128;
+    for (auto &cd : cand) {
+        TileShape ts = tile_shape(cd.id);
+        double total = 0;
+        if (p->schedule == FICCO_FINE_PERSISTENT) {
+            int64_t tiles = (int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+            double rounds = std::ceil((double)tiles / (cus * cd.occ));
+            total = rounds * ts.bm * ts.bn / cd.eff / cd.occ;
+        } else {
+            for (auto &g : p->groups) {
+                LaunchShape ls = launch_shape(p, g);
+                int64_t tiles = (int64_t)ls.n_blocks * ((ls.rows_per_block + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+                double rounds = std::ceil((double)tiles / (cus * cd.occ));
+                total += rounds * ts.bm * ts.bn / cd.eff / cd.occ;
+            }
+        }
+        if (total < best * 0.999) { best = total; best_id = cd.id; }
+    }
+    return best_id;
+}
+
+void release(ficco_plan_t *p)
+{
+    auto ev = [](hipEvent_t &e) { if (e) { (void)hipEventDestroy(e); e = nullptr; } };
+    ev(p->ev_begin); ev(p->ev_end); ev(p->ev_copy_first); ev(p->ev_copy_last);
+    ev(p->ev_gemm_first); ev(p->ev_gemm_last);
+    for (auto *v : {&p->ev_dep, &p->ev_copy_b, &p->ev_copy_e, &p->ev_gemm_b, &p->ev_gemm_e}) {
+        for (auto &e : *v) ev(e);
+        v->clear();
+    }
+    if (p->d_words) (void)hipFree(p->d_words);
+    if (p->d_tables) (void)hipFree(p->d_tables);
+    if (p->d_wt) (void)hipFree(p->d_wt);
+    if (p->h_epochs) (void)hipHostFree(p->h_epochs);
+    p->d_words = nullptr; p->d_tables = nullptr; p->d_wt = nullptr; p->h_epochs = nullptr;
+    p->finalized = false;
+}
+
+int make_events(std::vector<hipEvent_t> &v, size_t n)
+{
+    while (v.size() < n) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        v.push_back(e);
+    }
+    return FICCO_OK;
+}
+
+int finalize(ficco_plan_t *p)
+{
+    if (p->finalized) return FICCO_OK;
+    if (p->d_words || p->d_tables || p->h_epochs) release(p);      // a previous attempt failed half way
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (p->device >= 0 && dev != p->device) return FICCO_ERR_ARG;
+    p->device = dev;
+    int rc = build_lists(p);
+    if (rc) return rc;
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    p->tile = p->tile_opt ? p->tile_opt : choose_tile(p, cus);
+    if (tile_shape(p->tile).bm == 0) return FICCO_ERR_ARG;
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0) p->wall_clock_khz = khz;
+
+    const int n = p->n_chunks;
+    const size_t words = (size_t)n * kFlagStrideWords + 2 * kFlagStrideWords;
+    if (hipMalloc((void **)&p->d_words, words * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    HIP_TRY(hipMemset(p->d_words, 0, words * 4));
+    p->d_flags = p->d_words;
+    p->d_ticket = p->d_words + (size_t)n * kFlagStrideWords;
+    p->d_status = p->d_ticket + kFlagStrideWords;
+    if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * 2 * (size_t)n) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    p->d_arrival = p->d_tables;
+    p->d_block_row0 = p->d_tables + n;
+    std::vector<int32_t> host(2 * (size_t)n);
+    for (int q = 0; q < n; ++q) {
+        host[q] = p->arrival[q];
+        host[n + q] = (int32_t)(p->arrival[q] * p->m);
+    }
+    HIP_TRY(hipMemcpy(p->d_tables, host.data(), host.size() * 4, hipMemcpyHostToDevice));
+    if (hipHostMalloc((void **)&p->h_epochs, sizeof(uint32_t) * kEpochSlots, hipHostMallocDefault) != hipSuccess) {
+        release(p);
+        return FICCO_ERR_ALLOC;
+    }
+    for (int i = 0; i < kEpochSlots; ++i) p->h_epochs[i] = (uint32_t)i;
+
+    HIP_TRY(hipEventCreate(&p->ev_begin));
+    HIP_TRY(hipEventCreate(&p->ev_end));
+    HIP_TRY(hipEventCreate(&p->ev_copy_first));
+    HIP_TRY(hipEventCreate(&p->ev_copy_last));
+    HIP_TRY(hipEventCreate(&p->ev_gemm_first));
+    HIP_TRY(hipEventCreate(&p->ev_gemm_last));
+    rc = make_events(p->ev_dep, p->groups.size());
+    if (rc) return rc;
+    if (p->schedule == FICCO_FINE_PERSISTENT) {
+        p->resident_grid = resident_grid_size(p->tile, dev);
+        if (p->resident_grid <= 0) return FICCO_ERR_HIP;
+        TileShape ts = tile_shape(p->tile);
+        int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+        if (tiles < p->resident_grid) p->resident_grid = (int)tiles;
+    }
+    p->finalized = true;
+    return FICCO_OK;
+}
+
+int pack_weight(ficco_plan_t *p, const void *W_dev, hipStream_t s)
+{
+    if (!p->d_wt) {
+        if (hipMalloc((void **)&p->d_wt, (size_t)p->K * p->N * 2) != hipSuccess) return FICCO_ERR_ALLOC;
+    }
+    HIP_TRY(launch_pack_weight((const uint16_t *)W_dev, p->d_wt, p->K, p->N, s));
+    p->packed_from = W_dev;
+    return FICCO_OK;
+}
+
+// hipMemcpyAsync with an explicit kind taken from where the source/destination live.
+int is_device_ptr(const void *ptr, bool *is_dev)
+{
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return FICCO_ERR_ARG;            // ordinary (pageable) host memory is not accepted
+    }
+    if (at.type == hipMemoryTypeDevice) { *is_dev = true; return FICCO_OK; }
+    if (at.type == hipMemoryTypeHost) { *is_dev = false; return FICCO_OK; }
+    return FICCO_ERR_ARG;
+}
+
+GemmLaunch make_launch(const ficco_plan_t *p, const Group &g, const void *A_dev, void *C_dev)
+{
+    GemmLaunch a{};
+    a.A = (const uint16_t *)A_dev;
+    a.Wt = p->d_wt;
+    a.C = (uint16_t *)C_dev;
+    a.lda = p->K;
+    a.ldc = p->N;
+    a.N = (int32_t)p->N;
+    a.K = (int32_t)p->K;
+    LaunchShape ls = launch_shape(p, g);
+    a.n_blocks = ls.n_blocks;
+    a.rows_per_block = (int32_t)ls.rows_per_block;
+    if (ls.contiguous) {
+        a.block_row0 = nullptr;
+        a.row0 = (int32_t)ls.row0;
+    } else {
+        a.block_row0 = p->d_block_row0 + g.pos_begin;
+        a.row0 = 0;
+    }
+    return a;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+int ficco_static_descriptors(int64_t m, int64_t N, int64_t K, double *otb, double *mt_bytes)
+{
+    if (m < 0 || N < 0 || K < 0) return FICCO_ERR_ARG;
+    const double bytes = 2.0 * ((double)m * K + (double)N * K + (double)m * N);
+    if (mt_bytes) *mt_bytes = bytes;
+    if (otb) *otb = bytes > 0 ? 2.0 * (double)m * (double)N * (double)K / bytes : 0.0;
+    return FICCO_OK;
+}
+
+double ficco_ideal_overlap_us(double t_comm_us, double t_gemm_us, int n)
+{
+    if (n < 1) n = 1;
+    // piece q's GEMM starts when its transfer has landed and the previous GEMM has finished
+    double copy_done = 0, gemm_done = 0;
+    for (int q = 0; q < n; ++q) {
+        copy_done += t_comm_us / n;
+        gemm_done = std::max(gemm_done, copy_done) + t_gemm_us / n;
+    }
+    return gemm_done;
+}
+
+int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
+{
+    if (M < 1 || K < 1 || N < 1 || shards < 1 || !schedule || !chunks) return FICCO_ERR_ARG;
+    if (M % shards) return FICCO_ERR_SHAPE;
+    // Decision rule of Sec. V-C on the step GEMM (M/shards rows): the combined op-to-byte and
+    // memory-traffic metric (their product, i.e. the step's flop count) against a machine
+    // threshold. Small steps are sensitive to decomposition loss: keep launches large (fused,
+    // few pieces). Large steps tolerate finer pieces, which shorten the exposed first transfer.
+    const int64_t ms = M / shards;
+    const double x = 2.0 * (double)ms * (double)N * (double)K;
+    const double T = 6.0e9, ratio = 5.0;
+    int sch, c;
+    if (x < T) { sch = FICCO_FINE_FUSED; c = 2; }
+    else if (x > ratio * T) { sch = FICCO_FINE_PERSISTENT; c = 4; }
+    else { sch = FICCO_FINE_PERSISTENT; c = 2; }
+    while (c > 1 && (ms % c || ms / c < 128)) c >>= 1;
+    *schedule = sch;
+    *chunks = c;
+    return FICCO_OK;
+}
+
+int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule, ficco_plan_t **out)
+{
+    if (!out) return FICCO_ERR_ARG;
+    if (M < 1 || K < 1 || N < 1 || shards < 1) return FICCO_ERR_SHAPE;
+    if (schedule == FICCO_AUTO) {
+        int rc = ficco_pick_schedule(M, K, N, shards, &schedule, &chunks);
+        if (rc) return rc;
+    }
+    if (schedule < FICCO_SERIAL || schedule > FICCO_FINE_PERSISTENT) return FICCO_ERR_ARG;
+    if (chunks < 1) return FICCO_ERR_SHAPE;
+    if ((schedule == FICCO_SERIAL || schedule == FICCO_SHARD) && chunks != 1) return FICCO_ERR_SHAPE;
+    if ((int64_t)shards * chunks > 4096 || M % ((int64_t)shards * chunks)) return FICCO_ERR_SHAPE;
+    if (K % 64 || N % 8) return FICCO_ERR_SHAPE;
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    ficco_plan_t *p = new (std::nothrow) ficco_plan_t();
+    if (!p) return FICCO_ERR_ALLOC;
+    p->M = M; p->K = K; p->N = N; p->G = shards; p->c = chunks; p->schedule = schedule;
+    p->device = -1;                      // bound to the current device on first use
+    p->order = (schedule == FICCO_SERIAL || schedule == FICCO_SHARD) ? FICCO_ORDER_SHARD_MAJOR : FICCO_ORDER_STEP_MAJOR;
+    int rc = build_lists(p);
+    if (rc) { delete p; return rc; }
+    *out = p;
+    return FICCO_OK;
+}
+
+int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
+{
+    if (!p) return FICCO_ERR_ARG;
+    const bool late_ok = option == FICCO_OPT_MODE || option == FICCO_OPT_TIMING || option == FICCO_OPT_HOLD_FLAGS ||
+                         option == FICCO_OPT_SPIN_LIMIT_US;
+    if (p->finalized && !late_ok) return FICCO_ERR_STATE;
+    switch (option) {
+    case FICCO_OPT_DIRECTION:
+        if (value != FICCO_DIR_AG_GEMM && value != FICCO_DIR_GEMM_RS) return FICCO_ERR_ARG;
+        p->direction = (int)value;
+        break;
+    case FICCO_OPT_ORDER:
+        if (value != FICCO_ORDER_STEP_MAJOR && value != FICCO_ORDER_SHARD_MAJOR) return FICCO_ERR_ARG;
+        if (p->schedule == FICCO_SERIAL || p->schedule == FICCO_SHARD) value = FICCO_ORDER_SHARD_MAJOR;
+        p->order = (int)value;
+        break;
+    case FICCO_OPT_MODE:
+        if (value < FICCO_MODE_PAIR || value > FICCO_MODE_INDEPENDENT) return FICCO_ERR_ARG;
+        p->mode = (int)value;
+        break;
+    case FICCO_OPT_TIMING:
+        if (value != 0 && value != 1) return FICCO_ERR_ARG;
+        p->timing = (int)value;
+        break;
+    case FICCO_OPT_TILE:
+        if (value != 0 && tile_shape((int)value).bm == 0) return FICCO_ERR_ARG;
+        p->tile_opt = (int)value;
+        break;
+    case FICCO_OPT_FLAG_WRITE:
+        if (value != 0 && value != 1) return FICCO_ERR_ARG;
+        p->flag_write = (int)value;
+        break;
+    case FICCO_OPT_SPIN_LIMIT_US:
+        if (value < 1 || value > 60000000) return FICCO_ERR_ARG;
+        p->spin_limit_us = value;
+        break;
+    case FICCO_OPT_LOCAL_SHARD:
+        if (value < -1 || value >= p->G) return FICCO_ERR_ARG;
+        p->local_shard = (int)value;
+        break;
+    case FICCO_OPT_HOLD_FLAGS:
+        if (value != 0 && value != 1) return FICCO_ERR_ARG;
+        p->hold_flags = (int)value;
+        break;
+    default:
+        return FICCO_ERR_ARG;
+    }
+    if (!p->finalized) return build_lists(p);
+    return FICCO_OK;
+}
+
+int ficco_plan_set_arrival(ficco_plan_t *p, const int32_t *chunk_ids, int n)
+{
+    if (!p || !chunk_ids) return FICCO_ERR_ARG;
+    if (p->finalized) return FICCO_ERR_STATE;
+    if (n != p->n_chunks) return FICCO_ERR_ARG;
+    std::vector<char> seen(n, 0);
+    for (int q = 0; q < n; ++q) {
+        if (chunk_ids[q] < 0 || chunk_ids[q] >= n || seen[chunk_ids[q]]) return FICCO_ERR_ARG;
+        seen[chunk_ids[q]] = 1;
+    }
+    p->arrival.assign(chunk_ids, chunk_ids + n);
+    p->order = FICCO_ORDER_CUSTOM;
+    return build_lists(p);
+}
+
+int ficco_plan_info(const ficco_plan_t *p, ficco_plan_info_t *out)
+{
+    if (!p || !out) return FICCO_ERR_ARG;
+    ficco_plan_info_t o{};
+    o.M = p->M; o.K = p->K; o.N = p->N;
+    o.shards = p->G; o.chunks = p->c;
+    o.schedule = p->schedule; o.direction = p->direction; o.order = p->order; o.mode = p->mode;
+    o.n_chunks = p->n_chunks;
+    o.n_groups = (int32_t)p->groups.size();
+    o.chunk_rows = p->m;
+    TileShape ts = tile_shape(p->tile);
+    o.tile_m = ts.bm; o.tile_n = ts.bn; o.tile_k = p->tile ? kBK : 0;
+    o.resident_grid = p->resident_grid;
+    // descriptors of one launch: the resident kernel's unit of work is one piece
+    int64_t rows = p->schedule == FICCO_FINE_PERSISTENT
+                       ? p->m
+                       : (int64_t)(p->groups[0].pos_end - p->groups[0].pos_begin) * p->m;
+    ficco_static_descriptors(rows, p->N, p->K, &o.otb, &o.mt_bytes);
+    *out = o;
+    return FICCO_OK;
+}
+
+int ficco_plan_arrival(const ficco_plan_t *p, int32_t *chunk_ids, int32_t *group_ids, int cap)
+{
+    if (!p) return FICCO_ERR_ARG;
+    if (cap < p->n_chunks) return FICCO_ERR_ARG;
+    for (int q = 0; q < p->n_chunks; ++q) {
+        if (chunk_ids) chunk_ids[q] = p->arrival[q];
+        if (group_ids) group_ids[q] = p->group_of[q];
+    }
+    return FICCO_OK;
+}
+
+int ficco_pack_weight(ficco_plan_t *p, const void *W_dev, void *stream)
+{
+    if (!p || !W_dev) return FICCO_ERR_ARG;
+    int rc = finalize(p);
+    if (rc) return rc;
+    bool dev = false;
+    rc = is_device_ptr(W_dev, &dev);
+    if (rc || !dev) return FICCO_ERR_ARG;
+    return pack_weight(p, W_dev, (hipStream_t)stream);
+}
+
+int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
+              void *const *peer_out, void *compute_stream, void *copy_stream)
+{
+    if (!p || !A_dev || !W_dev || !C_dev) return FICCO_ERR_ARG;
+    hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
+    if (cs == xs) return FICCO_ERR_ARG;
+    const bool rs = p->direction == FICCO_DIR_GEMM_RS;
+    const int mode = p->mode;
+    const bool do_copy = mode != FICCO_MODE_GEMM_ONLY;
+    const bool do_gemm = mode != FICCO_MODE_COPY_ONLY;
+    const bool dependent = mode == FICCO_MODE_PAIR;
+    if (rs) {
+        if (A_src) return FICCO_ERR_ARG;
+        if (do_copy && !peer_out) return FICCO_ERR_ARG;
+        if (p->schedule == FICCO_FINE_PERSISTENT || p->local_shard >= 0) return FICCO_ERR_ARG;
+    } else {
+        if (peer_out) return FICCO_ERR_ARG;
+        if (do_copy && !A_src) return FICCO_ERR_ARG;
+    }
+    int rc = finalize(p);
+    if (rc) return rc;
+
+    bool dev = false;
+    for (const void *ptr : {(const void *)A_dev, W_dev, (const void *)C_dev}) {
+        rc = is_device_ptr(ptr, &dev);
+        if (rc || !dev) return FICCO_ERR_ARG;
+    }
+    bool src_dev = false;
+    if (!rs && do_copy) {
+        rc = is_device_ptr(A_src, &src_dev);
+        if (rc) return rc;
+    }
+    std::vector<char> peer_dev;
+    if (rs && do_copy) {
+        peer_dev.resize(p->G);
+        for (int j = 0; j < p->G; ++j) {
+            if (!peer_out[j]) return FICCO_ERR_ARG;
+            bool d = false;
+            rc = is_device_ptr(peer_out[j], &d);
+            if (rc) return rc;
+            peer_dev[j] = d;
+        }
+    }
+    if (do_gemm && p->packed_from != W_dev) {
+        rc = pack_weight(p, W_dev, cs);
+        if (rc) return rc;
+    }
+    const bool timing = p->timing != 0;
+    const int n = p->n_chunks;
+    if (timing) {
+        if ((rc = make_events(p->ev_copy_b, n))) return rc;
+        if ((rc = make_events(p->ev_copy_e, n))) return rc;
+        if ((rc = make_events(p->ev_gemm_b, p->groups.size()))) return rc;
+        if ((rc = make_events(p->ev_gemm_e, p->groups.size()))) return rc;
+    }
+
+    const bool first = p->run_index == 0;
+    p->run_index += 1;
+    const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
+    const size_t row_bytes_a = (size_t)p->K * 2, row_bytes_c = (size_t)p->N * 2;
+    const int c = p->c;
+
+    // Order this run after the previous one on both streams, then start the clock on the stream
+    // that moves first.
+    if (!first) {
+        HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+        HIP_TRY(hipStreamWaitEvent(cs, p->ev_end, 0));
+    }
+    hipStream_t lead = (rs || !do_copy) ? cs : xs, follow = (rs || !do_copy) ? xs : cs;
+    HIP_TRY(hipEventRecord(p->ev_begin, lead));
+    HIP_TRY(hipStreamWaitEvent(follow, p->ev_begin, 0));
+
+    int n_copies = 0, n_launches = 0;
+    int64_t copy_bytes = 0;
+    bool copy_first_recorded = false, gemm_first_recorded = false;
+
+    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && chunk / c == p->local_shard; };
+
+    auto issue_copy_ag = [&](int q) -> int {
+        const int chunk = p->arrival[q];
+        if (is_local(chunk)) return FICCO_OK;
+        const size_t off = (size_t)chunk * p->m * row_bytes_a, bytes = (size_t)p->m * row_bytes_a;
+        if (timing) HIP_TRY(hipEventRecord(p->ev_copy_b[q], xs));
+        if (!copy_first_recorded) {
+            if (timing) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+            copy_first_recorded = true;
+        }
+        HIP_TRY(hipMemcpyAsync((char *)A_dev + off, (const char *)A_src + off, bytes,
+                               src_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, xs));
+        if (timing) HIP_TRY(hipEventRecord(p->ev_copy_e[q], xs));
+        ++n_copies;
+        copy_bytes += (int64_t)bytes;
+        return FICCO_OK;
+    };
+    auto issue_copy_rs = [&](int q) -> int {
+        const int chunk = p->arrival[q];
+        const int peer = chunk / c;
+        const size_t off = (size_t)chunk * p->m * row_bytes_c, bytes = (size_t)p->m * row_bytes_c;
+        const size_t peer_off = (size_t)(chunk % c) * p->m * row_bytes_c;
+        if (timing) HIP_TRY(hipEventRecord(p->ev_copy_b[q], xs));
+        HIP_TRY(hipMemcpyAsync((char *)peer_out[peer] + peer_off, (const char *)C_dev + off, bytes,
+                               peer_dev[peer] ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, xs));
+        if (timing) HIP_TRY(hipEventRecord(p->ev_copy_e[q], xs));
+        ++n_copies;
+        copy_bytes += (int64_t)bytes;
+        return FICCO_OK;
+    };
+    auto issue_gemm = [&](size_t g) -> int {
+        if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[g], cs));
+        if (!gemm_first_recorded) {
+            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+            gemm_first_recorded = true;
+        }
+        GemmLaunch a = make_launch(p, p->groups[g], A_dev, C_dev);
+        HIP_TRY(launch_gemm(p->tile, a, cs));
+        if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[g], cs));
+        ++n_launches;
+        return FICCO_OK;
+    };
+
+    if (!timing) {
+        // span events: first/last of each kind are recorded once, outside the per-piece path
+        if (do_copy && !rs) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+        if (do_gemm) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+    }
+
+    if (p->schedule == FICCO_FINE_PERSISTENT) {
+        // ---- one resident kernel; transfers raise per-piece flags
+        if (do_gemm) {
+            ResidentLaunch r{};
+            Group all{0, n};
+            r.g = make_launch(p, all, A_dev, C_dev);
+            r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
+            r.arrival = p->d_arrival;
+            r.n_chunks = n;
+            r.flags = p->d_flags;
+            r.epoch = epoch;
+            r.ticket = p->d_ticket;
+            r.ticket_base = p->ticket_total;
+            r.status = p->d_status;
+            r.spin_limit_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
+            r.grid = p->resident_grid;
+            if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
+            else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
+            else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
+            TileShape ts = tile_shape(p->tile);
+            const int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+            p->ticket_total += (uint32_t)tiles + (uint32_t)r.grid;
+            if (timing) {
+                HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
+                HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+            }
+            gemm_first_recorded = true;
+            HIP_TRY(launch_resident(p->tile, r, cs));
+            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
+            ++n_launches;
+        }
+        if (do_copy) {
+            for (int q = 0; q < n; ++q) {
+                if ((rc = issue_copy_ag(q))) return rc;
+                const int chunk = p->arrival[q];
+                if (dependent && !is_local(chunk) && !p->hold_flags) {
+                    uint32_t *flag = p->d_flags + (size_t)chunk * kFlagStrideWords;
+                    if (p->flag_write == 0)
+                        HIP_TRY(hipMemcpyAsync(flag, p->h_epochs + epoch, 4, hipMemcpyHostToDevice, xs));
+                    else
+                        HIP_TRY(hipStreamWriteValue32(xs, flag, epoch, 0));
+                }
+            }
+        }
+    } else if (!rs) {
+        // ---- all-gather -> GEMM, one launch per group of landed pieces
+        if (!dependent) {
+            if (do_copy) for (int q = 0; q < n; ++q) if ((rc = issue_copy_ag(q))) return rc;
+            if (do_gemm) for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
+        } else {
+            for (size_t g = 0; g < p->groups.size(); ++g) {
+                bool any = false;
+                for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q) {
+                    if (!is_local(p->arrival[q])) any = true;
+                    if ((rc = issue_copy_ag(q))) return rc;
+                }
+                if (any) {
+                    // the copy stream is in order: the event after the group's last transfer covers all of them
+                    HIP_TRY(hipEventRecord(p->ev_dep[g], xs));
+                    HIP_TRY(hipStreamWaitEvent(cs, p->ev_dep[g], 0));
+                }
+                if ((rc = issue_gemm(g))) return rc;
+            }
+        }
+    } else {
+        // ---- GEMM -> reduce-scatter (data movement): a group's rows leave as soon as its launch is done
+        if (!dependent) {
+            if (do_gemm) for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
+            if (do_copy) {
+                HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+                for (int q = 0; q < n; ++q) if ((rc = issue_copy_rs(q))) return rc;
+            }
+        } else {
+            for (size_t g = 0; g < p->groups.size(); ++g) {
+                if ((rc = issue_gemm(g))) return rc;
+                HIP_TRY(hipEventRecord(p->ev_dep[g], cs));
+                HIP_TRY(hipStreamWaitEvent(xs, p->ev_dep[g], 0));
+                if (g == 0) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+                for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q)
+                    if ((rc = issue_copy_rs(q))) return rc;
+            }
+        }
+    }
+
+    // ---- join: the run ends when both streams are done; ev_end is recorded on the compute stream
+    if (do_gemm) HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+    HIP_TRY(hipEventRecord(p->ev_copy_last, xs));
+    HIP_TRY(hipStreamWaitEvent(cs, p->ev_copy_last, 0));
+    HIP_TRY(hipEventRecord(p->ev_end, cs));
+    HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+
+    p->last_had_copies = n_copies > 0;
+    p->last_had_gemm = n_launches > 0;
+    p->last_timing = timing;
+    p->last_copy_bytes = copy_bytes;
+    p->last_n_copies = n_copies;
+    p->last_n_launches = n_launches;
+    return FICCO_OK;
+}
+
+int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
+{
+    if (!p || !out) return FICCO_ERR_ARG;
+    if (!p->finalized || p->run_index == 0) return FICCO_ERR_STATE;
+    HIP_TRY(hipEventSynchronize(p->ev_end));
+    ficco_stats_t s{};
+    float ms = 0;
+    HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_end));
+    s.wall_us = ms * 1e3;
+    if (p->last_had_copies) {
+        HIP_TRY(hipEventElapsedTime(&ms, p->ev_copy_first, p->ev_copy_last));
+        s.copy_span_us = ms * 1e3;
+    }
+    if (p->last_had_gemm) {
+        HIP_TRY(hipEventElapsedTime(&ms, p->ev_gemm_first, p->ev_gemm_last));
+        s.gemm_span_us = ms * 1e3;
+    }
+    s.gemm_busy_us = s.gemm_span_us;
+    s.copy_busy_us = s.copy_span_us;
+    if (p->last_timing) {
+        double gb = 0, cb = 0;
+        if (p->last_had_gemm) {
+            const size_t ng = p->schedule == FICCO_FINE_PERSISTENT ? 1 : p->groups.size();
+            for (size_t g = 0; g < ng; ++g) {
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_gemm_b[g], p->ev_gemm_e[g]));
+                gb += ms * 1e3;
+            }
+            s.gemm_busy_us = gb;
+        }
+        if (p->last_had_copies) {
+            for (int q = 0; q < p->n_chunks; ++q) {
+                const int chunk = p->arrival[q];
+                if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_copy_b[q], p->ev_copy_e[q]));
+                cb += ms * 1e3;
+            }
+            s.copy_busy_us = cb;
+        }
+    }
+    s.exposed_comm_us = s.wall_us - s.gemm_busy_us;
+    s.flops = 2 * p->M * p->N * p->K;
+    s.eff_tflops = s.wall_us > 0 ? (double)s.flops / s.wall_us * 1e-6 : 0.0;
+    s.copy_bytes = p->last_copy_bytes;
+    s.copy_gbps = s.copy_span_us > 0 ? (double)s.copy_bytes / s.copy_span_us * 1e-3 : 0.0;
+    s.n_copies = p->last_n_copies;
+    s.n_launches = p->last_n_launches;
+    s.run_index = (int32_t)p->run_index;
+    if (p->schedule == FICCO_FINE_PERSISTENT && p->last_had_gemm) {
+        uint32_t st = 0;
+        HIP_TRY(hipMemcpy(&st, p->d_status, 4, hipMemcpyDeviceToHost));
+        if (st) {
+            s.timed_out = 1;
+            HIP_TRY(hipMemset(p->d_status, 0, 4));
+        }
+    }
+    *out = s;
+    return s.timed_out ? FICCO_ERR_TIMEOUT : FICCO_OK;
+}
+
+int ficco_query_spans(ficco_plan_t *p, double *copy_begin_us, double *copy_end_us, int cap_chunks,
+                      double *gemm_begin_us, double *gemm_end_us, int cap_groups)
+{
+    if (!p) return FICCO_ERR_ARG;
+    if (!p->finalized || p->run_index == 0 || !p->last_timing) return FICCO_ERR_STATE;
+    HIP_TRY(hipEventSynchronize(p->ev_end));
+    float ms = 0;
+    if (copy_begin_us || copy_end_us) {
+        if (cap_chunks < p->n_chunks) return FICCO_ERR_ARG;
+        for (int q = 0; q < p->n_chunks; ++q) {
+            const int chunk = p->arrival[q];
+            const bool local = p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard;
+            double b = 0, e = 0;
+            if (p->last_had_copies && !local) {
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_copy_b[q])); b = ms * 1e3;
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_copy_e[q])); e = ms * 1e3;
+            }
+            if (copy_begin_us) copy_begin_us[q] = b;
+            if (copy_end_us) copy_end_us[q] = e;
+        }
+    }
+    if (gemm_begin_us || gemm_end_us) {
+        const int ng = (int)p->groups.size();
+        if (cap_groups < ng) return FICCO_ERR_ARG;
+        for (int g = 0; g < ng; ++g) {
+            double b = 0, e = 0;
+            if (p->last_had_gemm) {
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_gemm_b[g])); b = ms * 1e3;
+                HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_gemm_e[g])); e = ms * 1e3;
+            }
+            if (gemm_begin_us) gemm_begin_us[g] = b;
+            if (gemm_end_us) gemm_end_us[g] = e;
+        }
+    }
+    return FICCO_OK;
+}
+
+int ficco_profile_losses(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
+                         void *compute_stream, void *copy_stream, int warmup, int iters, ficco_losses_t *out)
+{
+    if (!p || !out || !A_src || !A_dev || !W_dev || !C_dev || iters < 1 || warmup < 0) return FICCO_ERR_ARG;
+    if (p->direction != FICCO_DIR_AG_GEMM) return FICCO_ERR_ARG;
+    ficco_plan_t *whole = nullptr;
+    int rc = ficco_plan(p->M, p->K, p->N, p->G, 1, FICCO_SERIAL, &whole);
+    if (rc) return rc;
+    const int saved_mode = p->mode, saved_timing = p->timing;
+
+    // mean span of one mode over `iters` runs after `warmup`
+    auto measure = [&](ficco_plan_t *q, int mode, double *gemm_us, double *copy_us) -> int {
+        int r = ficco_plan_set(q, FICCO_OPT_MODE, mode);
+        if (r) return r;
+        if ((r = ficco_plan_set(q, FICCO_OPT_TIMING, 0))) return r;
+        double g = 0, cp = 0;
+        for (int it = 0; it < warmup + iters; ++it) {
+            if ((r = ficco_run(q, A_src, A_dev, W_dev, C_dev, nullptr, compute_stream, copy_stream))) return r;
+            ficco_stats_t s;
+            if ((r = ficco_query_stats(q, &s))) return r;
+            if (it >= warmup) { g += s.gemm_span_us; cp += s.copy_span_us; }
+        }
+        if (gemm_us) *gemm_us = g / iters;
+        if (copy_us) *copy_us = cp / iters;
+        return FICCO_OK;
+    };
+
+    ficco_losses_t L{};
+    do {
+        if ((rc = measure(whole, FICCO_MODE_GEMM_ONLY, &L.t_gemm_whole_us, nullptr))) break;
+        if ((rc = measure(whole, FICCO_MODE_COPY_ONLY, nullptr, &L.t_copy_whole_us))) break;
+        if ((rc = measure(p, FICCO_MODE_GEMM_ONLY, &L.t_gemm_pieces_us, nullptr))) break;
+        if ((rc = measure(p, FICCO_MODE_COPY_ONLY, nullptr, &L.t_copy_pieces_us))) break;
+        if ((rc = measure(p, FICCO_MODE_INDEPENDENT, &L.t_gemm_pieces_cont_us, &L.t_copy_pieces_cont_us))) break;
+    } while (0);
+    ficco_destroy(whole);
+    p->mode = saved_mode;
+    p->timing = saved_timing;
+    if (rc) return rc;
+    L.gemm_dil = L.t_gemm_pieces_us / L.t_gemm_whole_us;
+    L.gemm_cil = L.t_gemm_pieces_cont_us / L.t_gemm_pieces_us;
+    L.comm_dil = L.t_copy_pieces_us / L.t_copy_whole_us;
+    L.comm_cil = L.t_copy_pieces_cont_us / L.t_copy_pieces_us;
+    L.ideal_us = ficco_ideal_overlap_us(L.t_copy_whole_us, L.t_gemm_whole_us, p->schedule == FICCO_SERIAL ? 1 : ((int)p->groups.size() > 1 ? (int)p->groups.size() : p->n_chunks));
+    *out = L;
+    return FICCO_OK;
+}
+
+void ficco_destroy(ficco_plan_t *p)
+{
+    if (!p) return;
+    if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
+    release(p);
+    delete p;
+}
+
+const char *ficco_strerror(int status)
+{
+    switch (status) {
+    case FICCO_OK: return "ok";
+    case FICCO_ERR_ARG: return "invalid argument";
+    case FICCO_ERR_SHAPE: return "shape rule violated";
+    case FICCO_ERR_ALLOC: return "allocation failed";
+    case FICCO_ERR_HIP: return "HIP call failed";
+    case FICCO_ERR_TIMEOUT: return "resident kernel gave up waiting for a ready flag";
+    case FICCO_ERR_STATE: return "call not valid in this state";
+    default: return "unknown status";
+    }
+}
+
+int ficco_last_hip_error(void) { return g_last_hip; }
+
+const char *ficco_version(void) { return "ficco-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

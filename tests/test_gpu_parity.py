@@ -1,0 +1,316 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+seeded inputs; plus bit-equality across schedules, dependency checks (NaN-poisoned destination,
+delayed and reordered transfers) and the error path of the resident kernel's bounded wait.
+
+Tolerance: max |gpu - ref| / (|ref| + 1) <= 8e-3 (one bf16 output rounding is <= 2^-8 relative;
+fp32 accumulation over K <= 8192 unit-variance products adds far less)."""
+import numpy as np
+import pytest
+
+import ficco_inputs as fi
+import paper_2512_10236_amd as ficco
+from oracle import gemm as og
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 8e-3
+NAN_BF16 = 0x7FC0
+ALL_SCHEDULES = [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4),
+                 (ficco.FICCO_FINE_FUSED, 4), (ficco.FICCO_FINE_PERSISTENT, 4)]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    ficco.load()                      # fails loudly if the HIP library is missing
+    return dict(dev=torch.device("cuda:0"), cs=torch.cuda.Stream(), xs=torch.cuda.Stream())
+
+
+def as_i16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+
+
+def widen(bits):
+    return fi.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, delay_copy=False,
+           timing=0, allow_timeout=False, runs=1):
+    """One all-gather -> GEMM through the C ABI; returns (C bits, stats)."""
+    dev = gpu["dev"]
+    A = np.concatenate(shards, 0)
+    M, K = A.shape
+    N = W.shape[1]
+    G = len(shards)
+    A_src = as_i16(A).pin_memory() if src == "pinned" else as_i16(A).to(dev)
+    W_dev = as_i16(W).to(dev)
+    A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)     # poison: unread rows show up as NaN
+    C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    torch.cuda.synchronize()
+    plan = ficco.ficco_plan(M, K, N, G, c, schedule)
+    try:
+        for o, v in opts:
+            ficco.ficco_plan_set(plan, o, v)
+        if arrival is not None:
+            ficco.ficco_plan_set_arrival(plan, arrival)
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_TIMING, timing)
+        for r in range(runs):
+            if r:
+                A_dev.fill_(NAN_BF16)
+                torch.cuda.synchronize()
+            if delay_copy:
+                with torch.cuda.stream(gpu["xs"]):
+                    torch.cuda._sleep(40_000_000)          # tens of ms before the first transfer may start
+            ficco.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
+            st = ficco.ficco_query_stats(plan, allow_timeout=allow_timeout)
+        info = ficco.ficco_plan_info(plan)
+    finally:
+        ficco.ficco_destroy(plan)
+    torch.cuda.synchronize()
+    return C_dev.cpu().numpy().view(np.uint16), st, info
+
+
+def check(bits, ref, what=""):
+    out = widen(bits)
+    assert np.isfinite(out).all(), f"{what}: non-finite output (a tile ran before its rows landed?)"
+    err = og.rel_err(out, ref)
+    assert err <= TOL, f"{what}: rel err {err}"
+    return err
+
+
+# ------------------------------------------------------------------------------------------------
+def test_cfg1_all_schedules_match_oracle_and_each_other(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    ref = og.ag_gemm(shards, W)
+    base = None
+    for sched, c in ALL_SCHEDULES + [(ficco.FICCO_FINE_UNFUSED, 1), (ficco.FICCO_FINE_PERSISTENT, 1)]:
+        bits, st, info = run_ag(gpu, shards, W, sched, c)
+        check(bits, ref, ficco.SCHEDULE_NAMES[sched])
+        if base is None:
+            base = bits
+        assert np.array_equal(bits, base), f"{ficco.SCHEDULE_NAMES[sched]} c={c} differs bitwise from serial"
+        assert st.n_copies == info.n_chunks and st.copy_bytes == 512 * 1024 * 2
+        assert st.wall_us > 0 and st.flops == 2 * 512 * 1024 * 1024
+
+
+@pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
+                                  ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256])
+def test_every_tile_shape_ragged(gpu, tile):
+    # 3 shards x 2 pieces of 88 rows (no tile height divides it), N = 328 (not a tile width), K = 192
+    G, c, m, K, N = 3, 2, 88, 192, 328
+    shards = fi.make_shards(21, G * c * m, K, G)
+    W = fi.make_weight(21, K, N)
+    ref = og.ag_gemm(shards, W)
+    outs = []
+    for sched, cc in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, c), (ficco.FICCO_FINE_PERSISTENT, c)]:
+        bits, _, info = run_ag(gpu, shards, W, sched, cc, opts=[(ficco.FICCO_OPT_TILE, tile)])
+        check(bits, ref, f"tile {tile} sched {sched}")
+        outs.append(bits)
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+    test_every_tile_shape_ragged.results = getattr(test_every_tile_shape_ragged, "results", []) + [outs[0]]
+    # tile shape must not change the bits either
+    assert np.array_equal(test_every_tile_shape_ragged.results[0], outs[0])
+
+
+def test_closed_forms_on_gpu(gpu):
+    G, ms, K = 4, 96, 256
+    M = G * ms
+    # identity: C == A bit for bit
+    shards = fi.make_shards(5, M, K, G)
+    eye = fi.f32_to_bf16_bits(np.eye(K, dtype=np.float32))
+    for sched, c in ALL_SCHEDULES:
+        bits, _, _ = run_ag(gpu, shards, eye, sched, c)
+        assert np.array_equal(bits, np.concatenate(shards, 0)), sched
+    # all ones: every entry equals K exactly (K is representable in bf16)
+    one = [np.full((ms, K), 0x3F80, np.uint16)] * G
+    Wone = np.full((K, 64), 0x3F80, np.uint16)
+    bits, _, _ = run_ag(gpu, one, Wone, ficco.FICCO_FINE_PERSISTENT, 2)
+    assert np.array_equal(widen(bits), np.full((M, 64), float(K)))
+    # row selector: C[i,:] = W[i mod K,:] bit for bit - a misplaced piece cannot hide
+    A = np.zeros((M, K), np.float32)
+    A[np.arange(M), np.arange(M) % K] = 1.0
+    Ab = fi.f32_to_bf16_bits(A)
+    W = fi.make_weight(9, K, 136)
+    for sched, c in ALL_SCHEDULES:
+        bits, _, _ = run_ag(gpu, [Ab[j * ms:(j + 1) * ms] for j in range(G)], W, sched, c)
+        assert np.array_equal(bits, W[np.arange(M) % K]), sched
+    # power-of-two scaling is exact
+    b1, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SHARD, 1)
+    twice = [fi.f32_to_bf16_bits(2.0 * fi.bf16_bits_to_f32(s)) for s in shards]
+    b2, _, _ = run_ag(gpu, twice, W, ficco.FICCO_SHARD, 1)
+    assert np.array_equal(widen(b2), 2.0 * widen(b1))
+
+
+def test_arrival_order_and_delay_do_not_change_bits(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    n = 16
+    rng = np.random.default_rng(0)
+    orders = [list(range(n - 1, -1, -1)), list(rng.permutation(n))]
+    for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+        for arr in orders:
+            bits, _, _ = run_ag(gpu, shards, W, sched, 4, arrival=arr)
+            assert np.array_equal(bits, base), (sched, arr)
+        bits, _, _ = run_ag(gpu, shards, W, sched, 4, opts=[(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)])
+        assert np.array_equal(bits, base)
+        # transfers held back for tens of ms: the GEMM must wait for them (poison would show)
+        bits, st, _ = run_ag(gpu, shards, W, sched, 4, delay_copy=True)
+        assert np.array_equal(bits, base), sched
+
+
+def test_repeated_runs_and_timing_spans(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    for sched, c in ALL_SCHEDULES:
+        bits, st, info = run_ag(gpu, shards, W, sched, c, timing=1, runs=3)
+        assert np.array_equal(bits, base)
+        assert st.run_index == 3 and st.n_launches == info.n_groups
+        assert 0 < st.gemm_busy_us <= st.wall_us * 1.05
+        assert 0 < st.copy_span_us <= st.wall_us * 1.05
+
+
+def test_flag_written_by_stream_write_value(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4, opts=[(ficco.FICCO_OPT_FLAG_WRITE, 1)], runs=2)
+    assert np.array_equal(bits, base)
+
+
+def test_device_staging_source(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    for sched, c in ALL_SCHEDULES:
+        bits, _, _ = run_ag(gpu, shards, W, sched, c, src="device")
+        assert np.array_equal(bits, base)
+
+
+def test_local_shard_needs_no_transfer(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    ref = og.ag_gemm(shards, W)
+    dev = gpu["dev"]
+    A = np.concatenate(shards, 0)
+    M, K, N, G = 512, 1024, 1024, 4
+    for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+        A_src = as_i16(A).pin_memory()
+        A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+        A_dev[256:384] = as_i16(A[256:384]).to(dev)            # shard 2 is already here
+        C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+        W_dev = as_i16(W).to(dev)
+        torch.cuda.synchronize()
+        plan = ficco.ficco_plan(M, K, N, G, 4, sched)
+        try:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_LOCAL_SHARD, 2)
+            ficco.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
+            st = ficco.ficco_query_stats(plan)
+        finally:
+            ficco.ficco_destroy(plan)
+        assert st.n_copies == 12 and st.copy_bytes == 384 * 1024 * 2
+        check(C_dev.cpu().numpy().view(np.uint16), ref, f"local shard, sched {sched}")
+
+
+def test_gemm_rs_streams_row_blocks_to_peers(gpu):
+    dev = gpu["dev"]
+    M, K, N, G = 1024, 256, 512, 8
+    A = fi.normal_bf16(3, fi.TENSOR_A, M, K)
+    W = fi.make_weight(3, K, N)
+    blocks = og.gemm_rs_blocks(A, W, G)
+    base = None
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4), (ficco.FICCO_FINE_FUSED, 2)]:
+        for kind in ("device", "pinned"):
+            A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+            C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+            if kind == "device":
+                peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16, device=dev) for _ in range(G)]
+            else:
+                peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16).pin_memory() for _ in range(G)]
+            torch.cuda.synchronize()
+            plan = ficco.ficco_plan(M, K, N, G, c, sched)
+            try:
+                ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+                ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
+                st = ficco.ficco_query_stats(plan)
+            finally:
+                ficco.ficco_destroy(plan)
+            torch.cuda.synchronize()
+            got = [p.cpu().numpy().view(np.uint16) for p in peers]
+            for j in range(G):
+                check(got[j], blocks[j], f"peer {j} {kind} sched {sched}")
+            allbits = np.concatenate(got, 0)
+            assert np.array_equal(allbits, C_dev.cpu().numpy().view(np.uint16))
+            if base is None:
+                base = allbits
+            assert np.array_equal(allbits, base)
+            assert st.copy_bytes == M * N * 2 and st.n_copies == G * c
+
+
+def test_resident_kernel_gives_up_when_flags_never_arrive(gpu):
+    # host-forced: the transfers are issued but the ready flags are withheld; the kernel's bounded
+    # wait must expire, every workgroup must drain, and the run must report a timeout
+    shards, W = fi.config_inputs("cfg1_tiny")
+    bits, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4,
+                         opts=[(ficco.FICCO_OPT_HOLD_FLAGS, 1), (ficco.FICCO_OPT_SPIN_LIMIT_US, 20000)],
+                         allow_timeout=True)
+    assert st.timed_out == 1
+    assert 15000 < st.wall_us < 2_000_000
+    # and the library is healthy afterwards
+    base, st2, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4)
+    assert st2.timed_out == 0
+    check(base, og.ag_gemm(shards, W))
+
+
+def test_run_rejects_bad_arguments(gpu):
+    dev = gpu["dev"]
+    t = torch.zeros((512, 1024), dtype=torch.int16, device=dev)
+    w = torch.zeros((1024, 1024), dtype=torch.int16, device=dev)
+    host_unpinned = torch.zeros((512, 1024), dtype=torch.int16)
+    plan = ficco.ficco_plan(512, 1024, 1024, 4, 1, ficco.FICCO_SHARD)
+    try:
+        for args in [(None, t, w, t, None), (host_unpinned, t, w, t, None), (t, None, w, t, None),
+                     (t, t, w, t, [t] * 4), (t, host_unpinned, w, t, None)]:
+            with pytest.raises(ficco.FiccoError) as e:
+                ficco.ficco_run(plan, *args, gpu["cs"], gpu["xs"])
+            assert e.value.status == ficco.FICCO_ERR_ARG
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_run(plan, t, t, w, t, None, gpu["cs"], gpu["cs"])       # same stream twice
+    finally:
+        ficco.ficco_destroy(plan)
+
+
+def test_cfg2_full_compare(gpu):
+    cfg = fi.CONFIGS["cfg2_qkv8b"]
+    shards, W = fi.config_inputs("cfg2_qkv8b")
+    ref = og.ag_gemm(shards, W)
+    base = None
+    ms = cfg["M"] // cfg["shards"]
+    cases = [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1)]
+    for rows in cfg["chunk_rows"]:
+        for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+            cases.append((sched, ms // rows))
+    for sched, c in cases:
+        bits, st, _ = run_ag(gpu, shards, W, sched, c)
+        if base is None:
+            check(bits, ref, "cfg2 serial")
+            base = bits
+        assert np.array_equal(bits, base), (sched, c)
+
+
+def test_cfg3_sampled_rows(gpu):
+    cfg = fi.CONFIGS["cfg3_ffn70b"]
+    shards, W = fi.config_inputs("cfg3_ffn70b")
+    M, G = cfg["M"], cfg["shards"]
+    rng = np.random.default_rng(3)
+    m = 512
+    rows = np.unique(np.concatenate([rng.integers(0, M, 32), np.arange(0, M, m), np.arange(m - 1, M, m)]))
+    ref = og.ag_gemm_rows(shards, W, rows)
+    base = None
+    for sched, c, src in [(ficco.FICCO_SERIAL, 1, "pinned"), (ficco.FICCO_SHARD, 1, "pinned"),
+                          (ficco.FICCO_FINE_FUSED, 4, "pinned"), (ficco.FICCO_FINE_UNFUSED, 2, "device"),
+                          (ficco.FICCO_FINE_PERSISTENT, 4, "pinned"), (ficco.FICCO_FINE_PERSISTENT, 2, "device")]:
+        bits, st, _ = run_ag(gpu, shards, W, sched, c, src=src)
+        if base is None:
+            check(bits[rows], ref, "cfg3 sampled rows")
+            base = bits
+        assert np.array_equal(bits, base), (sched, c, src)

@@ -1,0 +1,139 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host-side logic (plans, arrival lists, groups, static descriptors, ideal-overlap model, shape
+rules) agrees with the oracle's plain-Python rules. No kernel is launched."""
+import os
+import re
+
+import pytest
+
+import paper_2512_10236_amd as ficco
+from oracle import schedule as sch
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    text = open(os.path.join(repo_root, "include", "ficco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ficco_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    lib = ficco.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in ficco.h but not exported"
+    assert declared == set(ficco.EXPORTS)
+    assert "gfx950" in ficco.ficco_version()
+
+
+def test_enum_values_match_header(repo_root):
+    text = open(os.path.join(repo_root, "include", "ficco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    for name, val in re.findall(r"\b(FICCO_[A-Z0-9_x]+)\s*=\s*(-?\d+)", text):
+        assert getattr(ficco, name) == int(val), name
+
+
+SCHEDS = [(ficco.FICCO_SERIAL, sch.SERIAL), (ficco.FICCO_SHARD, sch.SHARD),
+          (ficco.FICCO_FINE_UNFUSED, sch.FINE_UNFUSED), (ficco.FICCO_FINE_FUSED, sch.FINE_FUSED),
+          (ficco.FICCO_FINE_PERSISTENT, sch.FINE_PERSISTENT)]
+
+
+@pytest.mark.parametrize("G,c", [(4, 1), (4, 4), (8, 2), (8, 32), (3, 5)])
+@pytest.mark.parametrize("lib_s,ora_s", SCHEDS)
+@pytest.mark.parametrize("order", [ficco.FICCO_ORDER_STEP_MAJOR, ficco.FICCO_ORDER_SHARD_MAJOR])
+def test_plan_lists_match_oracle(G, c, lib_s, ora_s, order):
+    if lib_s in (ficco.FICCO_SERIAL, ficco.FICCO_SHARD):
+        c = 1
+    M = G * c * 16
+    plan = ficco.ficco_plan(M, 64, 8, G, c, lib_s)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_ORDER, order)
+        arrival, group_ids = ficco.ficco_plan_arrival(plan)
+        info = ficco.ficco_plan_info(plan)
+    finally:
+        ficco.ficco_destroy(plan)
+    ref = sch.plan(M, G, c, ora_s, order)
+    assert arrival == ref["arrival"]
+    groups = [[] for _ in range(info.n_groups)]
+    for chunk, g in zip(arrival, group_ids):
+        groups[g].append(chunk)
+    assert groups == ref["groups"]
+    assert info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
+
+
+def test_custom_arrival_and_local_shard():
+    plan = ficco.ficco_plan(512, 64, 8, 4, 4, ficco.FICCO_FINE_FUSED)
+    try:
+        rev = list(range(15, -1, -1))
+        ficco.ficco_plan_set_arrival(plan, rev)
+        arrival, gids = ficco.ficco_plan_arrival(plan)
+        assert arrival == rev and gids == [q // 4 for q in range(16)]
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set_arrival(plan, [0] * 16)          # not a permutation
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set_arrival(plan, list(range(8)))    # wrong length
+    finally:
+        ficco.ficco_destroy(plan)
+    plan = ficco.ficco_plan(512, 64, 8, 4, 2, ficco.FICCO_FINE_UNFUSED)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_LOCAL_SHARD, 2)
+        arrival, _ = ficco.ficco_plan_arrival(plan)
+        # the local shard's pieces (ids 4, 5) move to the front, the rest keep step-major order
+        assert arrival == [4, 5, 0, 2, 6, 1, 3, 7]
+    finally:
+        ficco.ficco_destroy(plan)
+
+
+@pytest.mark.parametrize("args", [
+    (0, 64, 8, 4, 1, 0), (512, 0, 8, 4, 1, 0), (512, 64, 0, 4, 1, 0),     # empty dimensions
+    (512, 64, 8, 0, 1, 0), (512, 64, 8, 4, 0, 2),                          # no shards / no pieces
+    (500, 64, 8, 4, 2, 2),                                                  # M not divisible
+    (512, 96, 8, 4, 1, 0), (512, 64, 12, 4, 1, 0),                          # K % 64, N % 8
+    (512, 64, 8, 4, 2, 0), (512, 64, 8, 4, 2, 1),                           # pieces with serial / shard
+    (1 << 20, 64, 8, 8192, 1, 2),                                           # too many pieces
+])
+def test_shape_rules(args):
+    with pytest.raises(ficco.FiccoError) as e:
+        ficco.ficco_plan(*args)
+    assert e.value.status == ficco.FICCO_ERR_SHAPE
+
+
+def test_argument_errors():
+    with pytest.raises(ficco.FiccoError) as e:
+        ficco.ficco_plan(512, 64, 8, 4, 1, 7)
+    assert e.value.status == ficco.FICCO_ERR_ARG
+    plan = ficco.ficco_plan(512, 64, 8, 4, 1, ficco.FICCO_SHARD)
+    try:
+        for opt, val in [(ficco.FICCO_OPT_DIRECTION, 5), (ficco.FICCO_OPT_MODE, 9), (ficco.FICCO_OPT_TILE, 99),
+                         (ficco.FICCO_OPT_LOCAL_SHARD, 4), (99, 0), (ficco.FICCO_OPT_SPIN_LIMIT_US, 0)]:
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_plan_set(plan, opt, val)
+        with pytest.raises(ficco.FiccoError) as e:
+            ficco.ficco_query_stats(plan)
+        assert e.value.status == ficco.FICCO_ERR_STATE
+    finally:
+        ficco.ficco_destroy(plan)
+    assert ficco.ficco_strerror(ficco.FICCO_ERR_TIMEOUT).startswith("resident")
+    ficco.ficco_destroy(None)
+
+
+@pytest.mark.parametrize("m,N,K", [(1, 1, 1), (512, 1024, 1024), (64, 768, 4096), (2048, 3584, 8192)])
+def test_static_descriptors_match_oracle(m, N, K):
+    otb, mt = ficco.ficco_static_descriptors(m, N, K)
+    assert mt == sch.mt_bytes(m, N, K)
+    assert otb == pytest.approx(sch.otb(m, N, K), rel=1e-15)
+
+
+@pytest.mark.parametrize("tc,tg,n", [(3.0, 5.0, 1), (3.0, 5.0, 4), (5.0, 3.0, 8), (2.0, 2.0, 64), (1200.0, 30.0, 32)])
+def test_ideal_overlap_matches_oracle(tc, tg, n):
+    assert ficco.ficco_ideal_overlap_us(tc, tg, n) == pytest.approx(sch.ideal_overlap_time(tc, tg, n), rel=1e-14)
+
+
+def test_pick_schedule_returns_a_valid_plan():
+    for M in (4096, 16384, 65536):
+        for K in (4096, 8192):
+            for N in (512, 1024, 3584, 14336):
+                s, c = ficco.ficco_pick_schedule(M, K, N, 8)
+                assert s in (ficco.FICCO_SERIAL, ficco.FICCO_SHARD, ficco.FICCO_FINE_UNFUSED,
+                             ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT)
+                assert c >= 1 and (M // 8) % c == 0
+                plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO)
+                info = ficco.ficco_plan_info(plan)
+                ficco.ficco_destroy(plan)
+                assert (info.schedule, info.chunks) == (s, c)
