@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the all-gather -> GEMM pair on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input: plan (built once),
+the piece transfers, the ready flags / events, the piece GEMMs and the statistics query.
+Prints ONE JSON line (see the design doc for every field). Only one GPU is used; --gpus > 1 exits.
+
+Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192 K=4096 N=768):
+  pair      - K timed steps of the best finer-grain schedule, source shards resident in HBM
+              (device staging buffer); also serial and shard-level schedules for the speedup
+  pcie      - the same with the shards in pinned host memory (PCIe-inclusive; never `value`)
+  roofline  - the GEMM launches of the timed plan in isolation, per-launch HIP events on the
+              compute stream -> achieved TFLOP/s against the bf16 dense MFMA peak
+  losses    - decomposition / contention losses (DIL, CIL) through ficco_profile_losses
+  cpu       - the CPU oracle timed on the host cores (a baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_qkv8b")
+    ap.add_argument("--legs", default="pair,pcie,roofline,losses,cpu")
+    ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4 (default: a small sweep)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box here has one); "
+              "run with --gpus 1. How the path would shard is described in DESIGN.md.", file=sys.stderr)
+        return 2
+    legs = set(args.legs.split(","))
+
+    import numpy as np
+    import torch
+
+    import ficco_inputs as fi
+    import paper_2512_10236_amd as F
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    F.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = fi.CONFIGS[args.workload]
+    M, K, N, G = cfg["M"], cfg["K"], cfg["N"], cfg["shards"]
+    shards, W = fi.config_inputs(args.workload)
+    A_host = torch.from_numpy(np.concatenate(shards, 0).view(np.int16))
+    A_pinned = A_host.pin_memory()
+    A_stage = A_host.to(dev)                              # device staging buffer ("peers' memory")
+    W_dev = torch.from_numpy(W.view(np.int16)).to(dev)
+    A_dev = torch.zeros((M, K), dtype=torch.int16, device=dev)
+    C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+    cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+    flops = 2 * M * N * K
+    ms_shard = M // G
+
+    def timed_steps(plan, A_src, steps, warmup):
+        """ms per step over `steps` back-to-back steps, synchronize on both sides."""
+        for _ in range(warmup):
+            F.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, cs, xs)
+            F.ficco_query_stats(plan)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            F.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, cs, xs)
+            F.ficco_query_stats(plan)                     # the step's last stage; blocks until the step is done
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def make(sched, c, opts=()):
+        plan = F.ficco_plan(M, K, N, G, c, sched)
+        for o, v in opts:
+            F.ficco_plan_set(plan, o, v)
+        F.ficco_pack_weight(plan, W_dev, cs)
+        return plan
+
+    if args.candidates:
+        cands = [tuple(int(x) for x in t.split(":")) for t in args.candidates.split(",")]
+    else:
+        cands = []
+        for rows in cfg["chunk_rows"]:
+            c = ms_shard // rows
+            for s in (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED):
+                if (s, c) not in cands:
+                    cands.append((s, c))
+
+    out = {"metric": "AG+GEMM effective TFLOP/s (overlapped pair, best finer-grain schedule)",
+           "value": None, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "M": M, "K": K, "N": N, "shards": G,
+                      "source": "device staging buffer (HBM-resident)"}}
+
+    def leg_pair(A_src, tag):
+        res = {}
+        # short screening of the candidates, then the full timed run of the winner
+        screen = {}
+        for s, c in cands:
+            plan = make(s, c)
+            screen[(s, c)] = timed_steps(plan, A_src, max(5, args.steps // 5), 3)
+            F.ficco_destroy(plan)
+        best = min(screen, key=screen.get)
+        plan = make(*best)
+        ms = timed_steps(plan, A_src, args.steps, args.warmup)
+        info = F.ficco_plan_info(plan)
+        st = F.ficco_query_stats(plan)
+        F.ficco_destroy(plan)
+        p_ser = make(F.FICCO_SERIAL, 1)
+        ms_ser = timed_steps(p_ser, A_src, args.steps, args.warmup)
+        st_ser = F.ficco_query_stats(p_ser)
+        F.ficco_destroy(p_ser)
+        p_sh = make(F.FICCO_SHARD, 1)
+        ms_sh = timed_steps(p_sh, A_src, args.steps, args.warmup)
+        F.ficco_destroy(p_sh)
+        res.update(ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
+                   schedule=F.SCHEDULE_NAMES[best[0]], chunks_per_shard=best[1], chunk_rows=ms_shard // best[1],
+                   tile=f"{info.tile_m}x{info.tile_n}", ms_serial=ms_ser, ms_shard_level=ms_sh,
+                   speedup_vs_serial=ms_ser / ms, speedup_vs_shard_level=ms_sh / ms,
+                   copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
+                   screen={f"{F.SCHEDULE_NAMES[s]}:{c}": round(v, 4) for (s, c), v in screen.items()})
+        return res, best
+
+    best = None
+    if "pair" in legs:
+        res, best = leg_pair(A_stage, "hbm")
+        out["value"] = round(res["eff_tflops"], 3)
+        out["ms_per_step"] = round(res["ms_per_step"], 5)
+        out["pair"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
+        out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"])
+    if "pcie" in legs:
+        res, _ = leg_pair(A_pinned, "pcie")
+        out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
+
+    if "roofline" in legs:
+        s, c = best if best else (F.FICCO_SERIAL, 1)
+        plan = make(s, c, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
+        busy, launches = [], 0
+        for it in range(args.warmup + args.steps):
+            F.ficco_run(plan, None, A_stage, W_dev, C_dev, None, cs, xs)
+            st = F.ficco_query_stats(plan)
+            if it >= args.warmup:
+                busy.append(st.gemm_busy_us)
+                launches = st.n_launches
+        info = F.ficco_plan_info(plan)
+        F.ficco_destroy(plan)
+        us_step = float(np.mean(busy))
+        achieved = flops / us_step * 1e-6
+        # the monolithic GEMM of the same shape, for reference
+        plan = make(F.FICCO_SERIAL, 1, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
+        whole = []
+        for it in range(args.warmup + args.steps):
+            F.ficco_run(plan, None, A_stage, W_dev, C_dev, None, cs, xs)
+            st = F.ficco_query_stats(plan)
+            if it >= args.warmup:
+                whole.append(st.gemm_busy_us)
+        winfo = F.ficco_plan_info(plan)
+        F.ficco_destroy(plan)
+        out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                           "kernel": ("gemm_resident_kernel" if s == F.FICCO_FINE_PERSISTENT else "gemm_blocks_kernel")
+                                     + f"<{info.tile_m}x{info.tile_n}>",
+                           "launches_per_step": launches, "avg_launch_us": round(us_step / max(launches, 1), 3),
+                           "flops_per_launch": flops // max(launches, 1),
+                           "monolithic_us": round(float(np.mean(whole)), 3),
+                           "monolithic_tflops": round(flops / float(np.mean(whole)) * 1e-6, 2),
+                           "monolithic_tile": f"{winfo.tile_m}x{winfo.tile_n}"}
+
+    if "losses" in legs:
+        s, c = best if best else (F.FICCO_FINE_FUSED, 2)
+        losses = {}
+        for tag, src in (("hbm", A_stage), ("pcie", A_pinned)):
+            plan = make(s, c)
+            L = F.ficco_profile_losses(plan, src, A_dev, W_dev, C_dev, cs, xs, 10, 5)
+            F.ficco_destroy(plan)
+            losses[tag] = {k: round(v, 4) for k, v in L.as_dict().items()}
+            losses[tag]["gemm_dil_pct"] = round((L.gemm_dil - 1) * 100, 2)
+            losses[tag]["gemm_cil_pct"] = round((L.gemm_cil - 1) * 100, 2)
+            losses[tag]["comm_dil_pct"] = round((L.comm_dil - 1) * 100, 2)
+            losses[tag]["comm_cil_pct"] = round((L.comm_cil - 1) * 100, 2)
+        out["losses"] = losses
+
+    if "cpu" in legs:
+        from oracle import gemm as og
+        # bounded sample: enough rows of the same workload for roughly 10-30 s of CPU work
+        rows_n = min(M, max(64, int(20e9 * 0.5 / (2 * N * K))))          # ~0.5-1 GFLOP/s/thread guess
+        rng = np.random.default_rng(0)
+        rows = np.sort(rng.choice(M, size=rows_n, replace=False)).astype(np.int64)
+        t0 = time.perf_counter()
+        ref = og.ag_gemm_rows(shards, W, rows)
+        dt = time.perf_counter() - t0
+        got = C_dev.cpu().numpy().view(np.uint16)[rows]
+        err = og.rel_err(fi.bf16_bits_to_f32(got).astype(np.float64), ref) if "pair" in legs or "roofline" in legs else None
+        out["cpu_baseline"] = {"value": round(2 * rows_n * N * K / dt * 1e-12, 6), "unit": "TFLOP/s",
+                               "cores": og.num_threads(), "kind": "oracle",
+                               "sample": f"{rows_n} random rows of the {M}x{K}x{N} product, all {N} columns, {dt:.1f} s",
+                               "gpu_vs_oracle_rel_err": err}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -127,29 +127,31 @@ LaunchShape launch_shape(const ficco_plan_t *p, const Group &g)
     return {g.pos_end - g.pos_begin, p->m, false, 0};
 }
 
-// Tile choice: estimated time = rounds of the launch over the machine x work per tile / relative
-// tile efficiency; padded (masked) rows and columns are paid in full.
+// Tile choice: estimated time of a launch = rounds over the machine x k-steps x measured time of
+// one k-step of that tile (microseconds on MI355X, workgroups co-resident as `occ` says); padded
+// (masked) rows and columns are paid in full.
 int choose_tile(const ficco_plan_t *p, int cus)
 {
-    static const struct { int id; double eff; int occ; } cand[] = {
-        {TILE_256x256, 1.00, 1}, {TILE_256x128, 0.88, 1}, {TILE_128x256, 0.88, 1},
-        {TILE_128x128, 0.72, 2}, {TILE_64x256, 0.60, 2},  {TILE_32x256, 0.40, 2},
+    static const struct { int id; double step_us; int occ; } cand[] = {
+        {TILE_256x256, 1.80, 1}, {TILE_128x256, 1.25, 1}, {TILE_256x128, 1.33, 1},
+        {TILE_128x128, 1.20, 2}, {TILE_64x256, 1.45, 2},  {TILE_32x256, 1.20, 2},
     };
     double best = 1e300;
     int best_id = TILE_128x128;
+    auto cost = [&](int64_t tiles, double step_us, int occ) {
+        return std::ceil((double)tiles / ((double)cus * occ)) * step_us;
+    };
     for (auto &cd : cand) {
         TileShape ts = tile_shape(cd.id);
         double total = 0;
         if (p->schedule == FICCO_FINE_PERSISTENT) {
             int64_t tiles = (int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-            double rounds = std::ceil((double)tiles / (cus * cd.occ));
-            total = rounds * ts.bm * ts.bn / cd.eff / cd.occ;
+            total = cost(tiles, cd.step_us, cd.occ);
         } else {
             for (auto &g : p->groups) {
                 LaunchShape ls = launch_shape(p, g);
                 int64_t tiles = (int64_t)ls.n_blocks * ((ls.rows_per_block + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-                double rounds = std::ceil((double)tiles / (cus * cd.occ));
-                total += rounds * ts.bm * ts.bn / cd.eff / cd.occ;
+                total += cost(tiles, cd.step_us, cd.occ);
             }
         }
         if (total < best * 0.999) { best = total; best_id = cd.id; }

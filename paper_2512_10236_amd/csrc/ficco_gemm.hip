@@ -9,7 +9,7 @@
 //                            counter in arrival order and wait on the piece's ready flag.
 //
 // Data flow per workgroup tile (BM x BN, 256 threads = 4 wavefronts of 64):
-//   global --16 B loads--> registers --> LDS (two stages of BK = 64, XOR-swizzled 16 B slots)
+//   global --global_load_lds_dwordx4--> LDS (two stages of BK = 64, XOR-swizzled 16 B slots)
 //   LDS --ds_read_b128--> 8-element bf16 fragments --> v_mfma_f32_32x32x16_bf16 --> fp32 accumulators
 // The weight is read from a packed copy Wt[N, K] (k contiguous), so A and Wt fragments use the
 // same access pattern. Every output element is accumulated over k ascending by the same
@@ -35,6 +35,16 @@ static __device__ __forceinline__ uint32_t pack2_bf16_rne(float lo, float hi)
     return (ra & 0xFFFFu) | (rb << 16);
 }
 
+// 64 lanes x 16 B from per-lane global addresses straight into 1 KiB of LDS starting at the
+// wave-uniform byte address lds_base (lane l lands at lds_base + 16 l). Issued through inline
+// assembly so that the waits are placed by hand (s_waitcnt vmcnt) and not widened by the compiler.
+static __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+static __device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+static __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
 template <int BM_, int BN_, int WGM_, int WGN_>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
@@ -42,16 +52,24 @@ struct TileCfg {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
     static constexpr int FM = WTM / 32, FN = WTN / 32;         // 32x32 MFMA blocks per wavefront
     static constexpr int A_STAGE = BM * kBK * 2, B_STAGE = BN * kBK * 2;   // bytes
-    static constexpr int LDS_BYTES = 2 * (A_STAGE + B_STAGE);
-    static constexpr int AL = (BM * 8) / THREADS, BL = (BN * 8) / THREADS; // 16 B loads per thread per stage
-    static_assert(THREADS == 256, "loaders assume 256 threads");
+    static constexpr int STAGE = A_STAGE + B_STAGE;
+    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int AB = BM / 8 / 4, BB = BN / 8 / 4;     // 8-row (1 KiB) blocks loaded per wavefront per stage
+    static_assert(THREADS == 256, "loaders assume 4 wavefronts");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile is made of 32x32 blocks");
-    static_assert(AL >= 1 && BL >= 1, "tile too small for the loader");
+    static_assert(AB >= 1 && BB >= 1, "tile too small for the loader");
 };
 
 // Computes one BM x BN tile. a_tile: first row of the tile in A; rows_valid in [1, BM] rows of
 // it exist (the others are neither stored nor allowed to fault: their loads are clamped to the
 // last valid row). wt_tile: first row (= output column) of the tile in Wt; cols_valid likewise.
+//
+// LDS holds two stages; a stage is BM + BN rows of 128 B (64 k values), the 16-byte slot kc of
+// row r stored at slot kc ^ ((r >> 1) & 7) so that the 16 lanes of a ds_read_b128 phase hit 64
+// different banks. Loads go global -> LDS directly (no staging registers): a wavefront
+// instruction fills 8 rows, lane l fetching the slot that belongs at position l. One barrier per
+// k-step: after it, the loads of the next k-tile are issued into the other stage (spread over the
+// first half of the step so that they do not hold up MFMA issue) and have the whole step to land.
 template <class T>
 static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__ a_tile, int rows_valid,
                                                     const uint16_t *__restrict__ wt_tile, int cols_valid,
@@ -60,33 +78,43 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
-    // ---- global -> LDS loader: 16-byte slot q = tid + 256*i holds row q/8, k-slot q%8
-    const uint16_t *ga[T::AL];
-    const uint16_t *gb[T::BL];
-    int sa[T::AL], sb[T::BL];
+    const uint16_t *ga[T::AB];
+    const uint16_t *gb[T::BB];
 #pragma unroll
-    for (int i = 0; i < T::AL; ++i) {
-        int q = tid + 256 * i, r = q >> 3, kc = q & 7;
-        int rr = r < rows_valid ? r : rows_valid - 1;
+    for (int i = 0; i < T::AB; ++i) {
+        const int row = (wave * T::AB + i) * 8 + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row >> 1) & 7);
+        const int rr = row < rows_valid ? row : rows_valid - 1;
         ga[i] = a_tile + (int64_t)rr * lda + kc * 8;
-        sa[i] = r * 128 + ((kc ^ ((r >> 1) & 7)) << 4);
     }
 #pragma unroll
-    for (int i = 0; i < T::BL; ++i) {
-        int q = tid + 256 * i, r = q >> 3, kc = q & 7;
-        int rr = r < cols_valid ? r : cols_valid - 1;
+    for (int i = 0; i < T::BB; ++i) {
+        const int row = (wave * T::BB + i) * 8 + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row >> 1) & 7);
+        const int rr = row < cols_valid ? row : cols_valid - 1;
         gb[i] = wt_tile + (int64_t)rr * ldw + kc * 8;
-        sb[i] = r * 128 + ((kc ^ ((r >> 1) & 7)) << 4);
     }
+    // quarter q of the loads of k-tile kt into `stage`
+    auto issue_part = [&](int stage, int kt, int q) {
+        const uint32_t sa = lds0 + stage * T::STAGE + wave * T::AB * 1024;
+        const uint32_t sb = lds0 + stage * T::STAGE + T::A_STAGE + wave * T::BB * 1024;
+#pragma unroll
+        for (int i = 0; i < T::AB; ++i)
+            if ((i & 3) == q || (T::AB < 4 && q == 0)) load_to_lds_16(ga[i] + (int64_t)kt * kBK, sa + i * 1024);
+#pragma unroll
+        for (int i = 0; i < T::BB; ++i)
+            if ((i & 3) == q || (T::BB < 4 && q == 0)) load_to_lds_16(gb[i] + (int64_t)kt * kBK, sb + i * 1024);
+    };
 
-    // ---- LDS -> fragment addresses: lane reads row (lane%32) of a 32-row block, k-slot
-    //      2*kk + lane/32, un-swizzled by ((row>>1)&7) which only depends on the lane
+    // LDS -> fragment addresses: lane reads row (lane%32) of a 32-row block, k-slot 2*kk + lane/32,
+    // un-swizzled by ((row>>1)&7), which only depends on the lane
     const int frow = lane & 31, fh = lane >> 5, fs = (lane >> 1) & 7;
-    const int a_frag_base = (wm * T::WTM + frow) * 128;
-    const int b_frag_base = (wn * T::WTN + frow) * 128;
+    const int a_base = (wm * T::WTM + frow) * 128;
+    const int b_base = T::A_STAGE + (wn * T::WTN + frow) * 128;
 
     f32x16_t acc[T::FN][T::FM];
 #pragma unroll
@@ -96,60 +124,53 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
-    unsigned char *smA = smem;
-    unsigned char *smB = smem + 2 * T::A_STAGE;
-
-    u32x4_t ra[T::AL], rb[T::BL];
     const int KT = K / kBK;
-
 #pragma unroll
-    for (int i = 0; i < T::AL; ++i) ra[i] = *reinterpret_cast<const u32x4_t *>(ga[i]);
-#pragma unroll
-    for (int i = 0; i < T::BL; ++i) rb[i] = *reinterpret_cast<const u32x4_t *>(gb[i]);
-#pragma unroll
-    for (int i = 0; i < T::AL; ++i) *reinterpret_cast<u32x4_t *>(smA + sa[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < T::BL; ++i) *reinterpret_cast<u32x4_t *>(smB + sb[i]) = rb[i];
-    __syncthreads();
-
+    for (int q = 0; q < 4; ++q) issue_part(0, 0, q);
     for (int kt = 0; kt < KT; ++kt) {
-        const int st = kt & 1;
+        const int cur = kt & 1;
+        wait_all_vmem();                   // this wavefront's part of k-tile kt has landed ...
+        wg_barrier();                      // ... and so has everyone else's; stage cur^1 is free again
         const bool more = kt + 1 < KT;
-        if (more) {
+        const unsigned char *base = smem + cur * T::STAGE;
+        bf16x8_t fa[2][T::FM], fb[2][T::FN];
+        {
+            const int slot = ((0 + fh) ^ fs) << 4;
 #pragma unroll
-            for (int i = 0; i < T::AL; ++i) ra[i] = *reinterpret_cast<const u32x4_t *>(ga[i] + (kt + 1) * kBK);
+            for (int i = 0; i < T::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t *>(base + a_base + i * 4096 + slot);
 #pragma unroll
-            for (int i = 0; i < T::BL; ++i) rb[i] = *reinterpret_cast<const u32x4_t *>(gb[i] + (kt + 1) * kBK);
+            for (int j = 0; j < T::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t *>(base + b_base + j * 4096 + slot);
         }
-        const unsigned char *cA = smA + st * T::A_STAGE;
-        const unsigned char *cB = smB + st * T::B_STAGE;
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
-            const int slot = ((2 * kk + fh) ^ fs) << 4;
-            bf16x8_t fa[T::FM], fb[T::FN];
+            const int c = kk & 1, n = c ^ 1;
+            if (more && kk < 2) {
+                issue_part(cur ^ 1, kt + 1, 2 * kk);
+                issue_part(cur ^ 1, kt + 1, 2 * kk + 1);
+            }
+            if (kk < 3) {
+                const int slot = ((2 * (kk + 1) + fh) ^ fs) << 4;
 #pragma unroll
-            for (int i = 0; i < T::FM; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8_t *>(cA + a_frag_base + i * 32 * 128 + slot);
+                for (int i = 0; i < T::FM; ++i) fa[n][i] = *reinterpret_cast<const bf16x8_t *>(base + a_base + i * 4096 + slot);
 #pragma unroll
-            for (int j = 0; j < T::FN; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8_t *>(cB + b_frag_base + j * 32 * 128 + slot);
+                for (int j = 0; j < T::FN; ++j) fb[n][j] = *reinterpret_cast<const bf16x8_t *>(base + b_base + j * 4096 + slot);
+            }
             // operands swapped on purpose: D[n][m], so each lane ends up with 4 consecutive
             // columns of one C row (8-byte stores in the epilogue)
 #pragma unroll
             for (int j = 0; j < T::FN; ++j)
 #pragma unroll
                 for (int i = 0; i < T::FM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
-        }
-        if (more) {
-            unsigned char *nA = smA + (st ^ 1) * T::A_STAGE;
-            unsigned char *nB = smB + (st ^ 1) * T::B_STAGE;
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][j], fa[c][i], acc[j][i], 0, 0, 0);
+            if (kk < 3) {
+                // one LDS read, then a few MFMAs: the next fragments arrive under the current MFMAs
 #pragma unroll
-            for (int i = 0; i < T::AL; ++i) *reinterpret_cast<u32x4_t *>(nA + sa[i]) = ra[i];
-#pragma unroll
-            for (int i = 0; i < T::BL; ++i) *reinterpret_cast<u32x4_t *>(nB + sb[i]) = rb[i];
+                for (int q = 0; q < T::FM + T::FN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, (T::FM * T::FN) / (T::FM + T::FN) > 0 ? (T::FM * T::FN) / (T::FM + T::FN) : 1, 0);
+                }
+            }
         }
-        __syncthreads();
     }
 
     // ---- epilogue: acc[j][i][v] is C[m][n] with m = wm*WTM + 32 i + lane%32,
@@ -188,7 +209,7 @@ static __device__ __forceinline__ int xcd_contiguous_id(int pid, int total)
 template <class T>
 __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_block = (a.rows_per_block + T::BM - 1) / T::BM;
     const int tiles_m = a.n_blocks * rt_per_block;
@@ -215,7 +236,7 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
 template <class T>
 __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ int s_tile;
     __shared__ int s_ok;
     const GemmLaunch &a = r.g;
