@@ -98,9 +98,38 @@ typedef enum ficco_option {
     FICCO_OPT_LOCAL_SHARD = 7,   /* -1 (default): every shard arrives by transfer. j >= 0: shard j is
                                     already in A_dev and is multiplied first without waiting
                                     ("hetero" start, Sec. V-A); its transfers are skipped              */
-    FICCO_OPT_HOLD_FLAGS  = 8    /* test hook, resident kernel: 1 = issue the transfers but never write
-                                    the ready flags, so that the kernel's bounded wait expires         */
+    FICCO_OPT_HOLD_FLAGS  = 8,   /* test hook: 1 = issue the transfers but never write the ready flags,
+                                    so that the kernels' bounded wait expires                          */
+    FICCO_OPT_COPY_BACKEND = 9,  /* ficco_copy_backend; default AUTO                                    */
+    FICCO_OPT_LINKS       = 10   /* copy-engine backend: number of copy engines used side by side, one
+                                    per emulated link (shard j travels on engine j mod links);
+                                    0 (default) = min(shards, engines available)                        */
 } ficco_option;
+
+/*
+ * How transfers are issued.
+ *   STREAM  - hipMemcpyAsync on the caller's copy stream. From pinned host memory this is one
+ *             copy-engine queue over the host link. From device memory the HIP runtime would
+ *             use a copy *kernel*, so AUTO never picks STREAM for device sources or peers.
+ *   ENGINES - the ROCr copy-on-engine call (hsa_amd_memory_async_copy_on_engine) with the copy
+ *             forced onto SDMA engines, several side by side: transfers of different shards run
+ *             concurrently like the links of a fully connected node (Sec. III-B/C), and with
+ *             FICCO_SHARD or FICCO_ORDER_SHARD_MAJOR they are chained one after the other like
+ *             peer-to-peer exchange over one link at a time (Fig. 3(c)). Every transfer is
+ *             followed on its engine by a 4-byte copy that raises the piece's ready flag; GEMM
+ *             launches are enqueued first and wait on the flags of their pieces inside the
+ *             kernel. The copy stream argument is not used. ficco_run() first waits on the host
+ *             for the plan's previous run; in the GEMM->RS direction it also waits for each GEMM
+ *             launch before it submits that launch's transfers.
+ *   AUTO    - ENGINES if the source (or any peer buffer) is device memory or the schedule is
+ *             FICCO_FINE_PERSISTENT, else STREAM. (On STREAM the resident kernel leaves 8 CUs
+ *             free: the HIP runtime writes the 4-byte flags with a helper kernel.)
+ */
+typedef enum ficco_copy_backend {
+    FICCO_COPY_AUTO    = 0,
+    FICCO_COPY_STREAM  = 1,
+    FICCO_COPY_ENGINES = 2
+} ficco_copy_backend;
 
 typedef enum ficco_tile {        /* workgroup tile (rows x columns of C); the k order is the same in all */
     FICCO_TILE_AUTO    = 0,
@@ -121,6 +150,7 @@ typedef struct ficco_plan_info {
     int64_t chunk_rows;              /* M / n_chunks                                             */
     int32_t tile_m, tile_n, tile_k;  /* chosen workgroup tile                                    */
     int32_t resident_grid;           /* workgroups of the resident kernel (0 if not used)        */
+    int32_t copy_backend, links;     /* as resolved by the last run (0 before the first run)     */
     double  otb;                     /* static op-to-byte of one launch's GEMM (Sec. IV-B)       */
     double  mt_bytes;                /* static memory traffic MK+NK+MN of it, in bytes (Sec. IV-C) */
 } ficco_plan_info_t;

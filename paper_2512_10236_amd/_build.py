@@ -43,7 +43,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out)
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs + ["-lhsa-runtime64"]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed: " + r.stdout)

@@ -19,7 +19,9 @@ FICCO_DIR_AG_GEMM, FICCO_DIR_GEMM_RS = 0, 1
 FICCO_ORDER_STEP_MAJOR, FICCO_ORDER_SHARD_MAJOR, FICCO_ORDER_CUSTOM = 0, 1, 2
 FICCO_MODE_PAIR, FICCO_MODE_GEMM_ONLY, FICCO_MODE_COPY_ONLY, FICCO_MODE_INDEPENDENT = 0, 1, 2, 3
 (FICCO_OPT_DIRECTION, FICCO_OPT_ORDER, FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_TILE,
- FICCO_OPT_FLAG_WRITE, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_LOCAL_SHARD, FICCO_OPT_HOLD_FLAGS) = range(9)
+ FICCO_OPT_FLAG_WRITE, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_LOCAL_SHARD, FICCO_OPT_HOLD_FLAGS,
+ FICCO_OPT_COPY_BACKEND, FICCO_OPT_LINKS) = range(11)
+FICCO_COPY_AUTO, FICCO_COPY_STREAM, FICCO_COPY_ENGINES = 0, 1, 2
 (FICCO_TILE_AUTO, FICCO_TILE_256x256, FICCO_TILE_128x128, FICCO_TILE_256x128, FICCO_TILE_128x256,
  FICCO_TILE_64x256, FICCO_TILE_32x256) = range(7)
 
@@ -33,7 +35,8 @@ class ficco_plan_info_t(C.Structure):
                 ("schedule", C.c_int32), ("direction", C.c_int32), ("order", C.c_int32), ("mode", C.c_int32),
                 ("n_chunks", C.c_int32), ("n_groups", C.c_int32), ("chunk_rows", C.c_int64),
                 ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32),
-                ("resident_grid", C.c_int32), ("otb", C.c_double), ("mt_bytes", C.c_double)]
+                ("resident_grid", C.c_int32), ("copy_backend", C.c_int32), ("links", C.c_int32),
+                ("otb", C.c_double), ("mt_bytes", C.c_double)]
 
 
 class ficco_stats_t(C.Structure):

@@ -4,8 +4,14 @@
 #include "../../include/ficco.h"
 #include "ficco_internal.h"
 
+#include <hsa/hsa.h>
+#include <hsa/hsa_ext_amd.h>
+
 #include <algorithm>
 #include <cmath>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -31,6 +37,81 @@ struct Group {
 
 constexpr int kEpochSlots = 65536;   // pinned source words for flag writes; epoch e lives in slot e
 
+// ------------------------------------------------------------------ copy-engine (SDMA) context
+struct EngineCtx {
+    bool ready = false;
+    int status = FICCO_OK;
+    hsa_agent_t gpu{}, cpu{};
+    uint32_t mask_dd = 0, mask_hd = 0, mask_dh = 0;   // engine-status hints: device->device, host->device, device->host
+    uint32_t validated = 0, failed = 0;               // engines that passed / failed the one-time self test
+    double ticks_per_us = 100.0;
+};
+EngineCtx g_engines;
+
+struct AgentPick { int want_gpu_index; int seen_gpu; bool have_gpu, have_cpu; hsa_agent_t gpu, cpu; };
+
+hsa_status_t pick_agents(hsa_agent_t a, void *data)
+{
+    AgentPick *pk = (AgentPick *)data;
+    hsa_device_type_t t;
+    if (hsa_agent_get_info(a, HSA_AGENT_INFO_DEVICE, &t) != HSA_STATUS_SUCCESS) return HSA_STATUS_SUCCESS;
+    if (t == HSA_DEVICE_TYPE_GPU) {
+        if (pk->seen_gpu == pk->want_gpu_index && !pk->have_gpu) { pk->gpu = a; pk->have_gpu = true; }
+        pk->seen_gpu += 1;
+    } else if (t == HSA_DEVICE_TYPE_CPU && !pk->have_cpu) {
+        pk->cpu = a;
+        pk->have_cpu = true;
+    }
+    return HSA_STATUS_SUCCESS;
+}
+
+// One-time set-up: the HSA runtime is already up underneath HIP (hsa_init only adds a reference,
+// which is never dropped), agents are looked up, the usable engines are queried and copy
+// timestamps are switched on.
+int engines_init(int hip_device)
+{
+    EngineCtx &c = g_engines;
+    if (c.ready) return c.status;
+    c.ready = true;
+    c.status = FICCO_ERR_HIP;
+    const bool dbg = getenv("FICCO_DEBUG") != nullptr;
+    hsa_status_t hs = hsa_init();
+    if (hs != HSA_STATUS_SUCCESS) { if (dbg) fprintf(stderr, "ficco: hsa_init 0x%x\n", (int)hs); return c.status; }
+    AgentPick pk{hip_device, 0, false, false, {}, {}};
+    hs = hsa_iterate_agents(pick_agents, &pk);
+    if (hs != HSA_STATUS_SUCCESS || !pk.have_gpu || !pk.have_cpu) {
+        if (dbg) fprintf(stderr, "ficco: agents 0x%x gpu=%d cpu=%d want=%d seen=%d\n", (int)hs, pk.have_gpu, pk.have_cpu, hip_device, pk.seen_gpu);
+        return c.status;
+    }
+    c.gpu = pk.gpu;
+    c.cpu = pk.cpu;
+    if (hsa_amd_memory_copy_engine_status(c.gpu, c.gpu, &c.mask_dd) != HSA_STATUS_SUCCESS) c.mask_dd = 0;
+    if (hsa_amd_memory_copy_engine_status(c.gpu, c.cpu, &c.mask_hd) != HSA_STATUS_SUCCESS) c.mask_hd = 0;
+    if (hsa_amd_memory_copy_engine_status(c.cpu, c.gpu, &c.mask_dh) != HSA_STATUS_SUCCESS) c.mask_dh = 0;
+    uint64_t freq = 0;
+    if (hsa_system_get_info(HSA_SYSTEM_INFO_TIMESTAMP_FREQUENCY, &freq) == HSA_STATUS_SUCCESS && freq > 0)
+        c.ticks_per_us = (double)freq * 1e-6;
+    (void)hsa_amd_profiling_async_copy_enable(true);
+    if (c.mask_hd == 0) c.mask_hd = 0xFFFFu;          // hint missing: let the self test decide
+    c.status = FICCO_OK;
+    if (getenv("FICCO_DEBUG"))
+        fprintf(stderr, "ficco: copy engines d2d=0x%x h2d=0x%x d2h=0x%x ticks/us=%.1f status=%d\n", c.mask_dd, c.mask_hd,
+                c.mask_dh, c.ticks_per_us, c.status);
+    return c.status;
+}
+
+// Waits (bounded) until a signal has dropped below 1. Returns false on timeout or on an error value.
+bool wait_signal(hsa_signal_t sgn, double limit_s)
+{
+    const auto t0 = std::chrono::steady_clock::now();
+    for (;;) {
+        hsa_signal_value_t v = hsa_signal_wait_scacquire(sgn, HSA_SIGNAL_CONDITION_LT, 1, 2000000, HSA_WAIT_STATE_BLOCKED);
+        if (v < 0) return false;
+        if (v < 1) return true;
+        if (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > limit_s) return false;
+    }
+}
+
 }  // namespace
 
 struct ficco_plan_s {
@@ -39,6 +120,8 @@ struct ficco_plan_s {
     int schedule = 0, direction = FICCO_DIR_AG_GEMM, order = FICCO_ORDER_STEP_MAJOR, mode = FICCO_MODE_PAIR;
     int timing = 0, tile_opt = 0, flag_write = 0, local_shard = -1, hold_flags = 0;
     int64_t spin_limit_us = 2000000;
+    int backend_opt = FICCO_COPY_AUTO, links_opt = 0;
+    int backend = 0, links = 0;             // as resolved by the last run
     int device = 0;
     int n_chunks = 0;
     int64_t m = 0;                       // rows per chunk
@@ -50,7 +133,8 @@ struct ficco_plan_s {
     bool finalized = false;
     int tile = 0;
     int resident_grid = 0;
-    uint32_t *d_words = nullptr;         // flags | ticket | status
+    uint32_t *d_words = nullptr;         // flags | status | scratch: fine-grained device memory, polled while engines write it
+    uint32_t *d_ticket_mem = nullptr;    // ticket counter: ordinary device memory (device-scope atomics)
     uint32_t *d_flags = nullptr, *d_ticket = nullptr, *d_status = nullptr;
     int32_t *d_tables = nullptr;         // arrival | block_row0 (by arrival position)
     int32_t *d_arrival = nullptr, *d_block_row0 = nullptr;
@@ -62,6 +146,9 @@ struct ficco_plan_s {
     std::vector<hipEvent_t> ev_dep;          // per group: transfers of the group done / launch done
     std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
     int wall_clock_khz = 100000;
+    std::vector<hsa_signal_t> sig_data, sig_flag;   // copy-engine backend: per arrival position
+    bool last_engines = false;
+    double last_engine_copy_span_us = 0, last_engine_copy_busy_us = 0;
 
     // run state
     uint32_t run_index = 0;
@@ -168,7 +255,13 @@ void release(ficco_plan_t *p)
         for (auto &e : *v) ev(e);
         v->clear();
     }
+    for (auto *v : {&p->sig_data, &p->sig_flag}) {
+        for (auto &sg : *v) (void)hsa_signal_destroy(sg);
+        v->clear();
+    }
     if (p->d_words) (void)hipFree(p->d_words);
+    if (p->d_ticket_mem) (void)hipFree(p->d_ticket_mem);
+    p->d_ticket_mem = nullptr;
     if (p->d_tables) (void)hipFree(p->d_tables);
     if (p->d_wt) (void)hipFree(p->d_wt);
     if (p->h_epochs) (void)hipHostFree(p->h_epochs);
@@ -204,12 +297,18 @@ int finalize(ficco_plan_t *p)
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0) p->wall_clock_khz = khz;
 
     const int n = p->n_chunks;
-    const size_t words = (size_t)n * kFlagStrideWords + 2 * kFlagStrideWords;
-    if (hipMalloc((void **)&p->d_words, words * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    const size_t words = (size_t)n * kFlagStrideWords + 2 * kFlagStrideWords + 32;   // flags | ticket | status | 128 B scratch
+    // Flags and the status word are read by running kernels at system scope while a copy engine or
+    // another queue writes them: that is only coherent for fine-grained memory (ordinary device
+    // memory is coherent at kernel boundaries only).
+    if (hipExtMallocWithFlags((void **)&p->d_words, words * 4, hipDeviceMallocFinegrained) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     HIP_TRY(hipMemset(p->d_words, 0, words * 4));
+    if (hipMalloc((void **)&p->d_ticket_mem, 256) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    HIP_TRY(hipMemset(p->d_ticket_mem, 0, 256));
+    HIP_TRY(hipDeviceSynchronize());
     p->d_flags = p->d_words;
-    p->d_ticket = p->d_words + (size_t)n * kFlagStrideWords;
-    p->d_status = p->d_ticket + kFlagStrideWords;
+    p->d_ticket = p->d_ticket_mem;
+    p->d_status = p->d_words + (size_t)n * kFlagStrideWords + kFlagStrideWords;
     if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * 2 * (size_t)n) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     p->d_arrival = p->d_tables;
     p->d_block_row0 = p->d_tables + n;
@@ -289,6 +388,246 @@ GemmLaunch make_launch(const ficco_plan_t *p, const Group &g, const void *A_dev,
         a.row0 = 0;
     }
     return a;
+}
+
+// ------------------------------------------------------------------ copy-engine backend
+// Engines for a run, in order of preference. The runtime's engine-status query is only a hint
+// (older ROCr releases report no engine for copies inside one device although the forced-SDMA copy
+// works), so every engine is validated once per process by a 64-byte device-to-device copy inside
+// plan-owned scratch with a bounded wait; that first use also creates the engine's queue, which
+// takes milliseconds and must not fall into a timed run.
+std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
+{
+    EngineCtx &c = g_engines;
+    std::vector<int> order;
+    if (touches_host) {
+        for (int i = 0; i < 16; ++i) order.push_back(i);             // low ids sit closest to the host link
+    } else {
+        for (int i = 2; i < 16; ++i) order.push_back(i);             // leave 0/1 to the runtime's own host copies
+        order.push_back(0);
+        order.push_back(1);
+    }
+    std::vector<int> out;
+    for (int e : order) {
+        if ((int)out.size() >= want) break;
+        const uint32_t bit = 1u << e;
+        if (!(c.mask_hd & bit) || (c.failed & bit)) continue;         // the flag copy is host -> device
+        if (!(c.validated & bit)) {
+            hsa_signal_t sg;
+            if (hsa_signal_create(1, 0, nullptr, &sg) != HSA_STATUS_SUCCESS) { c.failed |= bit; continue; }
+            hsa_status_t st = hsa_amd_memory_async_copy_on_engine((char *)scratch64x2 + 64, c.gpu, scratch64x2, c.gpu, 64, 0, nullptr,
+                                                                  sg, (hsa_amd_sdma_engine_id_t)bit, true);
+            const bool ok = st == HSA_STATUS_SUCCESS && wait_signal(sg, 2.0);
+            if (st != HSA_STATUS_SUCCESS || ok) (void)hsa_signal_destroy(sg);   // a copy that never finished keeps its signal
+            if (!ok) { c.failed |= bit; continue; }
+            c.validated |= bit;
+        }
+        out.push_back(e);
+    }
+    return out;
+}
+
+int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, void *const *peer_out,
+                hipStream_t cs, bool src_dev, const std::vector<char> &peer_dev)
+{
+    const bool rs = p->direction == FICCO_DIR_GEMM_RS;
+    const int mode = p->mode;
+    const bool do_copy = mode != FICCO_MODE_GEMM_ONLY;
+    const bool do_gemm = mode != FICCO_MODE_COPY_ONLY;
+    const bool dependent = mode == FICCO_MODE_PAIR;
+    const bool timing = p->timing != 0;
+    const int n = p->n_chunks, c = p->c;
+    int rc = engines_init(p->device);
+    if (rc) return rc;
+    EngineCtx &ctx = g_engines;
+
+    // engines: one per emulated link
+    bool touches_host = !src_dev;
+    if (rs) {
+        touches_host = false;
+        for (int j = 0; j < p->G; ++j) touches_host |= !peer_dev[j];
+    }
+    int links = p->links_opt > 0 ? p->links_opt : p->G;
+    links = std::min(links, 16);
+    std::vector<int> eng = usable_engines(touches_host, links, p->d_status + kFlagStrideWords);
+    if (eng.empty()) { if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: no usable engine\n"); return FICCO_ERR_HIP; }
+    links = std::min(links, (int)eng.size());
+    p->links = links;
+
+    // signals, one pair per arrival position
+    while ((int)p->sig_data.size() < n) {
+        hsa_signal_t a, b;
+        if (hsa_signal_create(0, 0, nullptr, &a) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
+        p->sig_data.push_back(a);
+        if (hsa_signal_create(0, 0, nullptr, &b) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
+        p->sig_flag.push_back(b);
+    }
+    // the previous run must be over before its buffers, flags and signals are reused
+    if (p->run_index > 0) {
+        HIP_TRY(hipEventSynchronize(p->ev_end));
+        for (int q = 0; q < n; ++q)
+            if (!wait_signal(p->sig_data[q], 5.0) || !wait_signal(p->sig_flag[q], 5.0)) return FICCO_ERR_TIMEOUT;
+    }
+    if (timing) {
+        if ((rc = make_events(p->ev_gemm_b, p->groups.size()))) return rc;
+        if ((rc = make_events(p->ev_gemm_e, p->groups.size()))) return rc;
+    }
+    p->run_index += 1;
+    const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
+    const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
+    const size_t row_bytes_a = (size_t)p->K * 2, row_bytes_c = (size_t)p->N * 2;
+    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && chunk / c == p->local_shard; };
+    // transfers are chained one after the other (peer-to-peer pattern) or run side by side (all-to-all)
+    const bool chained = p->schedule == FICCO_SHARD ||
+                         (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
+
+    int n_copies = 0, n_launches = 0;
+    int64_t copy_bytes = 0;
+    int prev_pos = -1;
+    // one piece: data copy, then the 4-byte flag copy behind it on the same engine
+    auto submit = [&](int q) -> int {
+        const int chunk = p->arrival[q];
+        hsa_signal_store_relaxed(p->sig_data[q], 0);
+        hsa_signal_store_relaxed(p->sig_flag[q], 0);
+        if (is_local(chunk)) return FICCO_OK;
+        const int lane = (chunk / c) % links;
+        const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[lane]);
+        void *dst;
+        const void *src;
+        size_t bytes;
+        hsa_agent_t dst_agent = ctx.gpu, src_agent = ctx.gpu;
+        bool force = true;
+        if (!rs) {
+            const size_t off = (size_t)chunk * p->m * row_bytes_a;
+            bytes = (size_t)p->m * row_bytes_a;
+            dst = (char *)A_dev + off;
+            src = (const char *)A_src + off;
+            if (!src_dev) { src_agent = ctx.cpu; force = false; }
+        } else {
+            const int peer = chunk / c;
+            bytes = (size_t)p->m * row_bytes_c;
+            src = (const char *)C_dev + (size_t)chunk * p->m * row_bytes_c;
+            dst = (char *)peer_out[peer] + (size_t)(chunk % c) * p->m * row_bytes_c;
+            if (!peer_dev[peer]) { dst_agent = ctx.cpu; force = false; }
+        }
+        hsa_signal_store_relaxed(p->sig_data[q], 1);
+        hsa_signal_t dep{};
+        int ndep = 0;
+        if (chained && prev_pos >= 0) { dep = p->sig_data[prev_pos]; ndep = 1; }
+        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? &dep : nullptr,
+                                                              p->sig_data[q], engine, force);
+        if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_data[q], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        prev_pos = q;
+        ++n_copies;
+        copy_bytes += (int64_t)bytes;
+        if (!p->hold_flags) {
+            hsa_signal_store_relaxed(p->sig_flag[q], 1);
+            uint32_t *flag = p->d_flags + (size_t)chunk * kFlagStrideWords;
+            st = hsa_amd_memory_async_copy_on_engine(flag, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4, 1, &p->sig_data[q],
+                                                     p->sig_flag[q], engine, false);
+            if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[q], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        }
+        return FICCO_OK;
+    };
+    auto launch_group = [&](size_t g, bool gated) -> int {
+        GemmLaunch a = make_launch(p, p->groups[g], A_dev, C_dev);
+        if (gated) {
+            // wait list = the group's pieces that arrive by transfer (arrival table slice)
+            int first = p->groups[g].pos_begin, last = p->groups[g].pos_end;
+            while (first < last && is_local(p->arrival[first])) ++first;     // local pieces sit at the front
+            a.flags = p->d_flags;
+            a.wait_chunks = p->d_arrival + first;
+            a.n_wait = last - first;
+            for (int q = first; q < last; ++q)
+                if (is_local(p->arrival[q])) return FICCO_ERR_ARG;           // cannot happen: stable partition
+            a.epoch = epoch;
+            a.status = p->d_status;
+            a.spin_limit_ticks = spin_ticks;
+        }
+        if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[g], cs));
+        HIP_TRY(launch_gemm(p->tile, a, cs));
+        if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[g], cs));
+        ++n_launches;
+        return FICCO_OK;
+    };
+
+    HIP_TRY(hipEventRecord(p->ev_begin, cs));
+    HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+    if (!rs) {
+        // ---- GEMM side first: the kernels wait on flags, so they can be resident before data moves
+        if (do_gemm) {
+            if (p->schedule == FICCO_FINE_PERSISTENT) {
+                ResidentLaunch r{};
+                Group all{0, n};
+                r.g = make_launch(p, all, A_dev, C_dev);
+                r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
+                r.arrival = p->d_arrival;
+                r.n_chunks = n;
+                r.flags = p->d_flags;
+                r.epoch = epoch;
+                r.ticket = p->d_ticket;
+                r.ticket_base = p->ticket_total;
+                r.status = p->d_status;
+                r.spin_limit_ticks = spin_ticks;
+                r.grid = p->resident_grid;
+                if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
+                else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
+                TileShape ts = tile_shape(p->tile);
+                const int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+                p->ticket_total += (uint32_t)tiles + (uint32_t)r.grid;
+                if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
+                HIP_TRY(launch_resident(p->tile, r, cs));
+                if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
+                ++n_launches;
+            } else {
+                for (size_t g = 0; g < p->groups.size(); ++g)
+                    if ((rc = launch_group(g, dependent))) return rc;
+            }
+            HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+        }
+        if (do_copy) {
+            for (int q = 0; q < n; ++q)
+                if ((rc = submit(q))) return rc;
+            if ((!dependent || !do_gemm) && !p->hold_flags) {
+                // nothing on the compute stream consumes the flags: join through a small waiting kernel
+                int first = 0;
+                while (first < n && is_local(p->arrival[first])) ++first;
+                if (first < n)
+                    HIP_TRY(launch_wait_flags(p->d_flags, p->d_arrival + first, n - first, epoch, p->d_status, spin_ticks, cs));
+            }
+        } else {
+            for (int q = 0; q < n; ++q) { hsa_signal_store_relaxed(p->sig_data[q], 0); hsa_signal_store_relaxed(p->sig_flag[q], 0); }
+        }
+    } else {
+        // ---- GEMM -> RS: a group's rows leave when its launch is done (the host relays the event)
+        if (do_gemm) {
+            for (size_t g = 0; g < p->groups.size(); ++g) {
+                if ((rc = launch_group(g, false))) return rc;
+                HIP_TRY(hipEventRecord(p->ev_dep[g], cs));
+            }
+            HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+        }
+        if (do_copy) {
+            for (size_t g = 0; g < p->groups.size(); ++g) {
+                if (do_gemm && dependent) HIP_TRY(hipEventSynchronize(p->ev_dep[g]));
+                for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q)
+                    if ((rc = submit(q))) return rc;
+            }
+            if (!p->hold_flags) HIP_TRY(launch_wait_flags(p->d_flags, p->d_arrival, n, epoch, p->d_status, spin_ticks, cs));
+        } else {
+            for (int q = 0; q < n; ++q) { hsa_signal_store_relaxed(p->sig_data[q], 0); hsa_signal_store_relaxed(p->sig_flag[q], 0); }
+        }
+    }
+    HIP_TRY(hipEventRecord(p->ev_end, cs));
+
+    p->last_had_copies = n_copies > 0;
+    p->last_had_gemm = n_launches > 0;
+    p->last_timing = timing;
+    p->last_copy_bytes = copy_bytes;
+    p->last_n_copies = n_copies;
+    p->last_n_launches = n_launches;
+    p->last_engines = true;
+    return FICCO_OK;
 }
 
 }  // namespace
@@ -407,6 +746,14 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
         if (value != 0 && value != 1) return FICCO_ERR_ARG;
         p->hold_flags = (int)value;
         break;
+    case FICCO_OPT_COPY_BACKEND:
+        if (value < FICCO_COPY_AUTO || value > FICCO_COPY_ENGINES) return FICCO_ERR_ARG;
+        p->backend_opt = (int)value;
+        break;
+    case FICCO_OPT_LINKS:
+        if (value < 0 || value > 16) return FICCO_ERR_ARG;
+        p->links_opt = (int)value;
+        break;
     default:
         return FICCO_ERR_ARG;
     }
@@ -442,6 +789,8 @@ int ficco_plan_info(const ficco_plan_t *p, ficco_plan_info_t *out)
     TileShape ts = tile_shape(p->tile);
     o.tile_m = ts.bm; o.tile_n = ts.bn; o.tile_k = p->tile ? kBK : 0;
     o.resident_grid = p->resident_grid;
+    o.copy_backend = p->backend;
+    o.links = p->links;
     // descriptors of one launch: the resident kernel's unit of work is one piece
     int64_t rows = p->schedule == FICCO_FINE_PERSISTENT
                        ? p->m
@@ -520,6 +869,23 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         rc = pack_weight(p, W_dev, cs);
         if (rc) return rc;
     }
+    // resolve the transfer backend
+    bool any_peer_dev = false;
+    for (char d : peer_dev) any_peer_dev |= (bool)d;
+    int backend = p->backend_opt;
+    // AUTO: engines whenever a kernel would otherwise have to be fed by copy kernels (device sources
+    // and peers) or by helper kernels that need a free CU while it spins (the resident schedule)
+    if (backend == FICCO_COPY_AUTO)
+        backend = (do_copy && (src_dev || any_peer_dev || (p->schedule == FICCO_FINE_PERSISTENT && dependent))) ? FICCO_COPY_ENGINES
+                                                                                                           : FICCO_COPY_STREAM;
+    p->backend = backend;
+    if (backend == FICCO_COPY_ENGINES) {
+        if (p->flag_write != 0) return FICCO_ERR_ARG;
+        return run_engines(p, A_src, A_dev, C_dev, peer_out, cs, src_dev, peer_dev);
+    }
+    p->last_engines = false;
+    p->links = 1;
+
     const bool timing = p->timing != 0;
     const int n = p->n_chunks;
     if (timing) {
@@ -615,6 +981,15 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
             r.status = p->d_status;
             r.spin_limit_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
             r.grid = p->resident_grid;
+            if (dependent && do_copy) {
+                // On this backend the 4-byte flag writes are done by a helper kernel of the HIP runtime,
+                // which needs a CU with free registers while the resident workgroups spin: leave 8 CUs'
+                // worth of slots unoccupied.
+                int cus = 0;
+                HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device));
+                const int per_cu = std::max(1, resident_grid_size(p->tile, p->device) / std::max(cus, 1));
+                r.grid = std::max(1, std::min(r.grid, per_cu * (cus - 8)));
+            }
             if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
             else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
             else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
@@ -708,7 +1083,29 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
     float ms = 0;
     HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_end));
     s.wall_us = ms * 1e3;
-    if (p->last_had_copies) {
+    if (p->last_had_copies && p->last_engines) {
+        // copy-engine timestamps (system clock ticks) of every transfer of the run
+        uint64_t t_min = ~0ull, t_max = 0;
+        double busy = 0;
+        for (int q = 0; q < p->n_chunks; ++q) {
+            const int chunk = p->arrival[q];
+            if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
+            if (!wait_signal(p->sig_data[q], 5.0) || !wait_signal(p->sig_flag[q], 5.0)) {
+                if (getenv("FICCO_DEBUG"))
+                    fprintf(stderr, "ficco: transfer %d (chunk %d) did not complete: data signal %lld flag signal %lld\n", q, chunk,
+                            (long long)hsa_signal_load_relaxed(p->sig_data[q]), (long long)hsa_signal_load_relaxed(p->sig_flag[q]));
+                return FICCO_ERR_TIMEOUT;
+            }
+            hsa_amd_profiling_async_copy_time_t t{};
+            if (hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &t) != HSA_STATUS_SUCCESS) continue;
+            t_min = std::min(t_min, (uint64_t)t.start);
+            t_max = std::max(t_max, (uint64_t)t.end);
+            busy += (double)(t.end - t.start) / g_engines.ticks_per_us;
+        }
+        if (t_max > t_min) s.copy_span_us = (double)(t_max - t_min) / g_engines.ticks_per_us;
+        p->last_engine_copy_span_us = s.copy_span_us;
+        p->last_engine_copy_busy_us = busy;
+    } else if (p->last_had_copies) {
         HIP_TRY(hipEventElapsedTime(&ms, p->ev_copy_first, p->ev_copy_last));
         s.copy_span_us = ms * 1e3;
     }
@@ -728,7 +1125,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
             }
             s.gemm_busy_us = gb;
         }
-        if (p->last_had_copies) {
+        if (p->last_had_copies && !p->last_engines) {
             for (int q = 0; q < p->n_chunks; ++q) {
                 const int chunk = p->arrival[q];
                 if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
@@ -738,6 +1135,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
             s.copy_busy_us = cb;
         }
     }
+    if (p->last_had_copies && p->last_engines) s.copy_busy_us = p->last_engine_copy_busy_us;
     s.exposed_comm_us = s.wall_us - s.gemm_busy_us;
     s.flops = 2 * p->M * p->N * p->K;
     s.eff_tflops = s.wall_us > 0 ? (double)s.flops / s.wall_us * 1e-6 : 0.0;
@@ -746,10 +1144,32 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
     s.n_copies = p->last_n_copies;
     s.n_launches = p->last_n_launches;
     s.run_index = (int32_t)p->run_index;
-    if (p->schedule == FICCO_FINE_PERSISTENT && p->last_had_gemm) {
+    if ((p->schedule == FICCO_FINE_PERSISTENT && p->last_had_gemm) || p->last_engines) {
         uint32_t st = 0;
         HIP_TRY(hipMemcpy(&st, p->d_status, 4, hipMemcpyDeviceToHost));
         if (st) {
+            if (getenv("FICCO_DEBUG")) {
+                fprintf(stderr, "ficco: a kernel's bounded wait expired (run %u)\n", p->run_index);
+                std::vector<uint32_t> fl((size_t)p->n_chunks * kFlagStrideWords);
+                if (hipMemcpy(fl.data(), p->d_flags, fl.size() * 4, hipMemcpyDeviceToHost) == hipSuccess) {
+                    fprintf(stderr, "ficco: flags now:");
+                    for (int i = 0; i < p->n_chunks; ++i) fprintf(stderr, " %u", fl[(size_t)i * kFlagStrideWords]);
+                    fprintf(stderr, "\n");
+                }
+                if (p->last_engines) {
+                    uint64_t t0 = ~0ull;
+                    std::vector<hsa_amd_profiling_async_copy_time_t> tt(p->n_chunks), tf(p->n_chunks);
+                    for (int q = 0; q < p->n_chunks; ++q) {
+                        hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &tt[q]);
+                        hsa_amd_profiling_get_async_copy_time(p->sig_flag[q], &tf[q]);
+                        if (tt[q].start && tt[q].start < t0) t0 = tt[q].start;
+                    }
+                    for (int q = 0; q < p->n_chunks; ++q)
+                        fprintf(stderr, "ficco: pos %d chunk %d data [%.1f, %.1f] us flag [%.1f, %.1f] us\n", q, p->arrival[q],
+                                (tt[q].start - t0) / g_engines.ticks_per_us, (tt[q].end - t0) / g_engines.ticks_per_us,
+                                (tf[q].start - t0) / g_engines.ticks_per_us, (tf[q].end - t0) / g_engines.ticks_per_us);
+                }
+            }
             s.timed_out = 1;
             HIP_TRY(hipMemset(p->d_status, 0, 4));
         }
@@ -771,7 +1191,24 @@ int ficco_query_spans(ficco_plan_t *p, double *copy_begin_us, double *copy_end_u
             const int chunk = p->arrival[q];
             const bool local = p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard;
             double b = 0, e = 0;
-            if (p->last_had_copies && !local) {
+            if (p->last_had_copies && !local && p->last_engines) {
+                // engine timestamps live on another clock: reported relative to the run's first transfer
+                static thread_local uint64_t t_first;
+                hsa_amd_profiling_async_copy_time_t t{};
+                if (q == 0 || t_first == 0) {
+                    t_first = ~0ull;
+                    for (int r = 0; r < p->n_chunks; ++r) {
+                        hsa_amd_profiling_async_copy_time_t u{};
+                        if (hsa_signal_load_relaxed(p->sig_data[r]) == 0 &&
+                            hsa_amd_profiling_get_async_copy_time(p->sig_data[r], &u) == HSA_STATUS_SUCCESS && u.end > u.start)
+                            t_first = std::min(t_first, (uint64_t)u.start);
+                    }
+                }
+                if (hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &t) == HSA_STATUS_SUCCESS && t.end > t.start) {
+                    b = (double)(t.start - t_first) / g_engines.ticks_per_us;
+                    e = (double)(t.end - t_first) / g_engines.ticks_per_us;
+                }
+            } else if (p->last_had_copies && !local) {
                 HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_copy_b[q])); b = ms * 1e3;
                 HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_copy_e[q])); e = ms * 1e3;
             }
@@ -803,6 +1240,9 @@ int ficco_profile_losses(ficco_plan_t *p, const void *A_src, void *A_dev, const 
     ficco_plan_t *whole = nullptr;
     int rc = ficco_plan(p->M, p->K, p->N, p->G, 1, FICCO_SERIAL, &whole);
     if (rc) return rc;
+    whole->backend_opt = p->backend_opt;
+    whole->links_opt = p->links_opt;
+    whole->spin_limit_us = p->spin_limit_us;
     const int saved_mode = p->mode, saved_timing = p->timing;
 
     // mean span of one mode over `iters` runs after `warmup`
@@ -847,6 +1287,8 @@ void ficco_destroy(ficco_plan_t *p)
 {
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
+    for (auto *v : {&p->sig_data, &p->sig_flag})
+        for (auto &sg : *v) (void)wait_signal(sg, 5.0);
     release(p);
     delete p;
 }

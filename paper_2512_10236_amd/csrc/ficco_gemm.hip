@@ -196,6 +196,23 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
     }
 }
 
+// Bounded wait of one thread for a ready flag written by a copy engine (or by a stream write).
+// Reads at system scope (past the caches). Returns 0 when the limit expires or another workgroup
+// has already given up; the caller then skips its work, so every wave still reaches its exit.
+static __device__ __forceinline__ int wait_flag(const uint32_t *f, uint32_t epoch, uint32_t *status, uint64_t limit)
+{
+    const uint64_t t0 = wall_clock64();
+    for (;;) {
+        if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == epoch) return 1;
+        if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) return 0;
+        if (wall_clock64() - t0 > limit) {
+            __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            return 0;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
 // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2). Renumber them so
 // that consecutive logical ids run on the same XCD, then walk the tile grid in groups of GROUP_M
 // row tiles so that one XCD works on few A row tiles and W column tiles at a time.
@@ -210,6 +227,17 @@ template <class T>
 __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    if (a.n_wait > 0) {
+        __shared__ int s_go;
+        if (threadIdx.x == 0) {
+            int ok = 1;
+            for (int i = 0; i < a.n_wait && ok; ++i)
+                ok = wait_flag(a.flags + (size_t)a.wait_chunks[i] * kFlagStrideWords, a.epoch, a.status, a.spin_limit_ticks);
+            s_go = ok;
+        }
+        __syncthreads();                   // also orders the tile's loads after the flag reads
+        if (!s_go) return;
+    }
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_block = (a.rows_per_block + T::BM - 1) / T::BM;
     const int tiles_m = a.n_blocks * rt_per_block;
@@ -255,20 +283,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         if (threadIdx.x == 0) {
             int ok = 1;
             if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) {
-                const uint32_t *f = r.flags + (size_t)chunk * kFlagStrideWords;
-                const uint64_t t0 = wall_clock64();
-                for (;;) {
-                    // system scope: read past the caches, the writer is a copy engine
-                    uint32_t v = __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                    if (v == r.epoch) break;
-                    if (__hip_atomic_load(r.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) { ok = 0; break; }
-                    if (wall_clock64() - t0 > r.spin_limit_ticks) {
-                        __hip_atomic_store(r.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                        ok = 0;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(8);
-                }
+                ok = wait_flag(r.flags + (size_t)chunk * kFlagStrideWords, r.epoch, r.status, r.spin_limit_ticks);
             }
             s_ok = ok;
         }
@@ -284,6 +299,14 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         }
         __syncthreads();                   // s_tile / s_ok / LDS stages are reused
     }
+}
+
+__global__ __launch_bounds__(64) void wait_flags_kernel(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch,
+                                                        uint32_t *status, uint64_t limit)
+{
+    if (threadIdx.x == 0)
+        for (int i = 0; i < n; ++i)
+            if (!wait_flag(flags + (size_t)chunks[i] * kFlagStrideWords, epoch, status, limit)) break;
 }
 
 // W[K,N] -> Wt[N,K] through a 64x64 LDS tile (padded), 256 threads.
@@ -401,6 +424,13 @@ int resident_grid_size(int tile, int device)
     case TILE_32x256:  return resident_grid_t<T32x256>(device);
     default: return 0;
     }
+}
+
+hipError_t launch_wait_flags(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch, uint32_t *status,
+                             uint64_t spin_limit_ticks, hipStream_t s)
+{
+    hipLaunchKernelGGL(wait_flags_kernel, dim3(1), dim3(64), 0, s, flags, chunks, n, epoch, status, spin_limit_ticks);
+    return hipGetLastError();
 }
 
 hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_t N, hipStream_t s)

@@ -28,6 +28,14 @@ struct GemmLaunch {
     int32_t row0;                // first row when block_row0 == nullptr (n_blocks == 1)
     int32_t n_blocks;
     int32_t rows_per_block;
+    // Optional gate (copy-engine transfers raise flags instead of HIP events): every workgroup
+    // waits until flags[wait_chunks[i]*kFlagStrideWords] == epoch for all i < n_wait.
+    const uint32_t *flags;
+    const int32_t *wait_chunks;
+    int32_t n_wait;
+    uint32_t epoch;
+    uint32_t *status;             // [0] set to 1 when a bounded wait expires
+    uint64_t spin_limit_ticks;    // in wall_clock64() ticks
 };
 
 // The resident kernel: tiles are taken from a ticket counter in arrival order; the tiles of the
@@ -48,6 +56,10 @@ struct ResidentLaunch {
 
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s);
 hipError_t launch_resident(int tile, const ResidentLaunch &a, hipStream_t s);
+// One wavefront that waits (bounded) for the flags of chunks[0..n) to reach epoch; used to join the
+// compute stream with copy-engine transfers when no GEMM consumes them.
+hipError_t launch_wait_flags(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch, uint32_t *status,
+                             uint64_t spin_limit_ticks, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_t N, hipStream_t s);
 int resident_grid_size(int tile, int device);
 

@@ -175,8 +175,10 @@ def test_repeated_runs_and_timing_spans(gpu):
 def test_flag_written_by_stream_write_value(gpu):
     shards, W = fi.config_inputs("cfg1_tiny")
     base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
-    bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4, opts=[(ficco.FICCO_OPT_FLAG_WRITE, 1)], runs=2)
-    assert np.array_equal(bits, base)
+    stream = (ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_STREAM)
+    for fw in (0, 1):
+        bits, _, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4, opts=[stream, (ficco.FICCO_OPT_FLAG_WRITE, fw)], runs=2)
+        assert np.array_equal(bits, base) and info.copy_backend == ficco.FICCO_COPY_STREAM
 
 
 def test_device_staging_source(gpu):
@@ -306,11 +308,66 @@ def test_cfg3_sampled_rows(gpu):
     rows = np.unique(np.concatenate([rng.integers(0, M, 32), np.arange(0, M, m), np.arange(m - 1, M, m)]))
     ref = og.ag_gemm_rows(shards, W, rows)
     base = None
-    for sched, c, src in [(ficco.FICCO_SERIAL, 1, "pinned"), (ficco.FICCO_SHARD, 1, "pinned"),
-                          (ficco.FICCO_FINE_FUSED, 4, "pinned"), (ficco.FICCO_FINE_UNFUSED, 2, "device"),
-                          (ficco.FICCO_FINE_PERSISTENT, 4, "pinned"), (ficco.FICCO_FINE_PERSISTENT, 2, "device")]:
-        bits, st, _ = run_ag(gpu, shards, W, sched, c, src=src)
+    S, E = ficco.FICCO_COPY_STREAM, ficco.FICCO_COPY_ENGINES
+    for sched, c, src, backend in [(ficco.FICCO_SERIAL, 1, "pinned", S), (ficco.FICCO_SHARD, 1, "pinned", S),
+                                   (ficco.FICCO_FINE_FUSED, 4, "pinned", S), (ficco.FICCO_FINE_UNFUSED, 2, "device", E),
+                                   (ficco.FICCO_FINE_PERSISTENT, 4, "pinned", S),      # full grid minus the helper-kernel headroom
+                                   (ficco.FICCO_FINE_PERSISTENT, 4, "pinned", E), (ficco.FICCO_FINE_PERSISTENT, 2, "device", E),
+                                   (ficco.FICCO_SERIAL, 1, "device", E)]:
+        bits, st, info = run_ag(gpu, shards, W, sched, c, src=src, opts=[(ficco.FICCO_OPT_COPY_BACKEND, backend)])
+        assert info.copy_backend == backend
         if base is None:
             check(bits[rows], ref, "cfg3 sampled rows")
             base = bits
         assert np.array_equal(bits, base), (sched, c, src)
+
+
+# ------------------------------------------------------------------ copy-engine (SDMA) backend
+def test_engines_backend_pinned_and_device_sources(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    for src in ("pinned", "device"):
+        for sched, c in ALL_SCHEDULES:
+            for links in (0, 1, 3):
+                bits, st, info = run_ag(gpu, shards, W, sched, c, src=src, runs=2,
+                                        opts=[(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_ENGINES),
+                                              (ficco.FICCO_OPT_LINKS, links)])
+                assert np.array_equal(bits, base), (src, sched, c, links)
+                assert info.copy_backend == ficco.FICCO_COPY_ENGINES
+                assert info.links == (4 if links == 0 else links)
+                assert st.n_copies == info.n_chunks and st.copy_span_us > 0
+
+
+def test_engines_backend_orders_and_local_shard(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    eng = [(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_ENGINES)]
+    rng = np.random.default_rng(1)
+    for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+        bits, _, _ = run_ag(gpu, shards, W, sched, 4, src="device", arrival=list(rng.permutation(16)), opts=eng)
+        assert np.array_equal(bits, base)
+        bits, _, _ = run_ag(gpu, shards, W, sched, 4, src="device",
+                            opts=eng + [(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)])
+        assert np.array_equal(bits, base)
+
+
+def test_engines_links_run_side_by_side(gpu):
+    # 8 shards of 8 MiB from a device staging buffer: all links at once must be several times
+    # faster than one transfer at a time (the peer-to-peer pattern of shard-level overlap)
+    M, K, N, G = 8192, 4096, 256, 8
+    shards = fi.make_shards(7, M, K, G)
+    W = fi.make_weight(7, K, N)
+    _, st_all, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device", runs=3)
+    _, st_one, _ = run_ag(gpu, shards, W, ficco.FICCO_SHARD, 1, src="device", runs=3)
+    assert st_all.copy_bytes == st_one.copy_bytes == M * K * 2
+    assert st_one.copy_span_us > 3.0 * st_all.copy_span_us, (st_one.copy_span_us, st_all.copy_span_us)
+
+
+def test_engines_bounded_wait_in_per_launch_kernels(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    _, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_FUSED, 4, src="device", allow_timeout=True,
+                      opts=[(ficco.FICCO_OPT_HOLD_FLAGS, 1), (ficco.FICCO_OPT_SPIN_LIMIT_US, 20000)])
+    assert st.timed_out == 1
+    bits, st2, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_FUSED, 4, src="device")
+    assert st2.timed_out == 0
+    check(bits, og.ag_gemm(shards, W))
