@@ -6,6 +6,7 @@
 
 #include <hsa/hsa.h>
 #include <hsa/hsa_ext_amd.h>
+#include <hsa/amd_hsa_signal.h>
 
 #include <algorithm>
 #include <cmath>
@@ -146,7 +147,9 @@ struct ficco_plan_s {
     std::vector<hipEvent_t> ev_dep;          // per group: transfers of the group done / launch done
     std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
     int wall_clock_khz = 100000;
-    std::vector<hsa_signal_t> sig_data, sig_flag;   // copy-engine backend: per arrival position
+    std::vector<hsa_signal_t> sig_data, sig_flag;   // copy-engine backend: per chunk id
+    uint64_t *d_sig_value = nullptr;                 // device table: address of each data signal's value word
+    int sig_poll = -1;                               // -1 unknown, 0 flags by 4-byte copies, 1 kernels poll the signals
     bool last_engines = false;
     double last_engine_copy_span_us = 0, last_engine_copy_busy_us = 0;
 
@@ -214,31 +217,32 @@ LaunchShape launch_shape(const ficco_plan_t *p, const Group &g)
     return {g.pos_end - g.pos_begin, p->m, false, 0};
 }
 
-// Tile choice: estimated time of a launch = rounds over the machine x k-steps x measured time of
-// one k-step of that tile (microseconds on MI355X, workgroups co-resident as `occ` says); padded
-// (masked) rows and columns are paid in full.
+// Tile choice. Estimated time of a launch = k-steps x [full rounds over the machine x step(1) +
+// step(fill of the last, partial round)], where step(f) = base + slope * f is the time of one k-step
+// of that tile shape when a fraction f of the machine's workgroup slots is occupied (microseconds,
+// fitted to a sweep of launch sizes on MI355X); padded (masked) rows and columns are paid in full.
 int choose_tile(const ficco_plan_t *p, int cus)
 {
-    static const struct { int id; double step_us; int occ; } cand[] = {
-        {TILE_256x256, 1.80, 1}, {TILE_128x256, 1.25, 1}, {TILE_256x128, 1.33, 1},
-        {TILE_128x128, 1.20, 2}, {TILE_64x256, 1.45, 2},  {TILE_32x256, 1.20, 2},
+    static const struct { int id; double base, slope; int occ; } cand[] = {
+        {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.85, 0.25, 1}, {TILE_256x128, 0.87, 0.30, 1},
+        {TILE_128x128, 0.60, 0.50, 2}, {TILE_64x256, 0.75, 0.80, 2},  {TILE_32x256, 0.65, 0.20, 2},
     };
     double best = 1e300;
     int best_id = TILE_128x128;
-    auto cost = [&](int64_t tiles, double step_us, int occ) {
-        return std::ceil((double)tiles / ((double)cus * occ)) * step_us;
-    };
     for (auto &cd : cand) {
         TileShape ts = tile_shape(cd.id);
+        const double cap = (double)cus * cd.occ;
+        auto cost = [&](int64_t tiles) {
+            const double full = std::floor((double)tiles / cap), rem = (double)tiles - full * cap;
+            return full * (cd.base + cd.slope) + (rem > 0 ? cd.base + cd.slope * rem / cap : 0.0);
+        };
         double total = 0;
         if (p->schedule == FICCO_FINE_PERSISTENT) {
-            int64_t tiles = (int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-            total = cost(tiles, cd.step_us, cd.occ);
+            total = cost((int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
         } else {
             for (auto &g : p->groups) {
                 LaunchShape ls = launch_shape(p, g);
-                int64_t tiles = (int64_t)ls.n_blocks * ((ls.rows_per_block + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-                total += cost(tiles, cd.step_us, cd.occ);
+                total += cost((int64_t)ls.n_blocks * ((ls.rows_per_block + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
             }
         }
         if (total < best * 0.999) { best = total; best_id = cd.id; }
@@ -261,6 +265,9 @@ void release(ficco_plan_t *p)
     }
     if (p->d_words) (void)hipFree(p->d_words);
     if (p->d_ticket_mem) (void)hipFree(p->d_ticket_mem);
+    if (p->d_sig_value) (void)hipFree(p->d_sig_value);
+    p->d_sig_value = nullptr;
+    p->sig_poll = -1;
     p->d_ticket_mem = nullptr;
     if (p->d_tables) (void)hipFree(p->d_tables);
     if (p->d_wt) (void)hipFree(p->d_wt);
@@ -454,7 +461,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     links = std::min(links, (int)eng.size());
     p->links = links;
 
-    // signals, one pair per arrival position
+    // signals, one pair per chunk
     while ((int)p->sig_data.size() < n) {
         hsa_signal_t a, b;
         if (hsa_signal_create(0, 0, nullptr, &a) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
@@ -462,11 +469,46 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (hsa_signal_create(0, 0, nullptr, &b) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
         p->sig_flag.push_back(b);
     }
+    // Can the kernels watch the transfers' own completion signals? The value word of a user signal
+    // (amd_signal_t, the layout AQL consumers use) must lie in memory the runtime reports as
+    // accessible to this GPU; its device-side address goes into a table. Otherwise, or when asked
+    // for (FICCO_OPT_FLAG_WRITE = 2), every transfer is followed by a 4-byte flag copy instead.
+    if (p->sig_poll < 0) {
+        p->sig_poll = 0;
+        std::vector<uint64_t> addr(n, 0);
+        bool ok = p->flag_write == 0;
+        for (int i = 0; i < n && ok; ++i) {
+            amd_signal_t *as = reinterpret_cast<amd_signal_t *>(p->sig_data[i].handle);
+            if (!as || as->kind != AMD_SIGNAL_KIND_USER) { ok = false; break; }
+            void *vp = (void *)&as->value;
+            hsa_amd_pointer_info_t info{};
+            info.size = sizeof(info);
+            uint32_t n_acc = 0;
+            hsa_agent_t *acc = nullptr;
+            if (hsa_amd_pointer_info(vp, &info, malloc, &n_acc, &acc) != HSA_STATUS_SUCCESS ||
+                info.type == HSA_EXT_POINTER_TYPE_UNKNOWN) { ok = false; if (acc) free(acc); break; }
+            bool mine = false;
+            for (uint32_t k = 0; k < n_acc; ++k) mine |= acc[k].handle == ctx.gpu.handle;
+            if (acc) free(acc);
+            const uintptr_t off = (uintptr_t)vp - (uintptr_t)info.hostBaseAddress;
+            if (!mine || !info.agentBaseAddress || !info.hostBaseAddress || off + 8 > info.sizeInBytes) { ok = false; break; }
+            addr[i] = (uint64_t)((uintptr_t)info.agentBaseAddress + off);
+        }
+        if (ok) {
+            if (hipMalloc((void **)&p->d_sig_value, sizeof(uint64_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemcpy(p->d_sig_value, addr.data(), sizeof(uint64_t) * (size_t)n, hipMemcpyHostToDevice));
+            p->sig_poll = 1;
+        }
+        if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: kernels %s\n", p->sig_poll ? "poll the transfers' completion signals" : "wait on flags raised by 4-byte copies");
+    }
+    // Signals live in host memory: when the transfers themselves cross the host link, hundreds of
+    // polling workgroups would compete with them for it, so flags in device memory are used then.
+    const bool poll_signals = p->sig_poll == 1 && !p->hold_flags && !touches_host;
     // the previous run must be over before its buffers, flags and signals are reused
     if (p->run_index > 0) {
         HIP_TRY(hipEventSynchronize(p->ev_end));
-        for (int q = 0; q < n; ++q)
-            if (!wait_signal(p->sig_data[q], 5.0) || !wait_signal(p->sig_flag[q], 5.0)) return FICCO_ERR_TIMEOUT;
+        for (int i = 0; i < n; ++i)
+            if (!wait_signal(p->sig_data[i], 5.0) || !wait_signal(p->sig_flag[i], 5.0)) return FICCO_ERR_TIMEOUT;
     }
     if (timing) {
         if ((rc = make_events(p->ev_gemm_b, p->groups.size()))) return rc;
@@ -480,15 +522,19 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     // transfers are chained one after the other (peer-to-peer pattern) or run side by side (all-to-all)
     const bool chained = p->schedule == FICCO_SHARD ||
                          (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
+    const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, spin_ticks};
+    // arm the signals before any kernel that watches them can start
+    for (int i = 0; i < n; ++i) {
+        hsa_signal_store_relaxed(p->sig_data[i], (do_copy && !is_local(i)) ? 1 : 0);
+        hsa_signal_store_relaxed(p->sig_flag[i], 0);
+    }
 
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
-    int prev_pos = -1;
     // one piece: data copy, then the 4-byte flag copy behind it on the same engine
+    int prev_chunk = -1;
     auto submit = [&](int q) -> int {
         const int chunk = p->arrival[q];
-        hsa_signal_store_relaxed(p->sig_data[q], 0);
-        hsa_signal_store_relaxed(p->sig_flag[q], 0);
         if (is_local(chunk)) return FICCO_OK;
         const int lane = (chunk / c) % links;
         const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[lane]);
@@ -510,22 +556,21 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             dst = (char *)peer_out[peer] + (size_t)(chunk % c) * p->m * row_bytes_c;
             if (!peer_dev[peer]) { dst_agent = ctx.cpu; force = false; }
         }
-        hsa_signal_store_relaxed(p->sig_data[q], 1);
         hsa_signal_t dep{};
         int ndep = 0;
-        if (chained && prev_pos >= 0) { dep = p->sig_data[prev_pos]; ndep = 1; }
+        if (chained && prev_chunk >= 0) { dep = p->sig_data[prev_chunk]; ndep = 1; }
         hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? &dep : nullptr,
-                                                              p->sig_data[q], engine, force);
-        if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_data[q], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
-        prev_pos = q;
+                                                              p->sig_data[chunk], engine, force);
+        if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        prev_chunk = chunk;
         ++n_copies;
         copy_bytes += (int64_t)bytes;
-        if (!p->hold_flags) {
-            hsa_signal_store_relaxed(p->sig_flag[q], 1);
+        if (!poll_signals && !p->hold_flags) {
+            hsa_signal_store_relaxed(p->sig_flag[chunk], 1);
             uint32_t *flag = p->d_flags + (size_t)chunk * kFlagStrideWords;
-            st = hsa_amd_memory_async_copy_on_engine(flag, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4, 1, &p->sig_data[q],
-                                                     p->sig_flag[q], engine, false);
-            if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[q], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+            st = hsa_amd_memory_async_copy_on_engine(flag, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4, 1, &p->sig_data[chunk],
+                                                     p->sig_flag[chunk], engine, false);
+            if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[chunk], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
         }
         return FICCO_OK;
     };
@@ -535,14 +580,11 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             // wait list = the group's pieces that arrive by transfer (arrival table slice)
             int first = p->groups[g].pos_begin, last = p->groups[g].pos_end;
             while (first < last && is_local(p->arrival[first])) ++first;     // local pieces sit at the front
-            a.flags = p->d_flags;
+            a.gate = gate;
             a.wait_chunks = p->d_arrival + first;
             a.n_wait = last - first;
             for (int q = first; q < last; ++q)
                 if (is_local(p->arrival[q])) return FICCO_ERR_ARG;           // cannot happen: stable partition
-            a.epoch = epoch;
-            a.status = p->d_status;
-            a.spin_limit_ticks = spin_ticks;
         }
         if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[g], cs));
         HIP_TRY(launch_gemm(p->tile, a, cs));
@@ -563,12 +605,9 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
                 r.arrival = p->d_arrival;
                 r.n_chunks = n;
-                r.flags = p->d_flags;
-                r.epoch = epoch;
+                r.g.gate = gate;
                 r.ticket = p->d_ticket;
                 r.ticket_base = p->ticket_total;
-                r.status = p->d_status;
-                r.spin_limit_ticks = spin_ticks;
                 r.grid = p->resident_grid;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
@@ -593,10 +632,8 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 int first = 0;
                 while (first < n && is_local(p->arrival[first])) ++first;
                 if (first < n)
-                    HIP_TRY(launch_wait_flags(p->d_flags, p->d_arrival + first, n - first, epoch, p->d_status, spin_ticks, cs));
+                    HIP_TRY(launch_wait_ready(gate, p->d_arrival + first, n - first, cs));
             }
-        } else {
-            for (int q = 0; q < n; ++q) { hsa_signal_store_relaxed(p->sig_data[q], 0); hsa_signal_store_relaxed(p->sig_flag[q], 0); }
         }
     } else {
         // ---- GEMM -> RS: a group's rows leave when its launch is done (the host relays the event)
@@ -613,9 +650,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q)
                     if ((rc = submit(q))) return rc;
             }
-            if (!p->hold_flags) HIP_TRY(launch_wait_flags(p->d_flags, p->d_arrival, n, epoch, p->d_status, spin_ticks, cs));
-        } else {
-            for (int q = 0; q < n; ++q) { hsa_signal_store_relaxed(p->sig_data[q], 0); hsa_signal_store_relaxed(p->sig_flag[q], 0); }
+            if (!p->hold_flags) HIP_TRY(launch_wait_ready(gate, p->d_arrival, n, cs));
         }
     }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
@@ -731,7 +766,7 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
         p->tile_opt = (int)value;
         break;
     case FICCO_OPT_FLAG_WRITE:
-        if (value != 0 && value != 1) return FICCO_ERR_ARG;
+        if (value < 0 || value > 2) return FICCO_ERR_ARG;
         p->flag_write = (int)value;
         break;
     case FICCO_OPT_SPIN_LIMIT_US:
@@ -880,7 +915,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                                                                                                            : FICCO_COPY_STREAM;
     p->backend = backend;
     if (backend == FICCO_COPY_ENGINES) {
-        if (p->flag_write != 0) return FICCO_ERR_ARG;
+        if (p->flag_write == 1) return FICCO_ERR_ARG;     // stream writes belong to the stream backend
         return run_engines(p, A_src, A_dev, C_dev, peer_out, cs, src_dev, peer_dev);
     }
     p->last_engines = false;
@@ -974,12 +1009,10 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
             r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
             r.arrival = p->d_arrival;
             r.n_chunks = n;
-            r.flags = p->d_flags;
-            r.epoch = epoch;
+            r.g.gate = Gate{p->d_flags, nullptr, epoch, p->d_status,
+                            (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u};
             r.ticket = p->d_ticket;
             r.ticket_base = p->ticket_total;
-            r.status = p->d_status;
-            r.spin_limit_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
             r.grid = p->resident_grid;
             if (dependent && do_copy) {
                 // On this backend the 4-byte flag writes are done by a helper kernel of the HIP runtime,
@@ -1090,14 +1123,14 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         for (int q = 0; q < p->n_chunks; ++q) {
             const int chunk = p->arrival[q];
             if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
-            if (!wait_signal(p->sig_data[q], 5.0) || !wait_signal(p->sig_flag[q], 5.0)) {
+            if (!wait_signal(p->sig_data[p->arrival[q]], 5.0) || !wait_signal(p->sig_flag[p->arrival[q]], 5.0)) {
                 if (getenv("FICCO_DEBUG"))
                     fprintf(stderr, "ficco: transfer %d (chunk %d) did not complete: data signal %lld flag signal %lld\n", q, chunk,
-                            (long long)hsa_signal_load_relaxed(p->sig_data[q]), (long long)hsa_signal_load_relaxed(p->sig_flag[q]));
+                            (long long)hsa_signal_load_relaxed(p->sig_data[p->arrival[q]]), (long long)hsa_signal_load_relaxed(p->sig_flag[p->arrival[q]]));
                 return FICCO_ERR_TIMEOUT;
             }
             hsa_amd_profiling_async_copy_time_t t{};
-            if (hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &t) != HSA_STATUS_SUCCESS) continue;
+            if (hsa_amd_profiling_get_async_copy_time(p->sig_data[p->arrival[q]], &t) != HSA_STATUS_SUCCESS) continue;
             t_min = std::min(t_min, (uint64_t)t.start);
             t_max = std::max(t_max, (uint64_t)t.end);
             busy += (double)(t.end - t.start) / g_engines.ticks_per_us;
@@ -1136,6 +1169,19 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         }
     }
     if (p->last_had_copies && p->last_engines) s.copy_busy_us = p->last_engine_copy_busy_us;
+    if (p->last_engines && p->last_had_copies && getenv("FICCO_DEBUG") && atoi(getenv("FICCO_DEBUG")) >= 2) {
+        uint64_t t0 = ~0ull;
+        std::vector<hsa_amd_profiling_async_copy_time_t> tt(p->n_chunks), tf(p->n_chunks);
+        for (int q = 0; q < p->n_chunks; ++q) {
+            hsa_amd_profiling_get_async_copy_time(p->sig_data[p->arrival[q]], &tt[q]);
+            hsa_amd_profiling_get_async_copy_time(p->sig_flag[p->arrival[q]], &tf[q]);
+            if (tt[q].start && tt[q].start < t0) t0 = tt[q].start;
+        }
+        for (int q = 0; q < p->n_chunks; ++q)
+            fprintf(stderr, "ficco: run %u pos %d chunk %d data [%.1f, %.1f] us flag [%.1f, %.1f] us\n", p->run_index, q, p->arrival[q],
+                    (tt[q].start - t0) / g_engines.ticks_per_us, (tt[q].end - t0) / g_engines.ticks_per_us,
+                    (tf[q].start - t0) / g_engines.ticks_per_us, (tf[q].end - t0) / g_engines.ticks_per_us);
+    }
     s.exposed_comm_us = s.wall_us - s.gemm_busy_us;
     s.flops = 2 * p->M * p->N * p->K;
     s.eff_tflops = s.wall_us > 0 ? (double)s.flops / s.wall_us * 1e-6 : 0.0;
@@ -1160,8 +1206,8 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
                     uint64_t t0 = ~0ull;
                     std::vector<hsa_amd_profiling_async_copy_time_t> tt(p->n_chunks), tf(p->n_chunks);
                     for (int q = 0; q < p->n_chunks; ++q) {
-                        hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &tt[q]);
-                        hsa_amd_profiling_get_async_copy_time(p->sig_flag[q], &tf[q]);
+                        hsa_amd_profiling_get_async_copy_time(p->sig_data[p->arrival[q]], &tt[q]);
+                        hsa_amd_profiling_get_async_copy_time(p->sig_flag[p->arrival[q]], &tf[q]);
                         if (tt[q].start && tt[q].start < t0) t0 = tt[q].start;
                     }
                     for (int q = 0; q < p->n_chunks; ++q)
@@ -1204,7 +1250,7 @@ int ficco_query_spans(ficco_plan_t *p, double *copy_begin_us, double *copy_end_u
                             t_first = std::min(t_first, (uint64_t)u.start);
                     }
                 }
-                if (hsa_amd_profiling_get_async_copy_time(p->sig_data[q], &t) == HSA_STATUS_SUCCESS && t.end > t.start) {
+                if (hsa_amd_profiling_get_async_copy_time(p->sig_data[p->arrival[q]], &t) == HSA_STATUS_SUCCESS && t.end > t.start) {
                     b = (double)(t.start - t_first) / g_engines.ticks_per_us;
                     e = (double)(t.end - t_first) / g_engines.ticks_per_us;
                 }

@@ -6,7 +6,7 @@
 //   * gemm_blocks_kernel   - one launch over a list of equal-height row blocks (a monolithic GEMM,
 //                            one landed piece, or the G pieces of a fused step read in place);
 //   * gemm_resident_kernel - one launch for the whole run; workgroups draw tiles from a ticket
-//                            counter in arrival order and wait on the piece's ready flag.
+//                            counter in arrival order and wait until the tile's piece is ready.
 //
 // Data flow per workgroup tile (BM x BN, 256 threads = 4 wavefronts of 64):
 //   global --global_load_lds_dwordx4--> LDS (two stages of BK = 64, XOR-swizzled 16 B slots)
@@ -196,17 +196,23 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
     }
 }
 
-// Bounded wait of one thread for a ready flag written by a copy engine (or by a stream write).
-// Reads at system scope (past the caches). Returns 0 when the limit expires or another workgroup
-// has already given up; the caller then skips its work, so every wave still reaches its exit.
-static __device__ __forceinline__ int wait_flag(const uint32_t *f, uint32_t epoch, uint32_t *status, uint64_t limit)
+// Bounded wait of one thread until a piece is ready (see Gate). Reads at system scope (past the
+// caches): the writer is a copy engine. Returns 0 when the limit expires or another workgroup has
+// already given up; the caller then skips its work, so every wave still reaches its exit.
+static __device__ __forceinline__ int wait_ready(const Gate &g, int chunk)
 {
     const uint64_t t0 = wall_clock64();
+    const uint32_t *f = g.flags + (size_t)chunk * kFlagStrideWords;
+    const int64_t *sv = g.sig_value ? reinterpret_cast<const int64_t *>(g.sig_value[chunk]) : nullptr;
     for (;;) {
-        if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == epoch) return 1;
-        if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) return 0;
-        if (wall_clock64() - t0 > limit) {
-            __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (sv) {
+            if (__hip_atomic_load(sv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) <= 0) return 1;
+        } else {
+            if (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == g.epoch) return 1;
+        }
+        if (__hip_atomic_load(g.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) return 0;
+        if (wall_clock64() - t0 > g.spin_limit_ticks) {
+            __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             return 0;
         }
         __builtin_amdgcn_s_sleep(8);
@@ -231,8 +237,7 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
         __shared__ int s_go;
         if (threadIdx.x == 0) {
             int ok = 1;
-            for (int i = 0; i < a.n_wait && ok; ++i)
-                ok = wait_flag(a.flags + (size_t)a.wait_chunks[i] * kFlagStrideWords, a.epoch, a.status, a.spin_limit_ticks);
+            for (int i = 0; i < a.n_wait && ok; ++i) ok = wait_ready(a.gate, a.wait_chunks[i]);
             s_go = ok;
         }
         __syncthreads();                   // also orders the tile's loads after the flag reads
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         if (threadIdx.x == 0) {
             int ok = 1;
             if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) {
-                ok = wait_flag(r.flags + (size_t)chunk * kFlagStrideWords, r.epoch, r.status, r.spin_limit_ticks);
+                ok = wait_ready(a.gate, chunk);
             }
             s_ok = ok;
         }
@@ -301,12 +306,11 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     }
 }
 
-__global__ __launch_bounds__(64) void wait_flags_kernel(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch,
-                                                        uint32_t *status, uint64_t limit)
+__global__ __launch_bounds__(64) void wait_ready_kernel(Gate gate, const int32_t *chunks, int n)
 {
     if (threadIdx.x == 0)
         for (int i = 0; i < n; ++i)
-            if (!wait_flag(flags + (size_t)chunks[i] * kFlagStrideWords, epoch, status, limit)) break;
+            if (!wait_ready(gate, chunks[i])) break;
 }
 
 // W[K,N] -> Wt[N,K] through a 64x64 LDS tile (padded), 256 threads.
@@ -426,10 +430,9 @@ int resident_grid_size(int tile, int device)
     }
 }
 
-hipError_t launch_wait_flags(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch, uint32_t *status,
-                             uint64_t spin_limit_ticks, hipStream_t s)
+hipError_t launch_wait_ready(const Gate &gate, const int32_t *chunks, int n, hipStream_t s)
 {
-    hipLaunchKernelGGL(wait_flags_kernel, dim3(1), dim3(64), 0, s, flags, chunks, n, epoch, status, spin_limit_ticks);
+    hipLaunchKernelGGL(wait_ready_kernel, dim3(1), dim3(64), 0, s, gate, chunks, n);
     return hipGetLastError();
 }
 

@@ -16,6 +16,19 @@ TileShape tile_shape(int tile);
 constexpr int kFlagStrideWords = 16;      // one ready flag per 64-byte line
 constexpr int kBK = 64;                   // k extent of one LDS stage
 
+// How a kernel learns that piece `chunk` has landed:
+//   flags     - flags[chunk*kFlagStrideWords] == epoch (a 4-byte copy or stream write queued behind the transfer)
+//   sig_value - the 64-bit word at sig_value[chunk] has dropped to 0: the value field of the transfer's
+//               own completion signal, decremented by the copy engine itself
+// Both are read at system scope; the wait is bounded (status[0] = 1 when it expires).
+struct Gate {
+    const uint32_t *flags;
+    const uint64_t *sig_value;    // device table of addresses, or nullptr to use flags
+    uint32_t epoch;
+    uint32_t *status;
+    uint64_t spin_limit_ticks;    // in wall_clock64() ticks
+};
+
 // One GEMM launch over a list of equal-height row blocks of A/C (one block for a monolithic or
 // per-piece launch, G blocks for a fused step).
 struct GemmLaunch {
@@ -28,38 +41,30 @@ struct GemmLaunch {
     int32_t row0;                // first row when block_row0 == nullptr (n_blocks == 1)
     int32_t n_blocks;
     int32_t rows_per_block;
-    // Optional gate (copy-engine transfers raise flags instead of HIP events): every workgroup
-    // waits until flags[wait_chunks[i]*kFlagStrideWords] == epoch for all i < n_wait.
-    const uint32_t *flags;
+    // Optional gate (copy-engine transfers): every workgroup waits until all of the pieces
+    // wait_chunks[0..n_wait) are ready.
+    Gate gate;
     const int32_t *wait_chunks;
     int32_t n_wait;
-    uint32_t epoch;
-    uint32_t *status;             // [0] set to 1 when a bounded wait expires
-    uint64_t spin_limit_ticks;    // in wall_clock64() ticks
 };
 
 // The resident kernel: tiles are taken from a ticket counter in arrival order; the tiles of the
-// piece issued p-th wait until flags[arrival[p]*kFlagStrideWords] == epoch.
+// piece issued p-th wait until that piece is ready (g.gate).
 struct ResidentLaunch {
-    GemmLaunch g;                 // block_row0/row0/n_blocks unused; rows_per_block = piece rows
+    GemmLaunch g;                 // block_row0/row0/n_blocks/wait_chunks unused; rows_per_block = piece rows
     const int32_t *arrival;       // device, n_chunks chunk ids in arrival order
     int32_t n_chunks;
-    const uint32_t *flags;        // device, n_chunks * kFlagStrideWords words
-    uint32_t epoch;
     uint32_t *ticket;             // device, monotonically increasing across runs
     uint32_t ticket_base;         // value of *ticket when this run starts
-    uint32_t *status;             // device, [0] set to 1 when a bounded wait expires
-    uint64_t spin_limit_ticks;    // in wall_clock64() ticks
     int32_t grid;
     int32_t local_chunk_begin, local_chunk_end;   // chunk ids that need no flag (already resident), or empty
 };
 
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s);
 hipError_t launch_resident(int tile, const ResidentLaunch &a, hipStream_t s);
-// One wavefront that waits (bounded) for the flags of chunks[0..n) to reach epoch; used to join the
+// One wavefront that waits (bounded) until the pieces chunks[0..n) are ready; used to join the
 // compute stream with copy-engine transfers when no GEMM consumes them.
-hipError_t launch_wait_flags(const uint32_t *flags, const int32_t *chunks, int n, uint32_t epoch, uint32_t *status,
-                             uint64_t spin_limit_ticks, hipStream_t s);
+hipError_t launch_wait_ready(const Gate &gate, const int32_t *chunks, int n, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_t N, hipStream_t s);
 int resident_grid_size(int tile, int device);
 

@@ -328,10 +328,12 @@ def test_engines_backend_pinned_and_device_sources(gpu):
     base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
     for src in ("pinned", "device"):
         for sched, c in ALL_SCHEDULES:
-            for links in (0, 1, 3):
+            # links: engines side by side; fw 0: kernels watch the transfers' completion signals when
+            # the runtime reports them reachable, fw 2: a 4-byte flag copy behind every transfer
+            for links, fw in ((0, 0), (1, 0), (3, 2), (0, 2)):
                 bits, st, info = run_ag(gpu, shards, W, sched, c, src=src, runs=2,
                                         opts=[(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_ENGINES),
-                                              (ficco.FICCO_OPT_LINKS, links)])
+                                              (ficco.FICCO_OPT_LINKS, links), (ficco.FICCO_OPT_FLAG_WRITE, fw)])
                 assert np.array_equal(bits, base), (src, sched, c, links)
                 assert info.copy_backend == ficco.FICCO_COPY_ENGINES
                 assert info.links == (4 if links == 0 else links)
