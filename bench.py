@@ -13,6 +13,8 @@ Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192
               compute stream -> achieved TFLOP/s against the bf16 dense MFMA peak
   losses    - decomposition / contention losses (DIL, CIL) through ficco_profile_losses
   cpu       - the CPU oracle timed on the host cores (a baseline, not a target)
+  calib     - (not in the default set) a plain device copy of 256 MiB, so that HBM counters read
+              under rocprofv3 --pmc can be scaled by what they show for a known amount of traffic
 """
 from __future__ import annotations
 
@@ -29,6 +31,17 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
 HBM_PEAK_GBPS = 8000.0
 
+# HBM-side traffic per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# summaries kept under profiles/ (gemm_isolated_<workload>.md): KiB per dispatch as the counters
+# read, and the factors by which a 256 MiB device copy's true traffic exceeds what they read for it.
+PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131089.7, "WRITE_SIZE": 262144.0 / 262144.0}
+PMC_KIB = {
+    ("cfg2_qkv8b", "gemm_resident_kernel<128x128>"): {"FETCH_SIZE": 156905.0, "WRITE_SIZE": 12317.5},
+    ("cfg2_qkv8b", "gemm_blocks_kernel<128x128>"): {"FETCH_SIZE": 69493.6, "WRITE_SIZE": 12289.0},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1377720.1, "WRITE_SIZE": 115515.5},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754123.9, "WRITE_SIZE": 114884.7},
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -38,6 +51,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2_qkv8b")
     ap.add_argument("--legs", default="pair,pcie,roofline,losses,cpu")
     ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4 (default: a small sweep)")
+    ap.add_argument("--roofline-plan", default="", help="schedule:chunks for the roofline leg when the pair leg is not run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box here has one); "
@@ -149,7 +163,12 @@ def main() -> int:
         out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
 
     if "roofline" in legs:
-        s, c = best if best else (F.FICCO_SERIAL, 1)
+        if best:
+            s, c = best
+        elif args.roofline_plan:
+            s, c = (int(x) for x in args.roofline_plan.split(":"))
+        else:
+            s, c = F.ficco_pick_schedule(M, K, N, G)
         plan = make(s, c, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
         busy, launches = [], 0
         for it in range(args.warmup + args.steps):
@@ -172,10 +191,14 @@ def main() -> int:
                 whole.append(st.gemm_busy_us)
         winfo = F.ficco_plan_info(plan)
         F.ficco_destroy(plan)
+        kname = ("gemm_resident_kernel" if s == F.FICCO_FINE_PERSISTENT else "gemm_blocks_kernel") + f"<{info.tile_m}x{info.tile_n}>"
+        pmc = PMC_KIB.get((args.workload, kname)) if launches == 1 else None
+        traffic = int(sum(pmc[k] * PMC_SCALE[k] for k in pmc) * 1024) if pmc else None
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                           "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                           "kernel": ("gemm_resident_kernel" if s == F.FICCO_FINE_PERSISTENT else "gemm_blocks_kernel")
-                                     + f"<{info.tile_m}x{info.tile_n}>",
+                           "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
+                           "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; see profiles/)",
+                           "algorithmic_bytes": 2 * (M * K + K * N + M * N),
+                           "kernel": kname,
                            "launches_per_step": launches, "avg_launch_us": round(us_step / max(launches, 1), 3),
                            "flops_per_launch": flops // max(launches, 1),
                            "monolithic_us": round(float(np.mean(whole)), 3),
@@ -195,6 +218,14 @@ def main() -> int:
             losses[tag]["comm_dil_pct"] = round((L.comm_dil - 1) * 100, 2)
             losses[tag]["comm_cil_pct"] = round((L.comm_cil - 1) * 100, 2)
         out["losses"] = losses
+
+    if "calib" in legs:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calib"] = {"kernel": "torch elementwise copy", "bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 3}
 
     if "cpu" in legs:
         from oracle import gemm as og
