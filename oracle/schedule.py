@@ -125,3 +125,19 @@ def heuristic_paper(M: int, N: int, K: int, G: int, threshold: float, ratio: flo
     if x > ratio * threshold:
         return "hetero-unfused-1D"
     return "hetero-fused-1D"
+
+
+def pick_pieces(M: int, K: int, N: int, G: int, piece_flops: float = 2.5e10, min_rows: int = 256, max_pieces: int = 16) -> int:
+    """This build's reading of the Sec. V-C rule for the piece count: the largest power-of-two split of
+    a shard whose pieces still carry ``piece_flops`` flops each (OTB x MT of the piece GEMM), pieces of
+    at least ``min_rows`` rows, at most ``max_pieces`` pieces per shard."""
+    ms = M // G
+    t = piece_flops / (2.0 * N * K)
+    m = 1
+    while m * 2 <= t:
+        m *= 2
+    m = max(min_rows, min(m, ms))
+    c = max(1, min(max_pieces, ms // m))
+    while c > 1 and ms % c:
+        c //= 2
+    return c

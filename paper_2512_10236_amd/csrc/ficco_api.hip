@@ -695,18 +695,21 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
 {
     if (M < 1 || K < 1 || N < 1 || shards < 1 || !schedule || !chunks) return FICCO_ERR_ARG;
     if (M % shards) return FICCO_ERR_SHAPE;
-    // Decision rule of Sec. V-C on the step GEMM (M/shards rows): the combined op-to-byte and
-    // memory-traffic metric (their product, i.e. the step's flop count) against a machine
-    // threshold. Small steps are sensitive to decomposition loss: keep launches large (fused,
-    // few pieces). Large steps tolerate finer pieces, which shorten the exposed first transfer.
+    // Static rule in the spirit of Sec. V-C: decomposition loss grows as the decomposed GEMM's combined
+    // op-to-byte and memory-traffic metric (their product = its flop count) falls, so a shard is cut
+    // into as many pieces as keep one piece's GEMM above a machine threshold (fitted on MI355X with
+    // the sweep tool: 2.5e10 flop, piece rows a power of two, at least 256 rows, at most 16 pieces).
+    // Among the schedules the resident kernel was the fastest at every point of the sweep, so the
+    // schedule itself needs no threshold here.
     const int64_t ms = M / shards;
-    const double x = 2.0 * (double)ms * (double)N * (double)K;
-    const double T = 6.0e9, ratio = 5.0;
-    int sch, c;
-    if (x < T) { sch = FICCO_FINE_FUSED; c = 2; }
-    else if (x > ratio * T) { sch = FICCO_FINE_PERSISTENT; c = 4; }
-    else { sch = FICCO_FINE_PERSISTENT; c = 2; }
-    while (c > 1 && (ms % c || ms / c < 128)) c >>= 1;
+    const double kPieceFlops = 2.5e10;
+    const double t = kPieceFlops / (2.0 * (double)N * (double)K);
+    int64_t m = 1;
+    while ((double)(m * 2) <= t && m < (int64_t)1 << 40) m *= 2;
+    m = std::max<int64_t>(256, std::min(m, ms));
+    int c = (int)std::max<int64_t>(1, std::min<int64_t>(16, ms / m));
+    while (c > 1 && ms % c) c /= 2;
+    const int sch = FICCO_FINE_PERSISTENT;
     *schedule = sch;
     *chunks = c;
     return FICCO_OK;

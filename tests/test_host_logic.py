@@ -133,7 +133,18 @@ def test_pick_schedule_returns_a_valid_plan():
                 assert s in (ficco.FICCO_SERIAL, ficco.FICCO_SHARD, ficco.FICCO_FINE_UNFUSED,
                              ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT)
                 assert c >= 1 and (M // 8) % c == 0
+                assert s == ficco.FICCO_FINE_PERSISTENT and c == sch.pick_pieces(M, K, N, 8)
                 plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO)
                 info = ficco.ficco_plan_info(plan)
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
+
+
+def test_pick_pieces_hand_cases():
+    # 2.5e10 flop per piece at N=3584, K=8192 is 426 rows; the power of two below it is 256
+    assert sch.pick_pieces(16384, 8192, 3584, 8) == 8          # 2048-row shards in 256-row pieces
+    assert sch.pick_pieces(4096, 4096, 512, 8) == 1            # threshold (5960 rows) exceeds the shard
+    assert sch.pick_pieces(65536, 8192, 14336, 8) == 16        # capped at 16 pieces
+    assert sch.pick_pieces(512, 1024, 1024, 4) == 1            # shard smaller than the minimum piece
+    for args in [(16384, 8192, 3584, 8), (4096, 4096, 512, 8), (65536, 8192, 14336, 8), (512, 1024, 1024, 4), (24576, 4096, 1024, 8)]:
+        assert ficco.ficco_pick_schedule(*args)[1] == sch.pick_pieces(*args)
