@@ -84,21 +84,37 @@ def main() -> int:
     flops = 2 * M * N * K
     ms_shard = M // G
 
-    def timed_steps(plan, A_src, steps, warmup):
+    rs = cfg["direction"] == "gemm_rs"
+    if rs:
+        # GEMM -> reduce-scatter (data movement): A is resident, row block p of C goes to peer buffer p
+        A_dev.copy_(A_stage)
+        peers_dev = [torch.zeros((ms_shard, N), dtype=torch.int16, device=dev) for _ in range(G)]
+        peers_pin = [torch.zeros((ms_shard, N), dtype=torch.int16).pin_memory() for _ in range(G)]
+        torch.cuda.synchronize()
+
+    def run_once(plan, src):
+        """One step. `src` is the shard source (all-gather direction) or the peer list (reduce-scatter)."""
+        if rs:
+            F.ficco_run(plan, None, A_dev, W_dev, C_dev, src, cs, xs)
+        else:
+            F.ficco_run(plan, src, A_dev, W_dev, C_dev, None, cs, xs)
+        return F.ficco_query_stats(plan)                  # the step's last stage; blocks until the step is done
+
+    def timed_steps(plan, src, steps, warmup):
         """ms per step over `steps` back-to-back steps, synchronize on both sides."""
         for _ in range(warmup):
-            F.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, cs, xs)
-            F.ficco_query_stats(plan)
+            run_once(plan, src)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            F.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, cs, xs)
-            F.ficco_query_stats(plan)                     # the step's last stage; blocks until the step is done
+            run_once(plan, src)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
     def make(sched, c, opts=()):
         plan = F.ficco_plan(M, K, N, G, c, sched)
+        if rs:
+            F.ficco_plan_set(plan, F.FICCO_OPT_DIRECTION, F.FICCO_DIR_GEMM_RS)
         for o, v in opts:
             F.ficco_plan_set(plan, o, v)
         F.ficco_pack_weight(plan, W_dev, cs)
@@ -110,11 +126,13 @@ def main() -> int:
         cands = []
         for rows in cfg["chunk_rows"]:
             c = ms_shard // rows
-            for s in (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED):
+            for s in ((F.FICCO_FINE_FUSED, F.FICCO_FINE_UNFUSED) if cfg["direction"] == "gemm_rs"
+                      else (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED)):
                 if (s, c) not in cands:
                     cands.append((s, c))
 
-    out = {"metric": "AG+GEMM effective TFLOP/s (overlapped pair, best finer-grain schedule)",
+    out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
+                     + " effective TFLOP/s (overlapped pair, best finer-grain schedule)",
            "value": None, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
@@ -153,13 +171,13 @@ def main() -> int:
 
     best = None
     if "pair" in legs:
-        res, best = leg_pair(A_stage, "hbm")
+        res, best = leg_pair(peers_dev if rs else A_stage, "hbm")
         out["value"] = round(res["eff_tflops"], 3)
         out["ms_per_step"] = round(res["ms_per_step"], 5)
         out["pair"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
         out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"])
     if "pcie" in legs:
-        res, _ = leg_pair(A_pinned, "pcie")
+        res, _ = leg_pair(peers_pin if rs else A_pinned, "pcie")
         out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
 
     if "roofline" in legs:
@@ -169,6 +187,8 @@ def main() -> int:
             s, c = (int(x) for x in args.roofline_plan.split(":"))
         else:
             s, c = F.ficco_pick_schedule(M, K, N, G)
+        if rs and s == F.FICCO_FINE_PERSISTENT:
+            s = F.FICCO_FINE_FUSED
         plan = make(s, c, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
         busy, launches = [], 0
         for it in range(args.warmup + args.steps):
@@ -205,7 +225,7 @@ def main() -> int:
                            "monolithic_tflops": round(flops / float(np.mean(whole)) * 1e-6, 2),
                            "monolithic_tile": f"{winfo.tile_m}x{winfo.tile_n}"}
 
-    if "losses" in legs:
+    if "losses" in legs and not rs:
         s, c = best if best else (F.FICCO_FINE_FUSED, 2)
         losses = {}
         for tag, src in (("hbm", A_stage), ("pcie", A_pinned)):
