@@ -38,7 +38,7 @@ PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131089.7, "WRITE_SIZE": 262144.0 / 262144.
 PMC_KIB = {
     ("cfg2_qkv8b", "gemm_resident_kernel<128x128>"): {"FETCH_SIZE": 156905.0, "WRITE_SIZE": 12317.5},
     ("cfg2_qkv8b", "gemm_blocks_kernel<128x128>"): {"FETCH_SIZE": 69493.6, "WRITE_SIZE": 12289.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1377720.1, "WRITE_SIZE": 115515.5},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1094099.6, "WRITE_SIZE": 115515.5},
     ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754123.9, "WRITE_SIZE": 114884.7},
 }
 

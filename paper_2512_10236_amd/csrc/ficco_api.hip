@@ -155,7 +155,7 @@ struct ficco_plan_s {
 
     // run state
     uint32_t run_index = 0;
-    uint32_t ticket_total = 0;           // tickets drawn by all resident runs so far
+    uint32_t ticket_total[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // tickets drawn from each list by all resident runs so far
     bool last_had_copies = false, last_had_gemm = false, last_timing = false;
     int64_t last_copy_bytes = 0;
     int last_n_copies = 0, last_n_launches = 0;
@@ -310,8 +310,8 @@ int finalize(ficco_plan_t *p)
     // memory is coherent at kernel boundaries only).
     if (hipExtMallocWithFlags((void **)&p->d_words, words * 4, hipDeviceMallocFinegrained) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     HIP_TRY(hipMemset(p->d_words, 0, words * 4));
-    if (hipMalloc((void **)&p->d_ticket_mem, 256) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
-    HIP_TRY(hipMemset(p->d_ticket_mem, 0, 256));
+    if (hipMalloc((void **)&p->d_ticket_mem, kTicketLists * kFlagStrideWords * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    HIP_TRY(hipMemset(p->d_ticket_mem, 0, kTicketLists * kFlagStrideWords * 4));
     HIP_TRY(hipDeviceSynchronize());
     p->d_flags = p->d_words;
     p->d_ticket = p->d_ticket_mem;
@@ -607,13 +607,15 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 r.n_chunks = n;
                 r.g.gate = gate;
                 r.ticket = p->d_ticket;
-                r.ticket_base = p->ticket_total;
                 r.grid = p->resident_grid;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
                 TileShape ts = tile_shape(p->tile);
-                const int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-                p->ticket_total += (uint32_t)tiles + (uint32_t)r.grid;
+                for (int x = 0; x < kTicketLists; ++x) {
+                    r.ticket_base[x] = p->ticket_total[x];
+                    p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
+                                                                        (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+                }
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(launch_resident(p->tile, r, cs));
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
@@ -1015,7 +1017,6 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
             r.g.gate = Gate{p->d_flags, nullptr, epoch, p->d_status,
                             (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u};
             r.ticket = p->d_ticket;
-            r.ticket_base = p->ticket_total;
             r.grid = p->resident_grid;
             if (dependent && do_copy) {
                 // On this backend the 4-byte flag writes are done by a helper kernel of the HIP runtime,
@@ -1030,8 +1031,11 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
             else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
             else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
             TileShape ts = tile_shape(p->tile);
-            const int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
-            p->ticket_total += (uint32_t)tiles + (uint32_t)r.grid;
+            for (int x = 0; x < kTicketLists; ++x) {
+                r.ticket_base[x] = p->ticket_total[x];
+                p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
+                                                                    (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+            }
             if (timing) {
                 HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));

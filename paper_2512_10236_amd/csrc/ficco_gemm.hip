@@ -266,6 +266,12 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
                     a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
 }
 
+// Tile order of the resident kernel. Row tiles are numbered in arrival order (R = arrival position x
+// row tiles per piece + row tile in the piece) and dealt round-robin to kTicketLists lists, one per
+// XCD, each with its own ticket counter: a workgroup first serves the list of the XCD it presumably
+// runs on (workgroups are dispatched round-robin over the XCDs), so that the tiles sharing an L2 at
+// any time are few row tiles times a run of column tiles, and then helps the other lists. Inside a
+// list tiles go in groups of 2 row tiles, row tile fastest.
 template <class T>
 __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
 {
@@ -275,34 +281,42 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_chunk = (a.rows_per_block + T::BM - 1) / T::BM;
-    const int per_chunk = rt_per_chunk * tiles_n;
-    const int total = r.n_chunks * per_chunk;
+    const int row_tiles = r.n_chunks * rt_per_chunk;
+    constexpr int GROUP = 2;
 
-    for (;;) {
-        if (threadIdx.x == 0) s_tile = (int)(atomicAdd(r.ticket, 1u) - r.ticket_base);
-        __syncthreads();
-        const int t = s_tile;
-        if (t >= total) break;            // every workgroup draws exactly one ticket past the end
-        const int p = t / per_chunk, w = t % per_chunk;
-        const int chunk = r.arrival[p];
-        if (threadIdx.x == 0) {
-            int ok = 1;
-            if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) {
-                ok = wait_ready(a.gate, chunk);
+    for (int turn = 0; turn < kTicketLists; ++turn) {
+        const int x = (blockIdx.x + turn) % kTicketLists;
+        const int my_rows = row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0;
+        const int total = my_rows * tiles_n;
+        for (;;) {
+            if (threadIdx.x == 0) s_tile = (int)(atomicAdd(r.ticket + x * kFlagStrideWords, 1u) - r.ticket_base[x]);
+            __syncthreads();
+            const int t = s_tile;
+            if (t >= total) break;        // every workgroup draws exactly one ticket past the end of every list
+            const int per_group = GROUP * tiles_n;
+            const int g = t / per_group, first = g * GROUP;
+            const int gsz = min(my_rows - first, GROUP);
+            const int rl = first + (t % per_group) % gsz, tn = (t % per_group) / gsz;
+            const int R = rl * kTicketLists + x;
+            const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
+            const int chunk = r.arrival[p];
+            if (threadIdx.x == 0) {
+                int ok = 1;
+                if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
+                s_ok = ok;
             }
-            s_ok = ok;
+            __syncthreads();               // also orders the tile's loads after the flag read
+            if (s_ok) {
+                const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
+                const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
+                const int col0 = tn * T::BN;
+                const int cols_valid = min(T::BN, a.N - col0);
+                compute_tile<T>(a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid,
+                                a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
+            }
+            __syncthreads();               // s_tile / s_ok / LDS stages are reused
         }
-        __syncthreads();                   // also orders the tile's loads after the flag read
-        if (s_ok) {
-            const int rt = w % rt_per_chunk, tn = w / rt_per_chunk;
-            const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
-            const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
-            const int col0 = tn * T::BN;
-            const int cols_valid = min(T::BN, a.N - col0);
-            compute_tile<T>(a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid,
-                            a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
-        }
-        __syncthreads();                   // s_tile / s_ok / LDS stages are reused
+        __syncthreads();
     }
 }
 

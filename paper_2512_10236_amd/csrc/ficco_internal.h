@@ -15,6 +15,14 @@ TileShape tile_shape(int tile);
 
 constexpr int kFlagStrideWords = 16;      // one ready flag per 64-byte line
 constexpr int kBK = 64;                   // k extent of one LDS stage
+constexpr int kTicketLists = 8;           // one tile list per XCD (each XCD has its own L2)
+
+// Tiles of the resident kernel that list x (of kTicketLists) holds: row tiles x, x+8, x+16, ... of the
+// arrival-ordered sequence of row tiles, times all column tiles.
+inline int64_t resident_list_tiles(int64_t row_tiles, int64_t tiles_n, int x)
+{
+    return (row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0) * tiles_n;
+}
 
 // How a kernel learns that piece `chunk` has landed:
 //   flags     - flags[chunk*kFlagStrideWords] == epoch (a 4-byte copy or stream write queued behind the transfer)
@@ -54,8 +62,8 @@ struct ResidentLaunch {
     GemmLaunch g;                 // block_row0/row0/n_blocks/wait_chunks unused; rows_per_block = piece rows
     const int32_t *arrival;       // device, n_chunks chunk ids in arrival order
     int32_t n_chunks;
-    uint32_t *ticket;             // device, monotonically increasing across runs
-    uint32_t ticket_base;         // value of *ticket when this run starts
+    uint32_t *ticket;             // device, kTicketLists counters kFlagStrideWords apart, monotonically increasing across runs
+    uint32_t ticket_base[8];      // value of each counter when this run starts
     int32_t grid;
     int32_t local_chunk_begin, local_chunk_end;   // chunk ids that need no flag (already resident), or empty
 };
