@@ -224,8 +224,9 @@ LaunchShape launch_shape(const ficco_plan_t *p, const Group &g)
 int choose_tile(const ficco_plan_t *p, int cus)
 {
     static const struct { int id; double base, slope; int occ; } cand[] = {
-        {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.85, 0.25, 1}, {TILE_256x128, 0.87, 0.30, 1},
-        {TILE_128x128, 0.60, 0.50, 2}, {TILE_64x256, 0.75, 0.80, 2},  {TILE_32x256, 0.65, 0.20, 2},
+        {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.80, 0.35, 1}, {TILE_256x128, 0.80, 0.40, 1},
+        {TILE_128x128, 0.60, 0.50, 2}, {TILE_128x128D, 0.48, 0.08, 1},
+        {TILE_64x256, 0.57, 0.15, 1},  {TILE_32x256, 0.45, 0.05, 1},
     };
     double best = 1e300;
     int best_id = TILE_128x128;

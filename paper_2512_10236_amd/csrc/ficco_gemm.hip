@@ -42,19 +42,24 @@ static __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
 }
-static __device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <int N>
+static __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 static __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <int BM_, int BN_, int WGM_, int WGN_>
+template <int BM_, int BN_, int WGM_, int WGN_, int NSTAGE_>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr int NSTAGE = NSTAGE_;                     // LDS stages in the ring; loads run NSTAGE-1 k-tiles ahead
     static constexpr int THREADS = WGM * WGN * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
     static constexpr int FM = WTM / 32, FN = WTN / 32;         // 32x32 MFMA blocks per wavefront
     static constexpr int A_STAGE = BM * kBK * 2, B_STAGE = BN * kBK * 2;   // bytes
     static constexpr int STAGE = A_STAGE + B_STAGE;
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static constexpr int AB = BM / 8 / 4, BB = BN / 8 / 4;     // 8-row (1 KiB) blocks loaded per wavefront per stage
+    static constexpr int LOADS = AB + BB;                      // load instructions per wavefront per k-tile
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2 to 4 stages");
+    static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS ring plus the kernels' few static words must fit one CU");
     static_assert(THREADS == 256, "loaders assume 4 wavefronts");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile is made of 32x32 blocks");
     static_assert(AB >= 1 && BB >= 1, "tile too small for the loader");
@@ -64,12 +69,14 @@ struct TileCfg {
 // it exist (the others are neither stored nor allowed to fault: their loads are clamped to the
 // last valid row). wt_tile: first row (= output column) of the tile in Wt; cols_valid likewise.
 //
-// LDS holds two stages; a stage is BM + BN rows of 128 B (64 k values), the 16-byte slot kc of
-// row r stored at slot kc ^ ((r >> 1) & 7) so that the 16 lanes of a ds_read_b128 phase hit 64
-// different banks. Loads go global -> LDS directly (no staging registers): a wavefront
+// LDS holds a ring of NSTAGE stages; a stage is BM + BN rows of 128 B (64 k values), the 16-byte
+// slot kc of row r stored at slot kc ^ ((r >> 1) & 7) so that the 16 lanes of a ds_read_b128 phase
+// hit 64 different banks. Loads go global -> LDS directly (no staging registers): a wavefront
 // instruction fills 8 rows, lane l fetching the slot that belongs at position l. One barrier per
-// k-step: after it, the loads of the next k-tile are issued into the other stage (spread over the
-// first half of the step so that they do not hold up MFMA issue) and have the whole step to land.
+// k-step: after it, the loads of k-tile kt+NSTAGE-1 are issued into the stage that k-tile kt-1 just
+// left (spread over the first half of the step so that they do not hold up MFMA issue). The big
+// tile only has room for two stages; the smaller tiles use three or four, which is what keeps
+// launches with few workgroups (small pieces) from being bound by load latency.
 template <class T>
 static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__ a_tile, int rows_valid,
                                                     const uint16_t *__restrict__ wt_tile, int cols_valid,
@@ -125,13 +132,26 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
     const int KT = K / kBK;
+    constexpr int D = T::NSTAGE - 1;      // prefetch distance in k-tiles
 #pragma unroll
-    for (int q = 0; q < 4; ++q) issue_part(0, 0, q);
+    for (int d = 0; d < D; ++d)
+        if (d < KT) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) issue_part(d, d, q);
+        }
     for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        wait_all_vmem();                   // this wavefront's part of k-tile kt has landed ...
-        wg_barrier();                      // ... and so has everyone else's; stage cur^1 is free again
-        const bool more = kt + 1 < KT;
+        const int cur = kt % T::NSTAGE;
+        // This wavefront's part of k-tile kt must have landed; the k-tiles kt+1 .. kt+D-1 that exist may
+        // still be in flight (loads complete in order, so a count is enough) ...
+        {
+            const int inflight = min(D - 1, KT - 1 - kt);
+            if (D >= 3 && inflight == 2) wait_vmem<2 * T::LOADS>();
+            else if (D >= 2 && inflight == 1) wait_vmem<T::LOADS>();
+            else wait_vmem<0>();
+        }
+        wg_barrier();                      // ... and so has everyone else's; the stage of k-tile kt-1 is free again
+        const bool more = kt + D < KT;
+        const int nxt = (kt + D) % T::NSTAGE;
         const unsigned char *base = smem + cur * T::STAGE;
         bf16x8_t fa[2][T::FM], fb[2][T::FN];
         {
@@ -145,8 +165,8 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
         for (int kk = 0; kk < kBK / 16; ++kk) {
             const int c = kk & 1, n = c ^ 1;
             if (more && kk < 2) {
-                issue_part(cur ^ 1, kt + 1, 2 * kk);
-                issue_part(cur ^ 1, kt + 1, 2 * kk + 1);
+                issue_part(nxt, kt + D, 2 * kk);
+                issue_part(nxt, kt + D, 2 * kk + 1);
             }
             if (kk < 3) {
                 const int slot = ((2 * (kk + 1) + fh) ^ fs) << 4;
@@ -345,12 +365,13 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__rest
 }
 
 // ------------------------------------------------------------------------------------------ host
-typedef TileCfg<256, 256, 2, 2> T256x256;
-typedef TileCfg<128, 128, 2, 2> T128x128;
-typedef TileCfg<256, 128, 2, 2> T256x128;
-typedef TileCfg<128, 256, 2, 2> T128x256;
-typedef TileCfg<64, 256, 1, 4> T64x256;
-typedef TileCfg<32, 256, 1, 4> T32x256;
+typedef TileCfg<256, 256, 2, 2, 2> T256x256;
+typedef TileCfg<128, 128, 2, 2, 2> T128x128;       // two workgroups per CU: for launches that fill the machine
+typedef TileCfg<128, 128, 2, 2, 4> T128x128D;      // deep ring, one workgroup per CU: for launches that do not
+typedef TileCfg<256, 128, 2, 2, 3> T256x128;
+typedef TileCfg<128, 256, 2, 2, 3> T128x256;
+typedef TileCfg<64, 256, 1, 4, 3> T64x256;
+typedef TileCfg<32, 256, 1, 4, 4> T32x256;
 
 TileShape tile_shape(int tile)
 {
@@ -361,6 +382,7 @@ TileShape tile_shape(int tile)
     case TILE_128x256: return {128, 256, T128x256::LDS_BYTES, 256};
     case TILE_64x256:  return {64, 256, T64x256::LDS_BYTES, 256};
     case TILE_32x256:  return {32, 256, T32x256::LDS_BYTES, 256};
+    case TILE_128x128D: return {128, 128, T128x128D::LDS_BYTES, 256};
     default: return {0, 0, 0, 0};
     }
 }
@@ -414,6 +436,7 @@ hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s)
     case TILE_128x256: return launch_gemm_t<T128x256>(a, s);
     case TILE_64x256:  return launch_gemm_t<T64x256>(a, s);
     case TILE_32x256:  return launch_gemm_t<T32x256>(a, s);
+    case TILE_128x128D: return launch_gemm_t<T128x128D>(a, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -427,6 +450,7 @@ hipError_t launch_resident(int tile, const ResidentLaunch &r, hipStream_t s)
     case TILE_128x256: return launch_resident_t<T128x256>(r, s);
     case TILE_64x256:  return launch_resident_t<T64x256>(r, s);
     case TILE_32x256:  return launch_resident_t<T32x256>(r, s);
+    case TILE_128x128D: return launch_resident_t<T128x128D>(r, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -440,6 +464,7 @@ int resident_grid_size(int tile, int device)
     case TILE_128x256: return resident_grid_t<T128x256>(device);
     case TILE_64x256:  return resident_grid_t<T64x256>(device);
     case TILE_32x256:  return resident_grid_t<T32x256>(device);
+    case TILE_128x128D: return resident_grid_t<T128x128D>(device);
     default: return 0;
     }
 }

@@ -97,7 +97,8 @@ def test_cfg1_all_schedules_match_oracle_and_each_other(gpu):
 
 
 @pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
-                                  ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256])
+                                  ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256,
+                                  ficco.FICCO_TILE_128x128_DEEP])
 def test_every_tile_shape_ragged(gpu, tile):
     # 3 shards x 2 pieces of 88 rows (no tile height divides it), N = 328 (not a tile width), K = 192
     G, c, m, K, N = 3, 2, 88, 192, 328
