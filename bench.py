@@ -92,6 +92,22 @@ def main() -> int:
         peers_pin = [torch.zeros((ms_shard, N), dtype=torch.int16).pin_memory() for _ in range(G)]
         torch.cuda.synchronize()
 
+    sliced = {}
+
+    def source(tag, sched, c):
+        """Shard source for a plan: the row-major staging buffer, or its K-sliced copy (same bytes, the
+        layout column pieces travel in) for the 2D schedule. `tag` is "hbm" or "pcie"."""
+        if rs:
+            return peers_dev if tag == "hbm" else peers_pin
+        base = A_stage if tag == "hbm" else A_pinned
+        if sched != F.FICCO_FINE_2D:
+            return base
+        if (tag, c) not in sliced:
+            t = base.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
+            sliced[(tag, c)] = t if tag == "hbm" else t.pin_memory()
+            torch.cuda.synchronize()
+        return sliced[(tag, c)]
+
     def run_once(plan, src):
         """One step. `src` is the shard source (all-gather direction) or the peer list (reduce-scatter)."""
         if rs:
@@ -130,6 +146,7 @@ def main() -> int:
                       else (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED)):
                 if (s, c) not in cands:
                     cands.append((s, c))
+        cands += [(F.FICCO_FINE_2D, c) for c in cfg.get("k_slices", [])]
 
     out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
                      + " effective TFLOP/s (overlapped pair, best finer-grain schedule)",
@@ -139,17 +156,18 @@ def main() -> int:
            "config": {"workload": args.workload, "M": M, "K": K, "N": N, "shards": G,
                       "source": "device staging buffer (HBM-resident), one SDMA engine per shard as its link"}}
 
-    def leg_pair(A_src, tag):
+    def leg_pair(tag):
         res = {}
+        A_src = source(tag, F.FICCO_SERIAL, 1)
         # short screening of the candidates, then the full timed run of the winner
         screen = {}
         for s, c in cands:
             plan = make(s, c)
-            screen[(s, c)] = timed_steps(plan, A_src, max(5, args.steps // 5), 3)
+            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3)
             F.ficco_destroy(plan)
         best = min(screen, key=screen.get)
         plan = make(*best)
-        ms = timed_steps(plan, A_src, args.steps, args.warmup)
+        ms = timed_steps(plan, source(tag, *best), args.steps, args.warmup)
         info = F.ficco_plan_info(plan)
         st = F.ficco_query_stats(plan)
         F.ficco_destroy(plan)
@@ -171,13 +189,13 @@ def main() -> int:
 
     best = None
     if "pair" in legs:
-        res, best = leg_pair(peers_dev if rs else A_stage, "hbm")
+        res, best = leg_pair("hbm")
         out["value"] = round(res["eff_tflops"], 3)
         out["ms_per_step"] = round(res["ms_per_step"], 5)
         out["pair"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
         out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"])
     if "pcie" in legs:
-        res, _ = leg_pair(peers_pin if rs else A_pinned, "pcie")
+        res, _ = leg_pair("pcie")
         out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
 
     if "roofline" in legs:
@@ -191,8 +209,9 @@ def main() -> int:
             s = F.FICCO_FINE_FUSED
         plan = make(s, c, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
         busy, launches = [], 0
+        A_res = source("hbm", s, c)                     # operands resident in the layout the plan reads
         for it in range(args.warmup + args.steps):
-            F.ficco_run(plan, None, A_stage, W_dev, C_dev, None, cs, xs)
+            F.ficco_run(plan, None, A_res, W_dev, C_dev, None, cs, xs)
             st = F.ficco_query_stats(plan)
             if it >= args.warmup:
                 busy.append(st.gemm_busy_us)
@@ -211,7 +230,8 @@ def main() -> int:
                 whole.append(st.gemm_busy_us)
         winfo = F.ficco_plan_info(plan)
         F.ficco_destroy(plan)
-        kname = ("gemm_resident_kernel" if s == F.FICCO_FINE_PERSISTENT else "gemm_blocks_kernel") + f"<{info.tile_m}x{info.tile_n}>"
+        kname = {F.FICCO_FINE_PERSISTENT: "gemm_resident_kernel", F.FICCO_FINE_2D: "gemm_resident2d_kernel"}.get(s, "gemm_blocks_kernel") \
+            + f"<{info.tile_m}x{info.tile_n}>"
         pmc = PMC_KIB.get((args.workload, kname)) if launches == 1 else None
         traffic = int(sum(pmc[k] * PMC_SCALE[k] for k in pmc) * 1024) if pmc else None
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -228,7 +248,8 @@ def main() -> int:
     if "losses" in legs and not rs:
         s, c = best if best else (F.FICCO_FINE_FUSED, 2)
         losses = {}
-        for tag, src in (("hbm", A_stage), ("pcie", A_pinned)):
+        for tag in ("hbm", "pcie"):
+            src = source(tag, s, c)
             plan = make(s, c)
             L = F.ficco_profile_losses(plan, src, A_dev, W_dev, C_dev, cs, xs, 10, 5)
             F.ficco_destroy(plan)

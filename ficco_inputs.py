@@ -108,11 +108,23 @@ CONFIGS = {
     # GEMM -> reduce-scatter share (data movement half): output streamed out in 8 row blocks
     "cfg4_gemm_rs": dict(M=16384, K=3584, N=8192, shards=8, chunk_rows=[2048, 512], seed=3,
                          direction="gemm_rs"),
+    # M <= K share (row-parallel projection at a small token count): the shape the paper's rule sends
+    # to the 2D decomposition; ``k_slices`` lists the slice counts exercised
+    "cfg5_2d_proj": dict(M=4096, K=16384, N=4096, shards=8, chunk_rows=[512, 256, 128], k_slices=[2, 4, 8], seed=5,
+                         direction="ag_gemm"),
 }
 
 # heuristic sweep (all-gather -> GEMM, 8 shards)
 SWEEP = dict(M=[4096, 16384, 65536], K=[4096, 8192], N=[512, 1024, 3584, 14336], shards=8,
              chunks_per_shard=[1, 2, 4, 8, 16, 32], seed=4)
+
+
+def to_k_sliced(A: np.ndarray, slices: int) -> np.ndarray:
+    """Layout change only: ``[M, K]`` row-major -> ``[slices, M, K/slices]``, slice s holding columns
+    ``[s*K/slices, (s+1)*K/slices)`` of every row (the layout in which column pieces travel)."""
+    M, K = A.shape
+    assert K % slices == 0
+    return np.ascontiguousarray(A.reshape(M, slices, K // slices).transpose(1, 0, 2))
 
 
 def config_inputs(name: str):

@@ -61,6 +61,14 @@ typedef enum ficco_schedule {
                                     the kernel reads the pieces in place through a row-block table,
                                     so no Gather/Scatter copies are issued                             */
     FICCO_FINE_PERSISTENT = 4,   /* one resident kernel; every tile waits on its piece's ready flag     */
+    FICCO_FINE_2D         = 5,   /* column pieces (the 2D decomposition of Sec. V-A/B, chosen by the
+                                    paper's rule when M <= K): the k range is cut into `chunks` slices,
+                                    step s moves slice s of every shard, and one resident kernel adds
+                                    slice s into its accumulators as it lands, so the partial products
+                                    of the paper's accumulating GEMMs never leave the registers. The
+                                    activation travels and is stored K-sliced (see ficco_run).
+                                    AG_GEMM only, no FICCO_OPT_LOCAL_SHARD, never picked by AUTO
+                                    because it changes the caller's layout                          */
     FICCO_AUTO            = 100  /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
 } ficco_schedule;
 
@@ -192,7 +200,8 @@ typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this p
  * (ficco_pack_weight or ficco_run), after which most options are frozen.
  * Shape rules (FICCO_ERR_SHAPE otherwise): M, K, N >= 1; shards >= 1; chunks >= 1;
  * M % (shards*chunks) == 0; K % 64 == 0; N % 8 == 0; chunks == 1 for SERIAL and SHARD;
- * shards*chunks <= 4096. With FICCO_AUTO, `chunks` is ignored and chosen by the heuristic.
+ * shards*chunks <= 4096. FICCO_FINE_2D instead needs M % shards == 0 and K % (64*chunks) == 0.
+ * With FICCO_AUTO, `chunks` is ignored and chosen by the heuristic.
  */
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule,
                ficco_plan_t **out);
@@ -209,8 +218,9 @@ int ficco_plan_set_arrival(ficco_plan_t *plan, const int32_t *chunk_ids, int n);
 int ficco_plan_info(const ficco_plan_t *plan, ficco_plan_info_t *out);
 
 /* Arrival list: chunk_ids[p] = chunk issued p-th (chunk i = piece i%chunks of shard i/chunks,
- * rows [i*chunk_rows, (i+1)*chunk_rows)); group_ids[p] = index of the GEMM launch that consumes
- * it. Both host arrays of at least n_chunks entries; `cap` is their length. */
+ * rows [i*chunk_rows, (i+1)*chunk_rows); with FICCO_FINE_2D chunk i = k slice i/shards of shard
+ * i%shards); group_ids[p] = index of the GEMM launch that consumes it. Both host arrays of at
+ * least n_chunks entries; `cap` is their length. */
 int ficco_plan_arrival(const ficco_plan_t *plan, int32_t *chunk_ids, int32_t *group_ids, int cap);
 
 /*
@@ -229,6 +239,11 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
  *             A_dev  - [M,K] device; written by the transfers, read by the GEMM.
  *             C_dev  - [M,N] device; written by the GEMM.
  *             peer_out must be NULL.
+ *             FICCO_FINE_2D: A_src and A_dev are K-sliced, [chunks][M][K/chunks] bf16 (slice s holds
+ *             columns [s*K/chunks, (s+1)*K/chunks) of every row, rows contiguous), so that piece
+ *             s*shards + j (slice s of shard j) is one contiguous block, as a sender that owns
+ *             shard j would lay its slices out for DMA. C is bitwise what FICCO_SERIAL computes
+ *             from the same matrix in row-major layout.
  *   GEMM_RS : A_src must be NULL; A_dev is read; C_dev is written by the GEMM and its row block
  *             p (rows [p*M/G, (p+1)*M/G)) is then copied on copy_stream to peer_out[p]
  *             ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces complete.

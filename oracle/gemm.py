@@ -89,6 +89,22 @@ def gemm_rs_blocks(A, W, peers: int):
     return [ref[p * rb:(p + 1) * rb] for p in range(peers)]
 
 
+def ag_gemm_2d(A_sliced, W, shards: int) -> np.ndarray:
+    """The 2D decomposition carried out step by step (Sec. V-A/B): ``A_sliced`` is
+    ``[c, M, K/c]`` (bf16 bits), step s gathers slice s of every shard and its partial product with
+    rows ``[s*K/c, (s+1)*K/c)`` of W is accumulated into the output. fp64 throughout."""
+    A_sliced = np.ascontiguousarray(A_sliced, dtype=np.uint16)
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    c, M, kc = A_sliced.shape
+    assert W.shape[0] == c * kc and M % shards == 0
+    ms = M // shards
+    acc = np.zeros((M, W.shape[1]), dtype=np.float64)
+    for s in range(c):
+        pieces = [A_sliced[s, j * ms:(j + 1) * ms] for j in range(shards)]
+        acc += ag_gemm(pieces, W[s * kc:(s + 1) * kc])
+    return acc
+
+
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
 

@@ -15,6 +15,7 @@ SHARD = 1             # Fig. 3(c): shard j arrives, GEMM on shard j
 FINE_UNFUSED = 2      # Sec. V-A "unfused": one GEMM per received piece
 FINE_FUSED = 3        # Sec. V-A "fused": one GEMM per step over every piece received in the step
 FINE_PERSISTENT = 4   # one resident kernel whose tiles wait for their own piece (this build's design)
+FINE_2D = 5           # Sec. V-A/B 2D decomposition: column pieces, step s moves k slice s of every shard
 
 ORDER_STEP_MAJOR = 0  # Sec. III-B: step s moves sub-chunk s of every shard (all-to-all pattern)
 ORDER_SHARD_MAJOR = 1 # all pieces of shard 0, then shard 1, ... (peer-to-peer pattern at finer grain)
@@ -26,6 +27,23 @@ def chunk_span(M: int, G: int, c: int, i: int) -> tuple[int, int]:
     m = M // (G * c)
     assert 0 <= i < G * c
     return i * m, m
+
+
+def piece_span_2d(M: int, K: int, G: int, c: int, i: int) -> tuple[int, int, int, int]:
+    """(first row, rows, first column, columns) of column piece ``i = s*G + j``: k slice ``s`` of
+    shard ``j`` (Sec. V-A: 2D decomposition cuts the shard along the contraction dimension)."""
+    assert M % G == 0 and K % c == 0 and 0 <= i < G * c
+    s, j = divmod(i, G)
+    return j * (M // G), M // G, s * (K // c), K // c
+
+
+def arrival_order_2d(G: int, c: int, order: int) -> list[int]:
+    """Column-piece ids in issue order: slice by slice (step-major) or shard by shard."""
+    if order == ORDER_STEP_MAJOR:
+        return [s * G + j for s in range(c) for j in range(G)]
+    if order == ORDER_SHARD_MAJOR:
+        return [s * G + j for j in range(G) for s in range(c)]
+    raise ValueError("order")
 
 
 def arrival_order(G: int, c: int, order: int) -> list[int]:
@@ -56,6 +74,11 @@ def plan(M: int, G: int, c: int, schedule: int, order: int | None = None) -> dic
             groups = [arr[g * G:(g + 1) * G] for g in range(c)]     # one launch per step of G pieces
         else:
             groups = [arr[:]]                                       # one launch; waits are per tile
+    elif schedule == FINE_2D:
+        if M % G:
+            raise ValueError("M must be a multiple of shards")
+        arr = arrival_order_2d(G, c, ORDER_STEP_MAJOR if order is None else order)
+        return dict(arrival=arr, groups=[arr[:]], m=M // G, n_chunks=G * c)
     else:
         raise ValueError("schedule")
     if M % (G * c):

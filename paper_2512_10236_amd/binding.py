@@ -13,7 +13,7 @@ from . import _build
 # ---- enums (mirrors of include/ficco.h)
 FICCO_OK, FICCO_ERR_ARG, FICCO_ERR_SHAPE, FICCO_ERR_ALLOC = 0, -1, -2, -3
 FICCO_ERR_HIP, FICCO_ERR_TIMEOUT, FICCO_ERR_STATE = -4, -5, -6
-FICCO_SERIAL, FICCO_SHARD, FICCO_FINE_UNFUSED, FICCO_FINE_FUSED, FICCO_FINE_PERSISTENT = 0, 1, 2, 3, 4
+FICCO_SERIAL, FICCO_SHARD, FICCO_FINE_UNFUSED, FICCO_FINE_FUSED, FICCO_FINE_PERSISTENT, FICCO_FINE_2D = 0, 1, 2, 3, 4, 5
 FICCO_AUTO = 100
 FICCO_DIR_AG_GEMM, FICCO_DIR_GEMM_RS = 0, 1
 FICCO_ORDER_STEP_MAJOR, FICCO_ORDER_SHARD_MAJOR, FICCO_ORDER_CUSTOM = 0, 1, 2
@@ -26,7 +26,8 @@ FICCO_COPY_AUTO, FICCO_COPY_STREAM, FICCO_COPY_ENGINES = 0, 1, 2
  FICCO_TILE_64x256, FICCO_TILE_32x256, FICCO_TILE_128x128_DEEP) = range(8)
 
 SCHEDULE_NAMES = {FICCO_SERIAL: "serial", FICCO_SHARD: "shard", FICCO_FINE_UNFUSED: "fine_unfused",
-                  FICCO_FINE_FUSED: "fine_fused", FICCO_FINE_PERSISTENT: "fine_persistent"}
+                  FICCO_FINE_FUSED: "fine_fused", FICCO_FINE_PERSISTENT: "fine_persistent",
+                  FICCO_FINE_2D: "fine_2d"}
 
 
 class ficco_plan_info_t(C.Structure):

@@ -92,7 +92,7 @@ int engines_init(int hip_device)
     uint64_t freq = 0;
     if (hsa_system_get_info(HSA_SYSTEM_INFO_TIMESTAMP_FREQUENCY, &freq) == HSA_STATUS_SUCCESS && freq > 0)
         c.ticks_per_us = (double)freq * 1e-6;
-    (void)hsa_amd_profiling_async_copy_enable(true);
+    if (!getenv("FICCO_NO_COPY_PROFILING")) (void)hsa_amd_profiling_async_copy_enable(true);
     if (c.mask_hd == 0) c.mask_hd = 0xFFFFu;          // hint missing: let the self test decide
     c.status = FICCO_OK;
     if (getenv("FICCO_DEBUG"))
@@ -140,6 +140,7 @@ struct ficco_plan_s {
     int32_t *d_tables = nullptr;         // arrival | block_row0 (by arrival position)
     int32_t *d_arrival = nullptr, *d_block_row0 = nullptr;
     uint32_t *h_epochs = nullptr;        // pinned
+    volatile uint32_t *h_status = nullptr;   // pinned, behind h_epochs
     uint16_t *d_wt = nullptr;            // packed weight [N,K]
     const void *packed_from = nullptr;
     hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_copy_first = nullptr, ev_copy_last = nullptr;
@@ -163,14 +164,27 @@ struct ficco_plan_s {
 
 namespace {
 
+inline bool is_2d(const ficco_plan_t *p) { return p->schedule == FICCO_FINE_2D; }
+inline bool is_resident(const ficco_plan_t *p) { return p->schedule == FICCO_FINE_PERSISTENT || p->schedule == FICCO_FINE_2D; }
+// shard a piece belongs to: row pieces are numbered shard-major (j*c + s), column pieces slice-major (s*G + j)
+inline int shard_of(const ficco_plan_t *p, int chunk) { return is_2d(p) ? chunk % p->G : chunk / p->c; }
+
 int build_lists(ficco_plan_t *p)
 {
     const int G = p->G, c = p->c, n = G * c;
     p->n_chunks = n;
-    p->m = p->M / n;
+    p->m = is_2d(p) ? p->M / p->G : p->M / n;      // rows of one piece (column pieces keep the shard's rows)
     if (p->order != FICCO_ORDER_CUSTOM) {
         p->arrival.clear();
-        if (p->schedule == FICCO_SERIAL || p->schedule == FICCO_SHARD || p->order == FICCO_ORDER_SHARD_MAJOR) {
+        if (is_2d(p)) {
+            // column pieces: id s*G + j; step-major = slice by slice (ascending ids), shard-major = shard by shard
+            if (p->order == FICCO_ORDER_SHARD_MAJOR) {
+                for (int j = 0; j < G; ++j)
+                    for (int sl = 0; sl < c; ++sl) p->arrival.push_back(sl * G + j);
+            } else {
+                for (int i = 0; i < n; ++i) p->arrival.push_back(i);
+            }
+        } else if (p->schedule == FICCO_SERIAL || p->schedule == FICCO_SHARD || p->order == FICCO_ORDER_SHARD_MAJOR) {
             for (int i = 0; i < n; ++i) p->arrival.push_back(i);
         } else {
             for (int s = 0; s < c; ++s)
@@ -178,7 +192,7 @@ int build_lists(ficco_plan_t *p)
         }
     }
     // "hetero" start: the local shard's pieces come first and need no transfer
-    if (p->local_shard >= 0) {
+    if (p->local_shard >= 0 && !is_2d(p)) {
         std::stable_partition(p->arrival.begin(), p->arrival.end(),
                               [&](int32_t i) { return i / c == p->local_shard; });
     }
@@ -187,6 +201,7 @@ int build_lists(ficco_plan_t *p)
     switch (p->schedule) {
     case FICCO_SERIAL:
     case FICCO_FINE_PERSISTENT:
+    case FICCO_FINE_2D:
         p->groups.push_back({0, n});
         break;
     case FICCO_SHARD:
@@ -238,7 +253,9 @@ int choose_tile(const ficco_plan_t *p, int cus)
             return full * (cd.base + cd.slope) + (rem > 0 ? cd.base + cd.slope * rem / cap : 0.0);
         };
         double total = 0;
-        if (p->schedule == FICCO_FINE_PERSISTENT) {
+        if (is_2d(p)) {
+            total = cost(((p->M + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
+        } else if (p->schedule == FICCO_FINE_PERSISTENT) {
             total = cost((int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
         } else {
             for (auto &g : p->groups) {
@@ -326,11 +343,13 @@ int finalize(ficco_plan_t *p)
         host[n + q] = (int32_t)(p->arrival[q] * p->m);
     }
     HIP_TRY(hipMemcpy(p->d_tables, host.data(), host.size() * 4, hipMemcpyHostToDevice));
-    if (hipHostMalloc((void **)&p->h_epochs, sizeof(uint32_t) * kEpochSlots, hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc((void **)&p->h_epochs, sizeof(uint32_t) * (kEpochSlots + 16), hipHostMallocDefault) != hipSuccess) {
         release(p);
         return FICCO_ERR_ALLOC;
     }
     for (int i = 0; i < kEpochSlots; ++i) p->h_epochs[i] = (uint32_t)i;
+    p->h_status = p->h_epochs + kEpochSlots;     // set by a kernel whose bounded wait expired
+    for (int i = 0; i < 16; ++i) p->h_status[i] = 0;
 
     HIP_TRY(hipEventCreate(&p->ev_begin));
     HIP_TRY(hipEventCreate(&p->ev_end));
@@ -340,11 +359,12 @@ int finalize(ficco_plan_t *p)
     HIP_TRY(hipEventCreate(&p->ev_gemm_last));
     rc = make_events(p->ev_dep, p->groups.size());
     if (rc) return rc;
-    if (p->schedule == FICCO_FINE_PERSISTENT) {
-        p->resident_grid = resident_grid_size(p->tile, dev);
+    if (is_resident(p)) {
+        p->resident_grid = is_2d(p) ? resident2d_grid_size(p->tile, dev) : resident_grid_size(p->tile, dev);
         if (p->resident_grid <= 0) return FICCO_ERR_HIP;
         TileShape ts = tile_shape(p->tile);
-        int64_t tiles = (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
+        int64_t tiles = is_2d(p) ? ((p->M + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn)
+                                 : (int64_t)n * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn);
         if (tiles < p->resident_grid) p->resident_grid = (int)tiles;
     }
     p->finalized = true;
@@ -435,6 +455,39 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
     return out;
 }
 
+// bytes of one row of a transferred piece of the activation
+inline size_t piece_row_bytes(const ficco_plan_t *p) { return (size_t)(is_2d(p) ? p->K / p->c : p->K) * 2; }
+
+// One resident launch of the K-sliced schedule: every tile owns its part of C for the whole k range
+// and waits, slice by slice, for the column pieces of the shards its rows come from.
+int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const void *A_dev, void *C_dev, hipStream_t cs)
+{
+    Resident2DLaunch r{};
+    r.g.A = (const uint16_t *)A_dev;
+    r.g.Wt = p->d_wt;
+    r.g.C = (uint16_t *)C_dev;
+    r.g.lda = p->K / p->c;
+    r.g.ldc = p->N;
+    r.g.N = (int32_t)p->N;
+    r.g.K = (int32_t)p->K;
+    r.g.gate = gate;
+    r.M = (int32_t)p->M;
+    r.slices = p->c;
+    r.shards = p->G;
+    r.rows_per_shard = (int32_t)(p->M / p->G);
+    r.k_per_slice = (int32_t)(p->K / p->c);
+    r.ticket = p->d_ticket;
+    r.grid = grid;
+    r.gated = gated ? 1 : 0;
+    TileShape ts = tile_shape(p->tile);
+    for (int x = 0; x < kTicketLists; ++x) {
+        r.ticket_base[x] = p->ticket_total[x];
+        p->ticket_total[x] += (uint32_t)resident_list_tiles((p->M + ts.bm - 1) / ts.bm, (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)grid;
+    }
+    HIP_TRY(launch_resident2d(p->tile, r, cs));
+    return FICCO_OK;
+}
+
 int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, void *const *peer_out,
                 hipStream_t cs, bool src_dev, const std::vector<char> &peer_dev)
 {
@@ -518,12 +571,12 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     p->run_index += 1;
     const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
     const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
-    const size_t row_bytes_a = (size_t)p->K * 2, row_bytes_c = (size_t)p->N * 2;
-    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && chunk / c == p->local_shard; };
+    const size_t row_bytes_a = piece_row_bytes(p), row_bytes_c = (size_t)p->N * 2;
+    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && shard_of(p, chunk) == p->local_shard; };
     // transfers are chained one after the other (peer-to-peer pattern) or run side by side (all-to-all)
     const bool chained = p->schedule == FICCO_SHARD ||
                          (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
-    const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, spin_ticks};
+    const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, (uint32_t *)p->h_status, spin_ticks};
     // arm the signals before any kernel that watches them can start
     for (int i = 0; i < n; ++i) {
         hsa_signal_store_relaxed(p->sig_data[i], (do_copy && !is_local(i)) ? 1 : 0);
@@ -537,7 +590,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     auto submit = [&](int q) -> int {
         const int chunk = p->arrival[q];
         if (is_local(chunk)) return FICCO_OK;
-        const int lane = (chunk / c) % links;
+        const int lane = shard_of(p, chunk) % links;
         const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[lane]);
         void *dst;
         const void *src;
@@ -599,7 +652,12 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     if (!rs) {
         // ---- GEMM side first: the kernels wait on flags, so they can be resident before data moves
         if (do_gemm) {
-            if (p->schedule == FICCO_FINE_PERSISTENT) {
+            if (is_2d(p)) {
+                if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
+                if ((rc = launch_2d(p, gate, dependent, p->resident_grid, A_dev, C_dev, cs))) return rc;
+                if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
+                ++n_launches;
+            } else if (p->schedule == FICCO_FINE_PERSISTENT) {
                 ResidentLaunch r{};
                 Group all{0, n};
                 r.g = make_launch(p, all, A_dev, C_dev);
@@ -726,10 +784,16 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
         int rc = ficco_pick_schedule(M, K, N, shards, &schedule, &chunks);
         if (rc) return rc;
     }
-    if (schedule < FICCO_SERIAL || schedule > FICCO_FINE_PERSISTENT) return FICCO_ERR_ARG;
+    if (schedule < FICCO_SERIAL || schedule > FICCO_FINE_2D) return FICCO_ERR_ARG;
     if (chunks < 1) return FICCO_ERR_SHAPE;
     if ((schedule == FICCO_SERIAL || schedule == FICCO_SHARD) && chunks != 1) return FICCO_ERR_SHAPE;
-    if ((int64_t)shards * chunks > 4096 || M % ((int64_t)shards * chunks)) return FICCO_ERR_SHAPE;
+    if ((int64_t)shards * chunks > 4096) return FICCO_ERR_SHAPE;
+    if (schedule == FICCO_FINE_2D) {
+        // column pieces: every shard keeps its rows, k is cut into `chunks` slices of whole k-tiles
+        if (M % shards || K % ((int64_t)64 * chunks)) return FICCO_ERR_SHAPE;
+    } else if (M % ((int64_t)shards * chunks)) {
+        return FICCO_ERR_SHAPE;
+    }
     if (K % 64 || N % 8) return FICCO_ERR_SHAPE;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
     ficco_plan_t *p = new (std::nothrow) ficco_plan_t();
@@ -752,6 +816,7 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
     switch (option) {
     case FICCO_OPT_DIRECTION:
         if (value != FICCO_DIR_AG_GEMM && value != FICCO_DIR_GEMM_RS) return FICCO_ERR_ARG;
+        if (value == FICCO_DIR_GEMM_RS && is_2d(p)) return FICCO_ERR_ARG;
         p->direction = (int)value;
         break;
     case FICCO_OPT_ORDER:
@@ -781,6 +846,7 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
         break;
     case FICCO_OPT_LOCAL_SHARD:
         if (value < -1 || value >= p->G) return FICCO_ERR_ARG;
+        if (value >= 0 && is_2d(p)) return FICCO_ERR_ARG;
         p->local_shard = (int)value;
         break;
     case FICCO_OPT_HOLD_FLAGS:
@@ -833,10 +899,9 @@ int ficco_plan_info(const ficco_plan_t *p, ficco_plan_info_t *out)
     o.copy_backend = p->backend;
     o.links = p->links;
     // descriptors of one launch: the resident kernel's unit of work is one piece
-    int64_t rows = p->schedule == FICCO_FINE_PERSISTENT
-                       ? p->m
-                       : (int64_t)(p->groups[0].pos_end - p->groups[0].pos_begin) * p->m;
-    ficco_static_descriptors(rows, p->N, p->K, &o.otb, &o.mt_bytes);
+    int64_t rows = is_resident(p) ? p->m
+                                  : (int64_t)(p->groups[0].pos_end - p->groups[0].pos_begin) * p->m;
+    ficco_static_descriptors(rows, p->N, is_2d(p) ? p->K / p->c : p->K, &o.otb, &o.mt_bytes);
     *out = o;
     return FICCO_OK;
 }
@@ -877,7 +942,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     if (rs) {
         if (A_src) return FICCO_ERR_ARG;
         if (do_copy && !peer_out) return FICCO_ERR_ARG;
-        if (p->schedule == FICCO_FINE_PERSISTENT || p->local_shard >= 0) return FICCO_ERR_ARG;
+        if (is_resident(p) || p->local_shard >= 0) return FICCO_ERR_ARG;
     } else {
         if (peer_out) return FICCO_ERR_ARG;
         if (do_copy && !A_src) return FICCO_ERR_ARG;
@@ -917,7 +982,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     // AUTO: engines whenever a kernel would otherwise have to be fed by copy kernels (device sources
     // and peers) or by helper kernels that need a free CU while it spins (the resident schedule)
     if (backend == FICCO_COPY_AUTO)
-        backend = (do_copy && (src_dev || any_peer_dev || (p->schedule == FICCO_FINE_PERSISTENT && dependent))) ? FICCO_COPY_ENGINES
+        backend = (do_copy && (src_dev || any_peer_dev || (is_resident(p) && dependent))) ? FICCO_COPY_ENGINES
                                                                                                            : FICCO_COPY_STREAM;
     p->backend = backend;
     if (backend == FICCO_COPY_ENGINES) {
@@ -939,7 +1004,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     const bool first = p->run_index == 0;
     p->run_index += 1;
     const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
-    const size_t row_bytes_a = (size_t)p->K * 2, row_bytes_c = (size_t)p->N * 2;
+    const size_t row_bytes_a = piece_row_bytes(p), row_bytes_c = (size_t)p->N * 2;
     const int c = p->c;
 
     // Order this run after the previous one on both streams, then start the clock on the stream
@@ -956,7 +1021,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     int64_t copy_bytes = 0;
     bool copy_first_recorded = false, gemm_first_recorded = false;
 
-    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && chunk / c == p->local_shard; };
+    auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && shard_of(p, chunk) == p->local_shard; };
 
     auto issue_copy_ag = [&](int q) -> int {
         const int chunk = p->arrival[q];
@@ -1006,43 +1071,50 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         if (do_gemm) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
     }
 
-    if (p->schedule == FICCO_FINE_PERSISTENT) {
+    if (is_resident(p)) {
         // ---- one resident kernel; transfers raise per-piece flags
         if (do_gemm) {
-            ResidentLaunch r{};
-            Group all{0, n};
-            r.g = make_launch(p, all, A_dev, C_dev);
-            r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
-            r.arrival = p->d_arrival;
-            r.n_chunks = n;
-            r.g.gate = Gate{p->d_flags, nullptr, epoch, p->d_status,
+            const Gate gate{p->d_flags, nullptr, epoch, p->d_status, (uint32_t *)p->h_status,
                             (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u};
-            r.ticket = p->d_ticket;
-            r.grid = p->resident_grid;
+            int grid = p->resident_grid;
             if (dependent && do_copy) {
                 // On this backend the 4-byte flag writes are done by a helper kernel of the HIP runtime,
                 // which needs a CU with free registers while the resident workgroups spin: leave 8 CUs'
                 // worth of slots unoccupied.
                 int cus = 0;
                 HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device));
-                const int per_cu = std::max(1, resident_grid_size(p->tile, p->device) / std::max(cus, 1));
-                r.grid = std::max(1, std::min(r.grid, per_cu * (cus - 8)));
-            }
-            if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
-            else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
-            else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
-            TileShape ts = tile_shape(p->tile);
-            for (int x = 0; x < kTicketLists; ++x) {
-                r.ticket_base[x] = p->ticket_total[x];
-                p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
-                                                                    (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+                const int full = is_2d(p) ? resident2d_grid_size(p->tile, p->device) : resident_grid_size(p->tile, p->device);
+                const int per_cu = std::max(1, full / std::max(cus, 1));
+                grid = std::max(1, std::min(grid, per_cu * (cus - 8)));
             }
             if (timing) {
                 HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
             }
             gemm_first_recorded = true;
-            HIP_TRY(launch_resident(p->tile, r, cs));
+            if (is_2d(p)) {
+                if ((rc = launch_2d(p, gate, dependent, grid, A_dev, C_dev, cs))) return rc;
+            } else {
+                ResidentLaunch r{};
+                Group all{0, n};
+                r.g = make_launch(p, all, A_dev, C_dev);
+                r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
+                r.arrival = p->d_arrival;
+                r.n_chunks = n;
+                r.g.gate = gate;
+                r.ticket = p->d_ticket;
+                r.grid = grid;
+                if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
+                else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
+                else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
+                TileShape ts = tile_shape(p->tile);
+                for (int x = 0; x < kTicketLists; ++x) {
+                    r.ticket_base[x] = p->ticket_total[x];
+                    p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
+                                                                        (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+                }
+                HIP_TRY(launch_resident(p->tile, r, cs));
+            }
             if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
             ++n_launches;
         }
@@ -1159,7 +1231,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
     if (p->last_timing) {
         double gb = 0, cb = 0;
         if (p->last_had_gemm) {
-            const size_t ng = p->schedule == FICCO_FINE_PERSISTENT ? 1 : p->groups.size();
+            const size_t ng = is_resident(p) ? 1 : p->groups.size();
             for (size_t g = 0; g < ng; ++g) {
                 HIP_TRY(hipEventElapsedTime(&ms, p->ev_gemm_b[g], p->ev_gemm_e[g]));
                 gb += ms * 1e3;
@@ -1198,9 +1270,8 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
     s.n_copies = p->last_n_copies;
     s.n_launches = p->last_n_launches;
     s.run_index = (int32_t)p->run_index;
-    if ((p->schedule == FICCO_FINE_PERSISTENT && p->last_had_gemm) || p->last_engines) {
-        uint32_t st = 0;
-        HIP_TRY(hipMemcpy(&st, p->d_status, 4, hipMemcpyDeviceToHost));
+    if ((is_resident(p) && p->last_had_gemm) || p->last_engines) {
+        const uint32_t st = p->h_status[0];     // the run has completed (event above): no copy needed
         if (st) {
             if (getenv("FICCO_DEBUG")) {
                 fprintf(stderr, "ficco: a kernel's bounded wait expired (run %u)\n", p->run_index);
@@ -1226,6 +1297,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
             }
             s.timed_out = 1;
             HIP_TRY(hipMemset(p->d_status, 0, 4));
+            p->h_status[0] = 0;
         }
     }
     *out = s;

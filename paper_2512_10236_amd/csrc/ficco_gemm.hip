@@ -78,11 +78,30 @@ struct TileCfg {
 // tile only has room for two stages; the smaller tiles use three or four, which is what keeps
 // launches with few workgroups (small pieces) from being bound by load latency.
 template <class T>
-static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__ a_tile, int rows_valid,
-                                                    const uint16_t *__restrict__ wt_tile, int cols_valid,
-                                                    uint16_t *__restrict__ c_tile, int64_t lda, int64_t ldw,
-                                                    int64_t ldc, int K, unsigned char *smem)
+struct TileAcc {
+    f32x16_t acc[T::FN][T::FM];
+};
+
+template <class T>
+static __device__ __forceinline__ void tile_zero(TileAcc<T> &ta)
 {
+#pragma unroll
+    for (int j = 0; j < T::FN; ++j)
+#pragma unroll
+        for (int i = 0; i < T::FM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ta.acc[j][i][v] = 0.f;
+}
+
+// Adds A[rows, k0 .. k0+K) * W[k0 .. k0+K, cols) to the tile's accumulators; a_tile / wt_tile point
+// at column k0 of the tile's first row of A / Wt. Calling it for consecutive k ranges in ascending
+// order gives exactly the accumulation sequence of one call over the whole range.
+template <class T>
+static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uint16_t *__restrict__ a_tile, int rows_valid,
+                                                       const uint16_t *__restrict__ wt_tile, int cols_valid,
+                                                       int64_t lda, int64_t ldw, int K, unsigned char *smem)
+{
+    f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -122,14 +141,6 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
     const int frow = lane & 31, fh = lane >> 5, fs = (lane >> 1) & 7;
     const int a_base = (wm * T::WTM + frow) * 128;
     const int b_base = T::A_STAGE + (wn * T::WTN + frow) * 128;
-
-    f32x16_t acc[T::FN][T::FM];
-#pragma unroll
-    for (int j = 0; j < T::FN; ++j)
-#pragma unroll
-        for (int i = 0; i < T::FM; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
     const int KT = K / kBK;
     constexpr int D = T::NSTAGE - 1;      // prefetch distance in k-tiles
@@ -193,6 +204,19 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
         }
     }
 
+    wg_barrier();                          // every wavefront is done with the ring before it is refilled
+}
+
+// Rounds the accumulators to bf16 (nearest even) and stores the valid part of the tile.
+template <class T>
+static __device__ __forceinline__ void tile_store(const TileAcc<T> &ta, uint16_t *__restrict__ c_tile, int rows_valid,
+                                                  int cols_valid, int64_t ldc)
+{
+    const f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const int frow = lane & 31, fh = lane >> 5;
     // ---- epilogue: acc[j][i][v] is C[m][n] with m = wm*WTM + 32 i + lane%32,
     //      n = wn*WTN + 32 j + 8 (v/4) + 4 (lane/32) + v%4
 #pragma unroll
@@ -216,6 +240,18 @@ static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__
     }
 }
 
+template <class T>
+static __device__ __forceinline__ void compute_tile(const uint16_t *__restrict__ a_tile, int rows_valid,
+                                                    const uint16_t *__restrict__ wt_tile, int cols_valid,
+                                                    uint16_t *__restrict__ c_tile, int64_t lda, int64_t ldw,
+                                                    int64_t ldc, int K, unsigned char *smem)
+{
+    TileAcc<T> ta;
+    tile_zero(ta);
+    tile_accumulate<T>(ta, a_tile, rows_valid, wt_tile, cols_valid, lda, ldw, K, smem);
+    tile_store<T>(ta, c_tile, rows_valid, cols_valid, ldc);
+}
+
 // Bounded wait of one thread until a piece is ready (see Gate). Reads at system scope (past the
 // caches): the writer is a copy engine. Returns 0 when the limit expires or another workgroup has
 // already given up; the caller then skips its work, so every wave still reaches its exit.
@@ -233,6 +269,7 @@ static __device__ __forceinline__ int wait_ready(const Gate &g, int chunk)
         if (__hip_atomic_load(g.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) return 0;
         if (wall_clock64() - t0 > g.spin_limit_ticks) {
             __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(g.status_host, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             return 0;
         }
         __builtin_amdgcn_s_sleep(8);
@@ -340,6 +377,65 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     }
 }
 
+// Column-piece variant of the resident kernel (the 2D communication shape of Sec. V-A, chosen when
+// M <= K): step s delivers K-slice s of every shard, and every tile of C can make progress at every
+// step. The accumulation order over k is that of the monolithic kernel, so the bits are the same.
+template <class T>
+__global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __shared__ int s_tile;
+    __shared__ int s_ok;
+    const GemmLaunch &a = r.g;
+    const int tiles_n = (a.N + T::BN - 1) / T::BN;
+    const int row_tiles = (r.M + T::BM - 1) / T::BM;
+    constexpr int GROUP = 2;
+
+    for (int turn = 0; turn < kTicketLists; ++turn) {
+        const int x = (blockIdx.x + turn) % kTicketLists;
+        const int my_rows = row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0;
+        const int total = my_rows * tiles_n;
+        for (;;) {
+            if (threadIdx.x == 0) s_tile = (int)(atomicAdd(r.ticket + x * kFlagStrideWords, 1u) - r.ticket_base[x]);
+            __syncthreads();
+            const int t = s_tile;
+            if (t >= total) break;
+            const int per_group = GROUP * tiles_n;
+            const int g = t / per_group, first = g * GROUP;
+            const int gsz = min(my_rows - first, GROUP);
+            const int rl = first + (t % per_group) % gsz, tn = (t % per_group) / gsz;
+            const int tm = rl * kTicketLists + x;
+            const int64_t row0 = (int64_t)tm * T::BM;
+            const int rows_valid = min(T::BM, r.M - (int)row0);
+            const int col0 = tn * T::BN;
+            const int cols_valid = min(T::BN, a.N - col0);
+            const int j0 = (int)(row0 / r.rows_per_shard), j1 = (int)((row0 + rows_valid - 1) / r.rows_per_shard);
+            TileAcc<T> ta;
+            tile_zero(ta);
+            int ok = 1;
+            for (int sl = 0; sl < r.slices && ok; ++sl) {
+                if (r.gated) {
+                    if (threadIdx.x == 0) {
+                        int o = 1;
+                        for (int j = j0; j <= j1 && o; ++j) o = wait_ready(a.gate, sl * r.shards + j);
+                        s_ok = o;
+                    }
+                    __syncthreads();       // also orders the slice's loads after the flag reads
+                    ok = s_ok;
+                    __syncthreads();
+                }
+                if (ok)
+                    tile_accumulate<T>(ta, a.A + ((int64_t)sl * r.M + row0) * r.k_per_slice, rows_valid,
+                                       a.Wt + (int64_t)col0 * a.K + (int64_t)sl * r.k_per_slice, cols_valid,
+                                       r.k_per_slice, a.K, r.k_per_slice, smem);
+            }
+            if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
+            __syncthreads();
+        }
+        __syncthreads();
+    }
+}
+
 __global__ __launch_bounds__(64) void wait_ready_kernel(Gate gate, const int32_t *chunks, int n)
 {
     if (threadIdx.x == 0)
@@ -417,6 +513,27 @@ static hipError_t launch_resident_t(const ResidentLaunch &r, hipStream_t s)
 }
 
 template <class T>
+static hipError_t launch_resident2d_t(const Resident2DLaunch &r, hipStream_t s)
+{
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
+    if (once != hipSuccess) return once;
+    if (r.grid <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gemm_resident2d_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    return hipGetLastError();
+}
+
+template <class T>
+static int resident2d_grid_t(int device)
+{
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
+    (void)once;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident2d_kernel<T>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
+template <class T>
 static int resident_grid_t(int device)
 {
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T>));
@@ -452,6 +569,34 @@ hipError_t launch_resident(int tile, const ResidentLaunch &r, hipStream_t s)
     case TILE_32x256:  return launch_resident_t<T32x256>(r, s);
     case TILE_128x128D: return launch_resident_t<T128x128D>(r, s);
     default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_resident2d(int tile, const Resident2DLaunch &r, hipStream_t s)
+{
+    switch (tile) {
+    case TILE_256x256: return launch_resident2d_t<T256x256>(r, s);
+    case TILE_128x128: return launch_resident2d_t<T128x128>(r, s);
+    case TILE_256x128: return launch_resident2d_t<T256x128>(r, s);
+    case TILE_128x256: return launch_resident2d_t<T128x256>(r, s);
+    case TILE_64x256:  return launch_resident2d_t<T64x256>(r, s);
+    case TILE_32x256:  return launch_resident2d_t<T32x256>(r, s);
+    case TILE_128x128D: return launch_resident2d_t<T128x128D>(r, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+int resident2d_grid_size(int tile, int device)
+{
+    switch (tile) {
+    case TILE_256x256: return resident2d_grid_t<T256x256>(device);
+    case TILE_128x128: return resident2d_grid_t<T128x128>(device);
+    case TILE_256x128: return resident2d_grid_t<T256x128>(device);
+    case TILE_128x256: return resident2d_grid_t<T128x256>(device);
+    case TILE_64x256:  return resident2d_grid_t<T64x256>(device);
+    case TILE_32x256:  return resident2d_grid_t<T32x256>(device);
+    case TILE_128x128D: return resident2d_grid_t<T128x128D>(device);
+    default: return 0;
     }
 }
 

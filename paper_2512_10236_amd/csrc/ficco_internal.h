@@ -33,7 +33,8 @@ struct Gate {
     const uint32_t *flags;
     const uint64_t *sig_value;    // device table of addresses, or nullptr to use flags
     uint32_t epoch;
-    uint32_t *status;
+    uint32_t *status;             // device word every waiting workgroup watches
+    uint32_t *status_host;        // pinned host word set together with it, so that the host needs no copy to see it
     uint64_t spin_limit_ticks;    // in wall_clock64() ticks
 };
 
@@ -68,7 +69,22 @@ struct ResidentLaunch {
     int32_t local_chunk_begin, local_chunk_end;   // chunk ids that need no flag (already resident), or empty
 };
 
+// The resident kernel for column (K) pieces: A is kept in K-sliced layout [slices][M][K/slices]; piece
+// s*shards + j is slice s of shard j (rows [j*rows_per_shard, (j+1)*rows_per_shard)). A workgroup owns
+// one tile of C for all of K, keeps its accumulators in registers, and before each slice waits for
+// the pieces that cover its rows.
+struct Resident2DLaunch {
+    GemmLaunch g;                 // A = K-sliced base, Wt, C, ldc, N, K (whole), gate; other fields unused
+    int32_t M, slices, shards, rows_per_shard, k_per_slice;
+    uint32_t *ticket;
+    uint32_t ticket_base[8];
+    int32_t grid;
+    int32_t gated;                // 0: operands resident, no waiting
+};
+
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s);
+hipError_t launch_resident2d(int tile, const Resident2DLaunch &a, hipStream_t s);
+int resident2d_grid_size(int tile, int device);
 hipError_t launch_resident(int tile, const ResidentLaunch &a, hipStream_t s);
 // One wavefront that waits (bounded) until the pieces chunks[0..n) are ready; used to join the
 // compute stream with copy-engine transfers when no GEMM consumes them.

@@ -45,6 +45,8 @@ def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, 
     M, K = A.shape
     N = W.shape[1]
     G = len(shards)
+    if schedule == ficco.FICCO_FINE_2D:
+        A = fi.to_k_sliced(A, c).reshape(M, K)         # same bytes, column pieces contiguous
     A_src = as_i16(A).pin_memory() if src == "pinned" else as_i16(A).to(dev)
     W_dev = as_i16(W).to(dev)
     A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)     # poison: unread rows show up as NaN
@@ -374,3 +376,73 @@ def test_engines_bounded_wait_in_per_launch_kernels(gpu):
     bits, st2, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_FUSED, 4, src="device")
     assert st2.timed_out == 0
     check(bits, og.ag_gemm(shards, W))
+
+
+# ------------------------------------------------------------------------------------------------
+# 2D decomposition: column pieces, one resident kernel accumulating slice by slice
+def test_2d_matches_oracle_and_serial_bits(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    A = np.concatenate(shards, 0)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    for c in (1, 2, 4, 16):
+        ref = og.ag_gemm_2d(fi.to_k_sliced(A, c), W, len(shards))
+        for src, opts in [("pinned", [(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_STREAM)]),
+                          ("pinned", [(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_ENGINES)]),
+                          ("device", [(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)]),
+                          ("device", [(ficco.FICCO_OPT_FLAG_WRITE, 2)]),
+                          ("device", [])]:
+            bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src=src, opts=opts, runs=2)
+            check(bits, ref, f"2D c={c} {src} {opts}")
+            assert np.array_equal(bits, base), f"2D c={c} {src} {opts}: differs bitwise from serial"
+            assert st.n_copies == 4 * c and st.copy_bytes == 512 * 1024 * 2 and st.n_launches == 1
+            assert info.n_groups == 1 and info.chunk_rows == 128
+
+
+@pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
+                                  ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256,
+                                  ficco.FICCO_TILE_128x128_DEEP])
+def test_2d_every_tile_shape_ragged(gpu, tile):
+    # 3 shards of 88 rows (tiles straddle shards), N = 328, K = 3 slices of 128
+    G, ms, K, N, c = 3, 88, 384, 328, 3
+    shards = fi.make_shards(23, G * ms, K, G)
+    W = fi.make_weight(23, K, N)
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, opts=[(ficco.FICCO_OPT_TILE, tile)])
+    bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", opts=[(ficco.FICCO_OPT_TILE, tile)])
+    check(bits, ref, f"2D tile {tile}")
+    assert np.array_equal(bits, base)
+
+
+def test_2d_waits_for_late_and_reordered_slices(gpu):
+    G, ms, K, N, c = 4, 256, 1024, 512, 4
+    shards = fi.make_shards(24, G * ms, K, G)
+    W = fi.make_weight(24, K, N)
+    ref = og.ag_gemm(shards, W)
+    rev = list(range(G * c - 1, -1, -1))                  # last slice lands first: tiles must still wait for slice 0
+    bits_rev, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", arrival=rev)
+    check(bits_rev, ref, "2D reversed arrival")
+    bits_late, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, delay_copy=True,
+                             opts=[(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_STREAM)])
+    check(bits_late, ref, "2D delayed transfers")
+    assert np.array_equal(bits_rev, bits_late)
+
+
+def test_2d_timeout_is_reported_not_hung(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    # flags are never raised: every waiting tile must give up after the spin limit and the run must end
+    _, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, 2, src="device",
+                      opts=[(ficco.FICCO_OPT_HOLD_FLAGS, 1), (ficco.FICCO_OPT_SPIN_LIMIT_US, 2000)], allow_timeout=True)
+    assert st.timed_out == 1
+
+
+def test_cfg5_2d_full_size_sampled_rows(gpu):
+    cfg = fi.CONFIGS["cfg5_2d_proj"]
+    shards, W = fi.config_inputs("cfg5_2d_proj")
+    rows = np.unique(np.concatenate([np.arange(0, cfg["M"], 331), [0, 255, 256, 511, 512, cfg["M"] - 1]]))
+    ref = og.ag_gemm_rows(shards, W, rows)
+    base, st0, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
+    check(base[rows], ref, "cfg5 serial")
+    for c in cfg["k_slices"]:
+        bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", runs=2)
+        check(bits[rows], ref, f"cfg5 2D c={c}")
+        assert np.array_equal(bits, base), f"cfg5 2D c={c} differs bitwise from serial"

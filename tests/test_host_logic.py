@@ -57,6 +57,27 @@ def test_plan_lists_match_oracle(G, c, lib_s, ora_s, order):
     assert info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
 
 
+@pytest.mark.parametrize("G,c", [(4, 1), (4, 4), (8, 2), (3, 5)])
+@pytest.mark.parametrize("order", [ficco.FICCO_ORDER_STEP_MAJOR, ficco.FICCO_ORDER_SHARD_MAJOR])
+def test_2d_plan_lists_match_oracle(G, c, order):
+    M, K = G * 16, 64 * c
+    plan = ficco.ficco_plan(M, K, 8, G, c, ficco.FICCO_FINE_2D)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_ORDER, order)
+        arrival, group_ids = ficco.ficco_plan_arrival(plan)
+        info = ficco.ficco_plan_info(plan)
+        for opt, val in [(ficco.FICCO_OPT_LOCAL_SHARD, 1), (ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)]:
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_plan_set(plan, opt, val)
+    finally:
+        ficco.ficco_destroy(plan)
+    ref = sch.plan(M, G, c, sch.FINE_2D, order)
+    assert arrival == ref["arrival"] and set(group_ids) == {0}
+    assert info.n_groups == 1 and info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
+    # descriptors of one column piece: an (M/G, N, K/c) GEMM
+    assert info.mt_bytes == sch.mt_bytes(M // G, 8, K // c)
+
+
 def test_custom_arrival_and_local_shard():
     plan = ficco.ficco_plan(512, 64, 8, 4, 4, ficco.FICCO_FINE_FUSED)
     try:
@@ -87,6 +108,7 @@ def test_custom_arrival_and_local_shard():
     (512, 96, 8, 4, 1, 0), (512, 64, 12, 4, 1, 0),                          # K % 64, N % 8
     (512, 64, 8, 4, 2, 0), (512, 64, 8, 4, 2, 1),                           # pieces with serial / shard
     (1 << 20, 64, 8, 8192, 1, 2),                                           # too many pieces
+    (512, 192, 8, 4, 2, 5), (510, 128, 8, 4, 2, 5),                         # 2D: slices of whole k-tiles, M % shards
 ])
 def test_shape_rules(args):
     with pytest.raises(ficco.FiccoError) as e:
@@ -96,7 +118,7 @@ def test_shape_rules(args):
 
 def test_argument_errors():
     with pytest.raises(ficco.FiccoError) as e:
-        ficco.ficco_plan(512, 64, 8, 4, 1, 7)
+        ficco.ficco_plan(512, 64, 8, 4, 1, 9)
     assert e.value.status == ficco.FICCO_ERR_ARG
     plan = ficco.ficco_plan(512, 64, 8, 4, 1, ficco.FICCO_SHARD)
     try:

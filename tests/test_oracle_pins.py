@@ -177,3 +177,51 @@ def test_bf16_rounding_is_nearest_even():
     assert fi.f32_to_bf16_bits(np.float32(1.0 + 2.0 ** -8)) == 0x3F80
     assert fi.f32_to_bf16_bits(np.float32(1.0 + 3 * 2.0 ** -8)) == 0x3F82
     assert fi.f32_to_bf16_bits(np.float32(1.0 + 2.0 ** -8 + 2.0 ** -20)) == 0x3F81
+
+
+# ------------------------------------------------------------------ 2D decomposition (Sec. V-A/B)
+def test_k_sliced_layout_is_a_column_partition():
+    A = np.arange(6 * 8, dtype=np.uint16).reshape(6, 8)
+    S = fi.to_k_sliced(A, 4)
+    assert S.shape == (4, 6, 2)
+    for s in range(4):
+        assert np.array_equal(S[s], A[:, 2 * s:2 * s + 2])
+    assert np.array_equal(fi.to_k_sliced(A, 1)[0], A)
+
+
+@pytest.mark.parametrize("G,ms,K,N,c,seed", [(2, 2, 8, 3, 2, 0), (4, 1, 12, 5, 3, 1), (1, 3, 4, 2, 4, 2)])
+def test_2d_steps_exact_rational_brute_force(G, ms, K, N, c, seed):
+    """Small-integer inputs: every partial sum is an integer far below 2^53, so accumulating slice
+    by slice is exact and must equal the rational row-times-column sums of the unsliced matrix."""
+    rng = np.random.default_rng(seed)
+    A = bits_of(rng.integers(-8, 9, size=(G * ms, K)).astype(np.float32))
+    W = bits_of(rng.integers(-8, 9, size=(K, N)).astype(np.float32))
+    out = og.ag_gemm_2d(fi.to_k_sliced(A, c), W, G)
+    for i in range(G * ms):
+        for j in range(N):
+            s = sum(Fraction(float(widen(A[i, k]))) * Fraction(float(widen(W[k, j]))) for k in range(K))
+            assert Fraction(float(out[i, j])) == s, (i, j)
+
+
+def test_2d_steps_pick_the_matching_weight_rows():
+    """A = [1 0 ... | 0 ... 1 ...]: one 1 per row in a known column; the result row must be that row
+    of W. A slice paired with the wrong rows of W, or a transposed slice, fails."""
+    K, N, M, G, c = 16, 5, 8, 4, 4
+    W = fi.make_weight(7, K, N)
+    cols = [(5 * i + 3) % K for i in range(M)]
+    A = np.zeros((M, K), dtype=np.float32)
+    A[np.arange(M), cols] = 1.0
+    out = og.ag_gemm_2d(fi.to_k_sliced(bits_of(A), c), W, G)
+    assert np.array_equal(out, widen(W)[cols])
+
+
+def test_2d_steps_equal_whole_product_on_random_inputs():
+    G, M, K, N, c = 4, 64, 256, 24, 4
+    shards = fi.make_shards(11, M, K, G)
+    W = fi.make_weight(11, K, N)
+    A = np.concatenate(shards, 0)
+    whole = og.ag_gemm(shards, W)
+    steps = og.ag_gemm_2d(fi.to_k_sliced(A, c), W, G)
+    # same terms, another association of the fp64 sums
+    assert np.max(np.abs(whole - steps)) <= 1e-12 * K
+    assert np.array_equal(og.ag_gemm_2d(fi.to_k_sliced(A, 1), W, G), whole)

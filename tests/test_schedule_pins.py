@@ -112,3 +112,28 @@ def test_heuristic_rule_structure():
     assert sch.heuristic_paper(M, N, K, 8, x / 2) == "hetero-fused-1D"
     assert sch.heuristic_paper(M, N, K, 8, x / 5.01) == "hetero-unfused-1D"
     assert sch.heuristic_paper(M, N, K, 8, x / 2, ratio=1.5) == "hetero-unfused-1D"
+
+
+@pytest.mark.parametrize("G,c", [(4, 1), (4, 4), (8, 2), (3, 5)])
+def test_column_pieces_tile_the_activation(G, c):
+    # Sec. V-A in words: the 2D decomposition cuts every shard along k; step s moves slice s of each shard
+    M, K = G * 6, c * 10
+    cover = [[0] * K for _ in range(M)]
+    for i in range(G * c):
+        r0, nr, k0, nk = sch.piece_span_2d(M, K, G, c, i)
+        assert nr == M // G and nk == K // c
+        for r in range(r0, r0 + nr):
+            for k in range(k0, k0 + nk):
+                cover[r][k] += 1
+    assert all(v == 1 for row in cover for v in row)
+    arr = sch.arrival_order_2d(G, c, sch.ORDER_STEP_MAJOR)
+    for s in range(c):
+        step = arr[s * G:(s + 1) * G]
+        spans = [sch.piece_span_2d(M, K, G, c, i) for i in step]
+        assert [sp[2] for sp in spans] == [s * (K // c)] * G           # one k slice per step ...
+        assert [sp[0] for sp in spans] == [j * (M // G) for j in range(G)]   # ... from every shard
+    by_shard = sch.arrival_order_2d(G, c, sch.ORDER_SHARD_MAJOR)
+    assert sorted(by_shard) == list(range(G * c))
+    assert [sch.piece_span_2d(M, K, G, c, i)[0] for i in by_shard] == [j * (M // G) for j in range(G) for _ in range(c)]
+    p = sch.plan(M, G, c, sch.FINE_2D)
+    assert p["arrival"] == arr and p["groups"] == [arr] and p["m"] == M // G and p["n_chunks"] == G * c
