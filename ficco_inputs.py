@@ -110,7 +110,7 @@ CONFIGS = {
                          direction="gemm_rs"),
     # M <= K share (row-parallel projection at a small token count): the shape the paper's rule sends
     # to the 2D decomposition; ``k_slices`` lists the slice counts exercised
-    "cfg5_2d_proj": dict(M=4096, K=16384, N=4096, shards=8, chunk_rows=[512, 256, 128], k_slices=[2, 4, 8], seed=5,
+    "cfg6_2d_proj": dict(M=4096, K=16384, N=4096, shards=8, chunk_rows=[512, 256, 128], k_slices=[2, 4, 8], seed=5,
                          direction="ag_gemm"),
 }
 

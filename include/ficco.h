@@ -147,8 +147,10 @@ typedef enum ficco_tile {        /* workgroup tile (rows x columns of C); the k 
     FICCO_TILE_128x256 = 4,
     FICCO_TILE_64x256  = 5,      /* for pieces of fewer than 128 rows */
     FICCO_TILE_32x256  = 6,      /* for pieces of fewer than 64 rows  */
-    FICCO_TILE_128x128_DEEP = 7  /* 128x128 with a four-stage LDS ring, one workgroup per CU: for launches
+    FICCO_TILE_128x128_DEEP = 7, /* 128x128 with a four-stage LDS ring, one workgroup per CU: for launches
                                     that do not fill the machine */
+    FICCO_TILE_128x192 = 8,      /* for N a multiple of 192 but not of 256 (e.g. 768) */
+    FICCO_TILE_256x192 = 9
 } ficco_tile;
 
 typedef struct ficco_plan_info {

@@ -23,7 +23,8 @@ FICCO_MODE_PAIR, FICCO_MODE_GEMM_ONLY, FICCO_MODE_COPY_ONLY, FICCO_MODE_INDEPEND
  FICCO_OPT_COPY_BACKEND, FICCO_OPT_LINKS) = range(11)
 FICCO_COPY_AUTO, FICCO_COPY_STREAM, FICCO_COPY_ENGINES = 0, 1, 2
 (FICCO_TILE_AUTO, FICCO_TILE_256x256, FICCO_TILE_128x128, FICCO_TILE_256x128, FICCO_TILE_128x256,
- FICCO_TILE_64x256, FICCO_TILE_32x256, FICCO_TILE_128x128_DEEP) = range(8)
+ FICCO_TILE_64x256, FICCO_TILE_32x256, FICCO_TILE_128x128_DEEP, FICCO_TILE_128x192,
+ FICCO_TILE_256x192) = range(10)
 
 SCHEDULE_NAMES = {FICCO_SERIAL: "serial", FICCO_SHARD: "shard", FICCO_FINE_UNFUSED: "fine_unfused",
                   FICCO_FINE_FUSED: "fine_fused", FICCO_FINE_PERSISTENT: "fine_persistent",

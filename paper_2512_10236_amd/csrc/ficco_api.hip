@@ -242,6 +242,7 @@ int choose_tile(const ficco_plan_t *p, int cus)
         {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.80, 0.35, 1}, {TILE_256x128, 0.80, 0.40, 1},
         {TILE_128x128, 0.60, 0.50, 2}, {TILE_128x128D, 0.48, 0.08, 1},
         {TILE_64x256, 0.57, 0.15, 1},  {TILE_32x256, 0.45, 0.05, 1},
+        {TILE_128x192, 0.72, 0.24, 1}, {TILE_256x192, 1.10, 0.50, 1},
     };
     double best = 1e300;
     int best_id = TILE_128x128;

@@ -468,17 +468,21 @@ typedef TileCfg<256, 128, 2, 2, 3> T256x128;
 typedef TileCfg<128, 256, 2, 2, 3> T128x256;
 typedef TileCfg<64, 256, 1, 4, 3> T64x256;
 typedef TileCfg<32, 256, 1, 4, 4> T32x256;
+typedef TileCfg<128, 192, 2, 2, 3> T128x192;       // column counts that are multiples of 192 but not of 256
+typedef TileCfg<256, 192, 2, 2, 2> T256x192;
+
+// every tile shape, for the dispatch switches below
+#define FICCO_FOR_EACH_TILE(X) \
+    X(TILE_256x256, T256x256) X(TILE_128x128, T128x128) X(TILE_256x128, T256x128) X(TILE_128x256, T128x256) \
+    X(TILE_64x256, T64x256) X(TILE_32x256, T32x256) X(TILE_128x128D, T128x128D) X(TILE_128x192, T128x192) \
+    X(TILE_256x192, T256x192)
 
 TileShape tile_shape(int tile)
 {
     switch (tile) {
-    case TILE_256x256: return {256, 256, T256x256::LDS_BYTES, 256};
-    case TILE_128x128: return {128, 128, T128x128::LDS_BYTES, 256};
-    case TILE_256x128: return {256, 128, T256x128::LDS_BYTES, 256};
-    case TILE_128x256: return {128, 256, T128x256::LDS_BYTES, 256};
-    case TILE_64x256:  return {64, 256, T64x256::LDS_BYTES, 256};
-    case TILE_32x256:  return {32, 256, T32x256::LDS_BYTES, 256};
-    case TILE_128x128D: return {128, 128, T128x128D::LDS_BYTES, 256};
+#define X(id, T) case id: return {T::BM, T::BN, T::LDS_BYTES, 256};
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return {0, 0, 0, 0};
     }
 }
@@ -547,13 +551,9 @@ static int resident_grid_t(int device)
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s)
 {
     switch (tile) {
-    case TILE_256x256: return launch_gemm_t<T256x256>(a, s);
-    case TILE_128x128: return launch_gemm_t<T128x128>(a, s);
-    case TILE_256x128: return launch_gemm_t<T256x128>(a, s);
-    case TILE_128x256: return launch_gemm_t<T128x256>(a, s);
-    case TILE_64x256:  return launch_gemm_t<T64x256>(a, s);
-    case TILE_32x256:  return launch_gemm_t<T32x256>(a, s);
-    case TILE_128x128D: return launch_gemm_t<T128x128D>(a, s);
+#define X(id, T) case id: return launch_gemm_t<T>(a, s);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return hipErrorInvalidValue;
     }
 }
@@ -561,13 +561,9 @@ hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s)
 hipError_t launch_resident(int tile, const ResidentLaunch &r, hipStream_t s)
 {
     switch (tile) {
-    case TILE_256x256: return launch_resident_t<T256x256>(r, s);
-    case TILE_128x128: return launch_resident_t<T128x128>(r, s);
-    case TILE_256x128: return launch_resident_t<T256x128>(r, s);
-    case TILE_128x256: return launch_resident_t<T128x256>(r, s);
-    case TILE_64x256:  return launch_resident_t<T64x256>(r, s);
-    case TILE_32x256:  return launch_resident_t<T32x256>(r, s);
-    case TILE_128x128D: return launch_resident_t<T128x128D>(r, s);
+#define X(id, T) case id: return launch_resident_t<T>(r, s);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return hipErrorInvalidValue;
     }
 }
@@ -575,13 +571,9 @@ hipError_t launch_resident(int tile, const ResidentLaunch &r, hipStream_t s)
 hipError_t launch_resident2d(int tile, const Resident2DLaunch &r, hipStream_t s)
 {
     switch (tile) {
-    case TILE_256x256: return launch_resident2d_t<T256x256>(r, s);
-    case TILE_128x128: return launch_resident2d_t<T128x128>(r, s);
-    case TILE_256x128: return launch_resident2d_t<T256x128>(r, s);
-    case TILE_128x256: return launch_resident2d_t<T128x256>(r, s);
-    case TILE_64x256:  return launch_resident2d_t<T64x256>(r, s);
-    case TILE_32x256:  return launch_resident2d_t<T32x256>(r, s);
-    case TILE_128x128D: return launch_resident2d_t<T128x128D>(r, s);
+#define X(id, T) case id: return launch_resident2d_t<T>(r, s);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return hipErrorInvalidValue;
     }
 }
@@ -589,13 +581,9 @@ hipError_t launch_resident2d(int tile, const Resident2DLaunch &r, hipStream_t s)
 int resident2d_grid_size(int tile, int device)
 {
     switch (tile) {
-    case TILE_256x256: return resident2d_grid_t<T256x256>(device);
-    case TILE_128x128: return resident2d_grid_t<T128x128>(device);
-    case TILE_256x128: return resident2d_grid_t<T256x128>(device);
-    case TILE_128x256: return resident2d_grid_t<T128x256>(device);
-    case TILE_64x256:  return resident2d_grid_t<T64x256>(device);
-    case TILE_32x256:  return resident2d_grid_t<T32x256>(device);
-    case TILE_128x128D: return resident2d_grid_t<T128x128D>(device);
+#define X(id, T) case id: return resident2d_grid_t<T>(device);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return 0;
     }
 }
@@ -603,13 +591,9 @@ int resident2d_grid_size(int tile, int device)
 int resident_grid_size(int tile, int device)
 {
     switch (tile) {
-    case TILE_256x256: return resident_grid_t<T256x256>(device);
-    case TILE_128x128: return resident_grid_t<T128x128>(device);
-    case TILE_256x128: return resident_grid_t<T256x128>(device);
-    case TILE_128x256: return resident_grid_t<T128x256>(device);
-    case TILE_64x256:  return resident_grid_t<T64x256>(device);
-    case TILE_32x256:  return resident_grid_t<T32x256>(device);
-    case TILE_128x128D: return resident_grid_t<T128x128D>(device);
+#define X(id, T) case id: return resident_grid_t<T>(device);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
     default: return 0;
     }
 }

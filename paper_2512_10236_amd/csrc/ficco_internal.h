@@ -8,7 +8,7 @@ namespace ficco {
 // Workgroup tile shapes. The k order (ascending, 16 at a time inside one 32x32x16 MFMA) is the
 // same in all of them, so the output bits do not depend on the choice.
 enum TileId : int { TILE_256x256 = 1, TILE_128x128 = 2, TILE_256x128 = 3, TILE_128x256 = 4,
-                    TILE_64x256 = 5, TILE_32x256 = 6, TILE_128x128D = 7, TILE_COUNT = 8 };
+                    TILE_64x256 = 5, TILE_32x256 = 6, TILE_128x128D = 7, TILE_128x192 = 8, TILE_256x192 = 9, TILE_COUNT = 10 };
 
 struct TileShape { int bm, bn, lds_bytes, threads; };
 TileShape tile_shape(int tile);

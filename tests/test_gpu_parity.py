@@ -100,7 +100,7 @@ def test_cfg1_all_schedules_match_oracle_and_each_other(gpu):
 
 @pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
                                   ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256,
-                                  ficco.FICCO_TILE_128x128_DEEP])
+                                  ficco.FICCO_TILE_128x128_DEEP, ficco.FICCO_TILE_128x192, ficco.FICCO_TILE_256x192])
 def test_every_tile_shape_ragged(gpu, tile):
     # 3 shards x 2 pieces of 88 rows (no tile height divides it), N = 328 (not a tile width), K = 192
     G, c, m, K, N = 3, 2, 88, 192, 328
@@ -400,7 +400,7 @@ def test_2d_matches_oracle_and_serial_bits(gpu):
 
 @pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
                                   ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256,
-                                  ficco.FICCO_TILE_128x128_DEEP])
+                                  ficco.FICCO_TILE_128x128_DEEP, ficco.FICCO_TILE_128x192, ficco.FICCO_TILE_256x192])
 def test_2d_every_tile_shape_ragged(gpu, tile):
     # 3 shards of 88 rows (tiles straddle shards), N = 328, K = 3 slices of 128
     G, ms, K, N, c = 3, 88, 384, 328, 3
@@ -435,14 +435,14 @@ def test_2d_timeout_is_reported_not_hung(gpu):
     assert st.timed_out == 1
 
 
-def test_cfg5_2d_full_size_sampled_rows(gpu):
-    cfg = fi.CONFIGS["cfg5_2d_proj"]
-    shards, W = fi.config_inputs("cfg5_2d_proj")
+def test_cfg6_2d_full_size_sampled_rows(gpu):
+    cfg = fi.CONFIGS["cfg6_2d_proj"]
+    shards, W = fi.config_inputs("cfg6_2d_proj")
     rows = np.unique(np.concatenate([np.arange(0, cfg["M"], 331), [0, 255, 256, 511, 512, cfg["M"] - 1]]))
     ref = og.ag_gemm_rows(shards, W, rows)
     base, st0, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
-    check(base[rows], ref, "cfg5 serial")
+    check(base[rows], ref, "cfg6 serial")
     for c in cfg["k_slices"]:
         bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", runs=2)
-        check(bits[rows], ref, f"cfg5 2D c={c}")
-        assert np.array_equal(bits, base), f"cfg5 2D c={c} differs bitwise from serial"
+        check(bits[rows], ref, f"cfg6 2D c={c}")
+        assert np.array_equal(bits, base), f"cfg6 2D c={c} differs bitwise from serial"
