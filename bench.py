@@ -34,12 +34,14 @@ HBM_PEAK_GBPS = 8000.0
 # HBM-side traffic per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # summaries kept under profiles/ (gemm_isolated_<workload>.md): KiB per dispatch as the counters
 # read, and the factors by which a 256 MiB device copy's true traffic exceeds what they read for it.
-PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131089.7, "WRITE_SIZE": 262144.0 / 262144.0}
+PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131090.5, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
-    ("cfg2_qkv8b", "gemm_resident_kernel<128x128>"): {"FETCH_SIZE": 156905.0, "WRITE_SIZE": 12317.5},
-    ("cfg2_qkv8b", "gemm_blocks_kernel<128x128>"): {"FETCH_SIZE": 69493.6, "WRITE_SIZE": 12289.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1094099.6, "WRITE_SIZE": 115515.5},
-    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754123.9, "WRITE_SIZE": 114884.7},
+    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57452.7, "WRITE_SIZE": 12362.4},
+    ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57452.0, "WRITE_SIZE": 12288.0},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1085005.7, "WRITE_SIZE": 117537.1},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754151.5, "WRITE_SIZE": 114753.3},
+    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 878411.3, "WRITE_SIZE": 32851.9},
+    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 523875.9, "WRITE_SIZE": 32894.0},
 }
 
 
@@ -207,29 +209,31 @@ def main() -> int:
             s, c = F.ficco_pick_schedule(M, K, N, G)
         if rs and s == F.FICCO_FINE_PERSISTENT:
             s = F.FICCO_FINE_FUSED
-        plan = make(s, c, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
-        busy, launches = [], 0
-        A_res = source("hbm", s, c)                     # operands resident in the layout the plan reads
-        for it in range(args.warmup + args.steps):
-            F.ficco_run(plan, None, A_res, W_dev, C_dev, None, cs, xs)
+        def launch_time(sched, chunks, A_res):
+            """Average duration of the plan's GEMM launches, operands resident: `steps` runs enqueued back
+            to back on the compute stream between two HIP events recorded on that stream (the gaps
+            between consecutive launches are inside the bracket)."""
+            plan = make(sched, chunks, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY)])
+            for _ in range(args.warmup):
+                F.ficco_run(plan, None, A_res, W_dev, C_dev, None, cs, xs)
             st = F.ficco_query_stats(plan)
-            if it >= args.warmup:
-                busy.append(st.gemm_busy_us)
-                launches = st.n_launches
-        info = F.ficco_plan_info(plan)
-        F.ficco_destroy(plan)
-        us_step = float(np.mean(busy))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(cs)
+            for _ in range(args.steps):
+                F.ficco_run(plan, None, A_res, W_dev, C_dev, None, cs, xs)
+            e1.record(cs)
+            torch.cuda.synchronize()
+            F.ficco_query_stats(plan)
+            info = F.ficco_plan_info(plan)
+            F.ficco_destroy(plan)
+            return e0.elapsed_time(e1) * 1e3 / args.steps, st.n_launches, info
+
+        us_step, launches, info = launch_time(s, c, source("hbm", s, c))   # operands in the layout the plan reads
         achieved = flops / us_step * 1e-6
         # the monolithic GEMM of the same shape, for reference
-        plan = make(F.FICCO_SERIAL, 1, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY), (F.FICCO_OPT_TIMING, 1)])
-        whole = []
-        for it in range(args.warmup + args.steps):
-            F.ficco_run(plan, None, A_stage, W_dev, C_dev, None, cs, xs)
-            st = F.ficco_query_stats(plan)
-            if it >= args.warmup:
-                whole.append(st.gemm_busy_us)
-        winfo = F.ficco_plan_info(plan)
-        F.ficco_destroy(plan)
+        whole_us, _, winfo = launch_time(F.FICCO_SERIAL, 1, A_stage)
+        whole = [whole_us]
         kname = {F.FICCO_FINE_PERSISTENT: "gemm_resident_kernel", F.FICCO_FINE_2D: "gemm_resident2d_kernel"}.get(s, "gemm_blocks_kernel") \
             + f"<{info.tile_m}x{info.tile_n}>"
         pmc = PMC_KIB.get((args.workload, kname)) if launches == 1 else None

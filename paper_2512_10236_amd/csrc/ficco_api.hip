@@ -145,6 +145,7 @@ struct ficco_plan_s {
     const void *packed_from = nullptr;
     hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_copy_first = nullptr, ev_copy_last = nullptr;
     hipEvent_t ev_gemm_first = nullptr, ev_gemm_last = nullptr;
+    bool last_lean = false;           // last run recorded ev_begin/ev_end only (GEMM alone, no per-launch timing)
     std::vector<hipEvent_t> ev_dep;          // per group: transfers of the group done / launch done
     std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
     int wall_clock_khz = 100000;
@@ -483,7 +484,7 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     TileShape ts = tile_shape(p->tile);
     for (int x = 0; x < kTicketLists; ++x) {
         r.ticket_base[x] = p->ticket_total[x];
-        p->ticket_total[x] += (uint32_t)resident_list_tiles((p->M + ts.bm - 1) / ts.bm, (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)grid;
+        p->ticket_total[x] += resident_list_draws(resident_list_tiles((p->M + ts.bm - 1) / ts.bm, (p->N + ts.bn - 1) / ts.bn, x), grid, x);
     }
     HIP_TRY(launch_resident2d(p->tile, r, cs));
     return FICCO_OK;
@@ -673,8 +674,8 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 TileShape ts = tile_shape(p->tile);
                 for (int x = 0; x < kTicketLists; ++x) {
                     r.ticket_base[x] = p->ticket_total[x];
-                    p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
-                                                                        (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+                    p->ticket_total[x] += resident_list_draws(resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
+                                                                                  (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
                 }
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(launch_resident(p->tile, r, cs));
@@ -724,6 +725,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     p->last_n_copies = n_copies;
     p->last_n_launches = n_launches;
     p->last_engines = true;
+    p->last_lean = false;
     return FICCO_OK;
 }
 
@@ -1010,13 +1012,16 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
 
     // Order this run after the previous one on both streams, then start the clock on the stream
     // that moves first.
+    // A run without transfers never touches the copy stream, and without per-launch timing it is
+    // bracketed by two events only, so that back-to-back launches stay close together.
+    const bool lean = !do_copy && !timing;
     if (!first) {
-        HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+        if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
         HIP_TRY(hipStreamWaitEvent(cs, p->ev_end, 0));
     }
     hipStream_t lead = (rs || !do_copy) ? cs : xs, follow = (rs || !do_copy) ? xs : cs;
     HIP_TRY(hipEventRecord(p->ev_begin, lead));
-    HIP_TRY(hipStreamWaitEvent(follow, p->ev_begin, 0));
+    if (do_copy) HIP_TRY(hipStreamWaitEvent(follow, p->ev_begin, 0));
 
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
@@ -1069,7 +1074,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     if (!timing) {
         // span events: first/last of each kind are recorded once, outside the per-piece path
         if (do_copy && !rs) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
-        if (do_gemm) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+        if (do_gemm && !lean) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
     }
 
     if (is_resident(p)) {
@@ -1111,8 +1116,8 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 TileShape ts = tile_shape(p->tile);
                 for (int x = 0; x < kTicketLists; ++x) {
                     r.ticket_base[x] = p->ticket_total[x];
-                    p->ticket_total[x] += (uint32_t)resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
-                                                                        (p->N + ts.bn - 1) / ts.bn, x) + (uint32_t)r.grid;
+                    p->ticket_total[x] += resident_list_draws(resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
+                                                                                  (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
                 }
                 HIP_TRY(launch_resident(p->tile, r, cs));
             }
@@ -1173,11 +1178,14 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     }
 
     // ---- join: the run ends when both streams are done; ev_end is recorded on the compute stream
-    if (do_gemm) HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
-    HIP_TRY(hipEventRecord(p->ev_copy_last, xs));
-    HIP_TRY(hipStreamWaitEvent(cs, p->ev_copy_last, 0));
+    if (do_gemm && !lean) HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+    if (do_copy) {
+        HIP_TRY(hipEventRecord(p->ev_copy_last, xs));
+        HIP_TRY(hipStreamWaitEvent(cs, p->ev_copy_last, 0));
+    }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
-    HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+    if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+    p->last_lean = lean;
 
     p->last_had_copies = n_copies > 0;
     p->last_had_gemm = n_launches > 0;
@@ -1224,7 +1232,8 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         s.copy_span_us = ms * 1e3;
     }
     if (p->last_had_gemm) {
-        HIP_TRY(hipEventElapsedTime(&ms, p->ev_gemm_first, p->ev_gemm_last));
+        if (p->last_lean) HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_end));
+        else HIP_TRY(hipEventElapsedTime(&ms, p->ev_gemm_first, p->ev_gemm_last));
         s.gemm_span_us = ms * 1e3;
     }
     s.gemm_busy_us = s.gemm_span_us;

@@ -323,57 +323,160 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
                     a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
 }
 
-// Tile order of the resident kernel. Row tiles are numbered in arrival order (R = arrival position x
+// Tile order of the resident kernels. Row tiles are numbered in arrival order (R = arrival position x
 // row tiles per piece + row tile in the piece) and dealt round-robin to kTicketLists lists, one per
 // XCD, each with its own ticket counter: a workgroup first serves the list of the XCD it presumably
 // runs on (workgroups are dispatched round-robin over the XCDs), so that the tiles sharing an L2 at
 // any time are few row tiles times a run of column tiles, and then helps the other lists. Inside a
 // list tiles go in groups of 2 row tiles, row tile fastest.
+//
+// TileWalk hands a workgroup its next (list, tile) pair. The first tile of the first list is the
+// workgroup's rank among the workgroups that start there (no memory access); later tiles are drawn
+// from the list's counter. Before it turns to the other lists it reads their counters once, all
+// loads in flight together: on a list that is already used up it only leaves its one
+// past-the-end draw (an atomic whose result nobody waits for), and a list that the ranks of its own
+// workgroups cover completely is never drawn from at all. Counter traffic is what a short launch
+// pays at its start and end, since a draw goes to memory shared by all XCDs.
+struct TileWalk {
+    int turn;        // lists visited so far; the current list is (home + turn) % kTicketLists
+    int first;       // the rank tile of the home list has not been handed out yet
+    int looked;      // the other lists' counters have been read
+    int spent;       // bit k: list (home + k) % kTicketLists was already used up at that look
+    int x, t;        // the result: list and tile in the list, x < 0 when there is nothing left
+};
+
+// Issues, ahead of time, the draw that the next tile_walk_next() call would start with (if it would
+// start with one) and returns 1 with the raw counter value in `drawn`; the caller puts this before
+// work whose duration then hides the draw's round trip. Returns 0 when the next step is not a plain draw.
+template <class TotalFn>
+static __device__ __forceinline__ int tile_walk_predraw(const TileWalk &w, uint32_t *ticket, int grid, TotalFn total_of,
+                                                        uint32_t &drawn)
+{
+    if (w.turn >= kTicketLists || w.first) return 0;
+    const int y = (blockIdx.x + w.turn) % kTicketLists;
+    if (total_of(y) <= resident_list_homes(grid, y)) return 0;
+    if (w.turn > 0 && (!w.looked || ((w.spent >> w.turn) & 1))) return 0;
+    drawn = __hip_atomic_fetch_add(ticket + y * kFlagStrideWords, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return 1;
+}
+
+template <class TotalFn>
+static __device__ __forceinline__ void tile_walk_next(TileWalk &w, uint32_t *ticket, const uint32_t *base, int grid,
+                                                      TotalFn total_of, int have_drawn = 0, uint32_t drawn = 0)
+{
+    const int home = blockIdx.x % kTicketLists, rank = blockIdx.x / kTicketLists;
+    w.x = -1;
+    while (w.turn < kTicketLists) {
+        const int y = (home + w.turn) % kTicketLists;
+        const int total = total_of(y), homes = resident_list_homes(grid, y);
+        uint32_t *ctr = ticket + y * kFlagStrideWords;
+        if (total <= homes) {
+            // the ranks of the workgroups that start on this list cover it: nobody draws from its counter
+            const bool mine = w.first && rank < total;
+            w.first = 0;
+            ++w.turn;
+            if (mine) { w.x = y; w.t = rank; return; }
+            continue;
+        }
+        if (w.turn > 0 && !w.looked) {
+            uint32_t seen[kTicketLists];
+#pragma unroll
+            for (int k = 1; k < kTicketLists; ++k)
+                seen[k] = __hip_atomic_load(ticket + ((home + k) % kTicketLists) * kFlagStrideWords, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+            int spent = 0;
+#pragma unroll
+            for (int k = 1; k < kTicketLists; ++k) {
+                const int yk = (home + k) % kTicketLists;
+                const int homes_k = resident_list_homes(grid, yk), total_k = total_of(yk);
+                if (total_k > homes_k && (int)(seen[k] - base[yk]) + homes_k >= total_k) spent |= 1 << k;
+            }
+            w.spent = spent;
+            w.looked = 1;
+        }
+        if (w.turn > 0 && ((w.spent >> w.turn) & 1)) {
+            (void)__hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // result unused: no wait
+            ++w.turn;
+            continue;
+        }
+        int cand;
+        if (w.first) {
+            w.first = 0;
+            if (rank >= total) continue;          // no tile at this rank: go on to the draws
+            cand = rank;
+        } else {
+            const uint32_t raw = have_drawn ? drawn : __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            have_drawn = 0;
+            cand = (int)(raw - base[y]) + homes;
+        }
+        if (cand < total) { w.x = y; w.t = cand; return; }
+        ++w.turn;                                  // that was this workgroup's one draw past the end of list y
+    }
+}
+
+// position of tile t of a list: groups of GROUP row tiles, row tile fastest inside a group
+static __device__ __forceinline__ void list_tile_position(int t, int my_rows, int tiles_n, int &row_in_list, int &tn)
+{
+    constexpr int GROUP = 2;
+    const int per_group = GROUP * tiles_n;
+    const int g = t / per_group, first = g * GROUP;
+    const int gsz = min(my_rows - first, GROUP);
+    row_in_list = first + (t % per_group) % gsz;
+    tn = (t % per_group) / gsz;
+}
+
 template <class T>
 __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    __shared__ int s_tile;
+    __shared__ TileWalk s_walk;
     __shared__ int s_ok;
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_chunk = (a.rows_per_block + T::BM - 1) / T::BM;
     const int row_tiles = r.n_chunks * rt_per_chunk;
-    constexpr int GROUP = 2;
+    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
+    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
 
-    for (int turn = 0; turn < kTicketLists; ++turn) {
-        const int x = (blockIdx.x + turn) % kTicketLists;
-        const int my_rows = row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0;
-        const int total = my_rows * tiles_n;
-        for (;;) {
-            if (threadIdx.x == 0) s_tile = (int)(atomicAdd(r.ticket + x * kFlagStrideWords, 1u) - r.ticket_base[x]);
-            __syncthreads();
-            const int t = s_tile;
-            if (t >= total) break;        // every workgroup draws exactly one ticket past the end of every list
-            const int per_group = GROUP * tiles_n;
-            const int g = t / per_group, first = g * GROUP;
-            const int gsz = min(my_rows - first, GROUP);
-            const int rl = first + (t % per_group) % gsz, tn = (t % per_group) / gsz;
+    if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
+    int have_drawn = 0;
+    uint32_t drawn = 0;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            TileWalk w = s_walk;
+            tile_walk_next(w, r.ticket, r.ticket_base, r.grid, total_of, have_drawn, drawn);
+            have_drawn = 0;
+            int ok = 1;
+            if (w.x >= 0) {
+                int rl, tn;
+                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn);
+                const int chunk = r.arrival[(rl * kTicketLists + w.x) / rt_per_chunk];
+                if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
+            }
+            s_walk = w;
+            s_ok = ok;
+        }
+        __syncthreads();                   // also orders the tile's loads after the flag read
+        const int x = s_walk.x, t = s_walk.t;
+        if (x < 0) break;
+        if (s_ok) {
+            int rl, tn;
+            list_tile_position(t, list_rows(x), tiles_n, rl, tn);
             const int R = rl * kTicketLists + x;
             const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
             const int chunk = r.arrival[p];
-            if (threadIdx.x == 0) {
-                int ok = 1;
-                if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
-                s_ok = ok;
-            }
-            __syncthreads();               // also orders the tile's loads after the flag read
-            if (s_ok) {
-                const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
-                const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
-                const int col0 = tn * T::BN;
-                const int cols_valid = min(T::BN, a.N - col0);
-                compute_tile<T>(a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid,
-                                a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
-            }
-            __syncthreads();               // s_tile / s_ok / LDS stages are reused
+            const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
+            const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
+            const int col0 = tn * T::BN;
+            const int cols_valid = min(T::BN, a.N - col0);
+            TileAcc<T> ta;
+            tile_zero(ta);
+            tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem);
+            // the next ticket's round trip runs under the epilogue
+            if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
+            tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
         }
-        __syncthreads();
+        __syncthreads();                   // s_walk / s_ok / LDS stages are reused
     }
 }
 
@@ -384,55 +487,57 @@ template <class T>
 __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    __shared__ int s_tile;
+    __shared__ TileWalk s_walk;
     __shared__ int s_ok;
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int row_tiles = (r.M + T::BM - 1) / T::BM;
-    constexpr int GROUP = 2;
+    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
+    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
 
-    for (int turn = 0; turn < kTicketLists; ++turn) {
-        const int x = (blockIdx.x + turn) % kTicketLists;
-        const int my_rows = row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0;
-        const int total = my_rows * tiles_n;
-        for (;;) {
-            if (threadIdx.x == 0) s_tile = (int)(atomicAdd(r.ticket + x * kFlagStrideWords, 1u) - r.ticket_base[x]);
-            __syncthreads();
-            const int t = s_tile;
-            if (t >= total) break;
-            const int per_group = GROUP * tiles_n;
-            const int g = t / per_group, first = g * GROUP;
-            const int gsz = min(my_rows - first, GROUP);
-            const int rl = first + (t % per_group) % gsz, tn = (t % per_group) / gsz;
-            const int tm = rl * kTicketLists + x;
-            const int64_t row0 = (int64_t)tm * T::BM;
-            const int rows_valid = min(T::BM, r.M - (int)row0);
-            const int col0 = tn * T::BN;
-            const int cols_valid = min(T::BN, a.N - col0);
-            const int j0 = (int)(row0 / r.rows_per_shard), j1 = (int)((row0 + rows_valid - 1) / r.rows_per_shard);
-            TileAcc<T> ta;
-            tile_zero(ta);
-            int ok = 1;
-            for (int sl = 0; sl < r.slices && ok; ++sl) {
-                if (r.gated) {
-                    if (threadIdx.x == 0) {
-                        int o = 1;
-                        for (int j = j0; j <= j1 && o; ++j) o = wait_ready(a.gate, sl * r.shards + j);
-                        s_ok = o;
-                    }
-                    __syncthreads();       // also orders the slice's loads after the flag reads
-                    ok = s_ok;
-                    __syncthreads();
-                }
-                if (ok)
-                    tile_accumulate<T>(ta, a.A + ((int64_t)sl * r.M + row0) * r.k_per_slice, rows_valid,
-                                       a.Wt + (int64_t)col0 * a.K + (int64_t)sl * r.k_per_slice, cols_valid,
-                                       r.k_per_slice, a.K, r.k_per_slice, smem);
-            }
-            if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
-            __syncthreads();
+    if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
+    int have_drawn = 0;
+    uint32_t drawn = 0;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            TileWalk w = s_walk;
+            tile_walk_next(w, r.ticket, r.ticket_base, r.grid, total_of, have_drawn, drawn);
+            have_drawn = 0;
+            s_walk = w;
         }
         __syncthreads();
+        const int x = s_walk.x, t = s_walk.t;
+        if (x < 0) break;
+        int rl, tn;
+        list_tile_position(t, list_rows(x), tiles_n, rl, tn);
+        const int tm = rl * kTicketLists + x;
+        const int64_t row0 = (int64_t)tm * T::BM;
+        const int rows_valid = min(T::BM, r.M - (int)row0);
+        const int col0 = tn * T::BN;
+        const int cols_valid = min(T::BN, a.N - col0);
+        const int j0 = (int)(row0 / r.rows_per_shard), j1 = (int)((row0 + rows_valid - 1) / r.rows_per_shard);
+        TileAcc<T> ta;
+        tile_zero(ta);
+        int ok = 1;
+        for (int sl = 0; sl < r.slices && ok; ++sl) {
+            if (r.gated) {
+                if (threadIdx.x == 0) {
+                    int o = 1;
+                    for (int j = j0; j <= j1 && o; ++j) o = wait_ready(a.gate, sl * r.shards + j);
+                    s_ok = o;
+                }
+                __syncthreads();           // also orders the slice's loads after the flag reads
+                ok = s_ok;
+                __syncthreads();
+            }
+            if (ok)
+                tile_accumulate<T>(ta, a.A + ((int64_t)sl * r.M + row0) * r.k_per_slice, rows_valid,
+                                   a.Wt + (int64_t)col0 * a.K + (int64_t)sl * r.k_per_slice, cols_valid,
+                                   r.k_per_slice, a.K, r.k_per_slice, smem);
+        }
+        if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
+        if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
+        __syncthreads();                   // s_walk / s_ok / LDS stages are reused
     }
 }
 

@@ -19,9 +19,23 @@ constexpr int kTicketLists = 8;           // one tile list per XCD (each XCD has
 
 // Tiles of the resident kernel that list x (of kTicketLists) holds: row tiles x, x+8, x+16, ... of the
 // arrival-ordered sequence of row tiles, times all column tiles.
-inline int64_t resident_list_tiles(int64_t row_tiles, int64_t tiles_n, int x)
+__host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_t tiles_n, int x)
 {
     return (row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0) * tiles_n;
+}
+
+// Workgroups of a resident launch whose first list is x (workgroup b starts on list b % kTicketLists).
+__host__ __device__ inline int resident_list_homes(int grid, int x) { return grid > x ? (grid - x + kTicketLists - 1) / kTicketLists : 0; }
+
+// Atomic draws one resident launch makes on list x's counter: a workgroup's first tile of its first list
+// is its rank there and needs no draw; if that covers the whole list nobody draws from it at all;
+// otherwise every later tile is drawn and every workgroup draws exactly one ticket past the end of the
+// list. The host advances its copy of each counter by this much per launch, so counters are never
+// reset.
+__host__ __device__ inline uint32_t resident_list_draws(int64_t list_tiles, int grid, int x)
+{
+    const int64_t homes = resident_list_homes(grid, x);
+    return list_tiles > homes ? (uint32_t)(list_tiles - homes + grid) : 0u;
 }
 
 // How a kernel learns that piece `chunk` has landed:
