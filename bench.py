@@ -229,7 +229,7 @@ def main() -> int:
             F.ficco_destroy(plan)
             return e0.elapsed_time(e1) * 1e3 / args.steps, st.n_launches, info
 
-        us_step, launches, info = launch_time(s, c, source("hbm", s, c))   # operands in the layout the plan reads
+        us_step, launches, info = launch_time(s, c, A_stage if rs else source("hbm", s, c))   # operands in the layout the plan reads
         achieved = flops / us_step * 1e-6
         # the monolithic GEMM of the same shape, for reference
         whole_us, _, winfo = launch_time(F.FICCO_SERIAL, 1, A_stage)
