@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2_qkv8b")
     ap.add_argument("--legs", default="pair,pcie,roofline,losses,cpu")
     ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4 (default: a small sweep)")
+    ap.add_argument("--backend", default="auto", choices=["auto", "stream", "engines"],
+                    help="transfer backend for every plan (default: the library's choice)")
     ap.add_argument("--roofline-plan", default="", help="schedule:chunks for the roofline leg when the pair leg is not run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -129,17 +131,30 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def sched_name(sched):
+        return F.SCHEDULE_NAMES[sched % PACKED] + ("+gather_scatter" if sched >= PACKED else "")
+
     def make(sched, c, opts=()):
+        if sched >= PACKED:
+            sched, opts = sched - PACKED, list(opts) + [(F.FICCO_OPT_PACKING, 1)]
         plan = F.ficco_plan(M, K, N, G, c, sched)
         if rs:
             F.ficco_plan_set(plan, F.FICCO_OPT_DIRECTION, F.FICCO_DIR_GEMM_RS)
         for o, v in opts:
             F.ficco_plan_set(plan, o, v)
+        if args.backend != "auto":
+            F.ficco_plan_set(plan, F.FICCO_OPT_COPY_BACKEND, {"stream": F.FICCO_COPY_STREAM, "engines": F.FICCO_COPY_ENGINES}[args.backend])
         F.ficco_pack_weight(plan, W_dev, cs)
         return plan
 
+    # a candidate is (schedule, pieces per shard); the fused schedule with explicit Gather/Scatter copies
+    # ("3p:4" on the command line) is schedule FICCO_FINE_FUSED + PACKED
+    PACKED = 1000
     if args.candidates:
-        cands = [tuple(int(x) for x in t.split(":")) for t in args.candidates.split(",")]
+        cands = []
+        for t in args.candidates.split(","):
+            a, b = t.split(":")
+            cands.append((int(a[:-1]) + PACKED, int(b)) if a.endswith("p") else (int(a), int(b)))
     else:
         cands = []
         for rows in cfg["chunk_rows"]:
@@ -182,11 +197,11 @@ def main() -> int:
         F.ficco_destroy(p_sh)
         res.update(copy_backend={1: "stream", 2: "engines"}.get(info.copy_backend), links=info.links,
                    ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
-                   schedule=F.SCHEDULE_NAMES[best[0]], chunks_per_shard=best[1], chunk_rows=ms_shard // best[1],
+                   schedule=sched_name(best[0]), chunks_per_shard=best[1], chunk_rows=ms_shard // best[1],
                    tile=f"{info.tile_m}x{info.tile_n}", ms_serial=ms_ser, ms_shard_level=ms_sh,
                    speedup_vs_serial=ms_ser / ms, speedup_vs_shard_level=ms_sh / ms,
                    copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
-                   screen={f"{F.SCHEDULE_NAMES[s]}:{c}": round(v, 4) for (s, c), v in screen.items()})
+                   screen={f"{sched_name(s)}:{c}": round(v, 4) for (s, c), v in screen.items()})
         return res, best
 
     best = None
@@ -207,6 +222,7 @@ def main() -> int:
             s, c = (int(x) for x in args.roofline_plan.split(":"))
         else:
             s, c = F.ficco_pick_schedule(M, K, N, G)
+        s %= PACKED                                    # Gather/Scatter only exists in the overlapped pair
         if rs and s == F.FICCO_FINE_PERSISTENT:
             s = F.FICCO_FINE_FUSED
         def launch_time(sched, chunks, A_res):
@@ -251,6 +267,7 @@ def main() -> int:
 
     if "losses" in legs and not rs:
         s, c = best if best else (F.FICCO_FINE_FUSED, 2)
+        s %= PACKED
         losses = {}
         for tag in ("hbm", "pcie"):
             src = source(tag, s, c)

@@ -109,9 +109,18 @@ typedef enum ficco_option {
     FICCO_OPT_HOLD_FLAGS  = 8,   /* test hook: 1 = issue the transfers but never write the ready flags,
                                     so that the kernels' bounded wait expires                          */
     FICCO_OPT_COPY_BACKEND = 9,  /* ficco_copy_backend; default AUTO                                    */
-    FICCO_OPT_LINKS       = 10   /* copy-engine backend: number of copy engines used side by side, one
+    FICCO_OPT_LINKS       = 10,  /* copy-engine backend: number of copy engines used side by side, one
                                     per emulated link (shard j travels on engine j mod links);
                                     0 (default) = min(shards, engines available)                        */
+    FICCO_OPT_PACKING     = 11   /* 1: run FICCO_FINE_FUSED the way an unmodified library GEMM forces it
+                                    (Sec. V-A): every landed piece is copied by DMA into its place in a
+                                    contiguous per-step input (Gather), one launch multiplies the step,
+                                    and its G output blocks are copied by DMA to their rows of C
+                                    (Scatter). AG_GEMM and the copy-engine backend only; applies to
+                                    FICCO_MODE_PAIR runs (the other modes measure the plain parts);
+                                    ficco_run() then waits on the host for each launch before it
+                                    submits that launch's Scatter copies. 0 (default): the kernel
+                                    reads the pieces in place through a row-block table             */
 } ficco_option;
 
 /*
@@ -129,9 +138,10 @@ typedef enum ficco_option {
  *             kernel. The copy stream argument is not used. ficco_run() first waits on the host
  *             for the plan's previous run; in the GEMM->RS direction it also waits for each GEMM
  *             launch before it submits that launch's transfers.
- *   AUTO    - ENGINES if the source (or any peer buffer) is device memory or the schedule is
- *             FICCO_FINE_PERSISTENT, else STREAM. (On STREAM the resident kernel leaves 8 CUs
- *             free: the HIP runtime writes the 4-byte flags with a helper kernel.)
+ *   AUTO    - ENGINES for every run that moves data, unless FICCO_OPT_FLAG_WRITE = 1 asks for
+ *             stream writes (then STREAM); measured faster than STREAM for pinned sources too.
+ *             (On STREAM the resident kernel leaves 8 CUs free: the HIP runtime writes the
+ *             4-byte flags with a helper kernel.)
  */
 typedef enum ficco_copy_backend {
     FICCO_COPY_AUTO    = 0,

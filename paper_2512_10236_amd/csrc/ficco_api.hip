@@ -122,6 +122,7 @@ struct ficco_plan_s {
     int timing = 0, tile_opt = 0, flag_write = 0, local_shard = -1, hold_flags = 0;
     int64_t spin_limit_us = 2000000;
     int backend_opt = FICCO_COPY_AUTO, links_opt = 0;
+    int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
     int backend = 0, links = 0;             // as resolved by the last run
     int device = 0;
     int n_chunks = 0;
@@ -139,6 +140,8 @@ struct ficco_plan_s {
     uint32_t *d_flags = nullptr, *d_ticket = nullptr, *d_status = nullptr;
     int32_t *d_tables = nullptr;         // arrival | block_row0 (by arrival position)
     int32_t *d_arrival = nullptr, *d_block_row0 = nullptr;
+    int32_t *d_gather_idx = nullptr, *d_scatter_idx = nullptr;   // by arrival position: n + chunk, 2n + chunk
+    uint16_t *d_pack_a = nullptr, *d_pack_c = nullptr;            // packing: step inputs [M,K] and step outputs [M,N], arrival order
     uint32_t *h_epochs = nullptr;        // pinned
     volatile uint32_t *h_status = nullptr;   // pinned, behind h_epochs
     uint16_t *d_wt = nullptr;            // packed weight [N,K]
@@ -150,6 +153,7 @@ struct ficco_plan_s {
     std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
     int wall_clock_khz = 100000;
     std::vector<hsa_signal_t> sig_data, sig_flag;   // copy-engine backend: per chunk id
+    std::vector<hsa_signal_t> sig_gather, sig_scatter;   // packing: per chunk id
     uint64_t *d_sig_value = nullptr;                 // device table: address of each data signal's value word
     int sig_poll = -1;                               // -1 unknown, 0 flags by 4-byte copies, 1 kernels poll the signals
     bool last_engines = false;
@@ -279,7 +283,7 @@ void release(ficco_plan_t *p)
         for (auto &e : *v) ev(e);
         v->clear();
     }
-    for (auto *v : {&p->sig_data, &p->sig_flag}) {
+    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter}) {
         for (auto &sg : *v) (void)hsa_signal_destroy(sg);
         v->clear();
     }
@@ -291,6 +295,9 @@ void release(ficco_plan_t *p)
     p->d_ticket_mem = nullptr;
     if (p->d_tables) (void)hipFree(p->d_tables);
     if (p->d_wt) (void)hipFree(p->d_wt);
+    if (p->d_pack_a) (void)hipFree(p->d_pack_a);
+    if (p->d_pack_c) (void)hipFree(p->d_pack_c);
+    p->d_pack_a = p->d_pack_c = nullptr;
     if (p->h_epochs) (void)hipHostFree(p->h_epochs);
     p->d_words = nullptr; p->d_tables = nullptr; p->d_wt = nullptr; p->h_epochs = nullptr;
     p->finalized = false;
@@ -336,13 +343,17 @@ int finalize(ficco_plan_t *p)
     p->d_flags = p->d_words;
     p->d_ticket = p->d_ticket_mem;
     p->d_status = p->d_words + (size_t)n * kFlagStrideWords + kFlagStrideWords;
-    if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * 2 * (size_t)n) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * 4 * (size_t)n) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     p->d_arrival = p->d_tables;
     p->d_block_row0 = p->d_tables + n;
-    std::vector<int32_t> host(2 * (size_t)n);
+    p->d_gather_idx = p->d_tables + 2 * (size_t)n;
+    p->d_scatter_idx = p->d_tables + 3 * (size_t)n;
+    std::vector<int32_t> host(4 * (size_t)n);
     for (int q = 0; q < n; ++q) {
         host[q] = p->arrival[q];
         host[n + q] = (int32_t)(p->arrival[q] * p->m);
+        host[2 * (size_t)n + q] = n + p->arrival[q];
+        host[3 * (size_t)n + q] = 2 * n + p->arrival[q];
     }
     HIP_TRY(hipMemcpy(p->d_tables, host.data(), host.size() * 4, hipMemcpyHostToDevice));
     if (hipHostMalloc((void **)&p->h_epochs, sizeof(uint32_t) * (kEpochSlots + 16), hipHostMallocDefault) != hipSuccess) {
@@ -525,16 +536,28 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (hsa_signal_create(0, 0, nullptr, &b) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
         p->sig_flag.push_back(b);
     }
+    const bool packed = p->packing && dependent && do_copy && do_gemm && !rs;
+    if (p->packing) {
+        for (auto *v : {&p->sig_gather, &p->sig_scatter})
+            while ((int)v->size() < n) {
+                hsa_signal_t a;
+                if (hsa_signal_create(0, 0, nullptr, &a) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
+                v->push_back(a);
+            }
+    }
     // Can the kernels watch the transfers' own completion signals? The value word of a user signal
     // (amd_signal_t, the layout AQL consumers use) must lie in memory the runtime reports as
     // accessible to this GPU; its device-side address goes into a table. Otherwise, or when asked
     // for (FICCO_OPT_FLAG_WRITE = 2), every transfer is followed by a 4-byte flag copy instead.
     if (p->sig_poll < 0) {
         p->sig_poll = 0;
-        std::vector<uint64_t> addr(n, 0);
+        // table entries: [0, n) transfers; with packing also [n, 2n) Gather and [2n, 3n) Scatter copies
+        const int n_tab = p->packing ? 3 * n : n;
+        std::vector<uint64_t> addr(n_tab, 0);
         bool ok = p->flag_write == 0;
-        for (int i = 0; i < n && ok; ++i) {
-            amd_signal_t *as = reinterpret_cast<amd_signal_t *>(p->sig_data[i].handle);
+        for (int i = 0; i < n_tab && ok; ++i) {
+            const hsa_signal_t sg_i = i < n ? p->sig_data[i] : i < 2 * n ? p->sig_gather[i - n] : p->sig_scatter[i - 2 * n];
+            amd_signal_t *as = reinterpret_cast<amd_signal_t *>(sg_i.handle);
             if (!as || as->kind != AMD_SIGNAL_KIND_USER) { ok = false; break; }
             void *vp = (void *)&as->value;
             hsa_amd_pointer_info_t info{};
@@ -551,8 +574,8 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             addr[i] = (uint64_t)((uintptr_t)info.agentBaseAddress + off);
         }
         if (ok) {
-            if (hipMalloc((void **)&p->d_sig_value, sizeof(uint64_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
-            HIP_TRY(hipMemcpy(p->d_sig_value, addr.data(), sizeof(uint64_t) * (size_t)n, hipMemcpyHostToDevice));
+            if (hipMalloc((void **)&p->d_sig_value, sizeof(uint64_t) * (size_t)n_tab) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemcpy(p->d_sig_value, addr.data(), sizeof(uint64_t) * (size_t)n_tab, hipMemcpyHostToDevice));
             p->sig_poll = 1;
         }
         if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: kernels %s\n", p->sig_poll ? "poll the transfers' completion signals" : "wait on flags raised by 4-byte copies");
@@ -560,11 +583,15 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     // Signals live in host memory: when the transfers themselves cross the host link, hundreds of
     // polling workgroups would compete with them for it, so flags in device memory are used then.
     const bool poll_signals = p->sig_poll == 1 && !p->hold_flags && !touches_host;
+    if (packed && p->sig_poll != 1) return FICCO_ERR_HIP;    // the packed launches watch the Gather copies' signals
     // the previous run must be over before its buffers, flags and signals are reused
     if (p->run_index > 0) {
         HIP_TRY(hipEventSynchronize(p->ev_end));
         for (int i = 0; i < n; ++i)
             if (!wait_signal(p->sig_data[i], 5.0) || !wait_signal(p->sig_flag[i], 5.0)) return FICCO_ERR_TIMEOUT;
+        for (auto *v : {&p->sig_gather, &p->sig_scatter})
+            for (auto &sg : *v)
+                if (!wait_signal(sg, 5.0)) return FICCO_ERR_TIMEOUT;
     }
     if (timing) {
         if ((rc = make_events(p->ev_gemm_b, p->groups.size()))) return rc;
@@ -583,6 +610,10 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     for (int i = 0; i < n; ++i) {
         hsa_signal_store_relaxed(p->sig_data[i], (do_copy && !is_local(i)) ? 1 : 0);
         hsa_signal_store_relaxed(p->sig_flag[i], 0);
+        if (p->packing) {
+            hsa_signal_store_relaxed(p->sig_gather[i], packed ? 1 : 0);
+            hsa_signal_store_relaxed(p->sig_scatter[i], packed ? 1 : 0);
+        }
     }
 
     int n_copies = 0, n_launches = 0;
@@ -621,7 +652,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         prev_chunk = chunk;
         ++n_copies;
         copy_bytes += (int64_t)bytes;
-        if (!poll_signals && !p->hold_flags) {
+        if (!poll_signals && !p->hold_flags && !packed) {
             hsa_signal_store_relaxed(p->sig_flag[chunk], 1);
             uint32_t *flag = p->d_flags + (size_t)chunk * kFlagStrideWords;
             st = hsa_amd_memory_async_copy_on_engine(flag, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4, 1, &p->sig_data[chunk],
@@ -651,7 +682,85 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
 
     HIP_TRY(hipEventRecord(p->ev_begin, cs));
     HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
-    if (!rs) {
+    if (packed) {
+        // ---- the fused schedule as the paper runs it with an unmodified GEMM (Sec. V-A): the G pieces of a
+        // step are gathered by DMA into one contiguous input, multiplied into one contiguous output,
+        // and the G output blocks are scattered by DMA to their rows of C.
+        if (!p->d_pack_a && hipMalloc((void **)&p->d_pack_a, (size_t)p->M * p->K * 2) != hipSuccess) return FICCO_ERR_ALLOC;
+        if (!p->d_pack_c && hipMalloc((void **)&p->d_pack_c, (size_t)p->M * p->N * 2) != hipSuccess) return FICCO_ERR_ALLOC;
+        // Gather and Scatter run on engines of their own where the machine has spare ones
+        std::vector<int> geng = usable_engines(false, 16, p->d_status + kFlagStrideWords);
+        if (geng.empty()) return FICCO_ERR_HIP;
+        auto aux_engine = [&](int chunk) {
+            const int spare = (int)geng.size() > links ? (int)geng.size() - links : 0;
+            const int lane = shard_of(p, chunk);
+            const int e = spare ? geng[links + lane % spare] : geng[lane % (int)geng.size()];
+            return (hsa_amd_sdma_engine_id_t)(1u << e);
+        };
+        // The launches watch the Gather copies' completion signals, or, when the transfers cross the host
+        // link (where polling host memory would compete with them), flags raised by a 4-byte copy
+        // behind each Gather copy. The final wait for the Scatter copies is a single wavefront.
+        const Gate pgate{p->d_flags, p->d_sig_value, epoch, p->d_status, (uint32_t *)p->h_status, spin_ticks};
+        const Gate ggate = poll_signals ? pgate : gate;
+        const size_t piece_a = (size_t)p->m * row_bytes_a, piece_c = (size_t)p->m * row_bytes_c;
+        for (size_t g = 0; g < p->groups.size(); ++g) {
+            const Group &gr = p->groups[g];
+            GemmLaunch a{};
+            a.A = p->d_pack_a;
+            a.Wt = p->d_wt;
+            a.C = p->d_pack_c;
+            a.lda = p->K; a.ldc = p->N; a.N = (int32_t)p->N; a.K = (int32_t)p->K;
+            a.block_row0 = nullptr;
+            a.row0 = (int32_t)((int64_t)gr.pos_begin * p->m);
+            a.n_blocks = 1;
+            a.rows_per_block = (int32_t)((int64_t)(gr.pos_end - gr.pos_begin) * p->m);
+            a.gate = ggate;
+            a.wait_chunks = (poll_signals ? p->d_gather_idx : p->d_arrival) + gr.pos_begin;
+            a.n_wait = gr.pos_end - gr.pos_begin;
+            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[g], cs));
+            HIP_TRY(launch_gemm(p->tile, a, cs));
+            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[g], cs));
+            HIP_TRY(hipEventRecord(p->ev_dep[g], cs));
+            ++n_launches;
+        }
+        HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+        // the run's last stage on the compute stream: wait (bounded) for every Scatter copy
+        HIP_TRY(launch_wait_ready(pgate, p->d_scatter_idx, n, cs));
+        for (int q = 0; q < n; ++q) {
+            const int chunk = p->arrival[q];
+            if ((rc = submit(q))) return rc;
+            // Gather: the piece's rows of A_dev -> position q of the packed input, behind its transfer
+            hsa_signal_t dep = p->sig_data[chunk];
+            const bool has_dep = !is_local(chunk);
+            hsa_status_t st = hsa_amd_memory_async_copy_on_engine((char *)p->d_pack_a + (size_t)q * piece_a, ctx.gpu,
+                                                                  (const char *)A_dev + (size_t)chunk * piece_a, ctx.gpu, piece_a,
+                                                                  has_dep ? 1 : 0, has_dep ? &dep : nullptr, p->sig_gather[chunk],
+                                                                  aux_engine(chunk), true);
+            if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
+            ++n_copies;
+            copy_bytes += (int64_t)piece_a;
+            if (!poll_signals) {
+                hsa_signal_store_relaxed(p->sig_flag[chunk], 1);
+                st = hsa_amd_memory_async_copy_on_engine(p->d_flags + (size_t)chunk * kFlagStrideWords, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4,
+                                                         1, &p->sig_gather[chunk], p->sig_flag[chunk], aux_engine(chunk), false);
+                if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[chunk], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+            }
+        }
+        // Scatter: a launch's output blocks leave when the launch is done (the host relays the event:
+        // a copy engine cannot wait on it)
+        for (size_t g = 0; g < p->groups.size(); ++g) {
+            HIP_TRY(hipEventSynchronize(p->ev_dep[g]));
+            for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q) {
+                const int chunk = p->arrival[q];
+                hsa_status_t st = hsa_amd_memory_async_copy_on_engine((char *)C_dev + (size_t)chunk * piece_c, ctx.gpu,
+                                                                      (const char *)p->d_pack_c + (size_t)q * piece_c, ctx.gpu, piece_c,
+                                                                      0, nullptr, p->sig_scatter[chunk], aux_engine(chunk), true);
+                if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
+                ++n_copies;
+                copy_bytes += (int64_t)piece_c;
+            }
+        }
+    } else if (!rs) {
         // ---- GEMM side first: the kernels wait on flags, so they can be resident before data moves
         if (do_gemm) {
             if (is_2d(p)) {
@@ -864,6 +973,11 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
         if (value < 0 || value > 16) return FICCO_ERR_ARG;
         p->links_opt = (int)value;
         break;
+    case FICCO_OPT_PACKING:
+        if (value != 0 && value != 1) return FICCO_ERR_ARG;
+        if (value == 1 && p->schedule != FICCO_FINE_FUSED) return FICCO_ERR_ARG;
+        p->packing = (int)value;
+        break;
     default:
         return FICCO_ERR_ARG;
     }
@@ -979,14 +1093,16 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         if (rc) return rc;
     }
     // resolve the transfer backend
-    bool any_peer_dev = false;
-    for (char d : peer_dev) any_peer_dev |= (bool)d;
     int backend = p->backend_opt;
-    // AUTO: engines whenever a kernel would otherwise have to be fed by copy kernels (device sources
-    // and peers) or by helper kernels that need a free CU while it spins (the resident schedule)
+    // AUTO: the copy engines driven directly. They beat the stream path for pinned sources as well
+    // (a transfer costs the host about a microsecond to submit against about ten for a stream copy,
+    // and launches are enqueued before data moves), and they are the only way to move device-resident
+    // shards without a copy kernel. The stream path remains for callers that ask for it, and for flag
+    // writes by stream operations.
+    const bool packed = p->packing && mode == FICCO_MODE_PAIR;     // the other modes measure the plain launches and transfers
+    if (packed && (rs || p->hold_flags || backend == FICCO_COPY_STREAM)) return FICCO_ERR_ARG;
     if (backend == FICCO_COPY_AUTO)
-        backend = (do_copy && (src_dev || any_peer_dev || (is_resident(p) && dependent))) ? FICCO_COPY_ENGINES
-                                                                                                           : FICCO_COPY_STREAM;
+        backend = (packed || (do_copy && p->flag_write != 1)) ? FICCO_COPY_ENGINES : FICCO_COPY_STREAM;
     p->backend = backend;
     if (backend == FICCO_COPY_ENGINES) {
         if (p->flag_write == 1) return FICCO_ERR_ARG;     // stream writes belong to the stream backend
@@ -1423,7 +1539,7 @@ void ficco_destroy(ficco_plan_t *p)
 {
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
-    for (auto *v : {&p->sig_data, &p->sig_flag})
+    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter})
         for (auto &sg : *v) (void)wait_signal(sg, 5.0);
     release(p);
     delete p;

@@ -16,6 +16,8 @@ pytestmark = pytest.mark.gpu
 
 TOL = 8e-3
 NAN_BF16 = 0x7FC0
+STREAM, ENGINES = ficco.FICCO_COPY_STREAM, ficco.FICCO_COPY_ENGINES
+BACKENDS = [STREAM, ENGINES]
 ALL_SCHEDULES = [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4),
                  (ficco.FICCO_FINE_FUSED, 4), (ficco.FICCO_FINE_PERSISTENT, 4)]
 
@@ -38,7 +40,7 @@ def widen(bits):
 
 
 def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, delay_copy=False,
-           timing=0, allow_timeout=False, runs=1):
+           timing=0, allow_timeout=False, runs=1, local_shard=None, backend=None):
     """One all-gather -> GEMM through the C ABI; returns (C bits, stats)."""
     dev = gpu["dev"]
     A = np.concatenate(shards, 0)
@@ -51,9 +53,20 @@ def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, 
     W_dev = as_i16(W).to(dev)
     A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)     # poison: unread rows show up as NaN
     C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    ms = M // G
+
+    def place_local():
+        if local_shard is not None:                     # the local shard is already in place, nothing moves it
+            A_dev[local_shard * ms:(local_shard + 1) * ms] = as_i16(A[local_shard * ms:(local_shard + 1) * ms]).to(dev)
+
+    place_local()
     torch.cuda.synchronize()
     plan = ficco.ficco_plan(M, K, N, G, c, schedule)
     try:
+        if local_shard is not None:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_LOCAL_SHARD, local_shard)
+        if backend is not None:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
         for o, v in opts:
             ficco.ficco_plan_set(plan, o, v)
         if arrival is not None:
@@ -62,6 +75,7 @@ def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, 
         for r in range(runs):
             if r:
                 A_dev.fill_(NAN_BF16)
+                place_local()
                 torch.cuda.synchronize()
             if delay_copy:
                 with torch.cuda.stream(gpu["xs"]):
@@ -88,14 +102,17 @@ def test_cfg1_all_schedules_match_oracle_and_each_other(gpu):
     shards, W = fi.config_inputs("cfg1_tiny")
     ref = og.ag_gemm(shards, W)
     base = None
-    for sched, c in ALL_SCHEDULES + [(ficco.FICCO_FINE_UNFUSED, 1), (ficco.FICCO_FINE_PERSISTENT, 1)]:
-        bits, st, info = run_ag(gpu, shards, W, sched, c)
-        check(bits, ref, ficco.SCHEDULE_NAMES[sched])
-        if base is None:
-            base = bits
-        assert np.array_equal(bits, base), f"{ficco.SCHEDULE_NAMES[sched]} c={c} differs bitwise from serial"
-        assert st.n_copies == info.n_chunks and st.copy_bytes == 512 * 1024 * 2
-        assert st.wall_us > 0 and st.flops == 2 * 512 * 1024 * 1024
+    for backend in BACKENDS + [None]:
+        for sched, c in ALL_SCHEDULES + [(ficco.FICCO_FINE_UNFUSED, 1), (ficco.FICCO_FINE_PERSISTENT, 1)]:
+            bits, st, info = run_ag(gpu, shards, W, sched, c, backend=backend)
+            check(bits, ref, ficco.SCHEDULE_NAMES[sched])
+            if base is None:
+                base = bits
+            assert np.array_equal(bits, base), f"{ficco.SCHEDULE_NAMES[sched]} c={c} backend {backend} differs bitwise from serial"
+            assert st.n_copies == info.n_chunks and st.copy_bytes == 512 * 1024 * 2
+            assert st.wall_us > 0 and st.flops == 2 * 512 * 1024 * 1024
+            # without a request the library moves the pieces with the copy engines
+            assert info.copy_backend == (backend if backend is not None else ENGINES)
 
 
 @pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
@@ -108,8 +125,9 @@ def test_every_tile_shape_ragged(gpu, tile):
     W = fi.make_weight(21, K, N)
     ref = og.ag_gemm(shards, W)
     outs = []
-    for sched, cc in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, c), (ficco.FICCO_FINE_PERSISTENT, c)]:
-        bits, _, info = run_ag(gpu, shards, W, sched, cc, opts=[(ficco.FICCO_OPT_TILE, tile)])
+    for sched, cc, backend in [(ficco.FICCO_SERIAL, 1, STREAM), (ficco.FICCO_FINE_FUSED, c, STREAM), (ficco.FICCO_FINE_FUSED, c, ENGINES),
+                               (ficco.FICCO_FINE_PERSISTENT, c, ENGINES)]:
+        bits, _, info = run_ag(gpu, shards, W, sched, cc, opts=[(ficco.FICCO_OPT_TILE, tile)], backend=backend)
         check(bits, ref, f"tile {tile} sched {sched}")
         outs.append(bits)
     assert all(np.array_equal(outs[0], o) for o in outs[1:])
@@ -154,25 +172,27 @@ def test_arrival_order_and_delay_do_not_change_bits(gpu):
     rng = np.random.default_rng(0)
     orders = [list(range(n - 1, -1, -1)), list(rng.permutation(n))]
     for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
-        for arr in orders:
-            bits, _, _ = run_ag(gpu, shards, W, sched, 4, arrival=arr)
-            assert np.array_equal(bits, base), (sched, arr)
-        bits, _, _ = run_ag(gpu, shards, W, sched, 4, opts=[(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)])
-        assert np.array_equal(bits, base)
-        # transfers held back for tens of ms: the GEMM must wait for them (poison would show)
-        bits, st, _ = run_ag(gpu, shards, W, sched, 4, delay_copy=True)
+        for backend in BACKENDS:
+            for arr in orders:
+                bits, _, _ = run_ag(gpu, shards, W, sched, 4, arrival=arr, backend=backend)
+                assert np.array_equal(bits, base), (sched, arr, backend)
+            bits, _, _ = run_ag(gpu, shards, W, sched, 4, opts=[(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)], backend=backend)
+            assert np.array_equal(bits, base)
+        # transfers held back for tens of ms on the copy stream: the GEMM must wait for them (poison would show)
+        bits, st, _ = run_ag(gpu, shards, W, sched, 4, delay_copy=True, backend=STREAM)
         assert np.array_equal(bits, base), sched
 
 
 def test_repeated_runs_and_timing_spans(gpu):
     shards, W = fi.config_inputs("cfg1_tiny")
     base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
-    for sched, c in ALL_SCHEDULES:
-        bits, st, info = run_ag(gpu, shards, W, sched, c, timing=1, runs=3)
-        assert np.array_equal(bits, base)
-        assert st.run_index == 3 and st.n_launches == info.n_groups
-        assert 0 < st.gemm_busy_us <= st.wall_us * 1.05
-        assert 0 < st.copy_span_us <= st.wall_us * 1.05
+    for backend in BACKENDS:
+        for sched, c in ALL_SCHEDULES:
+            bits, st, info = run_ag(gpu, shards, W, sched, c, timing=1, runs=3, backend=backend)
+            assert np.array_equal(bits, base)
+            assert st.run_index == 3 and st.n_launches == info.n_groups
+            assert 0 < st.gemm_busy_us <= st.wall_us * 1.05
+            assert 0 < st.copy_span_us <= st.wall_us * 1.05
 
 
 def test_flag_written_by_stream_write_value(gpu):
@@ -198,7 +218,8 @@ def test_local_shard_needs_no_transfer(gpu):
     dev = gpu["dev"]
     A = np.concatenate(shards, 0)
     M, K, N, G = 512, 1024, 1024, 4
-    for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+    for sched, backend in [(s_, b_) for s_ in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT)
+                           for b_ in BACKENDS]:
         A_src = as_i16(A).pin_memory()
         A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
         A_dev[256:384] = as_i16(A[256:384]).to(dev)            # shard 2 is already here
@@ -208,6 +229,7 @@ def test_local_shard_needs_no_transfer(gpu):
         plan = ficco.ficco_plan(M, K, N, G, 4, sched)
         try:
             ficco.ficco_plan_set(plan, ficco.FICCO_OPT_LOCAL_SHARD, 2)
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
             ficco.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
             st = ficco.ficco_query_stats(plan)
         finally:
@@ -224,7 +246,7 @@ def test_gemm_rs_streams_row_blocks_to_peers(gpu):
     blocks = og.gemm_rs_blocks(A, W, G)
     base = None
     for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4), (ficco.FICCO_FINE_FUSED, 2)]:
-        for kind in ("device", "pinned"):
+        for kind, backend in (("device", None), ("pinned", STREAM), ("pinned", ENGINES)):
             A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
             C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
             if kind == "device":
@@ -235,6 +257,8 @@ def test_gemm_rs_streams_row_blocks_to_peers(gpu):
             plan = ficco.ficco_plan(M, K, N, G, c, sched)
             try:
                 ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+                if backend is not None:
+                    ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
                 ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
                 st = ficco.ficco_query_stats(plan)
             finally:
@@ -446,3 +470,35 @@ def test_cfg6_2d_full_size_sampled_rows(gpu):
         bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", runs=2)
         check(bits[rows], ref, f"cfg6 2D c={c}")
         assert np.array_equal(bits, base), f"cfg6 2D c={c} differs bitwise from serial"
+
+
+# ------------------------------------------------------------------------------------------------
+# fused schedule with explicit Gather / Scatter copies on the copy engines
+def test_packed_fused_matches_in_place_fused(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    pk = (ficco.FICCO_OPT_PACKING, 1)
+    for c, src, opts, local in [(4, "device", [pk], None), (1, "device", [pk], None), (4, "pinned", [pk], None),
+                                (4, "device", [pk], 2),
+                                (2, "device", [pk, (ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR), (ficco.FICCO_OPT_LINKS, 3)], None)]:
+        bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_FUSED, c, src=src, opts=opts, runs=2, local_shard=local)
+        check(bits, ref, f"packed c={c} {src} {opts} local={local}")
+        assert np.array_equal(bits, base), f"packed c={c} {src} {opts}: differs bitwise from serial"
+        n = 4 * c
+        assert st.n_copies == 3 * n - (c if local is not None else 0) and st.n_launches == info.n_groups
+        assert info.copy_backend == ficco.FICCO_COPY_ENGINES
+
+
+def test_packed_fused_ragged_pieces(gpu):
+    G, c, m, K, N = 3, 2, 88, 192, 328
+    shards = fi.make_shards(25, G * c * m, K, G)
+    W = fi.make_weight(25, K, N)
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    rev = list(range(G * c - 1, -1, -1))
+    for arrival in (None, rev):
+        bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_FUSED, c, src="device", arrival=arrival,
+                            opts=[(ficco.FICCO_OPT_PACKING, 1)], timing=1)
+        check(bits, ref, "packed ragged")
+        assert np.array_equal(bits, base)

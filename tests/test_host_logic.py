@@ -78,6 +78,23 @@ def test_2d_plan_lists_match_oracle(G, c, order):
     assert info.mt_bytes == sch.mt_bytes(M // G, 8, K // c)
 
 
+def test_packing_is_an_option_of_the_fused_schedule_only():
+    for sched, c, ok in [(ficco.FICCO_FINE_FUSED, 2, True), (ficco.FICCO_FINE_UNFUSED, 2, False),
+                         (ficco.FICCO_FINE_PERSISTENT, 2, False), (ficco.FICCO_SERIAL, 1, False), (ficco.FICCO_FINE_2D, 2, False)]:
+        plan = ficco.ficco_plan(512, 128, 8, 4, c, sched)
+        try:
+            if ok:
+                ficco.ficco_plan_set(plan, ficco.FICCO_OPT_PACKING, 1)
+                ficco.ficco_plan_set(plan, ficco.FICCO_OPT_PACKING, 0)
+                with pytest.raises(ficco.FiccoError):
+                    ficco.ficco_plan_set(plan, ficco.FICCO_OPT_PACKING, 2)
+            else:
+                with pytest.raises(ficco.FiccoError):
+                    ficco.ficco_plan_set(plan, ficco.FICCO_OPT_PACKING, 1)
+        finally:
+            ficco.ficco_destroy(plan)
+
+
 def test_custom_arrival_and_local_shard():
     plan = ficco.ficco_plan(512, 64, 8, 4, 4, ficco.FICCO_FINE_FUSED)
     try:
