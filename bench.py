@@ -9,10 +9,11 @@ Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192
   pair      - K timed steps of the best finer-grain schedule, source shards resident in HBM
               (device staging buffer); also serial and shard-level schedules for the speedup
   pcie      - the same with the shards in pinned host memory (PCIe-inclusive; never `value`)
-  roofline  - the GEMM launches of the timed plan in isolation, per-launch HIP events on the
-              compute stream -> achieved TFLOP/s against the bf16 dense MFMA peak
+  roofline  - the GEMM launches of the timed plan in isolation, enqueued back to back between two
+              HIP events on the compute stream -> achieved TFLOP/s against the bf16 dense MFMA peak
   losses    - decomposition / contention losses (DIL, CIL) through ficco_profile_losses
   cpu       - the CPU oracle timed on the host cores (a baseline, not a target)
+  graph     - (not run by default) HIP-graph replays against call-by-call enqueue, stream backend
   calib     - (not in the default set) a plain device copy of 256 MiB, so that HBM counters read
               under rocprofv3 --pmc can be scaled by what they show for a known amount of traffic
 """
@@ -280,6 +281,41 @@ def main() -> int:
             losses[tag]["comm_dil_pct"] = round((L.comm_dil - 1) * 100, 2)
             losses[tag]["comm_cil_pct"] = round((L.comm_cil - 1) * 100, 2)
         out["losses"] = losses
+
+    if "graph" in legs and not rs:
+        # HIP-graph replay of one run against the same run enqueued call by call (stream backend, shards in
+        # pinned host memory): mean step time, and the host time one enqueue takes
+        res = {}
+        for sname, sched, c in (("serial", F.FICCO_SERIAL, 1), ("fine_fused", F.FICCO_FINE_FUSED, 4), ("fine_unfused", F.FICCO_FINE_UNFUSED, 4)):
+            plan = make(sched, c, [(F.FICCO_OPT_COPY_BACKEND, F.FICCO_COPY_STREAM)])
+            row = {}
+            for how in ("eager", "graph"):
+                if how == "graph":
+                    F.ficco_graph_capture(plan, A_pinned, A_dev, W_dev, C_dev, None)
+
+                def step():
+                    if how == "eager":
+                        F.ficco_run(plan, A_pinned, A_dev, W_dev, C_dev, None, cs, xs)
+                    else:
+                        F.ficco_graph_launch(plan, cs)
+                for _ in range(args.warmup):
+                    step()
+                    F.ficco_query_stats(plan)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    step()
+                    F.ficco_query_stats(plan)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3 / args.steps
+                h0 = time.perf_counter()
+                step()
+                h1 = time.perf_counter()
+                F.ficco_query_stats(plan)
+                row[how] = {"ms_per_step": round(ms, 4), "host_enqueue_us": round((h1 - h0) * 1e6, 1)}
+            F.ficco_destroy(plan)
+            res[f"{sname}:{c}"] = row
+        out["graph"] = res
 
     if "calib" in legs:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

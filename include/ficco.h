@@ -266,6 +266,26 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
 int ficco_run(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
               void *const *peer_out, void *compute_stream, void *copy_stream);
 
+/*
+ * Capture one run of the plan into a HIP graph (the paper notes the cost of enqueueing many small
+ * operations, Sec. IV-B; a graph replays the whole run with one call). For the per-launch schedules
+ * (SERIAL, SHARD, FINE_UNFUSED, FINE_FUSED) in FICCO_MODE_PAIR on the stream backend, with the far
+ * side (A_src, or every peer_out[j]) in pinned host memory; FICCO_OPT_TIMING must be 0 and
+ * FICCO_OPT_COPY_BACKEND must not be ENGINES (FICCO_ERR_ARG otherwise). Arguments as in ficco_run();
+ * the pointers are baked into the graph. The weight is packed before the capture if needed. The
+ * graph holds copies, kernel launches and their dependencies only: no memset nodes.
+ * ficco_graph_launch() enqueues one replay on `stream` (any stream; replays on one stream run in
+ * order) and returns at once; ficco_query_stats() then reports wall time, flops and the captured
+ * counts (the span fields are 0). A new capture replaces the old graph. FICCO_ERR_STATE if no
+ * graph has been captured.
+ * Measured on ROCm 7.2 / MI355X: the runtime executes a replay's host-to-device copy nodes with its
+ * copy kernel instead of an SDMA engine, and replays of the decomposed schedules were slower than
+ * the same runs enqueued call by call; prefer ficco_run() unless a capturable path is required.
+ */
+int ficco_graph_capture(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_dev,
+                        void *C_dev, void *const *peer_out);
+int ficco_graph_launch(ficco_plan_t *plan, void *stream);
+
 /* Block until the plan's last run has completed, then report its timings (Sec. IV-A quantities
  * are in ficco_profile_losses). FICCO_ERR_TIMEOUT (with *out filled) if the resident kernel's
  * bounded wait expired; FICCO_ERR_STATE if the plan has not run. */

@@ -65,7 +65,7 @@ class ficco_losses_t(C.Structure):
 
 
 EXPORTS = ["ficco_plan", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
-           "ficco_pack_weight", "ficco_run", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
+           "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
            "ficco_pick_schedule", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
@@ -95,6 +95,8 @@ def load():
     lib.ficco_plan_arrival.argtypes = [vp, i32p, i32p, C.c_int]
     lib.ficco_pack_weight.argtypes = [vp, vp, vp]
     lib.ficco_run.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp]
+    lib.ficco_graph_capture.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp)]
+    lib.ficco_graph_launch.argtypes = [vp, vp]
     lib.ficco_query_stats.argtypes = [vp, C.POINTER(ficco_stats_t)]
     lib.ficco_query_spans.argtypes = [vp, dp, dp, C.c_int, dp, dp, C.c_int]
     lib.ficco_profile_losses.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(ficco_losses_t)]
@@ -180,6 +182,18 @@ def ficco_run(plan, A_src, A_dev, W_dev, C_dev, peer_out, compute_stream, copy_s
         peers = (C.c_void_p * len(peer_out))(*[_ptr(p) for p in peer_out])
     return _ok(load().ficco_run(plan, _ptr(A_src), _ptr(A_dev), _ptr(W_dev), _ptr(C_dev), peers,
                                 _ptr(compute_stream), _ptr(copy_stream)), "ficco_run")
+
+
+def ficco_graph_capture(plan, A_src, A_dev, W_dev, C_dev, peer_out):
+    peers = None
+    if peer_out is not None:
+        peers = (C.c_void_p * len(peer_out))(*[_ptr(p) for p in peer_out])
+    return _ok(load().ficco_graph_capture(plan, _ptr(A_src), _ptr(A_dev), _ptr(W_dev), _ptr(C_dev), peers),
+               "ficco_graph_capture")
+
+
+def ficco_graph_launch(plan, stream):
+    return _ok(load().ficco_graph_launch(plan, _ptr(stream)), "ficco_graph_launch")
 
 
 def ficco_query_stats(plan, allow_timeout: bool = False) -> ficco_stats_t:

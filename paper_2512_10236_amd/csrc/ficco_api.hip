@@ -149,6 +149,15 @@ struct ficco_plan_s {
     hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_copy_first = nullptr, ev_copy_last = nullptr;
     hipEvent_t ev_gemm_first = nullptr, ev_gemm_last = nullptr;
     bool last_lean = false;           // last run recorded ev_begin/ev_end only (GEMM alone, no per-launch timing)
+    // HIP graph of one run (stream backend, per-launch schedules): ficco_graph_capture / ficco_graph_launch
+    bool capturing = false, last_graph = false;
+    hipStream_t cap_cs = nullptr, cap_xs = nullptr;
+    hipEvent_t cap_fork = nullptr, cap_join = nullptr;
+    std::vector<hipEvent_t> cap_dep;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    int graph_copies = 0, graph_launches = 0;
+    int64_t graph_copy_bytes = 0;
     std::vector<hipEvent_t> ev_dep;          // per group: transfers of the group done / launch done
     std::vector<hipEvent_t> ev_copy_b, ev_copy_e, ev_gemm_b, ev_gemm_e;   // TIMING=1
     int wall_clock_khz = 100000;
@@ -279,7 +288,12 @@ void release(ficco_plan_t *p)
     auto ev = [](hipEvent_t &e) { if (e) { (void)hipEventDestroy(e); e = nullptr; } };
     ev(p->ev_begin); ev(p->ev_end); ev(p->ev_copy_first); ev(p->ev_copy_last);
     ev(p->ev_gemm_first); ev(p->ev_gemm_last);
-    for (auto *v : {&p->ev_dep, &p->ev_copy_b, &p->ev_copy_e, &p->ev_gemm_b, &p->ev_gemm_e}) {
+    ev(p->cap_fork); ev(p->cap_join);
+    if (p->graph_exec) { (void)hipGraphExecDestroy(p->graph_exec); p->graph_exec = nullptr; }
+    if (p->graph) { (void)hipGraphDestroy(p->graph); p->graph = nullptr; }
+    if (p->cap_cs) { (void)hipStreamDestroy(p->cap_cs); p->cap_cs = nullptr; }
+    if (p->cap_xs) { (void)hipStreamDestroy(p->cap_xs); p->cap_xs = nullptr; }
+    for (auto *v : {&p->ev_dep, &p->cap_dep, &p->ev_copy_b, &p->ev_copy_e, &p->ev_gemm_b, &p->ev_gemm_e}) {
         for (auto &e : *v) ev(e);
         v->clear();
     }
@@ -835,6 +849,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     p->last_n_launches = n_launches;
     p->last_engines = true;
     p->last_lean = false;
+    p->last_graph = false;
     return FICCO_OK;
 }
 
@@ -1131,13 +1146,23 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     // A run without transfers never touches the copy stream, and without per-launch timing it is
     // bracketed by two events only, so that back-to-back launches stay close together.
     const bool lean = !do_copy && !timing;
-    if (!first) {
-        if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
-        HIP_TRY(hipStreamWaitEvent(cs, p->ev_end, 0));
+    // Under graph capture (ficco_graph_capture) the compute stream is the capture's origin: the copy
+    // stream joins through a fork event, only dependency events are recorded (from a set of their
+    // own), and the timing events stay outside the graph.
+    const bool cap = p->capturing;
+    std::vector<hipEvent_t> &dep_ev = cap ? p->cap_dep : p->ev_dep;
+    if (cap) {
+        HIP_TRY(hipEventRecord(p->cap_fork, cs));
+        if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->cap_fork, 0));
+    } else {
+        if (!first) {
+            if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
+            HIP_TRY(hipStreamWaitEvent(cs, p->ev_end, 0));
+        }
+        hipStream_t lead = (rs || !do_copy) ? cs : xs, follow = (rs || !do_copy) ? xs : cs;
+        HIP_TRY(hipEventRecord(p->ev_begin, lead));
+        if (do_copy) HIP_TRY(hipStreamWaitEvent(follow, p->ev_begin, 0));
     }
-    hipStream_t lead = (rs || !do_copy) ? cs : xs, follow = (rs || !do_copy) ? xs : cs;
-    HIP_TRY(hipEventRecord(p->ev_begin, lead));
-    if (do_copy) HIP_TRY(hipStreamWaitEvent(follow, p->ev_begin, 0));
 
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
@@ -1187,7 +1212,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         return FICCO_OK;
     };
 
-    if (!timing) {
+    if (!timing && !cap) {
         // span events: first/last of each kind are recorded once, outside the per-piece path
         if (do_copy && !rs) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
         if (do_gemm && !lean) HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
@@ -1267,8 +1292,8 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 }
                 if (any) {
                     // the copy stream is in order: the event after the group's last transfer covers all of them
-                    HIP_TRY(hipEventRecord(p->ev_dep[g], xs));
-                    HIP_TRY(hipStreamWaitEvent(cs, p->ev_dep[g], 0));
+                    HIP_TRY(hipEventRecord(dep_ev[g], xs));
+                    HIP_TRY(hipStreamWaitEvent(cs, dep_ev[g], 0));
                 }
                 if ((rc = issue_gemm(g))) return rc;
             }
@@ -1278,15 +1303,15 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         if (!dependent) {
             if (do_gemm) for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
             if (do_copy) {
-                HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+                if (!cap) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
                 for (int q = 0; q < n; ++q) if ((rc = issue_copy_rs(q))) return rc;
             }
         } else {
             for (size_t g = 0; g < p->groups.size(); ++g) {
                 if ((rc = issue_gemm(g))) return rc;
-                HIP_TRY(hipEventRecord(p->ev_dep[g], cs));
-                HIP_TRY(hipStreamWaitEvent(xs, p->ev_dep[g], 0));
-                if (g == 0) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
+                HIP_TRY(hipEventRecord(dep_ev[g], cs));
+                HIP_TRY(hipStreamWaitEvent(xs, dep_ev[g], 0));
+                if (g == 0 && !cap) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
                 for (int q = p->groups[g].pos_begin; q < p->groups[g].pos_end; ++q)
                     if ((rc = issue_copy_rs(q))) return rc;
             }
@@ -1294,6 +1319,17 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     }
 
     // ---- join: the run ends when both streams are done; ev_end is recorded on the compute stream
+    if (cap) {
+        // the copy stream rejoins the capture's origin; nothing else is recorded inside the graph
+        if (do_copy) {
+            HIP_TRY(hipEventRecord(p->cap_join, xs));
+            HIP_TRY(hipStreamWaitEvent(cs, p->cap_join, 0));
+        }
+        p->graph_copies = n_copies;
+        p->graph_launches = n_launches;
+        p->graph_copy_bytes = copy_bytes;
+        return FICCO_OK;
+    }
     if (do_gemm && !lean) HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
     if (do_copy) {
         HIP_TRY(hipEventRecord(p->ev_copy_last, xs));
@@ -1302,6 +1338,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     HIP_TRY(hipEventRecord(p->ev_end, cs));
     if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
     p->last_lean = lean;
+    p->last_graph = false;
 
     p->last_had_copies = n_copies > 0;
     p->last_had_gemm = n_launches > 0;
@@ -1309,6 +1346,83 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     p->last_copy_bytes = copy_bytes;
     p->last_n_copies = n_copies;
     p->last_n_launches = n_launches;
+    return FICCO_OK;
+}
+
+int ficco_graph_capture(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
+                        void *const *peer_out)
+{
+    if (!p || !A_dev || !W_dev || !C_dev) return FICCO_ERR_ARG;
+    if (is_resident(p) || p->timing || p->packing || p->mode != FICCO_MODE_PAIR) return FICCO_ERR_ARG;
+    if (p->backend_opt == FICCO_COPY_ENGINES) return FICCO_ERR_ARG;      // engine submissions are host calls, not stream work
+    const bool rs = p->direction == FICCO_DIR_GEMM_RS;
+    if (rs ? (A_src || !peer_out) : (!A_src || peer_out)) return FICCO_ERR_ARG;
+    int rc = finalize(p);
+    if (rc) return rc;
+    // only pinned host memory on the far side: a device-to-device stream copy would be a copy kernel
+    bool dev = true;
+    if (!rs) {
+        if ((rc = is_device_ptr(A_src, &dev))) return rc;
+        if (dev) return FICCO_ERR_ARG;
+    } else {
+        for (int j = 0; j < p->G; ++j) {
+            if (!peer_out[j]) return FICCO_ERR_ARG;
+            if ((rc = is_device_ptr(peer_out[j], &dev))) return rc;
+            if (dev) return FICCO_ERR_ARG;
+        }
+    }
+    if (!p->cap_cs) HIP_TRY(hipStreamCreateWithFlags(&p->cap_cs, hipStreamNonBlocking));
+    if (!p->cap_xs) HIP_TRY(hipStreamCreateWithFlags(&p->cap_xs, hipStreamNonBlocking));
+    if (!p->cap_fork) HIP_TRY(hipEventCreateWithFlags(&p->cap_fork, hipEventDisableTiming));
+    if (!p->cap_join) HIP_TRY(hipEventCreateWithFlags(&p->cap_join, hipEventDisableTiming));
+    while (p->cap_dep.size() < p->groups.size()) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        p->cap_dep.push_back(e);
+    }
+    // the weight is packed outside the graph
+    if (p->packed_from != W_dev) {
+        if ((rc = pack_weight(p, W_dev, p->cap_cs))) return rc;
+        HIP_TRY(hipStreamSynchronize(p->cap_cs));
+    }
+    if (p->graph_exec) { (void)hipGraphExecDestroy(p->graph_exec); p->graph_exec = nullptr; }
+    if (p->graph) { (void)hipGraphDestroy(p->graph); p->graph = nullptr; }
+
+    const int saved_backend = p->backend_opt;
+    const uint32_t saved_run = p->run_index;
+    p->backend_opt = FICCO_COPY_STREAM;
+    HIP_TRY(hipStreamBeginCapture(p->cap_cs, hipStreamCaptureModeRelaxed));
+    p->capturing = true;
+    rc = ficco_run(p, A_src, A_dev, W_dev, C_dev, peer_out, p->cap_cs, p->cap_xs);
+    p->capturing = false;
+    p->backend_opt = saved_backend;
+    p->run_index = saved_run;            // a capture is not a run
+    hipGraph_t g = nullptr;
+    hipError_t e = hipStreamEndCapture(p->cap_cs, &g);
+    if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+    if (e != hipSuccess || !g) { g_last_hip = (int)e; (void)hipGetLastError(); return FICCO_ERR_HIP; }
+    p->graph = g;
+    e = hipGraphInstantiate(&p->graph_exec, p->graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); p->graph_exec = nullptr; return FICCO_ERR_HIP; }
+    return FICCO_OK;
+}
+
+int ficco_graph_launch(ficco_plan_t *p, void *stream)
+{
+    if (!p) return FICCO_ERR_ARG;
+    if (!p->graph_exec) return FICCO_ERR_STATE;
+    hipStream_t s = (hipStream_t)stream;
+    if (p->run_index > 0) HIP_TRY(hipStreamWaitEvent(s, p->ev_end, 0));
+    HIP_TRY(hipEventRecord(p->ev_begin, s));
+    HIP_TRY(hipGraphLaunch(p->graph_exec, s));
+    HIP_TRY(hipEventRecord(p->ev_end, s));
+    p->run_index += 1;
+    p->last_graph = true;
+    p->last_engines = false;
+    p->last_lean = false;
+    p->last_had_copies = false;
+    p->last_had_gemm = false;
+    p->last_timing = false;
     return FICCO_OK;
 }
 
@@ -1321,6 +1435,17 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
     float ms = 0;
     HIP_TRY(hipEventElapsedTime(&ms, p->ev_begin, p->ev_end));
     s.wall_us = ms * 1e3;
+    if (p->last_graph) {
+        // a graph replay is bracketed by the two events only; what it holds was counted at capture
+        s.run_index = (int32_t)p->run_index;
+        s.n_copies = p->graph_copies;
+        s.n_launches = p->graph_launches;
+        s.copy_bytes = p->graph_copy_bytes;
+        s.flops = 2 * p->M * p->N * p->K;
+        s.eff_tflops = s.wall_us > 0 ? (double)s.flops / s.wall_us * 1e-6 : 0.0;
+        *out = s;
+        return FICCO_OK;
+    }
     if (p->last_had_copies && p->last_engines) {
         // copy-engine timestamps (system clock ticks) of every transfer of the run
         uint64_t t_min = ~0ull, t_max = 0;

@@ -502,3 +502,90 @@ def test_packed_fused_ragged_pieces(gpu):
                             opts=[(ficco.FICCO_OPT_PACKING, 1)], timing=1)
         check(bits, ref, "packed ragged")
         assert np.array_equal(bits, base)
+
+
+# ------------------------------------------------------------------------------------------------
+# HIP graph of one run of the per-launch schedules (stream backend, pinned far side)
+def test_graph_replays_match_eager_runs(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    ref = og.ag_gemm(shards, W)
+    dev = gpu["dev"]
+    A = np.concatenate(shards, 0)
+    M, K = A.shape
+    N, G = W.shape[1], len(shards)
+    A_src = as_i16(A).pin_memory()
+    W_dev = as_i16(W).to(dev)
+    A_dev = torch.empty((M, K), dtype=torch.int16, device=dev)
+    C_dev = torch.empty((M, N), dtype=torch.int16, device=dev)
+    eager, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4), (ficco.FICCO_FINE_FUSED, 4)]:
+        plan = ficco.ficco_plan(M, K, N, G, c, sched)
+        try:
+            with pytest.raises(ficco.FiccoError) as e:
+                ficco.ficco_graph_launch(plan, gpu["cs"])
+            assert e.value.status == ficco.FICCO_ERR_STATE
+            ficco.ficco_graph_capture(plan, A_src, A_dev, W_dev, C_dev, None)
+            info = ficco.ficco_plan_info(plan)
+            for replay in range(4):
+                # the program's own eager work and a synchronisation between replays
+                A_dev.fill_(NAN_BF16)
+                C_dev.fill_(0x7FFF)
+                torch.cuda.synchronize()
+                if replay == 2:                 # an eager run of the same plan between two replays
+                    ficco.ficco_run(plan, A_src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
+                    ficco.ficco_query_stats(plan)
+                    A_dev.fill_(NAN_BF16)
+                    C_dev.fill_(0x7FFF)
+                    torch.cuda.synchronize()
+                ficco.ficco_graph_launch(plan, gpu["cs"])
+                st = ficco.ficco_query_stats(plan)
+                torch.cuda.synchronize()
+                bits = C_dev.cpu().numpy().view(np.uint16)
+                check(bits, ref, f"graph sched {sched} replay {replay}")
+                assert np.array_equal(bits, eager), f"graph sched {sched} replay {replay}: differs from the eager run"
+                assert st.n_copies == info.n_chunks and st.n_launches == info.n_groups and st.wall_us > 0
+        finally:
+            ficco.ficco_destroy(plan)
+
+
+def test_graph_of_gemm_rs_and_argument_checks(gpu):
+    dev = gpu["dev"]
+    M, K, N, G = 1024, 256, 512, 8
+    A = fi.normal_bf16(3, fi.TENSOR_A, M, K)
+    W = fi.make_weight(3, K, N)
+    blocks = og.gemm_rs_blocks(A, W, G)
+    A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+    C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+    peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16).pin_memory() for _ in range(G)]
+    plan = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_FUSED)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+        ficco.ficco_graph_capture(plan, None, A_dev, W_dev, C_dev, peers)
+        for replay in range(3):
+            for p_ in peers:
+                p_.fill_(NAN_BF16)
+            C_dev.zero_()
+            torch.cuda.synchronize()
+            ficco.ficco_graph_launch(plan, gpu["cs"])
+            ficco.ficco_query_stats(plan)
+            torch.cuda.synchronize()
+            for j in range(G):
+                check(peers[j].numpy().view(np.uint16), blocks[j], f"graph RS peer {j} replay {replay}")
+    finally:
+        ficco.ficco_destroy(plan)
+    # what a graph cannot hold is refused
+    dev_peers = [torch.zeros((M // G, N), dtype=torch.int16, device=dev) for _ in range(G)]
+    for sched, c, opts, args in [
+            (ficco.FICCO_FINE_PERSISTENT, 2, [], (as_i16(A).pin_memory(), A_dev, W_dev, C_dev, None)),     # waits inside the kernel
+            (ficco.FICCO_FINE_FUSED, 2, [], (A_dev.clone(), A_dev, W_dev, C_dev, None)),                  # device source: copy kernels
+            (ficco.FICCO_FINE_FUSED, 2, [(ficco.FICCO_OPT_COPY_BACKEND, ENGINES)], (as_i16(A).pin_memory(), A_dev, W_dev, C_dev, None)),
+            (ficco.FICCO_FINE_FUSED, 2, [(ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)], (None, A_dev, W_dev, C_dev, dev_peers))]:
+        plan = ficco.ficco_plan(M, K, N, G, c, sched)
+        try:
+            for o, v in opts:
+                ficco.ficco_plan_set(plan, o, v)
+            with pytest.raises(ficco.FiccoError) as e:
+                ficco.ficco_graph_capture(plan, *args)
+            assert e.value.status == ficco.FICCO_ERR_ARG
+        finally:
+            ficco.ficco_destroy(plan)
