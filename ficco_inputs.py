@@ -22,6 +22,7 @@ import numpy as np
 
 TENSOR_A = 0
 TENSOR_W = 1
+TENSOR_P = 2          # peers' partial output blocks (receiver side of a reduce-scatter)
 
 _MASK64 = np.uint64(0xFFFFFFFFFFFFFFFF)
 
@@ -117,6 +118,12 @@ CONFIGS = {
 # heuristic sweep (all-gather -> GEMM, 8 shards)
 SWEEP = dict(M=[4096, 16384, 65536], K=[4096, 8192], N=[512, 1024, 3584, 14336], shards=8,
              chunks_per_shard=[1, 2, 4, 8, 16, 32], seed=4)
+
+
+def make_partials(seed: int, peers: int, rows: int, N: int) -> np.ndarray:
+    """``[peers, rows, N]`` bf16 bits ~N(0,1): the partial row blocks the GPUs of a reduce-scatter hold
+    for one receiver (a GEMM output with unit-variance entries, like C of the configs)."""
+    return normal_bf16(seed, TENSOR_P, peers * rows, N, 1.0).reshape(peers, rows, N)
 
 
 def to_k_sliced(A: np.ndarray, slices: int) -> np.ndarray:
