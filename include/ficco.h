@@ -267,6 +267,28 @@ int ficco_run(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_
               void *const *peer_out, void *compute_stream, void *copy_stream);
 
 /*
+ * Receiver side of a true reduce-scatter (the paper leaves it out because a DMA engine cannot add,
+ * Sec. V): this GPU owns row block `block` of the output; every other GPU j sends its partial block.
+ *   P_src  - [shards][M/shards][N] bf16, the peers' partial blocks where they come from (device
+ *            staging or pinned host memory; slot `block` is never read)
+ *   P_dev  - [shards][M/shards][N] bf16 device landing buffer, written by the transfers (slot `block`
+ *            is not touched)
+ *   own    - [M/shards][N] bf16 device, this GPU's own partial block (for instance rows
+ *            [block*M/shards, ...) of the C_dev a GEMM_RS run produced earlier on `stream`)
+ *   out    - [M/shards][N] bf16 device: out[i][j] = bf16_rne(x_0[i][j] + x_1[i][j] + ... ), the sum
+ *            taken in fp32 in ascending GPU order with x_block = own and the others from P_dev
+ * A block travels in `chunks` row pieces per peer, in the plan's arrival order and pattern (all
+ * links side by side in step-major order; one transfer after the other for FICCO_SHARD and
+ * FICCO_ORDER_SHARD_MAJOR), on the copy engines; one reduction launch is enqueued first on `stream`
+ * and every tile waits (bounded, as in ficco_run) for the pieces it adds. With FICCO_SERIAL or
+ * chunks = 1 a tile needs every transfer, which is the serial "receive, then add" execution.
+ * ficco_query_stats() reports wall time, copy spans, and flops = the additions made. Not for
+ * FICCO_FINE_2D plans; FICCO_OPT_COPY_BACKEND must not be STREAM.
+ */
+int ficco_rs_reduce(ficco_plan_t *plan, int block, const void *P_src, void *P_dev, const void *own,
+                    void *out, void *stream);
+
+/*
  * Capture one run of the plan into a HIP graph (the paper notes the cost of enqueueing many small
  * operations, Sec. IV-B; a graph replays the whole run with one call). For the per-launch schedules
  * (SERIAL, SHARD, FINE_UNFUSED, FINE_FUSED) in FICCO_MODE_PAIR on the stream backend, with the far

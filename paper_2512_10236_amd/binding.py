@@ -65,7 +65,7 @@ class ficco_losses_t(C.Structure):
 
 
 EXPORTS = ["ficco_plan", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
-           "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
+           "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
            "ficco_pick_schedule", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
@@ -97,6 +97,7 @@ def load():
     lib.ficco_run.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp]
     lib.ficco_graph_capture.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp)]
     lib.ficco_graph_launch.argtypes = [vp, vp]
+    lib.ficco_rs_reduce.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
     lib.ficco_query_stats.argtypes = [vp, C.POINTER(ficco_stats_t)]
     lib.ficco_query_spans.argtypes = [vp, dp, dp, C.c_int, dp, dp, C.c_int]
     lib.ficco_profile_losses.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(ficco_losses_t)]
@@ -190,6 +191,11 @@ def ficco_graph_capture(plan, A_src, A_dev, W_dev, C_dev, peer_out):
         peers = (C.c_void_p * len(peer_out))(*[_ptr(p) for p in peer_out])
     return _ok(load().ficco_graph_capture(plan, _ptr(A_src), _ptr(A_dev), _ptr(W_dev), _ptr(C_dev), peers),
                "ficco_graph_capture")
+
+
+def ficco_rs_reduce(plan, block, P_src, P_dev, own, out, stream):
+    return _ok(load().ficco_rs_reduce(plan, block, _ptr(P_src), _ptr(P_dev), _ptr(own), _ptr(out), _ptr(stream)),
+               "ficco_rs_reduce")
 
 
 def ficco_graph_launch(plan, stream):

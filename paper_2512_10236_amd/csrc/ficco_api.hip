@@ -166,6 +166,8 @@ struct ficco_plan_s {
     uint64_t *d_sig_value = nullptr;                 // device table: address of each data signal's value word
     int sig_poll = -1;                               // -1 unknown, 0 flags by 4-byte copies, 1 kernels poll the signals
     bool last_engines = false;
+    bool last_reduce = false;                       // last run was ficco_rs_reduce (flops are adds, not a GEMM)
+    int last_skip_shard = -1;                       // shard whose pieces the last run did not move (local shard, own block)
     double last_engine_copy_span_us = 0, last_engine_copy_busy_us = 0;
 
     // run state
@@ -515,29 +517,21 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     return FICCO_OK;
 }
 
-int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, void *const *peer_out,
-                hipStream_t cs, bool src_dev, const std::vector<char> &peer_dev)
+// What every run on the copy-engine backend needs before it submits anything: the runtime, one
+// validated engine per emulated link (eng, links), one pair of completion signals per piece (plus the
+// Gather / Scatter signals of a packing plan), and - decided once per plan - whether kernels can watch
+// the signals' value words directly (p->sig_poll).
+int engines_prepare(ficco_plan_t *p, bool touches_host, std::vector<int> &eng, int &links)
 {
-    const bool rs = p->direction == FICCO_DIR_GEMM_RS;
-    const int mode = p->mode;
-    const bool do_copy = mode != FICCO_MODE_GEMM_ONLY;
-    const bool do_gemm = mode != FICCO_MODE_COPY_ONLY;
-    const bool dependent = mode == FICCO_MODE_PAIR;
-    const bool timing = p->timing != 0;
-    const int n = p->n_chunks, c = p->c;
+    const int n = p->n_chunks;
     int rc = engines_init(p->device);
     if (rc) return rc;
     EngineCtx &ctx = g_engines;
 
     // engines: one per emulated link
-    bool touches_host = !src_dev;
-    if (rs) {
-        touches_host = false;
-        for (int j = 0; j < p->G; ++j) touches_host |= !peer_dev[j];
-    }
-    int links = p->links_opt > 0 ? p->links_opt : p->G;
+    links = p->links_opt > 0 ? p->links_opt : p->G;
     links = std::min(links, 16);
-    std::vector<int> eng = usable_engines(touches_host, links, p->d_status + kFlagStrideWords);
+    eng = usable_engines(touches_host, links, p->d_status + kFlagStrideWords);
     if (eng.empty()) { if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: no usable engine\n"); return FICCO_ERR_HIP; }
     links = std::min(links, (int)eng.size());
     p->links = links;
@@ -550,7 +544,6 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (hsa_signal_create(0, 0, nullptr, &b) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
         p->sig_flag.push_back(b);
     }
-    const bool packed = p->packing && dependent && do_copy && do_gemm && !rs;
     if (p->packing) {
         for (auto *v : {&p->sig_gather, &p->sig_scatter})
             while ((int)v->size() < n) {
@@ -594,6 +587,31 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         }
         if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: kernels %s\n", p->sig_poll ? "poll the transfers' completion signals" : "wait on flags raised by 4-byte copies");
     }
+    return FICCO_OK;
+}
+
+int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, void *const *peer_out,
+                hipStream_t cs, bool src_dev, const std::vector<char> &peer_dev)
+{
+    const bool rs = p->direction == FICCO_DIR_GEMM_RS;
+    const int mode = p->mode;
+    const bool do_copy = mode != FICCO_MODE_GEMM_ONLY;
+    const bool do_gemm = mode != FICCO_MODE_COPY_ONLY;
+    const bool dependent = mode == FICCO_MODE_PAIR;
+    const bool timing = p->timing != 0;
+    const int n = p->n_chunks, c = p->c;
+    // engines: one per emulated link
+    bool touches_host = !src_dev;
+    if (rs) {
+        touches_host = false;
+        for (int j = 0; j < p->G; ++j) touches_host |= !peer_dev[j];
+    }
+    std::vector<int> eng;
+    int links = 0;
+    int rc = engines_prepare(p, touches_host, eng, links);
+    if (rc) return rc;
+    EngineCtx &ctx = g_engines;
+    const bool packed = p->packing && dependent && do_copy && do_gemm && !rs;
     // Signals live in host memory: when the transfers themselves cross the host link, hundreds of
     // polling workgroups would compete with them for it, so flags in device memory are used then.
     const bool poll_signals = p->sig_poll == 1 && !p->hold_flags && !touches_host;
@@ -850,6 +868,8 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     p->last_engines = true;
     p->last_lean = false;
     p->last_graph = false;
+    p->last_skip_shard = rs ? -1 : p->local_shard;
+    p->last_reduce = false;
     return FICCO_OK;
 }
 
@@ -1339,6 +1359,8 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     if (do_copy) HIP_TRY(hipStreamWaitEvent(xs, p->ev_end, 0));
     p->last_lean = lean;
     p->last_graph = false;
+    p->last_skip_shard = rs ? -1 : p->local_shard;
+    p->last_reduce = false;
 
     p->last_had_copies = n_copies > 0;
     p->last_had_gemm = n_launches > 0;
@@ -1346,6 +1368,99 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     p->last_copy_bytes = copy_bytes;
     p->last_n_copies = n_copies;
     p->last_n_launches = n_launches;
+    return FICCO_OK;
+}
+
+int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, const void *own, void *out, void *stream)
+{
+    if (!p || !P_src || !P_dev || !own || !out) return FICCO_ERR_ARG;
+    if (is_2d(p) || block < 0 || block >= p->G) return FICCO_ERR_ARG;
+    if (p->backend_opt == FICCO_COPY_STREAM || p->flag_write == 1) return FICCO_ERR_ARG;   // copy engines only
+    hipStream_t cs = (hipStream_t)stream;
+    int rc = finalize(p);
+    if (rc) return rc;
+    bool dev = false, src_dev = false;
+    for (const void *ptr : {(const void *)P_dev, own, (const void *)out}) {
+        rc = is_device_ptr(ptr, &dev);
+        if (rc || !dev) return FICCO_ERR_ARG;
+    }
+    if ((rc = is_device_ptr(P_src, &src_dev))) return rc;
+    const int n = p->n_chunks, c = p->c;
+    const bool touches_host = !src_dev;
+    std::vector<int> eng;
+    int links = 0;
+    if ((rc = engines_prepare(p, touches_host, eng, links))) return rc;
+    EngineCtx &ctx = g_engines;
+    p->backend = FICCO_COPY_ENGINES;
+    const bool poll_signals = p->sig_poll == 1 && !p->hold_flags && !touches_host;
+    if (p->run_index > 0) {
+        HIP_TRY(hipEventSynchronize(p->ev_end));
+        for (int i = 0; i < n; ++i)
+            if (!wait_signal(p->sig_data[i], 5.0) || !wait_signal(p->sig_flag[i], 5.0)) return FICCO_ERR_TIMEOUT;
+    }
+    p->run_index += 1;
+    const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
+    const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
+    const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, (uint32_t *)p->h_status, spin_ticks};
+    for (int i = 0; i < n; ++i) {
+        hsa_signal_store_relaxed(p->sig_data[i], i / c == block ? 0 : 1);
+        hsa_signal_store_relaxed(p->sig_flag[i], 0);
+    }
+    const size_t piece_bytes = (size_t)p->m * (size_t)p->N * 2;
+
+    // the reduction is enqueued first: its tiles wait for their pieces
+    ReduceLaunch r{};
+    r.in = (const uint16_t *)P_dev;
+    r.own = (const uint16_t *)own;
+    r.out = (uint16_t *)out;
+    r.piece_vecs = (int64_t)(piece_bytes / 16);
+    r.G = p->G; r.block = block; r.pieces = c; r.gated = 1;
+    r.gate = gate;
+    int grid = reduce_grid_size(p->device);
+    if (grid <= 0) return FICCO_ERR_HIP;
+    const int64_t tiles = (int64_t)c * ((r.piece_vecs + 1023) / 1024);
+    if (tiles < grid) grid = (int)tiles;
+    HIP_TRY(hipEventRecord(p->ev_begin, cs));
+    HIP_TRY(launch_reduce(r, grid, cs));
+    HIP_TRY(hipEventRecord(p->ev_end, cs));
+
+    // incoming partial blocks: piece s of peer j's block travels on link j; side by side in step-major
+    // order (all links at once), one after the other for the shard-level and shard-major patterns
+    const bool chained = p->schedule == FICCO_SHARD || (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
+    int n_copies = 0, prev_chunk = -1;
+    int64_t copy_bytes = 0;
+    for (int q = 0; q < n; ++q) {
+        const int chunk = p->arrival[q];
+        if (chunk / c == block) continue;
+        const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[(chunk / c) % links]);
+        hsa_signal_t dep{};
+        int ndep = 0;
+        if (chained && prev_chunk >= 0) { dep = p->sig_data[prev_chunk]; ndep = 1; }
+        hsa_status_t st = hsa_amd_memory_async_copy_on_engine((char *)P_dev + (size_t)chunk * piece_bytes, ctx.gpu,
+                                                              (const char *)P_src + (size_t)chunk * piece_bytes, src_dev ? ctx.gpu : ctx.cpu,
+                                                              piece_bytes, ndep, ndep ? &dep : nullptr, p->sig_data[chunk], engine, src_dev);
+        if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        prev_chunk = chunk;
+        ++n_copies;
+        copy_bytes += (int64_t)piece_bytes;
+        if (!poll_signals && !p->hold_flags) {
+            hsa_signal_store_relaxed(p->sig_flag[chunk], 1);
+            st = hsa_amd_memory_async_copy_on_engine(p->d_flags + (size_t)chunk * kFlagStrideWords, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4,
+                                                     1, &p->sig_data[chunk], p->sig_flag[chunk], engine, false);
+            if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[chunk], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        }
+    }
+    p->last_had_copies = n_copies > 0;
+    p->last_had_gemm = false;
+    p->last_timing = false;
+    p->last_copy_bytes = copy_bytes;
+    p->last_n_copies = n_copies;
+    p->last_n_launches = 1;
+    p->last_engines = true;
+    p->last_lean = false;
+    p->last_graph = false;
+    p->last_skip_shard = block;
+    p->last_reduce = true;
     return FICCO_OK;
 }
 
@@ -1418,6 +1533,7 @@ int ficco_graph_launch(ficco_plan_t *p, void *stream)
     HIP_TRY(hipEventRecord(p->ev_end, s));
     p->run_index += 1;
     p->last_graph = true;
+    p->last_reduce = false;
     p->last_engines = false;
     p->last_lean = false;
     p->last_had_copies = false;
@@ -1452,7 +1568,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         double busy = 0;
         for (int q = 0; q < p->n_chunks; ++q) {
             const int chunk = p->arrival[q];
-            if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
+            if (p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) continue;
             if (!wait_signal(p->sig_data[p->arrival[q]], 5.0) || !wait_signal(p->sig_flag[p->arrival[q]], 5.0)) {
                 if (getenv("FICCO_DEBUG"))
                     fprintf(stderr, "ficco: transfer %d (chunk %d) did not complete: data signal %lld flag signal %lld\n", q, chunk,
@@ -1492,7 +1608,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         if (p->last_had_copies && !p->last_engines) {
             for (int q = 0; q < p->n_chunks; ++q) {
                 const int chunk = p->arrival[q];
-                if (p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard) continue;
+                if (p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) continue;
                 HIP_TRY(hipEventElapsedTime(&ms, p->ev_copy_b[q], p->ev_copy_e[q]));
                 cb += ms * 1e3;
             }
@@ -1514,7 +1630,8 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
                     (tf[q].start - t0) / g_engines.ticks_per_us, (tf[q].end - t0) / g_engines.ticks_per_us);
     }
     s.exposed_comm_us = s.wall_us - s.gemm_busy_us;
-    s.flops = 2 * p->M * p->N * p->K;
+    s.flops = p->last_reduce ? (int64_t)(p->G - 1) * (p->M / p->G) * p->N      // the reduction's additions
+                             : 2 * p->M * p->N * p->K;
     s.eff_tflops = s.wall_us > 0 ? (double)s.flops / s.wall_us * 1e-6 : 0.0;
     s.copy_bytes = p->last_copy_bytes;
     s.copy_gbps = s.copy_span_us > 0 ? (double)s.copy_bytes / s.copy_span_us * 1e-3 : 0.0;
@@ -1566,7 +1683,7 @@ int ficco_query_spans(ficco_plan_t *p, double *copy_begin_us, double *copy_end_u
         if (cap_chunks < p->n_chunks) return FICCO_ERR_ARG;
         for (int q = 0; q < p->n_chunks; ++q) {
             const int chunk = p->arrival[q];
-            const bool local = p->direction == FICCO_DIR_AG_GEMM && p->local_shard >= 0 && chunk / p->c == p->local_shard;
+            const bool local = p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard;
             double b = 0, e = 0;
             if (p->last_had_copies && !local && p->last_engines) {
                 // engine timestamps live on another clock: reported relative to the run's first transfer

@@ -96,6 +96,21 @@ struct Resident2DLaunch {
     int32_t gated;                // 0: operands resident, no waiting
 };
 
+// One receiver-side reduction (see ficco_reduce.hip): `in` is the landing buffer [G][rows][N] of the
+// peers' partial blocks (slot `block` is not read), `own` this GPU's own partial block, `out` the
+// reduced block; a block is `pieces` pieces of piece_vecs 16-byte vectors each; piece s of peer p is
+// gate piece p * pieces + s.
+struct ReduceLaunch {
+    const uint16_t *in;
+    const uint16_t *own;
+    uint16_t *out;
+    int64_t piece_vecs;
+    int32_t G, block, pieces, gated;
+    Gate gate;
+};
+hipError_t launch_reduce(const ReduceLaunch &r, int grid, hipStream_t s);
+int reduce_grid_size(int device);
+
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s);
 hipError_t launch_resident2d(int tile, const Resident2DLaunch &a, hipStream_t s);
 int resident2d_grid_size(int tile, int device);
