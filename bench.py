@@ -14,6 +14,9 @@ Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192
   losses    - decomposition / contention losses (DIL, CIL) through ficco_profile_losses
   cpu       - the CPU oracle timed on the host cores (a baseline, not a target)
   graph     - (not run by default) HIP-graph replays against call-by-call enqueue, stream backend
+  reduce    - (not run by default) receiver side of the reduce-scatter on the workload's output block:
+              serial / shard-level / finer-grain step times and the add kernel against the HBM roofline
+              (reduce_kernel: the kernel part only, for profiling)
   calib     - (not in the default set) a plain device copy of 256 MiB, so that HBM counters read
               under rocprofv3 --pmc can be scaled by what they show for a known amount of traffic
 """
@@ -43,6 +46,7 @@ PMC_KIB = {
     ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754151.5, "WRITE_SIZE": 114753.3},
     ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 878411.3, "WRITE_SIZE": 32851.9},
     ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 523875.9, "WRITE_SIZE": 32894.0},
+    ("cfg4_gemm_rs", "rs_reduce_kernel"): {"FETCH_SIZE": 131151.5, "WRITE_SIZE": 32768.0},      # profiles/rs_reduce_cfg4_gemm_rs.md
 }
 
 
@@ -316,6 +320,72 @@ def main() -> int:
             F.ficco_destroy(plan)
             res[f"{sname}:{c}"] = row
         out["graph"] = res
+
+    if "reduce" in legs or "reduce_kernel" in legs:
+        # receiver side of the reduce-scatter: G-1 partial blocks [M/G, N] arrive over the links and are added
+        # to this GPU's own; serial (receive, then add) against pieces added as they land
+        from oracle import reduce as orr
+        rows = M // G
+        x = fi.make_partials(cfg["seed"], G, rows, N)
+        P_stage = torch.from_numpy(x.view(np.int16)).to(dev)
+        P_land = torch.zeros((G, rows, N), dtype=torch.int16, device=dev)
+        own = P_stage[0].clone()
+        red = torch.zeros((rows, N), dtype=torch.int16, device=dev)
+        torch.cuda.synchronize()
+
+        def reduce_plan(sched, c, opts=()):
+            plan = F.ficco_plan(M, K, N, G, c, sched)
+            for o, v in opts:
+                F.ficco_plan_set(plan, o, v)
+            return plan
+
+        def reduce_steps(plan, steps, warmup):
+            for _ in range(warmup):
+                F.ficco_rs_reduce(plan, 0, P_stage, P_land, own, red, cs)
+                F.ficco_query_stats(plan)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                F.ficco_rs_reduce(plan, 0, P_stage, P_land, own, red, cs)
+                st = F.ficco_query_stats(plan)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps, st
+
+        rres = {}
+        cases = [("serial", F.FICCO_SERIAL, 1), ("shard_level", F.FICCO_SHARD, 1)] + \
+                [(f"fine:{c}", F.FICCO_FINE_FUSED, c) for c in (2, 4, 8, 16) if rows % c == 0]
+        for name, sched, c in (cases if "reduce" in legs else cases[2:3]):      # reduce_kernel: one pass, for the parity check
+            plan = reduce_plan(sched, c)
+            ms, st = reduce_steps(plan, args.steps if "reduce" in legs else 1, args.warmup if "reduce" in legs else 0)
+            F.ficco_destroy(plan)
+            rres[name] = round(ms, 4)
+        best_name = min((k for k in rres if k.startswith("fine")), key=rres.get)
+        got = red.cpu().numpy().view(np.uint16)
+        # the kernel alone, landing buffer resident: HIP events recorded on the stream around each launch
+        plan = reduce_plan(F.FICCO_FINE_FUSED, int(best_name.split(":")[1]), [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY)])
+        spans = []
+        for it in range(args.warmup + args.steps):
+            F.ficco_rs_reduce(plan, 0, P_stage, P_land, own, red, cs)
+            st = F.ficco_query_stats(plan)
+            if it >= args.warmup:
+                spans.append(st.wall_us)
+        F.ficco_destroy(plan)
+        us = float(np.mean(spans))
+        alg_bytes = (G + 1) * rows * N * 2
+        t0 = time.perf_counter()
+        want = orr.rs_reduce(list(x))
+        dt = time.perf_counter() - t0
+        out["reduce"] = {"block": [rows, N], "peers": G, "ms_per_step": rres if "reduce" in legs else None, "best": best_name,
+                         "speedup_vs_serial": round(rres["serial"] / rres[best_name], 4) if "reduce" in legs else None,
+                         "speedup_vs_shard_level": round(rres["shard_level"] / rres[best_name], 4) if "reduce" in legs else None,
+                         "bits_equal_oracle": bool(np.array_equal(got, want)),
+                         "roofline": {"bound": "hbm", "achieved": round(alg_bytes / us * 1e-3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                      "frac": round(alg_bytes / us * 1e-3 / HBM_PEAK_GBPS, 4),
+                                      "traffic": (lambda t: int(sum(t[k] * PMC_SCALE[k] for k in t) * 1024) if t else None)(
+                                          PMC_KIB.get((args.workload, "rs_reduce_kernel"))),
+                                      "algorithmic_bytes": alg_bytes, "kernel": "rs_reduce_kernel", "avg_launch_us": round(us, 3)},
+                         "cpu_baseline": {"value": round(alg_bytes / dt * 1e-9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                          "sample": f"the whole block, {dt:.2f} s"}}
 
     if "calib" in legs:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

@@ -1386,6 +1386,10 @@ int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, 
     }
     if ((rc = is_device_ptr(P_src, &src_dev))) return rc;
     const int n = p->n_chunks, c = p->c;
+    // modes as in ficco_run: the pair, the reduction alone on a landing buffer that is already filled,
+    // the transfers alone, or both without dependency
+    const bool do_copy = p->mode != FICCO_MODE_GEMM_ONLY, do_add = p->mode != FICCO_MODE_COPY_ONLY;
+    const bool dependent = p->mode == FICCO_MODE_PAIR;
     const bool touches_host = !src_dev;
     std::vector<int> eng;
     int links = 0;
@@ -1403,7 +1407,7 @@ int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, 
     const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
     const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, (uint32_t *)p->h_status, spin_ticks};
     for (int i = 0; i < n; ++i) {
-        hsa_signal_store_relaxed(p->sig_data[i], i / c == block ? 0 : 1);
+        hsa_signal_store_relaxed(p->sig_data[i], (i / c == block || !do_copy) ? 0 : 1);
         hsa_signal_store_relaxed(p->sig_flag[i], 0);
     }
     const size_t piece_bytes = (size_t)p->m * (size_t)p->N * 2;
@@ -1414,14 +1418,25 @@ int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, 
     r.own = (const uint16_t *)own;
     r.out = (uint16_t *)out;
     r.piece_vecs = (int64_t)(piece_bytes / 16);
-    r.G = p->G; r.block = block; r.pieces = c; r.gated = 1;
+    r.G = p->G; r.block = block; r.pieces = c; r.gated = dependent ? 1 : 0;
     r.gate = gate;
     int grid = reduce_grid_size(p->device);
     if (grid <= 0) return FICCO_ERR_HIP;
     const int64_t tiles = (int64_t)c * ((r.piece_vecs + 1023) / 1024);
     if (tiles < grid) grid = (int)tiles;
     HIP_TRY(hipEventRecord(p->ev_begin, cs));
-    HIP_TRY(launch_reduce(r, grid, cs));
+    if (do_add) HIP_TRY(launch_reduce(r, grid, cs));
+    if (do_copy && !dependent && !p->hold_flags) {
+        // nothing on the stream consumes the flags: join through the small waiting kernel, one launch per
+        // run of arrival positions that belong to other blocks (the receiver's own pieces never travel)
+        for (int q = 0; q < n;) {
+            if (p->arrival[q] / c == block) { ++q; continue; }
+            int e = q;
+            while (e < n && p->arrival[e] / c != block) ++e;
+            HIP_TRY(launch_wait_ready(gate, p->d_arrival + q, e - q, cs));
+            q = e;
+        }
+    }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
 
     // incoming partial blocks: piece s of peer j's block travels on link j; side by side in step-major
@@ -1429,7 +1444,7 @@ int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, 
     const bool chained = p->schedule == FICCO_SHARD || (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
     int n_copies = 0, prev_chunk = -1;
     int64_t copy_bytes = 0;
-    for (int q = 0; q < n; ++q) {
+    for (int q = 0; q < n && do_copy; ++q) {
         const int chunk = p->arrival[q];
         if (chunk / c == block) continue;
         const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[(chunk / c) % links]);
@@ -1455,7 +1470,7 @@ int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, 
     p->last_timing = false;
     p->last_copy_bytes = copy_bytes;
     p->last_n_copies = n_copies;
-    p->last_n_launches = 1;
+    p->last_n_launches = do_add ? 1 : 0;
     p->last_engines = true;
     p->last_lean = false;
     p->last_graph = false;

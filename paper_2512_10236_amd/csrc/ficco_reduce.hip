@@ -66,9 +66,22 @@ __global__ __launch_bounds__(256) void rs_reduce_kernel(ReduceLaunch r)
         const int s = t / tiles_per_piece, tt = t % tiles_per_piece;
         if (r.gated) {
             if (threadIdx.x == 0) {
+                // Only the first tile of a piece watches the G-1 transfers (their signals live in host
+                // memory: thousands of workgroups polling them would swamp the host link). It then raises
+                // the piece's word in device memory - the flag slot of the receiver's own piece, which no
+                // transfer ever uses - and the piece's other tiles wait on that word.
+                const int mine = r.block * r.pieces + s;
                 int ok = 1;
-                for (int p = 0; p < r.G && ok; ++p)
-                    if (p != r.block) ok = piece_ready(r.gate, p * r.pieces + s);
+                if (tt == 0) {
+                    for (int p = 0; p < r.G && ok; ++p)
+                        if (p != r.block) ok = piece_ready(r.gate, p * r.pieces + s);
+                    if (ok) __hip_atomic_store(const_cast<uint32_t *>(r.gate.flags) + (size_t)mine * kFlagStrideWords, r.gate.epoch,
+                                               __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                } else {
+                    Gate word = r.gate;
+                    word.sig_value = nullptr;          // wait on the flag word, whatever the transfers are watched through
+                    ok = piece_ready(word, mine);
+                }
                 s_ok = ok;
             }
             __syncthreads();               // also orders the tile's loads after the flag reads
