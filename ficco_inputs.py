@@ -23,6 +23,7 @@ import numpy as np
 TENSOR_A = 0
 TENSOR_W = 1
 TENSOR_P = 2          # peers' partial output blocks (receiver side of a reduce-scatter)
+TENSOR_T = 3          # token counts of an expert-parallel dispatch
 
 _MASK64 = np.uint64(0xFFFFFFFFFFFFFFFF)
 
@@ -109,6 +110,10 @@ CONFIGS = {
     # GEMM -> reduce-scatter share (data movement half): output streamed out in 8 row blocks
     "cfg4_gemm_rs": dict(M=16384, K=3584, N=8192, shards=8, chunk_rows=[2048, 512], seed=3,
                          direction="gemm_rs"),
+    # expert-parallel dispatch -> grouped expert GEMM: 8 peers send unequal token counts to 2 local experts
+    # (Mixtral-like expert width: K = 4096, N = a quarter of the fused gate+up projection)
+    "cfg7_ep_grouped": dict(K=4096, N=7168, shards=8, experts=2, tokens=16384, skew=0.6, pieces=[1, 2, 4, 8], seed=6,
+                            direction="ep_grouped"),
     # M <= K share (row-parallel projection at a small token count): the shape the paper's rule sends
     # to the 2D decomposition; ``k_slices`` lists the slice counts exercised
     "cfg6_2d_proj": dict(M=4096, K=16384, N=4096, shards=8, chunk_rows=[512, 256, 128], k_slices=[2, 4, 8], seed=5,
@@ -124,6 +129,18 @@ def make_partials(seed: int, peers: int, rows: int, N: int) -> np.ndarray:
     """``[peers, rows, N]`` bf16 bits ~N(0,1): the partial row blocks the GPUs of a reduce-scatter hold
     for one receiver (a GEMM output with unit-variance entries, like C of the configs)."""
     return normal_bf16(seed, TENSOR_P, peers * rows, N, 1.0).reshape(peers, rows, N)
+
+
+def make_token_counts(seed: int, peers: int, experts: int, total: int, skew: float = 0.6) -> np.ndarray:
+    """``[peers, experts]`` token counts that sum to ``total``: log-normal shares (sigma = ``skew``), the
+    kind of imbalance a learned router produces; deterministic in the seed. ``skew`` 0 gives equal shares."""
+    z = standard_normal_f64(seed, TENSOR_T, 0, peers * experts)
+    w = np.exp(skew * z)
+    share = w / w.sum() * total
+    counts = np.floor(share).astype(np.int64)
+    order = np.argsort(-(share - counts), kind="stable")
+    counts[order[: total - int(counts.sum())]] += 1          # largest remainders get the leftover rows
+    return counts.reshape(peers, experts)
 
 
 def to_k_sliced(A: np.ndarray, slices: int) -> np.ndarray:

@@ -9,6 +9,8 @@ this package. It imports nothing from the HIP package and the HIP package import
                            descriptors OTB and MT (Sec. IV-B, IV-C), the ideal-overlap model and
                            the DIL/CIL ratios (Sec. IV-A), and the schedule heuristic's decision
                            rule (Sec. V-C), in plain Python.
+* :mod:`oracle.grouped`  - expert-parallel dispatch -> grouped expert GEMM: piece layout for unequal
+                           per-peer token counts and the per-expert products.
 * :mod:`oracle.reduce`   - the adding half of a reduce-scatter (fp32 in ascending GPU order, one
                            rounding), in numpy.
 """
