@@ -218,6 +218,31 @@ typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this p
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule,
                ficco_plan_t **out);
 
+/*
+ * Plan for an expert-parallel dispatch followed by the expert layers' GEMM (the all-to-all of
+ * Sec. II-A; the amounts differ per pair of GPUs, Sec. III-C): this GPU hosts `experts` experts with
+ * weights W_e [K,N]; peer j sends rows[j*experts + e] >= 0 token rows for expert e. Every (peer, expert)
+ * block is cut into `chunks` pieces as equal as integers allow (the first T mod chunks one row longer).
+ * Piece (e, s, j) has id (e*chunks + s)*peers + j; rows are laid out in id order, i.e. expert-major,
+ * then step, then peer (ficco_plan_pieces() reports first row and row count of every piece), in
+ * A_src, A_dev [M,K] and C_dev [M,N] alike, M = the sum of `rows`; W_dev is [experts][K][N].
+ * C row r = A row r times the weight of the expert whose segment holds r.
+ * Schedules: FICCO_SERIAL (every tile waits for every transfer), FICCO_SHARD (whole blocks, one
+ * peer after the other, a tile waits for its own blocks), FICCO_FINE_PERSISTENT (step s moves
+ * piece s of every peer over all links; FICCO_ORDER_SHARD_MAJOR: peer by peer). One resident
+ * grouped kernel in all three; transfers on the copy engines, peer j on link j; ficco_run() as for
+ * the all-gather direction (peer_out NULL). Not available: GEMM_RS, LOCAL_SHARD, PACKING, TIMING,
+ * the stream backend, ficco_profile_losses, graphs.
+ * Shape rules: K % 64 == 0, N % 8 == 0, peers*experts*chunks <= 4096, 1 <= M < 2^31, chunks == 1
+ * for SERIAL and SHARD.
+ */
+int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64_t *rows, int chunks,
+                       int schedule, ficco_plan_t **out);
+
+/* First row and row count of every piece, by piece id (host arrays of at least n_chunks entries,
+ * either may be NULL). For ordinary plans all pieces have chunk_rows rows. */
+int ficco_plan_pieces(const ficco_plan_t *plan, int64_t *row0, int64_t *rows, int cap);
+
 /* Set an option; only before the plan's first use (FICCO_ERR_STATE afterwards), except
  * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US and FICCO_OPT_HOLD_FLAGS, which may
  * change between runs. */

@@ -64,7 +64,7 @@ class ficco_losses_t(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
-EXPORTS = ["ficco_plan", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
+EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
            "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
            "ficco_pick_schedule", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
@@ -89,6 +89,8 @@ def load():
     vp, i64, i32p = C.c_void_p, C.c_int64, C.POINTER(C.c_int32)
     dp = C.POINTER(C.c_double)
     lib.ficco_plan.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ficco_plan_grouped.argtypes = [i64, i64, C.c_int, C.c_int, C.POINTER(i64), C.c_int, C.c_int, C.POINTER(vp)]
+    lib.ficco_plan_pieces.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.c_int]
     lib.ficco_plan_set.argtypes = [vp, C.c_int, i64]
     lib.ficco_plan_set_arrival.argtypes = [vp, i32p, C.c_int]
     lib.ficco_plan_info.argtypes = [vp, C.POINTER(ficco_plan_info_t)]
@@ -149,6 +151,22 @@ def ficco_plan(M, K, N, shards, chunks, schedule):
     out = C.c_void_p()
     _ok(load().ficco_plan(M, K, N, shards, chunks, schedule, C.byref(out)), "ficco_plan")
     return out
+
+
+def ficco_plan_grouped(K, N, rows, chunks, schedule):
+    """``rows``: nested sequence ``[peers][experts]`` of token counts."""
+    peers, experts = len(rows), len(rows[0])
+    flat = (C.c_int64 * (peers * experts))(*[int(rows[j][e]) for j in range(peers) for e in range(experts)])
+    out = C.c_void_p()
+    _ok(load().ficco_plan_grouped(K, N, peers, experts, flat, chunks, schedule, C.byref(out)), "ficco_plan_grouped")
+    return out
+
+
+def ficco_plan_pieces(plan):
+    n = ficco_plan_info(plan).n_chunks
+    r0, nr = (C.c_int64 * n)(), (C.c_int64 * n)()
+    _ok(load().ficco_plan_pieces(plan, r0, nr, n), "ficco_plan_pieces")
+    return list(r0), list(nr)
 
 
 def ficco_plan_set(plan, option, value):

@@ -123,6 +123,14 @@ struct ficco_plan_s {
     int64_t spin_limit_us = 2000000;
     int backend_opt = FICCO_COPY_AUTO, links_opt = 0;
     int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
+    // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
+    bool grouped = false;
+    int E = 1;
+    std::vector<int64_t> token_rows;     // [G][E]
+    std::vector<int64_t> piece_row0, piece_nrows;   // by piece id
+    std::vector<int64_t> expert_row0, expert_nrows;
+    int32_t *d_row_tiles = nullptr;
+    int n_row_tiles = 0;
     int backend = 0, links = 0;             // as resolved by the last run
     int device = 0;
     int n_chunks = 0;
@@ -185,8 +193,50 @@ inline bool is_resident(const ficco_plan_t *p) { return p->schedule == FICCO_FIN
 // shard a piece belongs to: row pieces are numbered shard-major (j*c + s), column pieces slice-major (s*G + j)
 inline int shard_of(const ficco_plan_t *p, int chunk) { return is_2d(p) ? chunk % p->G : chunk / p->c; }
 
+// Grouped plans: piece (e, s, j) has id (e*c + s)*G + j; the T[j][e] rows of a (peer, expert) block are cut
+// into c pieces as equal as integers allow (the first T mod c one row longer); rows follow in id
+// order, so an expert's rows are contiguous and, inside them, what arrives in one step.
+int build_lists_grouped(ficco_plan_t *p)
+{
+    const int G = p->G, c = p->c, E = p->E, n = E * c * G;
+    p->n_chunks = n;
+    p->m = 0;
+    p->piece_nrows.assign(n, 0);
+    p->piece_row0.assign(n, 0);
+    p->expert_row0.assign(E, 0);
+    p->expert_nrows.assign(E, 0);
+    for (int e = 0; e < E; ++e)
+        for (int j = 0; j < G; ++j) {
+            const int64_t T = p->token_rows[(size_t)j * E + e];
+            p->expert_nrows[e] += T;
+            for (int s = 0; s < c; ++s) p->piece_nrows[(size_t)(e * c + s) * G + j] = T / c + (s < T % c ? 1 : 0);
+        }
+    int64_t r = 0;
+    for (int i = 0; i < n; ++i) { p->piece_row0[i] = r; r += p->piece_nrows[i]; }
+    r = 0;
+    for (int e = 0; e < E; ++e) { p->expert_row0[e] = r; r += p->expert_nrows[e]; }
+    if (p->order != FICCO_ORDER_CUSTOM) {
+        p->arrival.clear();
+        const bool by_peer = p->schedule == FICCO_SHARD || p->order == FICCO_ORDER_SHARD_MAJOR;
+        if (by_peer) {
+            for (int j = 0; j < G; ++j)
+                for (int s = 0; s < c; ++s)
+                    for (int e = 0; e < E; ++e) p->arrival.push_back((e * c + s) * G + j);
+        } else {
+            for (int s = 0; s < c; ++s)
+                for (int j = 0; j < G; ++j)
+                    for (int e = 0; e < E; ++e) p->arrival.push_back((e * c + s) * G + j);
+        }
+    }
+    p->groups.clear();
+    p->groups.push_back({0, n});
+    p->group_of.assign(n, 0);
+    return FICCO_OK;
+}
+
 int build_lists(ficco_plan_t *p)
 {
+    if (p->grouped) return build_lists_grouped(p);
     const int G = p->G, c = p->c, n = G * c;
     p->n_chunks = n;
     p->m = is_2d(p) ? p->M / p->G : p->M / n;      // rows of one piece (column pieces keep the shard's rows)
@@ -270,7 +320,11 @@ int choose_tile(const ficco_plan_t *p, int cus)
             return full * (cd.base + cd.slope) + (rem > 0 ? cd.base + cd.slope * rem / cap : 0.0);
         };
         double total = 0;
-        if (is_2d(p)) {
+        if (p->grouped) {
+            int64_t rt = 0;
+            for (int64_t me : p->expert_nrows) rt += (me + ts.bm - 1) / ts.bm;
+            total = cost(rt * ((p->N + ts.bn - 1) / ts.bn));
+        } else if (is_2d(p)) {
             total = cost(((p->M + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
         } else if (p->schedule == FICCO_FINE_PERSISTENT) {
             total = cost((int64_t)p->n_chunks * ((p->m + ts.bm - 1) / ts.bm) * ((p->N + ts.bn - 1) / ts.bn));
@@ -311,6 +365,8 @@ void release(ficco_plan_t *p)
     p->d_ticket_mem = nullptr;
     if (p->d_tables) (void)hipFree(p->d_tables);
     if (p->d_wt) (void)hipFree(p->d_wt);
+    if (p->d_row_tiles) (void)hipFree(p->d_row_tiles);
+    p->d_row_tiles = nullptr;
     if (p->d_pack_a) (void)hipFree(p->d_pack_a);
     if (p->d_pack_c) (void)hipFree(p->d_pack_c);
     p->d_pack_a = p->d_pack_c = nullptr;
@@ -388,7 +444,41 @@ int finalize(ficco_plan_t *p)
     HIP_TRY(hipEventCreate(&p->ev_gemm_last));
     rc = make_events(p->ev_dep, p->groups.size());
     if (rc) return rc;
-    if (is_resident(p)) {
+    if (p->grouped) {
+        // row tiles never cross an expert's segment; each lists the pieces that cover its rows (all of
+        // them for the serial schedule); sorted by the step in which the last of those pieces arrives
+        TileShape ts = tile_shape(p->tile);
+        const int c = p->c, G = p->G;
+        struct RT { int64_t row0; int32_t rows, expert, first, last, step; };
+        std::vector<RT> rts;
+        for (int e = 0; e < p->E; ++e) {
+            int pc = e * c * G;                                   // first piece of the expert
+            const int pc_end = (e + 1) * c * G;
+            for (int64_t r0 = p->expert_row0[e]; r0 < p->expert_row0[e] + p->expert_nrows[e]; r0 += ts.bm) {
+                const int64_t r1 = std::min<int64_t>(r0 + ts.bm, p->expert_row0[e] + p->expert_nrows[e]);
+                while (pc < pc_end && p->piece_row0[pc] + p->piece_nrows[pc] <= r0) ++pc;
+                int last = pc;
+                while (last + 1 < pc_end && p->piece_row0[last + 1] < r1) ++last;
+                while (p->piece_nrows[last] == 0 && last > pc) --last;   // trailing pieces without rows cover nothing
+                RT t{r0, (int32_t)(r1 - r0), e, pc, last, (last / G) % c};
+                if (p->schedule == FICCO_SERIAL) { t.first = 0; t.last = n - 1; t.step = 0; }
+                rts.push_back(t);
+            }
+        }
+        std::stable_sort(rts.begin(), rts.end(), [](const RT &a, const RT &b) { return a.step < b.step; });
+        p->n_row_tiles = (int)rts.size();
+        std::vector<int32_t> tab((size_t)std::max<size_t>(rts.size(), 1) * kRowTileWords, 0);
+        for (size_t i = 0; i < rts.size(); ++i) {
+            int32_t *w = &tab[i * kRowTileWords];
+            w[0] = (int32_t)rts[i].row0; w[1] = rts[i].rows; w[2] = rts[i].expert; w[3] = rts[i].first; w[4] = rts[i].last;
+        }
+        if (hipMalloc((void **)&p->d_row_tiles, tab.size() * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+        HIP_TRY(hipMemcpy(p->d_row_tiles, tab.data(), tab.size() * 4, hipMemcpyHostToDevice));
+        p->resident_grid = grouped_grid_size(p->tile, dev);
+        if (p->resident_grid <= 0) return FICCO_ERR_HIP;
+        const int64_t tiles = (int64_t)p->n_row_tiles * ((p->N + ts.bn - 1) / ts.bn);
+        if (tiles < p->resident_grid) p->resident_grid = (int)std::max<int64_t>(tiles, 1);
+    } else if (is_resident(p)) {
         p->resident_grid = is_2d(p) ? resident2d_grid_size(p->tile, dev) : resident_grid_size(p->tile, dev);
         if (p->resident_grid <= 0) return FICCO_ERR_HIP;
         TileShape ts = tile_shape(p->tile);
@@ -402,10 +492,12 @@ int finalize(ficco_plan_t *p)
 
 int pack_weight(ficco_plan_t *p, const void *W_dev, hipStream_t s)
 {
+    const size_t one = (size_t)p->K * p->N;
     if (!p->d_wt) {
-        if (hipMalloc((void **)&p->d_wt, (size_t)p->K * p->N * 2) != hipSuccess) return FICCO_ERR_ALLOC;
+        if (hipMalloc((void **)&p->d_wt, one * 2 * (size_t)p->E) != hipSuccess) return FICCO_ERR_ALLOC;
     }
-    HIP_TRY(launch_pack_weight((const uint16_t *)W_dev, p->d_wt, p->K, p->N, s));
+    for (int e = 0; e < p->E; ++e)       // one matrix per expert (a single one for the other plans)
+        HIP_TRY(launch_pack_weight((const uint16_t *)W_dev + e * one, p->d_wt + e * one, p->K, p->N, s));
     p->packed_from = W_dev;
     return FICCO_OK;
 }
@@ -587,6 +679,104 @@ int engines_prepare(ficco_plan_t *p, bool touches_host, std::vector<int> &eng, i
         }
         if (getenv("FICCO_DEBUG")) fprintf(stderr, "ficco: kernels %s\n", p->sig_poll ? "poll the transfers' completion signals" : "wait on flags raised by 4-byte copies");
     }
+    return FICCO_OK;
+}
+
+// One run of an expert-parallel plan: the grouped kernel is enqueued first and waits per tile for the
+// pieces that cover its rows; piece (e, s, j) travels on peer j's link.
+int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hipStream_t cs, bool src_dev)
+{
+    const int mode = p->mode;
+    const bool do_copy = mode != FICCO_MODE_GEMM_ONLY, do_gemm = mode != FICCO_MODE_COPY_ONLY;
+    const bool dependent = mode == FICCO_MODE_PAIR;
+    const int n = p->n_chunks, G = p->G;
+    const bool touches_host = !src_dev;
+    std::vector<int> eng;
+    int links = 0;
+    int rc = engines_prepare(p, touches_host, eng, links);
+    if (rc) return rc;
+    EngineCtx &ctx = g_engines;
+    p->backend = FICCO_COPY_ENGINES;
+    const bool poll_signals = p->sig_poll == 1 && !p->hold_flags && !touches_host;
+    if (p->run_index > 0) {
+        HIP_TRY(hipEventSynchronize(p->ev_end));
+        for (int i = 0; i < n; ++i)
+            if (!wait_signal(p->sig_data[i], 5.0) || !wait_signal(p->sig_flag[i], 5.0)) return FICCO_ERR_TIMEOUT;
+    }
+    p->run_index += 1;
+    const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
+    const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
+    const Gate gate{p->d_flags, poll_signals ? p->d_sig_value : nullptr, epoch, p->d_status, (uint32_t *)p->h_status, spin_ticks};
+    for (int i = 0; i < n; ++i) {
+        hsa_signal_store_relaxed(p->sig_data[i], (do_copy && p->piece_nrows[i] > 0) ? 1 : 0);
+        hsa_signal_store_relaxed(p->sig_flag[i], 0);
+    }
+    int n_copies = 0, n_launches = 0;
+    int64_t copy_bytes = 0;
+    HIP_TRY(hipEventRecord(p->ev_begin, cs));
+    HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
+    if (do_gemm && p->n_row_tiles > 0) {
+        GroupedLaunch r{};
+        r.g.A = (const uint16_t *)A_dev;
+        r.g.Wt = p->d_wt;
+        r.g.C = (uint16_t *)C_dev;
+        r.g.lda = p->K; r.g.ldc = p->N; r.g.N = (int32_t)p->N; r.g.K = (int32_t)p->K;
+        r.g.gate = gate;
+        r.row_tiles = p->d_row_tiles;
+        r.n_row_tiles = p->n_row_tiles;
+        r.ticket = p->d_ticket;
+        r.grid = p->resident_grid;
+        r.gated = (dependent && do_copy) ? 1 : 0;
+        TileShape ts = tile_shape(p->tile);
+        for (int x = 0; x < kTicketLists; ++x) {
+            r.ticket_base[x] = p->ticket_total[x];
+            p->ticket_total[x] += resident_list_draws(resident_list_tiles(p->n_row_tiles, (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
+        }
+        HIP_TRY(launch_grouped(p->tile, r, cs));
+        ++n_launches;
+    }
+    HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+    if (do_copy && (!dependent || !do_gemm) && !p->hold_flags)
+        HIP_TRY(launch_wait_ready(gate, p->d_arrival, n, cs));       // nothing else on the stream consumes the flags
+    HIP_TRY(hipEventRecord(p->ev_end, cs));
+
+    const bool chained = p->schedule == FICCO_SHARD || (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
+    int prev_chunk = -1;
+    for (int q = 0; q < n && do_copy; ++q) {
+        const int chunk = p->arrival[q];
+        const hsa_amd_sdma_engine_id_t engine = (hsa_amd_sdma_engine_id_t)(1u << eng[(chunk % G) % links]);
+        const size_t off = (size_t)p->piece_row0[chunk] * p->K * 2, bytes = (size_t)p->piece_nrows[chunk] * p->K * 2;
+        hsa_status_t st;
+        if (bytes) {
+            hsa_signal_t dep{};
+            int ndep = 0;
+            if (chained && prev_chunk >= 0) { dep = p->sig_data[prev_chunk]; ndep = 1; }
+            st = hsa_amd_memory_async_copy_on_engine((char *)A_dev + off, ctx.gpu, (const char *)A_src + off, src_dev ? ctx.gpu : ctx.cpu, bytes,
+                                                     ndep, ndep ? &dep : nullptr, p->sig_data[chunk], engine, src_dev);
+            if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
+            prev_chunk = chunk;
+            ++n_copies;
+            copy_bytes += (int64_t)bytes;
+        }
+        if (!poll_signals && !p->hold_flags) {
+            // the flag follows the piece's data; a piece without rows gets its flag at once
+            hsa_signal_store_relaxed(p->sig_flag[chunk], 1);
+            st = hsa_amd_memory_async_copy_on_engine(p->d_flags + (size_t)chunk * kFlagStrideWords, ctx.gpu, p->h_epochs + epoch, ctx.cpu, 4,
+                                                     bytes ? 1 : 0, bytes ? &p->sig_data[chunk] : nullptr, p->sig_flag[chunk], engine, false);
+            if (st != HSA_STATUS_SUCCESS) { hsa_signal_store_relaxed(p->sig_flag[chunk], 0); g_last_hip = (int)st; return FICCO_ERR_HIP; }
+        }
+    }
+    p->last_had_copies = n_copies > 0;
+    p->last_had_gemm = n_launches > 0;
+    p->last_timing = false;
+    p->last_copy_bytes = copy_bytes;
+    p->last_n_copies = n_copies;
+    p->last_n_launches = n_launches;
+    p->last_engines = true;
+    p->last_lean = false;
+    p->last_graph = false;
+    p->last_reduce = false;
+    p->last_skip_shard = -1;
     return FICCO_OK;
 }
 
@@ -954,9 +1144,52 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
     return FICCO_OK;
 }
 
+int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64_t *rows, int chunks, int schedule,
+                       ficco_plan_t **out)
+{
+    if (!out || !rows) return FICCO_ERR_ARG;
+    if (K < 1 || N < 1 || peers < 1 || experts < 1 || chunks < 1) return FICCO_ERR_SHAPE;
+    if (schedule != FICCO_SERIAL && schedule != FICCO_SHARD && schedule != FICCO_FINE_PERSISTENT) return FICCO_ERR_ARG;
+    if ((schedule == FICCO_SERIAL || schedule == FICCO_SHARD) && chunks != 1) return FICCO_ERR_SHAPE;
+    if ((int64_t)peers * experts * chunks > 4096) return FICCO_ERR_SHAPE;
+    if (K % 64 || N % 8 || K > 0x7FFFFFFF || N > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    int64_t M = 0;
+    for (int i = 0; i < peers * experts; ++i) {
+        if (rows[i] < 0) return FICCO_ERR_SHAPE;
+        M += rows[i];
+    }
+    if (M < 1 || M > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    ficco_plan_t *p = new (std::nothrow) ficco_plan_t();
+    if (!p) return FICCO_ERR_ALLOC;
+    p->M = M; p->K = K; p->N = N; p->G = peers; p->E = experts; p->c = chunks; p->schedule = schedule;
+    p->grouped = true;
+    p->token_rows.assign(rows, rows + (size_t)peers * experts);
+    p->device = -1;
+    p->order = schedule == FICCO_SHARD ? FICCO_ORDER_SHARD_MAJOR : FICCO_ORDER_STEP_MAJOR;
+    int rc = build_lists(p);
+    if (rc) { delete p; return rc; }
+    *out = p;
+    return FICCO_OK;
+}
+
+int ficco_plan_pieces(const ficco_plan_t *p, int64_t *row0, int64_t *rows, int cap)
+{
+    if (!p || cap < p->n_chunks) return FICCO_ERR_ARG;
+    for (int i = 0; i < p->n_chunks; ++i) {
+        const int64_t r0 = p->grouped ? p->piece_row0[i] : (is_2d(p) ? (int64_t)(i % p->G) * p->m : (int64_t)i * p->m);
+        const int64_t nr = p->grouped ? p->piece_nrows[i] : p->m;
+        if (row0) row0[i] = r0;
+        if (rows) rows[i] = nr;
+    }
+    return FICCO_OK;
+}
+
 int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
 {
     if (!p) return FICCO_ERR_ARG;
+    if (p->grouped && (option == FICCO_OPT_DIRECTION || option == FICCO_OPT_LOCAL_SHARD || option == FICCO_OPT_PACKING ||
+                       option == FICCO_OPT_TIMING) && value != (option == FICCO_OPT_LOCAL_SHARD ? -1 : 0))
+        return FICCO_ERR_ARG;          // expert-parallel plans: all-gather direction, every piece travels, no per-launch timing
     const bool late_ok = option == FICCO_OPT_MODE || option == FICCO_OPT_TIMING || option == FICCO_OPT_HOLD_FLAGS ||
                          option == FICCO_OPT_SPIN_LIMIT_US;
     if (p->finalized && !late_ok) return FICCO_ERR_STATE;
@@ -1053,6 +1286,7 @@ int ficco_plan_info(const ficco_plan_t *p, ficco_plan_info_t *out)
     // descriptors of one launch: the resident kernel's unit of work is one piece
     int64_t rows = is_resident(p) ? p->m
                                   : (int64_t)(p->groups[0].pos_end - p->groups[0].pos_begin) * p->m;
+    if (p->grouped) rows = p->M / p->n_chunks;      // descriptors of an average piece
     ficco_static_descriptors(rows, p->N, is_2d(p) ? p->K / p->c : p->K, &o.otb, &o.mt_bytes);
     *out = o;
     return FICCO_OK;
@@ -1126,6 +1360,10 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     if (do_gemm && p->packed_from != W_dev) {
         rc = pack_weight(p, W_dev, cs);
         if (rc) return rc;
+    }
+    if (p->grouped) {
+        if (rs || p->backend_opt == FICCO_COPY_STREAM || p->flag_write == 1) return FICCO_ERR_ARG;   // copy engines only
+        return run_grouped(p, A_src, A_dev, C_dev, cs, src_dev);
     }
     // resolve the transfer backend
     int backend = p->backend_opt;
@@ -1374,7 +1612,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
 int ficco_rs_reduce(ficco_plan_t *p, int block, const void *P_src, void *P_dev, const void *own, void *out, void *stream)
 {
     if (!p || !P_src || !P_dev || !own || !out) return FICCO_ERR_ARG;
-    if (is_2d(p) || block < 0 || block >= p->G) return FICCO_ERR_ARG;
+    if (is_2d(p) || p->grouped || block < 0 || block >= p->G) return FICCO_ERR_ARG;
     if (p->backend_opt == FICCO_COPY_STREAM || p->flag_write == 1) return FICCO_ERR_ARG;   // copy engines only
     hipStream_t cs = (hipStream_t)stream;
     int rc = finalize(p);
@@ -1483,7 +1721,7 @@ int ficco_graph_capture(ficco_plan_t *p, const void *A_src, void *A_dev, const v
                         void *const *peer_out)
 {
     if (!p || !A_dev || !W_dev || !C_dev) return FICCO_ERR_ARG;
-    if (is_resident(p) || p->timing || p->packing || p->mode != FICCO_MODE_PAIR) return FICCO_ERR_ARG;
+    if (is_resident(p) || p->grouped || p->timing || p->packing || p->mode != FICCO_MODE_PAIR) return FICCO_ERR_ARG;
     if (p->backend_opt == FICCO_COPY_ENGINES) return FICCO_ERR_ARG;      // engine submissions are host calls, not stream work
     const bool rs = p->direction == FICCO_DIR_GEMM_RS;
     if (rs ? (A_src || !peer_out) : (!A_src || peer_out)) return FICCO_ERR_ARG;
@@ -1583,7 +1821,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         double busy = 0;
         for (int q = 0; q < p->n_chunks; ++q) {
             const int chunk = p->arrival[q];
-            if (p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) continue;
+            if ((p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) || (p->grouped && p->piece_nrows[chunk] == 0)) continue;
             if (!wait_signal(p->sig_data[p->arrival[q]], 5.0) || !wait_signal(p->sig_flag[p->arrival[q]], 5.0)) {
                 if (getenv("FICCO_DEBUG"))
                     fprintf(stderr, "ficco: transfer %d (chunk %d) did not complete: data signal %lld flag signal %lld\n", q, chunk,
@@ -1623,7 +1861,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
         if (p->last_had_copies && !p->last_engines) {
             for (int q = 0; q < p->n_chunks; ++q) {
                 const int chunk = p->arrival[q];
-                if (p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) continue;
+                if ((p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) || (p->grouped && p->piece_nrows[chunk] == 0)) continue;
                 HIP_TRY(hipEventElapsedTime(&ms, p->ev_copy_b[q], p->ev_copy_e[q]));
                 cb += ms * 1e3;
             }
@@ -1698,7 +1936,7 @@ int ficco_query_spans(ficco_plan_t *p, double *copy_begin_us, double *copy_end_u
         if (cap_chunks < p->n_chunks) return FICCO_ERR_ARG;
         for (int q = 0; q < p->n_chunks; ++q) {
             const int chunk = p->arrival[q];
-            const bool local = p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard;
+            const bool local = (p->last_skip_shard >= 0 && shard_of(p, chunk) == p->last_skip_shard) || (p->grouped && p->piece_nrows[chunk] == 0);
             double b = 0, e = 0;
             if (p->last_had_copies && !local && p->last_engines) {
                 // engine timestamps live on another clock: reported relative to the run's first transfer
@@ -1745,7 +1983,7 @@ int ficco_profile_losses(ficco_plan_t *p, const void *A_src, void *A_dev, const 
                          void *compute_stream, void *copy_stream, int warmup, int iters, ficco_losses_t *out)
 {
     if (!p || !out || !A_src || !A_dev || !W_dev || !C_dev || iters < 1 || warmup < 0) return FICCO_ERR_ARG;
-    if (p->direction != FICCO_DIR_AG_GEMM) return FICCO_ERR_ARG;
+    if (p->direction != FICCO_DIR_AG_GEMM || p->grouped) return FICCO_ERR_ARG;
     ficco_plan_t *whole = nullptr;
     int rc = ficco_plan(p->M, p->K, p->N, p->G, 1, FICCO_SERIAL, &whole);
     if (rc) return rc;

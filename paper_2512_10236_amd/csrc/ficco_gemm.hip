@@ -541,6 +541,63 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
     }
 }
 
+// Expert-parallel variant of the resident kernel (all-to-all token dispatch before the expert layers,
+// Sec. II-A; unequal amounts per pair of GPUs, Sec. III-C): the rows of A are ragged segments, one per
+// expert, each multiplied by that expert's weight. Row tiles never cross a segment; the host lists
+// them in the order they become ready together with the pieces that cover them.
+template <class T>
+__global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __shared__ TileWalk s_walk;
+    __shared__ int s_ok;
+    const GemmLaunch &a = r.g;
+    const int tiles_n = (a.N + T::BN - 1) / T::BN;
+    const int row_tiles = r.n_row_tiles;
+    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
+    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
+
+    if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
+    int have_drawn = 0;
+    uint32_t drawn = 0;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            TileWalk w = s_walk;
+            tile_walk_next(w, r.ticket, r.ticket_base, r.grid, total_of, have_drawn, drawn);
+            have_drawn = 0;
+            int ok = 1;
+            if (w.x >= 0 && r.gated) {
+                int rl, tn;
+                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn);
+                const int32_t *rt = r.row_tiles + (size_t)(rl * kTicketLists + w.x) * kRowTileWords;
+                for (int pc = rt[3]; pc <= rt[4] && ok; ++pc) ok = wait_ready(a.gate, pc);
+            }
+            s_walk = w;
+            s_ok = ok;
+        }
+        __syncthreads();                   // also orders the tile's loads after the flag reads
+        const int x = s_walk.x, t = s_walk.t;
+        if (x < 0) break;
+        if (s_ok) {
+            int rl, tn;
+            list_tile_position(t, list_rows(x), tiles_n, rl, tn);
+            const int32_t *rt = r.row_tiles + (size_t)(rl * kTicketLists + x) * kRowTileWords;
+            const int64_t row0 = rt[0];
+            const int rows_valid = rt[1];
+            const int64_t expert = rt[2];
+            const int col0 = tn * T::BN;
+            const int cols_valid = min(T::BN, a.N - col0);
+            TileAcc<T> ta;
+            tile_zero(ta);
+            tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (expert * a.N + col0) * (int64_t)a.K, cols_valid,
+                               a.lda, a.K, a.K, smem);
+            if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
+            tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
+        }
+        __syncthreads();                   // s_walk / s_ok / LDS stages are reused
+    }
+}
+
 __global__ __launch_bounds__(64) void wait_ready_kernel(Gate gate, const int32_t *chunks, int n)
 {
     if (threadIdx.x == 0)
@@ -643,6 +700,27 @@ static int resident2d_grid_t(int device)
 }
 
 template <class T>
+static hipError_t launch_grouped_t(const GroupedLaunch &r, hipStream_t s)
+{
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_grouped_kernel<T>));
+    if (once != hipSuccess) return once;
+    if (r.grid <= 0 || r.n_row_tiles <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gemm_grouped_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    return hipGetLastError();
+}
+
+template <class T>
+static int grouped_grid_t(int device)
+{
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_grouped_kernel<T>));
+    (void)once;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_grouped_kernel<T>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
+template <class T>
 static int resident_grid_t(int device)
 {
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T>));
@@ -714,6 +792,26 @@ hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64));
     hipLaunchKernelGGL(pack_weight_kernel, grid, dim3(256), 0, s, W, Wt, K, N);
     return hipGetLastError();
+}
+
+hipError_t launch_grouped(int tile, const GroupedLaunch &r, hipStream_t s)
+{
+    switch (tile) {
+#define X(id, T) case id: return launch_grouped_t<T>(r, s);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
+    default: return hipErrorInvalidValue;
+    }
+}
+
+int grouped_grid_size(int tile, int device)
+{
+    switch (tile) {
+#define X(id, T) case id: return grouped_grid_t<T>(device);
+    FICCO_FOR_EACH_TILE(X)
+#undef X
+    default: return 0;
+    }
 }
 
 }  // namespace ficco

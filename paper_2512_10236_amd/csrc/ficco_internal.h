@@ -111,6 +111,23 @@ struct ReduceLaunch {
 hipError_t launch_reduce(const ReduceLaunch &r, int grid, hipStream_t s);
 int reduce_grid_size(int device);
 
+// Grouped (per-expert) resident GEMM over ragged row segments. row_tiles: n_row_tiles entries of
+// kRowTileWords int32 {first row, rows (1..BM), expert, first piece, last piece, 0, 0, 0} in the order
+// they become ready; a tile waits for pieces first..last (ids into the gate's tables) and multiplies
+// its rows by Wt + expert * N * K.
+constexpr int kRowTileWords = 8;
+struct GroupedLaunch {
+    GemmLaunch g;                 // A, Wt (all experts, [E][N][K]), C, lda, ldc, N, K, gate
+    const int32_t *row_tiles;
+    int32_t n_row_tiles;
+    uint32_t *ticket;
+    uint32_t ticket_base[8];
+    int32_t grid;
+    int32_t gated;
+};
+hipError_t launch_grouped(int tile, const GroupedLaunch &a, hipStream_t s);
+int grouped_grid_size(int tile, int device);
+
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s);
 hipError_t launch_resident2d(int tile, const Resident2DLaunch &a, hipStream_t s);
 int resident2d_grid_size(int tile, int device);

@@ -187,3 +187,43 @@ def test_pick_pieces_hand_cases():
     assert sch.pick_pieces(512, 1024, 1024, 4) == 1            # shard smaller than the minimum piece
     for args in [(16384, 8192, 3584, 8), (4096, 4096, 512, 8), (65536, 8192, 14336, 8), (512, 1024, 1024, 4), (24576, 4096, 1024, 8)]:
         assert ficco.ficco_pick_schedule(*args)[1] == sch.pick_pieces(*args)
+
+
+# ------------------------------------------------------------------ expert-parallel (grouped) plans
+from oracle import grouped as ogr  # noqa: E402
+
+
+@pytest.mark.parametrize("rows,c,sched", [([[3, 0], [5, 2], [0, 7]], 2, ficco.FICCO_FINE_PERSISTENT),
+                                          ([[40], [13], [0], [91]], 4, ficco.FICCO_FINE_PERSISTENT),
+                                          ([[10, 20, 30], [5, 0, 1]], 1, ficco.FICCO_SHARD),
+                                          ([[10, 20], [7, 9]], 1, ficco.FICCO_SERIAL)])
+def test_grouped_plan_layout_and_arrival_match_oracle(rows, c, sched):
+    G, E = len(rows), len(rows[0])
+    plan = ficco.ficco_plan_grouped(64, 8, rows, c, sched)
+    try:
+        r0, nr = ficco.ficco_plan_pieces(plan)
+        arrival, gids = ficco.ficco_plan_arrival(plan)
+        info = ficco.ficco_plan_info(plan)
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)
+        by_peer, _ = ficco.ficco_plan_arrival(plan)
+        for opt, val in [(ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS), (ficco.FICCO_OPT_LOCAL_SHARD, 0),
+                         (ficco.FICCO_OPT_PACKING, 1), (ficco.FICCO_OPT_TIMING, 1)]:
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_plan_set(plan, opt, val)
+    finally:
+        ficco.ficco_destroy(plan)
+    o_r0, o_nr, _, _ = ogr.layout(rows, c)
+    assert r0 == list(o_r0) and nr == list(o_nr)
+    assert info.M == sum(map(sum, rows)) and info.n_chunks == G * E * c and info.shards == G and set(gids) == {0}
+    assert arrival == ogr.arrival_order(G, E, c, step_major=sched != ficco.FICCO_SHARD)
+    assert by_peer == ogr.arrival_order(G, E, c, step_major=False)
+
+
+@pytest.mark.parametrize("args,status", [
+    ((64, 8, [[0, 0]], 1, 4), "SHAPE"), ((64, 8, [[-1, 2]], 1, 4), "SHAPE"), ((96, 8, [[4]], 1, 4), "SHAPE"),
+    ((64, 12, [[4]], 1, 4), "SHAPE"), ((64, 8, [[4]], 2, 0), "SHAPE"), ((64, 8, [[4]] * 70, 64, 4), "SHAPE"),
+    ((64, 8, [[4]], 1, 2), "ARG"), ((64, 8, [[4]], 1, 3), "ARG"), ((64, 8, [[4]], 1, 5), "ARG")])
+def test_grouped_plan_rules(args, status):
+    with pytest.raises(ficco.FiccoError) as e:
+        ficco.ficco_plan_grouped(*args)
+    assert e.value.status == getattr(ficco, "FICCO_ERR_" + status)
