@@ -286,7 +286,11 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
  *             ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces complete.
  *             peer_out is a host array of `shards` pointers.
  *   W_dev   - [K,N] device (see ficco_pack_weight).
- * compute_stream and copy_stream must differ and have the default priority.
+ * compute_stream and copy_stream must differ and have the default priority. On the stream backend
+ * with a resident schedule they must also not share a hardware queue (HIP maps streams round-robin
+ * onto GPU_MAX_HW_QUEUES queues, so create few streams): otherwise the flag writes sit behind the
+ * kernel that waits for them and the run ends with FICCO_ERR_TIMEOUT. The engine backend (the
+ * default) does not use copy_stream and has no such constraint.
  */
 int ficco_run(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_dev, void *C_dev,
               void *const *peer_out, void *compute_stream, void *copy_stream);

@@ -22,15 +22,6 @@ ALL_SCHEDULES = [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_F
                  (ficco.FICCO_FINE_FUSED, 4), (ficco.FICCO_FINE_PERSISTENT, 4)]
 
 
-@pytest.fixture(scope="module")
-def gpu():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    torch.cuda.set_device(0)
-    ficco.load()                      # fails loudly if the HIP library is missing
-    return dict(dev=torch.device("cuda:0"), cs=torch.cuda.Stream(), xs=torch.cuda.Stream())
-
-
 def as_i16(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
 

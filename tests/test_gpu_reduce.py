@@ -14,15 +14,6 @@ pytestmark = pytest.mark.gpu
 NAN_BF16 = 0x7FC0
 
 
-@pytest.fixture(scope="module")
-def gpu():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    torch.cuda.set_device(0)
-    ficco.load()
-    return dict(dev=torch.device("cuda:0"), cs=torch.cuda.Stream(), xs=torch.cuda.Stream())
-
-
 def as_i16(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
 
