@@ -3,7 +3,7 @@
 
 One "step" = one pass of the whole hot path over one batch of synthetic input: plan (built once),
 the piece transfers, the ready flags / events, the piece GEMMs and the statistics query.
-Prints ONE JSON line (see the design doc for every field). Only one GPU is used; --gpus > 1 exits.
+Prints ONE JSON line. Only one GPU is used; --gpus > 1 exits.
 
 Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192 K=4096 N=768):
   pair      - K timed steps of the best finer-grain schedule, source shards resident in HBM
@@ -163,7 +163,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box here has one); "
-              "run with --gpus 1. How the path would shard is described in DESIGN.md.", file=sys.stderr)
+              "run with --gpus 1 (across GPUs every GPU computes its own column share and only the gather of "
+              "A is exchanged, one copy engine per peer link).", file=sys.stderr)
         return 2
     legs = set(args.legs.split(","))
 

@@ -3,8 +3,8 @@
 all-gather -> GEMM shapes on this GPU, fit the thresholds of the static schedule rule, and report
 how often the rule picks the measured best.
 
-    python -m paper_2512_10236_amd.sweep --out gpurun_out/sweep.jsonl            # measure
-    python -m paper_2512_10236_amd.sweep --fit gpurun_out/sweep.jsonl            # fit + accuracy
+    python -m paper_2512_10236_amd.sweep --out sweep.jsonl            # measure
+    python -m paper_2512_10236_amd.sweep --fit sweep.jsonl            # fit + accuracy
 
 Shapes default to the grid M in {4096,16384,65536} x K in {4096,8192} x N in {512,1024,3584,14336},
 8 shards, pieces per shard in {1,2,4,8,16,32}; shards are moved from a device staging buffer by one
@@ -44,7 +44,13 @@ def measure(args) -> int:
                 C_ref = None
                 cases = [(F.FICCO_SERIAL, 1), (F.FICCO_SHARD, 1)]
                 cases += [(s, c) for c in args.chunks for s in FINE if (M // G) % c == 0 and c * G <= 4096]
+                # the 2D schedule (k slices) wherever the slices are whole k-tiles; its source is the K-sliced copy
+                cases += [(F.FICCO_FINE_2D, c) for c in args.chunks if c > 1 and K % (64 * c) == 0 and c * G <= 4096]
                 for sched, c in cases:
+                    src = A_stage
+                    if sched == F.FICCO_FINE_2D:
+                        src = A_stage.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
+                        torch.cuda.synchronize()
                     plan = F.ficco_plan(M, K, N, G, c, sched)
                     try:
                         F.ficco_pack_weight(plan, W, cs)
@@ -53,7 +59,7 @@ def measure(args) -> int:
                             if it == 0:
                                 C.zero_()
                                 torch.cuda.synchronize()
-                            F.ficco_run(plan, A_stage, A_dev, W, C, None, cs, xs)
+                            F.ficco_run(plan, src, A_dev, W, C, None, cs, xs)
                             st = F.ficco_query_stats(plan)
                             if it >= args.warmup:
                                 ts.append(st.wall_us)
@@ -111,9 +117,16 @@ def fit(args) -> int:
         shard = next(r for r in rs if r["schedule"] == "shard")["wall_us"]
         fine = [r for r in rs if r["sched_id"] in FINE]
         best = min(fine, key=lambda r: r["wall_us"])
-        table.append(dict(key=k, serial=serial, shard=shard, best=best, fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in fine}))
+        two_d = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D]
+        if two_d:
+            b2 = min(two_d, key=lambda r: r["wall_us"])
+            note_2d = f"  best 2D x{b2['chunks']} {b2['wall_us']:9.1f} us ({best['wall_us'] / b2['wall_us']:.3f}x of best 1D)"
+        else:
+            note_2d = ""
+        table.append(dict(key=k, serial=serial, shard=shard, best=best, fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in fine},
+                          best_2d=min((r["wall_us"] for r in two_d), default=None)))
         print(f"M={k[0]:6d} K={k[1]:5d} N={k[2]:6d}: serial {serial:9.1f} us  shard-level {shard:9.1f} us  best {best['schedule']} x{best['chunks']} "
-              f"{best['wall_us']:9.1f} us  speedup {serial / best['wall_us']:.3f}x (vs shard-level {shard / best['wall_us']:.2f}x)")
+              f"{best['wall_us']:9.1f} us  speedup {serial / best['wall_us']:.3f}x (vs shard-level {shard / best['wall_us']:.2f}x){note_2d}")
 
     def score(consts, subset):
         hit = near = 0
@@ -146,6 +159,18 @@ def fit(args) -> int:
         ml = 100 * sum(loss) / len(loss) if loss else 0.0
         print(f"{name}: exact pick {h}/{len(subset)}, within 3% of best {n}/{len(subset)}, mean loss of optimal speedup on misses {ml:.1f}%")
     print("fitted constants: piece flops %.3g, min rows %d, max pieces %d" % best_c)
+    # the shape rule of Sec. V-C: column pieces (2D) when M <= K, row pieces (1D) otherwise
+    with_2d = [t for t in table if t["best_2d"] is not None]
+    if with_2d:
+        ok = near = 0
+        for t in with_2d:
+            M, K = t["key"][0], t["key"][1]
+            picked, other = (t["best_2d"], t["best"]["wall_us"]) if M <= K else (t["best"]["wall_us"], t["best_2d"])
+            ok += picked <= other
+            near += picked <= 1.03 * other
+        n_le = sum(1 for t in with_2d if t["key"][0] <= t["key"][1])
+        print(f"shape rule (2D when M <= K, else 1D): picks the faster family at {ok}/{len(with_2d)} shapes, "
+              f"within 3% of it at {near}/{len(with_2d)} ({n_le} shapes have M <= K)")
     h, n, loss = score((2.5e10, 256, 16), table)
     print(f"constants compiled into ficco_pick_schedule (2.5e10, 256, 16): exact {h}/{len(table)}, within 3% {n}/{len(table)}")
     return 0
