@@ -588,6 +588,19 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
     return out;
 }
 
+// Row tiles per group in a resident launch's lists: what one step delivers to each of the kTicketLists
+// lists (all shards' pieces of a step arrive together in step-major order); with other orders pieces
+// arrive one by one, so tiles are taken row tile by row tile.
+inline int resident_group(const ficco_plan_t *p)
+{
+    static const char *force = getenv("FICCO_GROUP");
+    if (force && atoi(force) >= 1 && atoi(force) <= 4) return atoi(force);
+    if (p->order != FICCO_ORDER_STEP_MAJOR) return 1;
+    TileShape ts = tile_shape(p->tile);
+    const int64_t per_step = (int64_t)p->G * ((p->m + ts.bm - 1) / ts.bm);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(4, per_step / kTicketLists));
+}
+
 // bytes of one row of a transferred piece of the activation
 inline size_t piece_row_bytes(const ficco_plan_t *p) { return (size_t)(is_2d(p) ? p->K / p->c : p->K) * 2; }
 
@@ -1012,6 +1025,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 r.g.gate = gate;
                 r.ticket = p->d_ticket;
                 r.grid = p->resident_grid;
+                r.group = resident_group(p);
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
                 TileShape ts = tile_shape(p->tile);
@@ -1521,6 +1535,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 r.g.gate = gate;
                 r.ticket = p->d_ticket;
                 r.grid = grid;
+                r.group = resident_group(p);
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
                 else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }

@@ -328,7 +328,8 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
 // XCD, each with its own ticket counter: a workgroup first serves the list of the XCD it presumably
 // runs on (workgroups are dispatched round-robin over the XCDs), so that the tiles sharing an L2 at
 // any time are few row tiles times a run of column tiles, and then helps the other lists. Inside a
-// list tiles go in groups of 2 row tiles, row tile fastest.
+// list tiles go in groups of a few row tiles, row tile fastest: as many as one step delivers to the
+// list (so that no workgroup draws a tile of the next step while tiles of this one are left), 1 to 4.
 //
 // TileWalk hands a workgroup its next (list, tile) pair. The first tile of the first list is the
 // workgroup's rank among the workgroups that start there (no memory access); later tiles are drawn
@@ -415,12 +416,11 @@ static __device__ __forceinline__ void tile_walk_next(TileWalk &w, uint32_t *tic
 }
 
 // position of tile t of a list: groups of GROUP row tiles, row tile fastest inside a group
-static __device__ __forceinline__ void list_tile_position(int t, int my_rows, int tiles_n, int &row_in_list, int &tn)
+static __device__ __forceinline__ void list_tile_position(int t, int my_rows, int tiles_n, int &row_in_list, int &tn, int group = 2)
 {
-    constexpr int GROUP = 2;
-    const int per_group = GROUP * tiles_n;
-    const int g = t / per_group, first = g * GROUP;
-    const int gsz = min(my_rows - first, GROUP);
+    const int per_group = group * tiles_n;
+    const int g = t / per_group, first = g * group;
+    const int gsz = min(my_rows - first, group);
     row_in_list = first + (t % per_group) % gsz;
     tn = (t % per_group) / gsz;
 }
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
             int ok = 1;
             if (w.x >= 0) {
                 int rl, tn;
-                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn);
+                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn, r.group);
                 const int chunk = r.arrival[(rl * kTicketLists + w.x) / rt_per_chunk];
                 if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
             }
@@ -461,7 +461,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         if (x < 0) break;
         if (s_ok) {
             int rl, tn;
-            list_tile_position(t, list_rows(x), tiles_n, rl, tn);
+            list_tile_position(t, list_rows(x), tiles_n, rl, tn, r.group);
             const int R = rl * kTicketLists + x;
             const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
             const int chunk = r.arrival[p];

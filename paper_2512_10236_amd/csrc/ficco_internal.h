@@ -80,6 +80,7 @@ struct ResidentLaunch {
     uint32_t *ticket;             // device, kTicketLists counters kFlagStrideWords apart, monotonically increasing across runs
     uint32_t ticket_base[8];      // value of each counter when this run starts
     int32_t grid;
+    int32_t group;                // row tiles per group of a list's tile order (1..4)
     int32_t local_chunk_begin, local_chunk_end;   // chunk ids that need no flag (already resident), or empty
 };
 
