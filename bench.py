@@ -38,14 +38,14 @@ HBM_PEAK_GBPS = 8000.0
 # HBM-side traffic per launch of the roofline kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # summaries kept under profiles/ (gemm_isolated_<workload>.md): KiB per dispatch as the counters
 # read, and the factors by which a 256 MiB device copy's true traffic exceeds what they read for it.
-PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131090.5, "WRITE_SIZE": 262144.0 / 262144.0}
+PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131086.7, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
-    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57452.7, "WRITE_SIZE": 12362.4},
+    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57475.2, "WRITE_SIZE": 12289.0},
     ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57452.0, "WRITE_SIZE": 12288.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1085005.7, "WRITE_SIZE": 117537.1},
-    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754151.5, "WRITE_SIZE": 114753.3},
-    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 878411.3, "WRITE_SIZE": 32851.9},
-    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 523875.9, "WRITE_SIZE": 32894.0},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 1086226.6, "WRITE_SIZE": 116527.9},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 754187.8, "WRITE_SIZE": 114754.0},
+    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 942450.4, "WRITE_SIZE": 32792.4},
+    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 521484.2, "WRITE_SIZE": 32973.7},
     ("cfg4_gemm_rs", "rs_reduce_kernel"): {"FETCH_SIZE": 131151.5, "WRITE_SIZE": 32768.0},      # profiles/rs_reduce_cfg4_gemm_rs.md
 }
 

@@ -139,7 +139,8 @@ typedef enum ficco_option {
  *             for the plan's previous run; in the GEMM->RS direction it also waits for each GEMM
  *             launch before it submits that launch's transfers.
  *   AUTO    - ENGINES for every run that moves data, unless FICCO_OPT_FLAG_WRITE = 1 asks for
- *             stream writes (then STREAM); measured faster than STREAM for pinned sources too.
+ *             stream writes or a GEMM_RS run sends every block to pinned host memory (then
+ *             STREAM); measured faster than STREAM for pinned sources too.
  *             (On STREAM the resident kernel leaves 8 CUs free: the HIP runtime writes the
  *             4-byte flags with a helper kernel.)
  */
