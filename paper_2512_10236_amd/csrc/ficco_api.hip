@@ -1008,7 +1008,14 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             }
         }
     } else if (!rs) {
-        // ---- GEMM side first: the kernels wait on flags, so they can be resident before data moves
+        // ---- The kernels wait on flags or signals inside, so the order of the two sides is free. Short runs
+        // enqueue the GEMM side first so that it is resident before data lands; long ones (a MiB or more per
+        // link) start the engines first and enqueue the launches while the first pieces are on their way,
+        // which takes the launch latency off the critical path.
+        const bool copies_first = do_copy && do_gemm && (size_t)p->M * row_bytes_a / (size_t)std::max(links, 1) >= ((size_t)1 << 20);
+        if (copies_first)
+            for (int q = 0; q < n; ++q)
+                if ((rc = submit(q))) return rc;
         if (do_gemm) {
             if (is_2d(p)) {
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
@@ -1045,7 +1052,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
         }
         if (do_copy) {
-            for (int q = 0; q < n; ++q)
+            for (int q = 0; q < n && !copies_first; ++q)
                 if ((rc = submit(q))) return rc;
             if ((!dependent || !do_gemm) && !p->hold_flags) {
                 // nothing on the compute stream consumes the flags: join through a small waiting kernel
