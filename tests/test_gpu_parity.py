@@ -580,3 +580,52 @@ def test_graph_of_gemm_rs_and_argument_checks(gpu):
             assert e.value.status == ficco.FICCO_ERR_ARG
         finally:
             ficco.ficco_destroy(plan)
+
+
+# ------------------------------------------------------------------------------------------------
+# full sizes of the remaining workload and the largest piece count the plan accepts
+def test_cfg4_gemm_rs_full_size_sampled_rows(gpu):
+    cfg = fi.CONFIGS["cfg4_gemm_rs"]
+    dev = gpu["dev"]
+    M, K, N, G = cfg["M"], cfg["K"], cfg["N"], cfg["shards"]
+    A = fi.normal_bf16(cfg["seed"], fi.TENSOR_A, M, K)
+    W = fi.make_weight(cfg["seed"], K, N)
+    rows = np.unique(np.concatenate([np.arange(0, M, 1021), [0, M // G - 1, M // G, M - 1]]))
+    ref = og.ag_gemm_rows([A], W, rows)
+    A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+    base = None
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, 4)]:        # bench.py times fused with 4 pieces
+        C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+        peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16, device=dev) for _ in range(G)]
+        torch.cuda.synchronize()
+        plan = ficco.ficco_plan(M, K, N, G, c, sched)
+        try:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+            ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
+            st = ficco.ficco_query_stats(plan)
+        finally:
+            ficco.ficco_destroy(plan)
+        torch.cuda.synchronize()
+        got = torch.cat(peers, 0).cpu().numpy().view(np.uint16)
+        check(got[rows], ref, f"cfg4 sched {sched}")
+        assert st.copy_bytes == M * N * 2
+        if base is None:
+            base = got
+        assert np.array_equal(got, base)
+
+
+def test_largest_piece_count(gpu):
+    # shards * pieces = 4096, the most a plan accepts: one-row pieces
+    G, c, K, N = 8, 512, 64, 16
+    M = G * c
+    shards = fi.make_shards(26, M, K, G)
+    W = fi.make_weight(26, K, N)
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
+    check(base, ref, "serial")
+    for sched in (ficco.FICCO_FINE_PERSISTENT, ficco.FICCO_FINE_FUSED):
+        bits, st, info = run_ag(gpu, shards, W, sched, c, src="device")
+        assert info.n_chunks == 4096 and st.n_copies == 4096
+        assert np.array_equal(bits, base), sched
+    with pytest.raises(ficco.FiccoError):
+        ficco.ficco_plan(2 * M, K, N, G, 2 * c, ficco.FICCO_FINE_PERSISTENT)

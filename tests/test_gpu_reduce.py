@@ -146,3 +146,14 @@ def test_reduce_rejects_bad_arguments(gpu):
             ficco.ficco_rs_reduce(plan, 0, t, t, o, o, gpu["cs"])
     finally:
         ficco.ficco_destroy(plan)
+
+
+def test_reduce_full_size_block(gpu):
+    # the block bench.py times: 2048 x 8192, 8 GPUs, two pieces per block
+    cfg = fi.CONFIGS["cfg4_gemm_rs"]
+    G, rows, N = cfg["shards"], cfg["M"] // cfg["shards"], cfg["N"]
+    x = fi.make_partials(cfg["seed"], G, rows, N)
+    want = orr.rs_reduce(list(x))
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, 2)]:
+        got, st = reduce_once(gpu, x, 0, sched, c)
+        assert np.array_equal(got, want), (sched, c)
