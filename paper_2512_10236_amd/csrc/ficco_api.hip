@@ -116,6 +116,7 @@ hsa_status_t make_signal(hsa_signal_t *out)
 
 bool wait_signal(hsa_signal_t sgn, double limit_s)
 {
+    if (hsa_signal_load_scacquire(sgn) < 1) return true;       // the usual case: already complete
     const auto t0 = std::chrono::steady_clock::now();
     for (;;) {
         hsa_signal_value_t v = hsa_signal_wait_scacquire(sgn, HSA_SIGNAL_CONDITION_LT, 1, 2000000, HSA_WAIT_STATE_BLOCKED);
