@@ -8,13 +8,17 @@
  * (Sec. III, Sec. V-A/B) cuts every shard once more into `chunks` row pieces, moves piece s of
  * every shard in step s, and multiplies pieces as they land. The mirror direction streams row
  * blocks of C = A * W out to G peer buffers as they are completed (the data-movement half of
- * GEMM -> reduce-scatter; the element-wise sum over GPUs is not part of this library).
+ * GEMM -> reduce-scatter; ficco_rs_reduce() is the receiving GPU's adding half). Also here: the
+ * paper's 2D (k-sliced) decomposition, the fused schedule with explicit Gather/Scatter copies, and
+ * an expert-parallel dispatch followed by a grouped expert GEMM (ficco_plan_grouped()).
  *
- * On one GPU the transfers are copy-engine (SDMA) copies issued with hipMemcpyAsync on the
- * caller's copy stream, from pinned host memory or from a device staging buffer; the GEMM is a
+ * On one GPU the transfers are copy-engine (SDMA) copies, from pinned host memory or from a device
+ * staging buffer that stands for the peers' memory: driven directly, one engine per emulated link
+ * (the default), or issued with hipMemcpyAsync on the caller's copy stream. The GEMM is a
  * hand-written bf16 MFMA kernel (fp32 accumulate, one round-to-nearest-even to bf16 at the end)
- * launched per group of landed pieces, or once as a resident kernel whose tiles wait on
- * per-piece ready flags in device memory (Sec. VI-A uses stream write/wait for the same purpose).
+ * launched per group of landed pieces, or once as a resident kernel whose tiles wait (bounded) for
+ * their own piece: on the transfer's completion signal or on a ready flag in device memory
+ * (Sec. VI-A uses stream write/wait between kernels for the same purpose).
  *
  * Conventions
  *   - All matrices are row-major bf16 (1-8-7). "device" = hipMalloc'ed memory of the current
@@ -48,7 +52,7 @@ typedef enum ficco_status {
     FICCO_ERR_SHAPE   = -2,   /* shape rule violated (see ficco_plan)                         */
     FICCO_ERR_ALLOC   = -3,   /* host or device allocation failed                             */
     FICCO_ERR_HIP     = -4,   /* a HIP call failed; ficco_last_hip_error() has the code       */
-    FICCO_ERR_TIMEOUT = -5,   /* a resident kernel gave up waiting for a ready flag           */
+    FICCO_ERR_TIMEOUT = -5,   /* a kernel's bounded wait for a piece expired (or a transfer never completed) */
     FICCO_ERR_STATE   = -6    /* call not valid in the plan's state (e.g. stats before a run) */
 } ficco_status;
 
@@ -98,9 +102,11 @@ typedef enum ficco_option {
     FICCO_OPT_TIMING      = 3,   /* 0: begin/end events only (default); 1: also per-piece and per-launch
                                     events (adds one barrier packet around every launch)                */
     FICCO_OPT_TILE        = 4,   /* 0: choose by shape (default); else a ficco_tile value               */
-    FICCO_OPT_FLAG_WRITE  = 5,   /* resident kernel only. 0 (default): the ready flag is written by a
-                                    4-byte copy-engine copy queued behind the piece's transfer;
-                                    1: by hipStreamWriteValue32                                         */
+    FICCO_OPT_FLAG_WRITE  = 5,   /* how a waiting kernel learns that a piece has landed. 0 (default): the
+                                    engine backend lets kernels read the transfers' completion signals
+                                    where it can, else a 4-byte copy behind the transfer raises a flag
+                                    (the stream backend always copies a flag); 1: hipStreamWriteValue32
+                                    raises the flag (stream backend only); 2: always a flag copy      */
     FICCO_OPT_SPIN_LIMIT_US = 6, /* resident kernel: give up after this long without the awaited flag
                                     (default 2,000,000); the run then reports FICCO_ERR_TIMEOUT        */
     FICCO_OPT_LOCAL_SHARD = 7,   /* -1 (default): every shard arrives by transfer. j >= 0: shard j is
@@ -132,10 +138,12 @@ typedef enum ficco_option {
  *             forced onto SDMA engines, several side by side: transfers of different shards run
  *             concurrently like the links of a fully connected node (Sec. III-B/C), and with
  *             FICCO_SHARD or FICCO_ORDER_SHARD_MAJOR they are chained one after the other like
- *             peer-to-peer exchange over one link at a time (Fig. 3(c)). Every transfer is
- *             followed on its engine by a 4-byte copy that raises the piece's ready flag; GEMM
- *             launches are enqueued first and wait on the flags of their pieces inside the
- *             kernel. The copy stream argument is not used. ficco_run() first waits on the host
+ *             peer-to-peer exchange over one link at a time (Fig. 3(c)). GEMM launches wait for
+ *             their pieces inside the kernel: they read the value word of the transfer's own
+ *             completion signal, or - when the transfers cross the host link, when the signals
+ *             are not readable from the GPU, or with FICCO_OPT_FLAG_WRITE = 2 - a ready flag
+ *             raised by a 4-byte copy queued on the same engine behind the transfer.
+ *             The copy stream argument is not used. ficco_run() first waits on the host
  *             for the plan's previous run; in the GEMM->RS direction it also waits for each GEMM
  *             launch before it submits that launch's transfers.
  *   AUTO    - ENGINES for every run that moves data, unless FICCO_OPT_FLAG_WRITE = 1 asks for
@@ -170,7 +178,8 @@ typedef struct ficco_plan_info {
     int32_t schedule, direction, order, mode;
     int32_t n_chunks;                /* shards * chunks                                          */
     int32_t n_groups;                /* GEMM launches per run                                    */
-    int64_t chunk_rows;              /* M / n_chunks                                             */
+    int64_t chunk_rows;              /* rows of one piece (M / n_chunks; M / shards for FICCO_FINE_2D; 0 for
+                                        grouped plans, whose pieces differ: see ficco_plan_pieces)   */
     int32_t tile_m, tile_n, tile_k;  /* chosen workgroup tile                                    */
     int32_t resident_grid;           /* workgroups of the resident kernel (0 if not used)        */
     int32_t copy_backend, links;     /* as resolved by the last run (0 before the first run)     */
@@ -190,7 +199,7 @@ typedef struct ficco_stats {
     int64_t flops;            /* 2*M*N*K                                                                */
     int64_t copy_bytes;       /* bytes moved by transfers in this run                                   */
     int32_t n_copies, n_launches;
-    int32_t timed_out;        /* 1 if the resident kernel's bounded wait expired                        */
+    int32_t timed_out;        /* 1 if a kernel's bounded wait for a piece expired                       */
     int32_t run_index;        /* 1 for the first run of the plan                                        */
 } ficco_stats_t;
 
