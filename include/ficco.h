@@ -118,7 +118,7 @@ typedef enum ficco_option {
     FICCO_OPT_LINKS       = 10,  /* copy-engine backend: number of copy engines used side by side, one
                                     per emulated link (shard j travels on engine j mod links);
                                     0 (default) = min(shards, engines available)                        */
-    FICCO_OPT_PACKING     = 11   /* 1: run FICCO_FINE_FUSED the way an unmodified library GEMM forces it
+    FICCO_OPT_PACKING     = 11,  /* 1: run FICCO_FINE_FUSED the way an unmodified library GEMM forces it
                                     (Sec. V-A): every landed piece is copied by DMA into its place in a
                                     contiguous per-step input (Gather), one launch multiplies the step,
                                     and its G output blocks are copied by DMA to their rows of C
@@ -127,6 +127,10 @@ typedef enum ficco_option {
                                     ficco_run() then waits on the host for each launch before it
                                     submits that launch's Scatter copies. 0 (default): the kernel
                                     reads the pieces in place through a row-block table             */
+    FICCO_OPT_REPEAT      = 12   /* measuring aid, 1..10000 (default 1): a FICCO_MODE_GEMM_ONLY run without
+                                    FICCO_OPT_TIMING on the stream path enqueues its GEMM launches this many
+                                    times back to back between its two events; wall_us then covers all of
+                                    them and n_launches counts them. May change between runs.         */
 } ficco_option;
 
 /*

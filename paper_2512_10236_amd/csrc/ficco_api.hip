@@ -136,6 +136,7 @@ struct ficco_plan_s {
     int64_t spin_limit_us = 2000000;
     int backend_opt = FICCO_COPY_AUTO, links_opt = 0;
     int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
+    int repeat = 1;                      // GEMM-only runs: launches enqueued this many times inside one bracket
     // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
     bool grouped = false;
     int E = 1;
@@ -1225,7 +1226,7 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
                        option == FICCO_OPT_TIMING) && value != (option == FICCO_OPT_LOCAL_SHARD ? -1 : 0))
         return FICCO_ERR_ARG;          // expert-parallel plans: all-gather direction, every piece travels, no per-launch timing
     const bool late_ok = option == FICCO_OPT_MODE || option == FICCO_OPT_TIMING || option == FICCO_OPT_HOLD_FLAGS ||
-                         option == FICCO_OPT_SPIN_LIMIT_US;
+                         option == FICCO_OPT_SPIN_LIMIT_US || option == FICCO_OPT_REPEAT;
     if (p->finalized && !late_ok) return FICCO_ERR_STATE;
     switch (option) {
     case FICCO_OPT_DIRECTION:
@@ -1274,6 +1275,10 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
     case FICCO_OPT_LINKS:
         if (value < 0 || value > 16) return FICCO_ERR_ARG;
         p->links_opt = (int)value;
+        break;
+    case FICCO_OPT_REPEAT:
+        if (value < 1 || value > 10000) return FICCO_ERR_ARG;
+        p->repeat = (int)value;
         break;
     case FICCO_OPT_PACKING:
         if (value != 0 && value != 1) return FICCO_ERR_ARG;
@@ -1536,6 +1541,8 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 HIP_TRY(hipEventRecord(p->ev_gemm_first, cs));
             }
             gemm_first_recorded = true;
+            const int reps = lean ? p->repeat : 1;       // measuring aid: the same launch back to back
+            for (int rp = 0; rp < reps; ++rp) {
             if (is_2d(p)) {
                 if ((rc = launch_2d(p, gate, dependent, grid, A_dev, C_dev, cs))) return rc;
             } else {
@@ -1560,8 +1567,9 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 }
                 HIP_TRY(launch_resident(p->tile, r, cs));
             }
-            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
             ++n_launches;
+            }
+            if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
         }
         if (do_copy) {
             for (int q = 0; q < n; ++q) {
@@ -1580,7 +1588,9 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         // ---- all-gather -> GEMM, one launch per group of landed pieces
         if (!dependent) {
             if (do_copy) for (int q = 0; q < n; ++q) if ((rc = issue_copy_ag(q))) return rc;
-            if (do_gemm) for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
+            if (do_gemm)
+                for (int rp = 0; rp < (lean ? p->repeat : 1); ++rp)
+                    for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
         } else {
             for (size_t g = 0; g < p->groups.size(); ++g) {
                 bool any = false;
@@ -1599,7 +1609,9 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     } else {
         // ---- GEMM -> reduce-scatter (data movement): a group's rows leave as soon as its launch is done
         if (!dependent) {
-            if (do_gemm) for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
+            if (do_gemm)
+                for (int rp = 0; rp < (lean ? p->repeat : 1); ++rp)
+                    for (size_t g = 0; g < p->groups.size(); ++g) if ((rc = issue_gemm(g))) return rc;
             if (do_copy) {
                 if (!cap) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));
                 for (int q = 0; q < n; ++q) if ((rc = issue_copy_rs(q))) return rc;
