@@ -108,7 +108,7 @@ CONFIGS = {
     "cfg3_ffn70b": dict(M=16384, K=8192, N=3584, shards=8, chunk_rows=[2048, 1024, 512], seed=2,
                         direction="ag_gemm"),
     # GEMM -> reduce-scatter share (data movement half): output streamed out in 8 row blocks
-    "cfg4_gemm_rs": dict(M=16384, K=3584, N=8192, shards=8, chunk_rows=[2048, 512], seed=3,
+    "cfg4_gemm_rs": dict(M=16384, K=3584, N=8192, shards=8, chunk_rows=[2048, 512, 256, 128], seed=3,
                          direction="gemm_rs"),
     # expert-parallel dispatch -> grouped expert GEMM: 8 peers send unequal token counts to 2 local experts
     # (Mixtral-like expert width: K = 4096, N = a quarter of the fused gate+up projection)

@@ -185,6 +185,9 @@ struct ficco_plan_s {
     int wall_clock_khz = 100000;
     std::vector<hsa_signal_t> sig_data, sig_flag;   // copy-engine backend: per chunk id
     std::vector<hsa_signal_t> sig_gather, sig_scatter;   // packing: per chunk id
+    std::vector<hsa_signal_t> sig_done;              // resident GEMM -> RS: per chunk id, released by the kernel
+    uint64_t *d_done_value = nullptr;                // device table: value-word addresses of sig_done
+    uint32_t *d_done_count = nullptr;                // device: tiles of each piece stored so far (never reset)
     uint64_t *d_sig_value = nullptr;                 // device table: address of each data signal's value word
     int sig_poll = -1;                               // -1 unknown, 0 flags by 4-byte copies, 1 kernels poll the signals
     bool last_engines = false;
@@ -367,13 +370,17 @@ void release(ficco_plan_t *p)
         for (auto &e : *v) ev(e);
         v->clear();
     }
-    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter}) {
+    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter, &p->sig_done}) {
         for (auto &sg : *v) (void)hsa_signal_destroy(sg);
         v->clear();
     }
     if (p->d_words) (void)hipFree(p->d_words);
     if (p->d_ticket_mem) (void)hipFree(p->d_ticket_mem);
     if (p->d_sig_value) (void)hipFree(p->d_sig_value);
+    if (p->d_done_value) (void)hipFree(p->d_done_value);
+    if (p->d_done_count) (void)hipFree(p->d_done_count);
+    p->d_done_value = nullptr;
+    p->d_done_count = nullptr;
     p->d_sig_value = nullptr;
     p->sig_poll = -1;
     p->d_ticket_mem = nullptr;
@@ -590,17 +597,39 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
     return out;
 }
 
-// Row tiles per group in a resident launch's lists: what one step delivers to each of the kTicketLists
-// lists (all shards' pieces of a step arrive together in step-major order); with other orders pieces
-// arrive one by one, so tiles are taken row tile by row tile.
-inline int resident_group(const ficco_plan_t *p)
+// Geometry of the resident kernel's tile lists (see resident_list_tiles and the tile order notes in
+// the kernel file). S = row tiles that become available together (a step of the step-major order
+// brings G pieces, the other orders one piece). The lists are cut into col_lists column blocks so
+// that what an XCD has in flight - `group` row tiles of a step times a run of column tiles, at most
+// one workgroup slot each - needs the fewest operand bytes (rows of A plus rows of the packed weight).
+// Ties go to the smaller col_lists.
+struct ListGeometry { int group, col_lists; };
+inline ListGeometry resident_lists(const ficco_plan_t *p)
 {
-    static const char *force = getenv("FICCO_GROUP");
-    if (force && atoi(force) >= 1 && atoi(force) <= 4) return atoi(force);
-    if (p->order != FICCO_ORDER_STEP_MAJOR) return 1;
-    TileShape ts = tile_shape(p->tile);
-    const int64_t per_step = (int64_t)p->G * ((p->m + ts.bm - 1) / ts.bm);
-    return (int)std::max<int64_t>(1, std::min<int64_t>(4, per_step / kTicketLists));
+    static const char *force_g = getenv("FICCO_GROUP"), *force_c = getenv("FICCO_COL_LISTS");
+    const TileShape ts = tile_shape(p->tile);
+    const int64_t rt = (p->m + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
+    const int64_t S = (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt;
+    const int64_t slots = std::max<int64_t>(1, p->resident_grid / kTicketLists);
+    ListGeometry best{1, 1};
+    int64_t best_cost = -1;
+    for (int cl = 1; cl <= kTicketLists; cl *= 2) {
+        if (cl > 1 && cl > tn) break;
+        const int classes = kTicketLists / cl;
+        const int64_t rows = std::max<int64_t>(1, std::min<int64_t>(8, S / classes));      // the group
+        const int64_t width = (tn + cl - 1) / cl;                                             // column tiles of a list
+        // in flight on an XCD: `slots` tiles = part of a group, or several whole groups
+        const int64_t rows_active = rows * width >= slots ? rows : rows * ((slots + rows * width - 1) / (rows * width));
+        const int64_t cols_active = std::min<int64_t>(width, std::max<int64_t>(1, slots / rows));
+        const int64_t cost = rows_active * ts.bm + cols_active * ts.bn;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {(int)rows, cl}; }
+    }
+    if (force_c && (atoi(force_c) == 1 || atoi(force_c) == 2 || atoi(force_c) == 4 || atoi(force_c) == 8) && atoi(force_c) <= std::max<int64_t>(tn, 1)) {
+        best.col_lists = atoi(force_c);
+        best.group = (int)std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / best.col_lists)));
+    }
+    if (force_g && atoi(force_g) >= 1 && atoi(force_g) <= 8) best.group = atoi(force_g);
+    return best;
 }
 
 // bytes of one row of a transferred piece of the activation
@@ -634,6 +663,29 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     }
     HIP_TRY(launch_resident2d(p->tile, r, cs));
     return FICCO_OK;
+}
+
+// Address, as this GPU sees it, of the value word of a user signal (amd_signal_t, the layout AQL consumers
+// use), or 0 when the runtime does not report the word as accessible to the GPU.
+uint64_t signal_value_address(hsa_signal_t sg)
+{
+    amd_signal_t *as = reinterpret_cast<amd_signal_t *>(sg.handle);
+    if (!as || as->kind != AMD_SIGNAL_KIND_USER) return 0;
+    void *vp = (void *)&as->value;
+    hsa_amd_pointer_info_t info{};
+    info.size = sizeof(info);
+    uint32_t n_acc = 0;
+    hsa_agent_t *acc = nullptr;
+    if (hsa_amd_pointer_info(vp, &info, malloc, &n_acc, &acc) != HSA_STATUS_SUCCESS || info.type == HSA_EXT_POINTER_TYPE_UNKNOWN) {
+        if (acc) free(acc);
+        return 0;
+    }
+    bool mine = false;
+    for (uint32_t k = 0; k < n_acc; ++k) mine |= acc[k].handle == g_engines.gpu.handle;
+    if (acc) free(acc);
+    const uintptr_t off = (uintptr_t)vp - (uintptr_t)info.hostBaseAddress;
+    if (!mine || !info.agentBaseAddress || !info.hostBaseAddress || off + 8 > info.sizeInBytes) return 0;
+    return (uint64_t)((uintptr_t)info.agentBaseAddress + off);
 }
 
 // What every run on the copy-engine backend needs before it submits anything: the runtime, one
@@ -683,21 +735,8 @@ int engines_prepare(ficco_plan_t *p, bool touches_host, std::vector<int> &eng, i
         bool ok = p->flag_write == 0;
         for (int i = 0; i < n_tab && ok; ++i) {
             const hsa_signal_t sg_i = i < n ? p->sig_data[i] : i < 2 * n ? p->sig_gather[i - n] : p->sig_scatter[i - 2 * n];
-            amd_signal_t *as = reinterpret_cast<amd_signal_t *>(sg_i.handle);
-            if (!as || as->kind != AMD_SIGNAL_KIND_USER) { ok = false; break; }
-            void *vp = (void *)&as->value;
-            hsa_amd_pointer_info_t info{};
-            info.size = sizeof(info);
-            uint32_t n_acc = 0;
-            hsa_agent_t *acc = nullptr;
-            if (hsa_amd_pointer_info(vp, &info, malloc, &n_acc, &acc) != HSA_STATUS_SUCCESS ||
-                info.type == HSA_EXT_POINTER_TYPE_UNKNOWN) { ok = false; if (acc) free(acc); break; }
-            bool mine = false;
-            for (uint32_t k = 0; k < n_acc; ++k) mine |= acc[k].handle == ctx.gpu.handle;
-            if (acc) free(acc);
-            const uintptr_t off = (uintptr_t)vp - (uintptr_t)info.hostBaseAddress;
-            if (!mine || !info.agentBaseAddress || !info.hostBaseAddress || off + 8 > info.sizeInBytes) { ok = false; break; }
-            addr[i] = (uint64_t)((uintptr_t)info.agentBaseAddress + off);
+            addr[i] = signal_value_address(sg_i);
+            ok = addr[i] != 0;
         }
         if (ok) {
             if (hipMalloc((void **)&p->d_sig_value, sizeof(uint64_t) * (size_t)n_tab) != hipSuccess) return FICCO_ERR_ALLOC;
@@ -869,6 +908,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     int64_t copy_bytes = 0;
     // one piece: data copy, then the 4-byte flag copy behind it on the same engine
     int prev_chunk = -1;
+    std::vector<hsa_signal_t> *extra_dep = nullptr;      // per chunk id: one more signal every transfer waits for
     auto submit = [&](int q) -> int {
         const int chunk = p->arrival[q];
         if (is_local(chunk)) return FICCO_OK;
@@ -892,10 +932,11 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             dst = (char *)peer_out[peer] + (size_t)(chunk % c) * p->m * row_bytes_c;
             if (!peer_dev[peer]) { dst_agent = ctx.cpu; force = false; }
         }
-        hsa_signal_t dep{};
+        hsa_signal_t dep[2];
         int ndep = 0;
-        if (chained && prev_chunk >= 0) { dep = p->sig_data[prev_chunk]; ndep = 1; }
-        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? &dep : nullptr,
+        if (chained && prev_chunk >= 0) dep[ndep++] = p->sig_data[prev_chunk];
+        if (extra_dep) dep[ndep++] = (*extra_dep)[chunk];
+        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? dep : nullptr,
                                                               p->sig_data[chunk], engine, force);
         if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
         prev_chunk = chunk;
@@ -1034,14 +1075,16 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 r.g.gate = gate;
                 r.ticket = p->d_ticket;
                 r.grid = p->resident_grid;
-                r.group = resident_group(p);
+                const ListGeometry lg = resident_lists(p);
+                r.group = lg.group;
+                r.col_lists = lg.col_lists;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
                 TileShape ts = tile_shape(p->tile);
                 for (int x = 0; x < kTicketLists; ++x) {
                     r.ticket_base[x] = p->ticket_total[x];
                     p->ticket_total[x] += resident_list_draws(resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
-                                                                                  (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
+                                                                                  (p->N + ts.bn - 1) / ts.bn, x, r.col_lists), r.grid, x);
                 }
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(launch_resident(p->tile, r, cs));
@@ -1064,6 +1107,59 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                     HIP_TRY(launch_wait_ready(gate, p->d_arrival + first, n - first, cs));
             }
         }
+    } else if (p->schedule == FICCO_FINE_PERSISTENT) {
+        // ---- GEMM -> RS with one resident kernel and no host in the loop: every transfer is submitted up
+        // front with a dependency signal of its own; the kernel counts the tiles of each piece and the
+        // one that completes a piece stores 0 into that signal's value word, which lets the copy go.
+        if (!(do_gemm && do_copy && dependent)) return FICCO_ERR_ARG;        // the pair only
+        while ((int)p->sig_done.size() < n) {
+            hsa_signal_t a;
+            if (make_signal(&a) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
+            p->sig_done.push_back(a);
+        }
+        if (!p->d_done_value) {
+            std::vector<uint64_t> addr(n);
+            for (int i = 0; i < n; ++i)
+                if (!(addr[i] = signal_value_address(p->sig_done[i]))) return FICCO_ERR_HIP;   // needs signals the GPU can write
+            if (hipMalloc((void **)&p->d_done_value, sizeof(uint64_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemcpy(p->d_done_value, addr.data(), sizeof(uint64_t) * (size_t)n, hipMemcpyHostToDevice));
+            if (hipMalloc((void **)&p->d_done_count, sizeof(uint32_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemset(p->d_done_count, 0, sizeof(uint32_t) * (size_t)n));
+        }
+        for (int i = 0; i < n; ++i) hsa_signal_store_relaxed(p->sig_done[i], 1);
+        // transfers first (they wait for their pieces), then the launch
+        extra_dep = &p->sig_done;
+        for (int q = 0; q < n; ++q)
+            if ((rc = submit(q))) return rc;
+        extra_dep = nullptr;
+        {
+            ResidentLaunch r{};
+            Group all{0, n};
+            r.g = make_launch(p, all, A_dev, C_dev);
+            r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
+            r.arrival = p->d_arrival;
+            r.n_chunks = n;
+            r.g.gate = gate;
+            r.ticket = p->d_ticket;
+            r.grid = p->resident_grid;
+            const ListGeometry lg = resident_lists(p);
+            r.group = lg.group;
+            r.col_lists = lg.col_lists;
+            r.local_chunk_begin = 0; r.local_chunk_end = n;                   // A is resident: nothing to wait for
+            TileShape ts = tile_shape(p->tile);
+            const int64_t rt = (p->m + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
+            r.done_count = p->d_done_count;
+            r.done_sig = p->d_done_value;
+            r.tiles_per_chunk = (int32_t)(rt * tn);
+            for (int x = 0; x < kTicketLists; ++x) {
+                r.ticket_base[x] = p->ticket_total[x];
+                p->ticket_total[x] += resident_list_draws(resident_list_tiles((int64_t)n * rt, tn, x, r.col_lists), r.grid, x);
+            }
+            HIP_TRY(launch_resident(p->tile, r, cs));
+            ++n_launches;
+        }
+        HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
+        if (!p->hold_flags) HIP_TRY(launch_wait_ready(gate, p->d_arrival, n, cs));
     } else {
         // ---- GEMM -> RS: a group's rows leave when its launch is done (the host relays the event)
         if (do_gemm) {
@@ -1367,7 +1463,13 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     if (rs) {
         if (A_src) return FICCO_ERR_ARG;
         if (do_copy && !peer_out) return FICCO_ERR_ARG;
-        if (is_resident(p) || p->local_shard >= 0) return FICCO_ERR_ARG;
+        if (is_2d(p) || p->local_shard >= 0) return FICCO_ERR_ARG;
+        // resident kernel: alone, or as the pair with its transfers released by the kernel itself (engines only)
+        if (is_resident(p) && mode != FICCO_MODE_GEMM_ONLY &&
+            (mode != FICCO_MODE_PAIR || p->backend_opt == FICCO_COPY_STREAM || p->timing))
+            return FICCO_ERR_ARG;
+        // its epilogue writes 16-byte row segments
+        if (is_resident(p) && (p->N % 8 != 0 || ((uintptr_t)C_dev & 15) != 0)) return FICCO_ERR_ARG;
     } else {
         if (peer_out) return FICCO_ERR_ARG;
         if (do_copy && !A_src) return FICCO_ERR_ARG;
@@ -1417,7 +1519,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     // device-to-host copies were faster than the engines picked here (cfg4: 5.0 ms against 5.9 ms).
     bool any_peer_dev = false;
     for (char d : peer_dev) any_peer_dev |= (bool)d;
-    const bool host_peers_only = rs && do_copy && !any_peer_dev;
+    const bool host_peers_only = rs && do_copy && !any_peer_dev && !is_resident(p);
     if (backend == FICCO_COPY_AUTO)
         backend = (packed || (do_copy && p->flag_write != 1 && !host_peers_only)) ? FICCO_COPY_ENGINES : FICCO_COPY_STREAM;
     p->backend = backend;
@@ -1555,7 +1657,9 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 r.g.gate = gate;
                 r.ticket = p->d_ticket;
                 r.grid = grid;
-                r.group = resident_group(p);
+                const ListGeometry lg = resident_lists(p);
+                r.group = lg.group;
+                r.col_lists = lg.col_lists;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
                 else if (p->local_shard >= 0) { r.local_chunk_begin = p->local_shard * c; r.local_chunk_end = (p->local_shard + 1) * c; }
                 else { r.local_chunk_begin = 0; r.local_chunk_end = 0; }
@@ -1563,7 +1667,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 for (int x = 0; x < kTicketLists; ++x) {
                     r.ticket_base[x] = p->ticket_total[x];
                     p->ticket_total[x] += resident_list_draws(resident_list_tiles((int64_t)n * ((p->m + ts.bm - 1) / ts.bm),
-                                                                                  (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
+                                                                                  (p->N + ts.bn - 1) / ts.bn, x, r.col_lists), r.grid, x);
                 }
                 HIP_TRY(launch_resident(p->tile, r, cs));
             }
@@ -1969,6 +2073,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
                 }
             }
             s.timed_out = 1;
+            for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);   // let parked copies go
             HIP_TRY(hipMemset(p->d_status, 0, 4));
             p->h_status[0] = 0;
         }
@@ -2086,6 +2191,7 @@ void ficco_destroy(ficco_plan_t *p)
 {
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
+    for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);      // nothing may stay parked behind a piece that never completed
     for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter})
         for (auto &sg : *v) (void)wait_signal(sg, 5.0);
     release(p);

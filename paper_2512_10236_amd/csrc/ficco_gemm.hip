@@ -93,13 +93,21 @@ static __device__ __forceinline__ void tile_zero(TileAcc<T> &ta)
             for (int v = 0; v < 16; ++v) ta.acc[j][i][v] = 0.f;
 }
 
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+
 // Adds A[rows, k0 .. k0+K) * W[k0 .. k0+K, cols) to the tile's accumulators; a_tile / wt_tile point
 // at column k0 of the tile's first row of A / Wt. Calling it for consecutive k ranges in ascending
 // order gives exactly the accumulation sequence of one call over the whole range.
-template <class T>
+// `after_first_wait` runs once, right after the first k-step's wait and barrier: vector memory
+// operations complete in issue order, so by then every store that any wavefront of the workgroup
+// issued before this call has been performed.
+template <class T, class Hook = NoHook>
 static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uint16_t *__restrict__ a_tile, int rows_valid,
                                                        const uint16_t *__restrict__ wt_tile, int cols_valid,
-                                                       int64_t lda, int64_t ldw, int K, unsigned char *smem)
+                                                       int64_t lda, int64_t ldw, int K, unsigned char *smem,
+                                                       Hook after_first_wait = Hook())
 {
     f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
     const int tid = threadIdx.x;
@@ -161,6 +169,7 @@ static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uin
             else wait_vmem<0>();
         }
         wg_barrier();                      // ... and so has everyone else's; the stage of k-tile kt-1 is free again
+        if (kt == 0) after_first_wait();
         const bool more = kt + D < KT;
         const int nxt = (kt + D) % T::NSTAGE;
         const unsigned char *base = smem + cur * T::STAGE;
@@ -236,6 +245,59 @@ static __device__ __forceinline__ void tile_store(const TileAcc<T> &ta, uint16_t
                         *reinterpret_cast<u32x2_t *>(crow + n) = p;
                     }
                 }
+        }
+    }
+}
+
+// The same result stored as whole row segments: a wavefront passes each 32-row block of its part of
+// the tile through LDS (rows padded by 16 B so that they spread over the banks) and reads it back
+// with consecutive lanes on consecutive 16-byte slots of a row, so a store instruction writes whole
+// 128-byte lines instead of 16 bytes in each of 32 rows. Written through the caches (system scope):
+// this is the epilogue for output that a copy engine reads while the kernel runs on, where partial
+// lines would each go to memory on their own. Needs ldc % 8 == 0 and a 16-byte aligned C; uses the
+// first 4 * 32 * (2 WTN + 16) bytes of the ring, which must be idle (tile_accumulate's final barrier)
+// and stay idle until a workgroup barrier after the call.
+template <class T>
+static __device__ __forceinline__ void tile_store_rows_through(const TileAcc<T> &ta, uint16_t *__restrict__ c_tile, int rows_valid,
+                                                               int cols_valid, int64_t ldc, unsigned char *smem)
+{
+    constexpr int SEG = T::WTN / 8;                 // 16-byte slots per row of the wavefront's part
+    constexpr int STRIDE = T::WTN * 2 + 16;         // bytes between rows in LDS
+    static_assert(4 * 32 * STRIDE <= T::LDS_BYTES, "staging area must fit the ring");
+    static_assert((32 * SEG) % 64 == 0, "whole wavefront instructions");
+    const f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const int frow = lane & 31, fh = lane >> 5;
+    unsigned char *mine = smem + wave * (32 * STRIDE);
+#pragma unroll
+    for (int i = 0; i < T::FM; ++i) {
+#pragma unroll
+        for (int j = 0; j < T::FN; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                u32x2_t p;
+                p.x = pack2_bf16_rne(acc[j][i][4 * b + 0], acc[j][i][4 * b + 1]);
+                p.y = pack2_bf16_rne(acc[j][i][4 * b + 2], acc[j][i][4 * b + 3]);
+                *reinterpret_cast<u32x2_t *>(mine + frow * STRIDE + (j * 32 + 8 * b + 4 * fh) * 2) = p;
+            }
+        // same wavefront, LDS operations execute in order: no barrier between the two phases
+#pragma unroll
+        for (int it = 0; it < (32 * SEG) / 64; ++it) {
+            const int q = it * 64 + lane;
+            const int row = q / SEG, seg = q % SEG;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(mine + row * STRIDE + seg * 16);
+            const int m = wm * T::WTM + i * 32 + row;
+            const int n = wn * T::WTN + seg * 8;
+            if (m < rows_valid && n < cols_valid) {
+                uint16_t *dst = c_tile + (int64_t)m * ldc + n;
+                if (n + 8 <= cols_valid)
+                    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst), "v"(v) : "memory");
+                else   // N is a multiple of 4: the last slot of a row may be half there
+                    __hip_atomic_store(reinterpret_cast<uint64_t *>(dst), (uint64_t)v.x | ((uint64_t)v.y << 32), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_SYSTEM);
+            }
         }
     }
 }
@@ -329,7 +391,11 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
 // runs on (workgroups are dispatched round-robin over the XCDs), so that the tiles sharing an L2 at
 // any time are few row tiles times a run of column tiles, and then helps the other lists. Inside a
 // list tiles go in groups of a few row tiles, row tile fastest: as many as one step delivers to the
-// list (so that no workgroup draws a tile of the next step while tiles of this one are left), 1 to 4.
+// list (so that no workgroup draws a tile of the next step while tiles of this one are left), 1 to 8.
+// When a step delivers few row tiles and there are many column tiles, one row tile times all columns
+// per XCD would stream the whole weight through every L2 once per round; the row-piece kernel then
+// splits the lists by column block as well (ResidentLaunch::col_lists), so that an XCD works on
+// several row tiles of the step times a run of columns, as a launch over the step's pieces would.
 //
 // TileWalk hands a workgroup its next (list, tile) pair. The first tile of the first list is the
 // workgroup's rank among the workgroups that start there (no memory access); later tiles are drawn
@@ -435,12 +501,32 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_chunk = (a.rows_per_block + T::BM - 1) / T::BM;
     const int row_tiles = r.n_chunks * rt_per_chunk;
-    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
-    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
+    // the lists as a grid of row classes x column blocks (see resident_list_tiles)
+    const int classes = kTicketLists / r.col_lists;
+    auto list_rows = [&](int x) { const int rc = x % classes; return row_tiles > rc ? (row_tiles - rc + classes - 1) / classes : 0; };
+    auto col_begin = [&](int x) { return (x / classes) * tiles_n / r.col_lists; };
+    auto list_cols = [&](int x) { return (x / classes + 1) * tiles_n / r.col_lists - col_begin(x); };
+    auto total_of = [&](int x) { return list_rows(x) * list_cols(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
     uint32_t drawn = 0;
+    // Output streaming (done_count set): a copy engine reads a piece of C while the kernel runs on, so
+    // the tiles are written through the caches, and a tile is counted for its piece once every thread's
+    // stores have been performed; whoever completes a piece lets its copy go. Ordering is by hand
+    // (stores, their completion, barrier, counter, signal): a release fence would write back the whole
+    // L2 once per tile. So that nobody waits for stores, a tile is counted under the next tile's
+    // first k-step, or after the loop if it was the workgroup's last.
+    int stored_chunk = -1;                 // thread 0: piece of the tile stored last and not yet counted
+    auto count_stored = [&]() {
+        if (threadIdx.x == 0 && stored_chunk >= 0) {
+            const uint32_t before = __hip_atomic_fetch_add(r.done_count + stored_chunk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((before + 1u) % (uint32_t)r.tiles_per_chunk == 0u)
+                __hip_atomic_store(reinterpret_cast<int64_t *>(r.done_sig[stored_chunk]), (int64_t)0, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            stored_chunk = -1;
+        }
+    };
     for (;;) {
         if (threadIdx.x == 0) {
             TileWalk w = s_walk;
@@ -449,8 +535,8 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
             int ok = 1;
             if (w.x >= 0) {
                 int rl, tn;
-                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn, r.group);
-                const int chunk = r.arrival[(rl * kTicketLists + w.x) / rt_per_chunk];
+                list_tile_position(w.t, list_rows(w.x), list_cols(w.x), rl, tn, r.group);
+                const int chunk = r.arrival[(rl * classes + w.x % classes) / rt_per_chunk];
                 if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
             }
             s_walk = w;
@@ -461,8 +547,9 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         if (x < 0) break;
         if (s_ok) {
             int rl, tn;
-            list_tile_position(t, list_rows(x), tiles_n, rl, tn, r.group);
-            const int R = rl * kTicketLists + x;
+            list_tile_position(t, list_rows(x), list_cols(x), rl, tn, r.group);
+            tn += col_begin(x);
+            const int R = rl * classes + x % classes;
             const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
             const int chunk = r.arrival[p];
             const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
@@ -471,12 +558,23 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
             const int cols_valid = min(T::BN, a.N - col0);
             TileAcc<T> ta;
             tile_zero(ta);
-            tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem);
+            tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem,
+                               count_stored);
             // the next ticket's round trip runs under the epilogue
             if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
-            tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
+            if (!r.done_count) {
+                tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
+            } else {
+                tile_store_rows_through<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc, smem);
+                stored_chunk = chunk;
+            }
         }
         __syncthreads();                   // s_walk / s_ok / LDS stages are reused
+    }
+    if (r.done_count) {
+        wait_vmem<0>();
+        __syncthreads();
+        count_stored();
     }
 }
 

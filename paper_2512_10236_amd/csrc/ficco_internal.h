@@ -17,11 +17,16 @@ constexpr int kFlagStrideWords = 16;      // one ready flag per 64-byte line
 constexpr int kBK = 64;                   // k extent of one LDS stage
 constexpr int kTicketLists = 8;           // one tile list per XCD (each XCD has its own L2)
 
-// Tiles of the resident kernel that list x (of kTicketLists) holds: row tiles x, x+8, x+16, ... of the
-// arrival-ordered sequence of row tiles, times all column tiles.
-__host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_t tiles_n, int x)
+// Tiles of the resident kernels that list x (of kTicketLists) holds. The lists form a grid of
+// kTicketLists / col_lists row classes by col_lists column blocks: list x takes the row tiles
+// rc, rc + classes, rc + 2 classes, ... (rc = x % classes) of the arrival-ordered sequence of row
+// tiles, times the column tiles of block x / classes (the column tiles cut into col_lists nearly
+// equal runs). col_lists = 1: every list spans all column tiles.
+__host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_t tiles_n, int x, int col_lists = 1)
 {
-    return (row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0) * tiles_n;
+    const int classes = kTicketLists / col_lists, rc = x % classes, cb = x / classes;
+    const int64_t rows = row_tiles > rc ? (row_tiles - rc + classes - 1) / classes : 0;
+    return rows * ((cb + 1) * tiles_n / col_lists - cb * tiles_n / col_lists);
 }
 
 // Workgroups of a resident launch whose first list is x (workgroup b starts on list b % kTicketLists).
@@ -80,8 +85,14 @@ struct ResidentLaunch {
     uint32_t *ticket;             // device, kTicketLists counters kFlagStrideWords apart, monotonically increasing across runs
     uint32_t ticket_base[8];      // value of each counter when this run starts
     int32_t grid;
-    int32_t group;                // row tiles per group of a list's tile order (1..4)
+    int32_t group;                // row tiles per group of a list's tile order (1..8)
+    int32_t col_lists;            // column blocks the lists are split into (1, 2, 4 or 8; see resident_list_tiles)
     int32_t local_chunk_begin, local_chunk_end;   // chunk ids that need no flag (already resident), or empty
+    // GEMM -> reduce-scatter: when the last tile of a piece has been stored, the kernel releases the copy
+    // that waits for the piece by storing 0 into the value word of the copy's dependency signal.
+    uint32_t *done_count;         // device, one counter per chunk id, never reset: a run adds tiles_per_chunk to each
+    const uint64_t *done_sig;     // device table: address of the value word of each chunk's dependency signal
+    int32_t tiles_per_chunk;      // row tiles per piece x column tiles
 };
 
 // The resident kernel for column (K) pieces: A is kept in K-sliced layout [slices][M][K/slices]; piece

@@ -236,8 +236,11 @@ def test_gemm_rs_streams_row_blocks_to_peers(gpu):
     W = fi.make_weight(3, K, N)
     blocks = og.gemm_rs_blocks(A, W, G)
     base = None
-    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4), (ficco.FICCO_FINE_FUSED, 2)]:
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_SHARD, 1), (ficco.FICCO_FINE_UNFUSED, 4), (ficco.FICCO_FINE_FUSED, 2),
+                     (ficco.FICCO_FINE_PERSISTENT, 4), (ficco.FICCO_FINE_PERSISTENT, 1)]:
         for kind, backend in (("device", None), ("pinned", STREAM), ("pinned", ENGINES)):
+            if sched == ficco.FICCO_FINE_PERSISTENT and backend == STREAM:
+                continue                                   # the kernel releases copy-engine transfers: engine backend only
             A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
             C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
             if kind == "device":
@@ -250,8 +253,12 @@ def test_gemm_rs_streams_row_blocks_to_peers(gpu):
                 ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
                 if backend is not None:
                     ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
-                ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
-                st = ficco.ficco_query_stats(plan)
+                for rep_ in range(2):                     # twice: the per-piece tile counters are never reset
+                    for p_ in peers:
+                        p_.fill_(NAN_BF16)
+                    torch.cuda.synchronize()
+                    ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
+                    st = ficco.ficco_query_stats(plan)
             finally:
                 ficco.ficco_destroy(plan)
             torch.cuda.synchronize()
@@ -594,7 +601,7 @@ def test_cfg4_gemm_rs_full_size_sampled_rows(gpu):
     ref = og.ag_gemm_rows([A], W, rows)
     A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
     base = None
-    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, 4)]:        # bench.py times fused with 4 pieces
+    for sched, c in [(ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, 4), (ficco.FICCO_FINE_PERSISTENT, 8)]:   # what bench.py screens
         C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
         peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16, device=dev) for _ in range(G)]
         torch.cuda.synchronize()
