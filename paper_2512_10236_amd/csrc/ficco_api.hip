@@ -600,9 +600,8 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
 // Geometry of the resident kernel's tile lists (see resident_list_tiles and the tile order notes in
 // the kernel file). S = row tiles that become available together (a step of the step-major order
 // brings G pieces, the other orders one piece). The lists are cut into col_lists column blocks so
-// that what an XCD has in flight - `group` row tiles of a step times a run of column tiles, at most
-// one workgroup slot each - needs the fewest operand bytes (rows of A plus rows of the packed weight).
-// Ties go to the smaller col_lists.
+// that what an XCD has in flight - groups of `group` row tiles of a step times a run of column tiles,
+// one workgroup slot each - costs least by tile_order_cost. Ties go to the smaller col_lists and group.
 struct ListGeometry { int group, col_lists; };
 inline ListGeometry resident_lists(const ficco_plan_t *p)
 {
@@ -611,24 +610,20 @@ inline ListGeometry resident_lists(const ficco_plan_t *p)
     const int64_t rt = (p->m + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
     const int64_t S = (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt;
     const int64_t slots = std::max<int64_t>(1, p->resident_grid / kTicketLists);
+    const bool big = (p->M + p->N) * p->K * 2 > kCacheBudgetBytes;
     ListGeometry best{1, 1};
-    int64_t best_cost = -1;
+    double best_cost = -1;
     for (int cl = 1; cl <= kTicketLists; cl *= 2) {
         if (cl > 1 && cl > tn) break;
-        const int classes = kTicketLists / cl;
-        const int64_t rows = std::max<int64_t>(1, std::min<int64_t>(8, S / classes));      // the group
-        const int64_t width = (tn + cl - 1) / cl;                                             // column tiles of a list
-        // in flight on an XCD: `slots` tiles = part of a group, or several whole groups
-        const int64_t rows_active = rows * width >= slots ? rows : rows * ((slots + rows * width - 1) / (rows * width));
-        const int64_t cols_active = std::min<int64_t>(width, std::max<int64_t>(1, slots / rows));
-        const int64_t cost = rows_active * ts.bm + cols_active * ts.bn;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {(int)rows, cl}; }
+        if (force_c && atoi(force_c) != cl) continue;
+        // a group must not span steps: no workgroup should draw a tile of the next step while tiles of this one are left
+        const int64_t g_max = std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / cl)));
+        for (int g = 1; g <= g_max; g *= 2) {
+            if (force_g && atoi(force_g) != g) continue;
+            const double cost = tile_order_cost(ts.bm, ts.bn, tn, slots, cl, g, big);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {g, cl}; }
+        }
     }
-    if (force_c && (atoi(force_c) == 1 || atoi(force_c) == 2 || atoi(force_c) == 4 || atoi(force_c) == 8) && atoi(force_c) <= std::max<int64_t>(tn, 1)) {
-        best.col_lists = atoi(force_c);
-        best.group = (int)std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / best.col_lists)));
-    }
-    if (force_g && atoi(force_g) >= 1 && atoi(force_g) <= 8) best.group = atoi(force_g);
     return best;
 }
 

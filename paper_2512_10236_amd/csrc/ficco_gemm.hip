@@ -16,6 +16,7 @@
 // instruction, whatever the tile shape or row block, which makes results bit-identical across
 // schedules.
 #include "ficco_internal.h"
+#include <stdlib.h>
 
 namespace ficco {
 
@@ -338,14 +339,18 @@ static __device__ __forceinline__ int wait_ready(const Gate &g, int chunk)
     }
 }
 
-// Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2). Renumber them so
-// that consecutive logical ids run on the same XCD, then walk the tile grid in groups of GROUP_M
-// row tiles so that one XCD works on few A row tiles and W column tiles at a time.
-static __device__ __forceinline__ int xcd_contiguous_id(int pid, int total)
+// Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2). The tiles are cut
+// into 8 runs of consecutive logical ids, one per XCD, and the tile grid is walked in groups of
+// group_m row tiles, so that one XCD works on few A row tiles and W column tiles at a time. A launch
+// with more tiles than the machine holds workgroups is started with that many workgroups only, and a
+// workgroup takes every stride-th tile of its XCD's run: what is in flight on an XCD is the same run of
+// ids that one workgroup per tile would give, without a workgroup start per tile.
+struct XcdRun { int start, count, first, stride; };
+static __device__ __forceinline__ XcdRun xcd_run(int pid, int grid, int total)
 {
     const int q = total >> 3, r = total & 7;
-    const int xcd = pid & 7, idx = pid >> 3;
-    return (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + idx;
+    const int xcd = pid & 7;
+    return {xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q, q + (xcd < r ? 1 : 0), pid >> 3, (grid - xcd + 7) >> 3};
 }
 
 template <class T>
@@ -366,23 +371,26 @@ __global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
     const int rt_per_block = (a.rows_per_block + T::BM - 1) / T::BM;
     const int tiles_m = a.n_blocks * rt_per_block;
     const int total = tiles_m * tiles_n;
-    const int lid = xcd_contiguous_id(blockIdx.x, total);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = lid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = min(tiles_m - first_m, GROUP_M);
-    const int tm = first_m + (lid % per_group) % gsz;
-    const int tn = (lid % per_group) / gsz;
+    const XcdRun run = xcd_run(blockIdx.x, gridDim.x, total);
+    const int per_group = a.group_m * tiles_n;
+    for (int t = run.first; t < run.count; t += run.stride) {
+        const int lid = run.start + t;
+        const int group = lid / per_group;
+        const int first_m = group * a.group_m;
+        const int gsz = min(tiles_m - first_m, a.group_m);
+        const int tm = first_m + (lid % per_group) % gsz;
+        const int tn = (lid % per_group) / gsz;
 
-    const int blk = tm / rt_per_block, rt = tm % rt_per_block;
-    const int brow0 = a.block_row0 ? a.block_row0[blk] : a.row0;
-    const int64_t row0 = (int64_t)brow0 + (int64_t)rt * T::BM;
-    const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
-    const int col0 = tn * T::BN;
-    const int cols_valid = min(T::BN, a.N - col0);
-    compute_tile<T>(a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid,
-                    a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
+        const int blk = tm / rt_per_block, rt = tm % rt_per_block;
+        const int brow0 = a.block_row0 ? a.block_row0[blk] : a.row0;
+        const int64_t row0 = (int64_t)brow0 + (int64_t)rt * T::BM;
+        const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
+        const int col0 = tn * T::BN;
+        const int cols_valid = min(T::BN, a.N - col0);
+        // (tile_accumulate ends with a barrier after the last LDS read, so the next tile may refill the ring)
+        compute_tile<T>(a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid,
+                        a.C + row0 * a.ldc + col0, a.lda, a.K, a.ldc, a.K, smem);
+    }
 }
 
 // Tile order of the resident kernels. Row tiles are numbered in arrival order (R = arrival position x
@@ -762,7 +770,38 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
     const int rt = (a.rows_per_block + T::BM - 1) / T::BM;
     const int64_t total = (int64_t)a.n_blocks * rt * tiles_n;
     if (total <= 0 || total > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_blocks_kernel<T>, dim3((unsigned)total), dim3(256), T::LDS_BYTES, s, a);
+    // at most as many workgroups as run at once (a multiple of 8, one share per XCD); the rest of the tiles
+    // are taken by the kernel's loop
+    static const bool loop = !(getenv("FICCO_BLOCKS_LOOP") && atoi(getenv("FICCO_BLOCKS_LOOP")) == 0);
+    int64_t grid = total;
+    if (loop) {
+        static int fit_of[64];                       // per device: 0 = not asked yet, -1 = could not be asked
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+        int fit = dev < 64 ? fit_of[dev] : 0;
+        if (fit == 0) {
+            int per_cu = 0, cus = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_blocks_kernel<T>, 256, T::LDS_BYTES) == hipSuccess &&
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu * cus >= 8)
+                fit = per_cu * cus / 8 * 8;
+            else
+                fit = -1;
+            if (dev < 64) fit_of[dev] = fit;
+        }
+        if (fit > 0 && total > fit) grid = fit;
+    }
+    // group height of the tile order: matters when the launch runs for several rounds
+    GemmLaunch b = a;
+    b.group_m = 8;
+    if (total > grid) {
+        const bool big = ((int64_t)a.n_blocks * a.rows_per_block + a.N) * a.K * 2 > kCacheBudgetBytes;
+        double best = -1;
+        for (int g = 1; g <= 8; g *= 2) {
+            const double c = tile_order_cost(T::BM, T::BN, tiles_n, grid / 8, 1, g, big);
+            if (best < 0 || c < best) { best = c; b.group_m = g; }
+        }
+    }
+    hipLaunchKernelGGL(gemm_blocks_kernel<T>, dim3((unsigned)grid), dim3(256), T::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 

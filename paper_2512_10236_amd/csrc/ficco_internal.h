@@ -1,6 +1,7 @@
 // Internal declarations shared by the kernel file and the C-ABI file of libficco. Not installed.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 namespace ficco {
@@ -28,6 +29,27 @@ __host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_
     const int64_t rows = row_tiles > rc ? (row_tiles - rc + classes - 1) / classes : 0;
     return rows * ((cb + 1) * tiles_n / col_lists - cb * tiles_n / col_lists);
 }
+
+// Relative cost of a tile order for one XCD, whose L2 is filled with what its workgroups have in
+// flight: `slots` tiles taken from groups of g row tiles x `width` column tiles (width = the tn column
+// tiles cut into col_lists blocks), i.e. part of one group or several whole groups. Counted in operand
+// rows per k-step: rows of A plus rows of the packed weight. When the operands are too large for the
+// memory-side cache (`big`), rows of A come from HBM and weigh double - unless the col_lists XCDs that
+// walk the same row tiles at the same time share the fetch, which only works while a group stays in
+// flight for at most two rounds. Fitted to sweeps of (col_lists, g) on shapes with 14 and 32 column tiles.
+__host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t slots, int col_lists, int g, bool big)
+{
+    const int64_t width = (tn + col_lists - 1) / col_lists;
+    const int64_t per_group = (int64_t)g * width;
+    const double rows_active = per_group >= slots ? (double)g : (double)g * (double)slots / (double)per_group;
+    int64_t cols_active = slots / g > 1 ? slots / g : 1;
+    if (cols_active > width) cols_active = width;
+    const double a_weight = !big ? 1.0 : (per_group > 2 * slots ? 2.0 : 1.0 + 1.0 / col_lists);
+    // among orders with the same footprint the sweeps favour groups of about three rounds of tiles
+    const double off = log2((double)per_group / (3.0 * (double)slots));
+    return (rows_active * bm * a_weight + (double)cols_active * bn) * (1.0 + 0.01 * (off < 0 ? -off : off));
+}
+constexpr int64_t kCacheBudgetBytes = 192ll << 20;    // operands beyond this do not stay in the 256 MB memory-side cache
 
 // Workgroups of a resident launch whose first list is x (workgroup b starts on list b % kTicketLists).
 __host__ __device__ inline int resident_list_homes(int grid, int x) { return grid > x ? (grid - x + kTicketLists - 1) / kTicketLists : 0; }
@@ -69,6 +91,7 @@ struct GemmLaunch {
     int32_t row0;                // first row when block_row0 == nullptr (n_blocks == 1)
     int32_t n_blocks;
     int32_t rows_per_block;
+    int32_t group_m;             // row tiles per group of the tile order (set by the launcher)
     // Optional gate (copy-engine transfers): every workgroup waits until all of the pieces
     // wait_chunks[0..n_wait) are ready.
     Gate gate;
