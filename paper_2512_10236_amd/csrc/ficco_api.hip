@@ -603,14 +603,9 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
 // that what an XCD has in flight - groups of `group` row tiles of a step times a run of column tiles,
 // one workgroup slot each - costs least by tile_order_cost. Ties go to the smaller col_lists and group.
 struct ListGeometry { int group, col_lists; };
-inline ListGeometry resident_lists(const ficco_plan_t *p)
+inline ListGeometry pick_lists(const TileShape &ts, int64_t tn, int64_t S, int64_t slots, bool big)
 {
     static const char *force_g = getenv("FICCO_GROUP"), *force_c = getenv("FICCO_COL_LISTS");
-    const TileShape ts = tile_shape(p->tile);
-    const int64_t rt = (p->m + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
-    const int64_t S = (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt;
-    const int64_t slots = std::max<int64_t>(1, p->resident_grid / kTicketLists);
-    const bool big = (p->M + p->N) * p->K * 2 > kCacheBudgetBytes;
     ListGeometry best{1, 1};
     double best_cost = -1;
     for (int cl = 1; cl <= kTicketLists; cl *= 2) {
@@ -620,11 +615,20 @@ inline ListGeometry resident_lists(const ficco_plan_t *p)
         const int64_t g_max = std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / cl)));
         for (int g = 1; g <= g_max; g *= 2) {
             if (force_g && atoi(force_g) != g) continue;
-            const double cost = tile_order_cost(ts.bm, ts.bn, tn, slots, cl, g, big);
+            const double cost = tile_order_cost(ts.bm, ts.bn, tn, std::max<int64_t>(1, slots), cl, g, big);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {g, cl}; }
         }
     }
     return best;
+}
+
+// row pieces: a step of the step-major order brings G pieces, the other orders one piece at a time
+inline ListGeometry resident_lists(const ficco_plan_t *p)
+{
+    const TileShape ts = tile_shape(p->tile);
+    const int64_t rt = (p->m + ts.bm - 1) / ts.bm;
+    return pick_lists(ts, (p->N + ts.bn - 1) / ts.bn, (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt,
+                      p->resident_grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
 }
 
 // bytes of one row of a transferred piece of the activation
@@ -652,9 +656,14 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     r.grid = grid;
     r.gated = gated ? 1 : 0;
     TileShape ts = tile_shape(p->tile);
+    const int64_t row_tiles = (p->M + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
+    // column pieces: every tile can start with the first step, so any group height goes
+    const ListGeometry lg = pick_lists(ts, tn, row_tiles, grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
+    r.group = lg.group;
+    r.col_lists = lg.col_lists;
     for (int x = 0; x < kTicketLists; ++x) {
         r.ticket_base[x] = p->ticket_total[x];
-        p->ticket_total[x] += resident_list_draws(resident_list_tiles((p->M + ts.bm - 1) / ts.bm, (p->N + ts.bn - 1) / ts.bn, x), grid, x);
+        p->ticket_total[x] += resident_list_draws(resident_list_tiles(row_tiles, tn, x, r.col_lists), grid, x);
     }
     HIP_TRY(launch_resident2d(p->tile, r, cs));
     return FICCO_OK;
@@ -789,9 +798,15 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
         r.grid = p->resident_grid;
         r.gated = (dependent && do_copy) ? 1 : 0;
         TileShape ts = tile_shape(p->tile);
+        const int64_t tn = (p->N + ts.bn - 1) / ts.bn;
+        // ragged steps: a step brings about 1/c of the row tiles
+        const ListGeometry lg = pick_lists(ts, tn, std::max<int64_t>(1, p->n_row_tiles / std::max(p->c, 1)), r.grid / kTicketLists,
+                                           (p->M + (int64_t)p->E * p->N) * p->K * 2 > kCacheBudgetBytes);
+        r.group = lg.group;
+        r.col_lists = lg.col_lists;
         for (int x = 0; x < kTicketLists; ++x) {
             r.ticket_base[x] = p->ticket_total[x];
-            p->ticket_total[x] += resident_list_draws(resident_list_tiles(p->n_row_tiles, (p->N + ts.bn - 1) / ts.bn, x), r.grid, x);
+            p->ticket_total[x] += resident_list_draws(resident_list_tiles(p->n_row_tiles, tn, x, r.col_lists), r.grid, x);
         }
         HIP_TRY(launch_grouped(p->tile, r, cs));
         ++n_launches;

@@ -489,15 +489,31 @@ static __device__ __forceinline__ void tile_walk_next(TileWalk &w, uint32_t *tic
     }
 }
 
-// position of tile t of a list: groups of GROUP row tiles, row tile fastest inside a group
-static __device__ __forceinline__ void list_tile_position(int t, int my_rows, int tiles_n, int &row_in_list, int &tn, int group = 2)
-{
-    const int per_group = group * tiles_n;
-    const int g = t / per_group, first = g * group;
-    const int gsz = min(my_rows - first, group);
-    row_in_list = first + (t % per_group) % gsz;
-    tn = (t % per_group) / gsz;
-}
+// The lists of a resident launch as a grid of row classes x column blocks (see resident_list_tiles):
+// which tiles list x holds and where tile t of it lies. Inside a list tiles go in groups of `group`
+// row tiles, row tile fastest.
+struct ListGrid {
+    int row_tiles, tiles_n, col_lists, group;
+    __device__ __forceinline__ int classes() const { return kTicketLists / col_lists; }
+    __device__ __forceinline__ int rows(int x) const
+    {
+        const int rc = x % classes();
+        return row_tiles > rc ? (row_tiles - rc + classes() - 1) / classes() : 0;
+    }
+    __device__ __forceinline__ int col_begin(int x) const { return (x / classes()) * tiles_n / col_lists; }
+    __device__ __forceinline__ int cols(int x) const { return (x / classes() + 1) * tiles_n / col_lists - col_begin(x); }
+    __device__ __forceinline__ int total(int x) const { return rows(x) * cols(x); }
+    // tile t of list x: R = its row tile in the arrival-ordered sequence, tn = its column tile
+    __device__ __forceinline__ void position(int x, int t, int &R, int &tn) const
+    {
+        const int my_rows = rows(x), my_cols = cols(x);
+        const int per_group = group * my_cols;
+        const int g = t / per_group, first = g * group;
+        const int gsz = min(my_rows - first, group);
+        R = (first + (t % per_group) % gsz) * classes() + x % classes();
+        tn = col_begin(x) + (t % per_group) / gsz;
+    }
+};
 
 template <class T>
 __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
@@ -509,12 +525,8 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_chunk = (a.rows_per_block + T::BM - 1) / T::BM;
     const int row_tiles = r.n_chunks * rt_per_chunk;
-    // the lists as a grid of row classes x column blocks (see resident_list_tiles)
-    const int classes = kTicketLists / r.col_lists;
-    auto list_rows = [&](int x) { const int rc = x % classes; return row_tiles > rc ? (row_tiles - rc + classes - 1) / classes : 0; };
-    auto col_begin = [&](int x) { return (x / classes) * tiles_n / r.col_lists; };
-    auto list_cols = [&](int x) { return (x / classes + 1) * tiles_n / r.col_lists - col_begin(x); };
-    auto total_of = [&](int x) { return list_rows(x) * list_cols(x); };
+    const ListGrid lists{row_tiles, tiles_n, r.col_lists, r.group};
+    auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
@@ -542,9 +554,9 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
             have_drawn = 0;
             int ok = 1;
             if (w.x >= 0) {
-                int rl, tn;
-                list_tile_position(w.t, list_rows(w.x), list_cols(w.x), rl, tn, r.group);
-                const int chunk = r.arrival[(rl * classes + w.x % classes) / rt_per_chunk];
+                int R, tn;
+                lists.position(w.x, w.t, R, tn);
+                const int chunk = r.arrival[R / rt_per_chunk];
                 if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
             }
             s_walk = w;
@@ -554,10 +566,8 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         const int x = s_walk.x, t = s_walk.t;
         if (x < 0) break;
         if (s_ok) {
-            int rl, tn;
-            list_tile_position(t, list_rows(x), list_cols(x), rl, tn, r.group);
-            tn += col_begin(x);
-            const int R = rl * classes + x % classes;
+            int R, tn;
+            lists.position(x, t, R, tn);
             const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
             const int chunk = r.arrival[p];
             const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
@@ -598,8 +608,8 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int row_tiles = (r.M + T::BM - 1) / T::BM;
-    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
-    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
+    const ListGrid lists{row_tiles, tiles_n, r.col_lists, r.group};
+    auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
@@ -614,9 +624,8 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
         __syncthreads();
         const int x = s_walk.x, t = s_walk.t;
         if (x < 0) break;
-        int rl, tn;
-        list_tile_position(t, list_rows(x), tiles_n, rl, tn);
-        const int tm = rl * kTicketLists + x;
+        int tm, tn;
+        lists.position(x, t, tm, tn);
         const int64_t row0 = (int64_t)tm * T::BM;
         const int rows_valid = min(T::BM, r.M - (int)row0);
         const int col0 = tn * T::BN;
@@ -659,9 +668,8 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
     __shared__ int s_ok;
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
-    const int row_tiles = r.n_row_tiles;
-    auto list_rows = [&](int x) { return row_tiles > x ? (row_tiles - x + kTicketLists - 1) / kTicketLists : 0; };
-    auto total_of = [&](int x) { return list_rows(x) * tiles_n; };
+    const ListGrid lists{r.n_row_tiles, tiles_n, r.col_lists, r.group};
+    auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
@@ -673,9 +681,9 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
             have_drawn = 0;
             int ok = 1;
             if (w.x >= 0 && r.gated) {
-                int rl, tn;
-                list_tile_position(w.t, list_rows(w.x), tiles_n, rl, tn);
-                const int32_t *rt = r.row_tiles + (size_t)(rl * kTicketLists + w.x) * kRowTileWords;
+                int R, tn;
+                lists.position(w.x, w.t, R, tn);
+                const int32_t *rt = r.row_tiles + (size_t)R * kRowTileWords;
                 for (int pc = rt[3]; pc <= rt[4] && ok; ++pc) ok = wait_ready(a.gate, pc);
             }
             s_walk = w;
@@ -685,9 +693,9 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
         const int x = s_walk.x, t = s_walk.t;
         if (x < 0) break;
         if (s_ok) {
-            int rl, tn;
-            list_tile_position(t, list_rows(x), tiles_n, rl, tn);
-            const int32_t *rt = r.row_tiles + (size_t)(rl * kTicketLists + x) * kRowTileWords;
+            int R, tn;
+            lists.position(x, t, R, tn);
+            const int32_t *rt = r.row_tiles + (size_t)R * kRowTileWords;
             const int64_t row0 = rt[0];
             const int rows_valid = rt[1];
             const int64_t expert = rt[2];

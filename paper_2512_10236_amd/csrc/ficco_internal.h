@@ -129,6 +129,7 @@ struct Resident2DLaunch {
     uint32_t ticket_base[8];
     int32_t grid;
     int32_t gated;                // 0: operands resident, no waiting
+    int32_t group, col_lists;     // tile order, as in ResidentLaunch
 };
 
 // One receiver-side reduction (see ficco_reduce.hip): `in` is the landing buffer [G][rows][N] of the
@@ -159,6 +160,7 @@ struct GroupedLaunch {
     uint32_t ticket_base[8];
     int32_t grid;
     int32_t gated;
+    int32_t group, col_lists;     // tile order, as in ResidentLaunch
 };
 hipError_t launch_grouped(int tile, const GroupedLaunch &a, hipStream_t s);
 int grouped_grid_size(int tile, int device);
