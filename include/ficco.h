@@ -64,7 +64,11 @@ typedef enum ficco_schedule {
     FICCO_FINE_FUSED      = 3,   /* one GEMM launch per step over the G pieces of that step ("fused");
                                     the kernel reads the pieces in place through a row-block table,
                                     so no Gather/Scatter copies are issued                             */
-    FICCO_FINE_PERSISTENT = 4,   /* one resident kernel; every tile waits on its piece's ready flag     */
+    FICCO_FINE_PERSISTENT = 4,   /* one resident kernel; every tile waits on its piece's ready flag.
+                                    In the GEMM -> RS direction the kernel itself releases a piece's
+                                    transfer when the piece's last tile has been stored (engine
+                                    backend, FICCO_MODE_PAIR or FICCO_MODE_GEMM_ONLY, no
+                                    FICCO_OPT_TIMING; N % 8 == 0 and C_dev 16-byte aligned)           */
     FICCO_FINE_2D         = 5,   /* column pieces (the 2D decomposition of Sec. V-A/B, chosen by the
                                     paper's rule when M <= K): the k range is cut into `chunks` slices,
                                     step s moves slice s of every shard, and one resident kernel adds
@@ -127,10 +131,16 @@ typedef enum ficco_option {
                                     ficco_run() then waits on the host for each launch before it
                                     submits that launch's Scatter copies. 0 (default): the kernel
                                     reads the pieces in place through a row-block table             */
-    FICCO_OPT_REPEAT      = 12   /* measuring aid, 1..10000 (default 1): a FICCO_MODE_GEMM_ONLY run without
+    FICCO_OPT_REPEAT      = 12,  /* measuring aid, 1..10000 (default 1): a FICCO_MODE_GEMM_ONLY run without
                                     FICCO_OPT_TIMING on the stream path enqueues its GEMM launches this many
                                     times back to back between its two events; wall_us then covers all of
                                     them and n_launches counts them. May change between runs.         */
+    FICCO_OPT_TILE_GROUP  = 13,  /* tile order, row tiles per group: 0 (default) = chosen per launch from the
+                                    shape, else 1, 2, 4 or 8. The order decides which tiles share an XCD's L2
+                                    at a time; it never changes a result bit.                         */
+    FICCO_OPT_TILE_COLUMN_LISTS = 14 /* resident kernels: column blocks their eight tile lists are split into:
+                                    0 (default) = chosen from the shape, else 1, 2, 4 or 8 (at most the
+                                    number of column tiles, otherwise the run fails with FICCO_ERR_ARG)   */
 } ficco_option;
 
 /*
@@ -149,7 +159,11 @@ typedef enum ficco_option {
  *             raised by a 4-byte copy queued on the same engine behind the transfer.
  *             The copy stream argument is not used. ficco_run() first waits on the host
  *             for the plan's previous run; in the GEMM->RS direction it also waits for each GEMM
- *             launch before it submits that launch's transfers.
+ *             launch before it submits that launch's transfers - except with
+ *             FICCO_FINE_PERSISTENT, where all transfers are submitted up front, each behind a
+ *             dependency signal that the resident kernel clears from the GPU.
+ *             Links are mapped to every second engine id first: engines with neighbouring ids
+ *             share a path and slow each other down when they copy at the same time.
  *   AUTO    - ENGINES for every run that moves data, unless FICCO_OPT_FLAG_WRITE = 1 asks for
  *             stream writes or a GEMM_RS run sends every block to pinned host memory (then
  *             STREAM); measured faster than STREAM for pinned sources too.
@@ -296,8 +310,9 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
  *             shard j would lay its slices out for DMA. C is bitwise what FICCO_SERIAL computes
  *             from the same matrix in row-major layout.
  *   GEMM_RS : A_src must be NULL; A_dev is read; C_dev is written by the GEMM and its row block
- *             p (rows [p*M/G, (p+1)*M/G)) is then copied on copy_stream to peer_out[p]
- *             ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces complete.
+ *             p (rows [p*M/G, (p+1)*M/G)) is then copied (on copy_stream, or by the engines) to
+ *             peer_out[p] ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces
+ *             complete.
  *             peer_out is a host array of `shards` pointers.
  *   W_dev   - [K,N] device (see ficco_pack_weight).
  * compute_stream and copy_stream must differ and have the default priority. On the stream backend

@@ -137,6 +137,7 @@ struct ficco_plan_s {
     int backend_opt = FICCO_COPY_AUTO, links_opt = 0;
     int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
     int repeat = 1;                      // GEMM-only runs: launches enqueued this many times inside one bracket
+    int tile_group = 0, tile_col_lists = 0;   // forced tile order (0 = chosen from the shape)
     // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
     bool grouped = false;
     int E = 1;
@@ -548,6 +549,7 @@ GemmLaunch make_launch(const ficco_plan_t *p, const Group &g, const void *A_dev,
     a.N = (int32_t)p->N;
     a.K = (int32_t)p->K;
     LaunchShape ls = launch_shape(p, g);
+    a.group_m = p->tile_group;          // 0: the launcher chooses
     a.n_blocks = ls.n_blocks;
     a.rows_per_block = (int32_t)ls.rows_per_block;
     if (ls.contiguous) {
@@ -607,23 +609,22 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
 // that what an XCD has in flight - groups of `group` row tiles of a step times a run of column tiles,
 // one workgroup slot each - costs least by tile_order_cost. Ties go to the smaller col_lists and group.
 struct ListGeometry { int group, col_lists; };
-inline ListGeometry pick_lists(const TileShape &ts, int64_t tn, int64_t S, int64_t slots, bool big)
+inline ListGeometry pick_lists(const ficco_plan_t *p, const TileShape &ts, int64_t tn, int64_t S, int64_t slots, bool big)
 {
-    static const char *force_g = getenv("FICCO_GROUP"), *force_c = getenv("FICCO_COL_LISTS");
-    ListGeometry best{1, 1};
+    ListGeometry best{0, 0};
     double best_cost = -1;
     for (int cl = 1; cl <= kTicketLists; cl *= 2) {
         if (cl > 1 && cl > tn) break;
-        if (force_c && atoi(force_c) != cl) continue;
+        if (p->tile_col_lists && p->tile_col_lists != cl) continue;
         // a group must not span steps: no workgroup should draw a tile of the next step while tiles of this one are left
-        const int64_t g_max = std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / cl)));
+        const int64_t g_max = p->tile_group ? 8 : std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / cl)));
         for (int g = 1; g <= g_max; g *= 2) {
-            if (force_g && atoi(force_g) != g) continue;
+            if (p->tile_group && p->tile_group != g) continue;
             const double cost = tile_order_cost(ts.bm, ts.bn, tn, std::max<int64_t>(1, slots), cl, g, big);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {g, cl}; }
         }
     }
-    return best;
+    return best;                 // {0, 0}: the forced column split does not fit the column tiles
 }
 
 // row pieces: a step of the step-major order brings G pieces, the other orders one piece at a time
@@ -631,7 +632,7 @@ inline ListGeometry resident_lists(const ficco_plan_t *p)
 {
     const TileShape ts = tile_shape(p->tile);
     const int64_t rt = (p->m + ts.bm - 1) / ts.bm;
-    return pick_lists(ts, (p->N + ts.bn - 1) / ts.bn, (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt,
+    return pick_lists(p, ts, (p->N + ts.bn - 1) / ts.bn, (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt,
                       p->resident_grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
 }
 
@@ -662,7 +663,8 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     TileShape ts = tile_shape(p->tile);
     const int64_t row_tiles = (p->M + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
     // column pieces: every tile can start with the first step, so any group height goes
-    const ListGeometry lg = pick_lists(ts, tn, row_tiles, grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
+    const ListGeometry lg = pick_lists(p, ts, tn, row_tiles, grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
+    if (!lg.col_lists) return FICCO_ERR_ARG;
     r.group = lg.group;
     r.col_lists = lg.col_lists;
     for (int x = 0; x < kTicketLists; ++x) {
@@ -804,8 +806,9 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
         TileShape ts = tile_shape(p->tile);
         const int64_t tn = (p->N + ts.bn - 1) / ts.bn;
         // ragged steps: a step brings about 1/c of the row tiles
-        const ListGeometry lg = pick_lists(ts, tn, std::max<int64_t>(1, p->n_row_tiles / std::max(p->c, 1)), r.grid / kTicketLists,
+        const ListGeometry lg = pick_lists(p, ts, tn, std::max<int64_t>(1, p->n_row_tiles / std::max(p->c, 1)), r.grid / kTicketLists,
                                            (p->M + (int64_t)p->E * p->N) * p->K * 2 > kCacheBudgetBytes);
+        if (!lg.col_lists) return FICCO_ERR_ARG;
         r.group = lg.group;
         r.col_lists = lg.col_lists;
         for (int x = 0; x < kTicketLists; ++x) {
@@ -1090,6 +1093,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 r.ticket = p->d_ticket;
                 r.grid = p->resident_grid;
                 const ListGeometry lg = resident_lists(p);
+                if (!lg.col_lists) return FICCO_ERR_ARG;
                 r.group = lg.group;
                 r.col_lists = lg.col_lists;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
@@ -1157,6 +1161,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             r.ticket = p->d_ticket;
             r.grid = p->resident_grid;
             const ListGeometry lg = resident_lists(p);
+            if (!lg.col_lists) return FICCO_ERR_ARG;
             r.group = lg.group;
             r.col_lists = lg.col_lists;
             r.local_chunk_begin = 0; r.local_chunk_end = n;                   // A is resident: nothing to wait for
@@ -1390,6 +1395,14 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
         if (value < 1 || value > 10000) return FICCO_ERR_ARG;
         p->repeat = (int)value;
         break;
+    case FICCO_OPT_TILE_GROUP:
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return FICCO_ERR_ARG;
+        p->tile_group = (int)value;
+        break;
+    case FICCO_OPT_TILE_COLUMN_LISTS:
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return FICCO_ERR_ARG;
+        p->tile_col_lists = (int)value;
+        break;
     case FICCO_OPT_PACKING:
         if (value != 0 && value != 1) return FICCO_ERR_ARG;
         if (value == 1 && p->schedule != FICCO_FINE_FUSED) return FICCO_ERR_ARG;
@@ -1490,6 +1503,10 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     }
     int rc = finalize(p);
     if (rc) return rc;
+    if (p->tile_col_lists > 1 && (is_resident(p) || p->grouped)) {     // refuse before anything is enqueued
+        const TileShape ts = tile_shape(p->tile);
+        if (p->tile_col_lists > (p->N + ts.bn - 1) / ts.bn) return FICCO_ERR_ARG;
+    }
 
     bool dev = false;
     for (const void *ptr : {(const void *)A_dev, W_dev, (const void *)C_dev}) {
@@ -1672,6 +1689,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
                 r.ticket = p->d_ticket;
                 r.grid = grid;
                 const ListGeometry lg = resident_lists(p);
+                if (!lg.col_lists) return FICCO_ERR_ARG;
                 r.group = lg.group;
                 r.col_lists = lg.col_lists;
                 if (!dependent) { r.local_chunk_begin = 0; r.local_chunk_end = n; }
@@ -2206,8 +2224,14 @@ void ficco_destroy(ficco_plan_t *p)
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
     for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);      // nothing may stay parked behind a piece that never completed
+    // transfers still in flight must not outlive their signals; one bound for all of them (a run that
+    // failed half-way may have armed signals whose transfers were never submitted)
+    const auto deadline = std::chrono::steady_clock::now() + std::chrono::seconds(5);
     for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter})
-        for (auto &sg : *v) (void)wait_signal(sg, 5.0);
+        for (auto &sg : *v) {
+            const double left = std::chrono::duration<double>(deadline - std::chrono::steady_clock::now()).count();
+            (void)wait_signal(sg, left > 0.001 ? left : 0.001);
+        }
     release(p);
     delete p;
 }

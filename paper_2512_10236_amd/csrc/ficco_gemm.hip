@@ -800,8 +800,9 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
     }
     // group height of the tile order: matters when the launch runs for several rounds
     GemmLaunch b = a;
-    b.group_m = 8;
-    if (total > grid) {
+    if (b.group_m != 1 && b.group_m != 2 && b.group_m != 4 && b.group_m != 8) b.group_m = 0;
+    if (!b.group_m) b.group_m = 8;
+    if (!a.group_m && total > grid) {
         const bool big = ((int64_t)a.n_blocks * a.rows_per_block + a.N) * a.K * 2 > kCacheBudgetBytes;
         double best = -1;
         for (int g = 1; g <= 8; g *= 2) {

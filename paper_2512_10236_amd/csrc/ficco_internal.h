@@ -91,7 +91,7 @@ struct GemmLaunch {
     int32_t row0;                // first row when block_row0 == nullptr (n_blocks == 1)
     int32_t n_blocks;
     int32_t rows_per_block;
-    int32_t group_m;             // row tiles per group of the tile order (set by the launcher)
+    int32_t group_m;             // row tiles per group of the tile order: 1, 2, 4, 8, or 0 = the launcher chooses
     // Optional gate (copy-engine transfers): every workgroup waits until all of the pieces
     // wait_chunks[0..n_wait) are ready.
     Gate gate;

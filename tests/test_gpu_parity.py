@@ -127,6 +127,34 @@ def test_every_tile_shape_ragged(gpu, tile):
     assert np.array_equal(test_every_tile_shape_ragged.results[0], outs[0])
 
 
+def test_every_tile_order_gives_the_same_bits(gpu):
+    # 42 row tiles x 9 column tiles of 32x256 (both ragged): more tiles than workgroups that fit, so the
+    # resident kernels draw tickets and steal, and the one-launch kernel loops
+    G, c, m, K, N = 3, 2, 200, 192, 2104
+    shards = fi.make_shards(27, G * c * m, K, G)
+    W = fi.make_weight(27, K, N)
+    ref = og.ag_gemm(shards, W)
+    tile = [(ficco.FICCO_OPT_TILE, ficco.FICCO_TILE_32x256)]
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, opts=tile)
+    check(base, ref, "serial")
+    for g in (1, 2, 4, 8):
+        order = tile + [(ficco.FICCO_OPT_TILE_GROUP, g)]
+        for sched, cc in ((ficco.FICCO_SERIAL, 1), (ficco.FICCO_FINE_FUSED, c)):
+            bits, _, _ = run_ag(gpu, shards, W, sched, cc, opts=order)
+            assert np.array_equal(bits, base), f"group {g} sched {sched}"
+        for cl in (1, 2, 4, 8):
+            lists = order + [(ficco.FICCO_OPT_TILE_COLUMN_LISTS, cl)]
+            bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, c, src="device", opts=lists)
+            assert np.array_equal(bits, base), f"resident, group {g}, {cl} column lists"
+            bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, 3, src="device", opts=lists)
+            assert np.array_equal(bits, base), f"column pieces, group {g}, {cl} column lists"
+    # more column lists than column tiles (1024 columns are 4 tiles of 256): refused when the run is enqueued
+    shards, W = fi.config_inputs("cfg1_tiny")
+    with pytest.raises(ficco.FiccoError):
+        run_ag(gpu, shards, W, ficco.FICCO_FINE_PERSISTENT, 4, src="device",
+               opts=[(ficco.FICCO_OPT_TILE, ficco.FICCO_TILE_256x256), (ficco.FICCO_OPT_TILE_COLUMN_LISTS, 8)])
+
+
 def test_closed_forms_on_gpu(gpu):
     G, ms, K = 4, 96, 256
     M = G * ms

@@ -95,6 +95,19 @@ def test_packing_is_an_option_of_the_fused_schedule_only():
             ficco.ficco_destroy(plan)
 
 
+def test_tile_order_options_take_powers_of_two_up_to_eight():
+    plan = ficco.ficco_plan(512, 128, 8, 4, 2, ficco.FICCO_FINE_PERSISTENT)
+    try:
+        for opt in (ficco.FICCO_OPT_TILE_GROUP, ficco.FICCO_OPT_TILE_COLUMN_LISTS):
+            for v in (0, 1, 2, 4, 8):
+                ficco.ficco_plan_set(plan, opt, v)
+            for v in (-1, 3, 5, 6, 7, 16):
+                with pytest.raises(ficco.FiccoError):
+                    ficco.ficco_plan_set(plan, opt, v)
+    finally:
+        ficco.ficco_destroy(plan)
+
+
 def test_custom_arrival_and_local_shard():
     plan = ficco.ficco_plan(512, 64, 8, 4, 4, ficco.FICCO_FINE_FUSED)
     try:
