@@ -493,15 +493,20 @@ static __device__ __forceinline__ void tile_walk_next(TileWalk &w, uint32_t *tic
 // which tiles list x holds and where tile t of it lies. Inside a list tiles go in groups of `group`
 // row tiles, row tile fastest.
 struct ListGrid {
-    int row_tiles, tiles_n, col_lists, group;
-    __device__ __forceinline__ int classes() const { return kTicketLists / col_lists; }
+    int row_tiles, tiles_n, group;
+    int cl_shift;                // log2 of the number of column blocks (1, 2, 4 or 8 of them): shifts, not divisions
+    __device__ __forceinline__ ListGrid(int row_tiles_, int tiles_n_, int col_lists, int group_)
+        : row_tiles(row_tiles_), tiles_n(tiles_n_), group(group_), cl_shift(31 - __clz(col_lists)) {}
+    __device__ __forceinline__ int class_shift() const { return 3 - cl_shift; }              // kTicketLists = 8 lists
+    __device__ __forceinline__ int row_class(int x) const { return x & ((1 << class_shift()) - 1); }
+    __device__ __forceinline__ int col_block(int x) const { return x >> class_shift(); }
     __device__ __forceinline__ int rows(int x) const
     {
-        const int rc = x % classes();
-        return row_tiles > rc ? (row_tiles - rc + classes() - 1) / classes() : 0;
+        const int rc = row_class(x);
+        return row_tiles > rc ? (row_tiles - rc + (1 << class_shift()) - 1) >> class_shift() : 0;
     }
-    __device__ __forceinline__ int col_begin(int x) const { return (x / classes()) * tiles_n / col_lists; }
-    __device__ __forceinline__ int cols(int x) const { return (x / classes() + 1) * tiles_n / col_lists - col_begin(x); }
+    __device__ __forceinline__ int col_begin(int x) const { return (col_block(x) * tiles_n) >> cl_shift; }
+    __device__ __forceinline__ int cols(int x) const { return (((col_block(x) + 1) * tiles_n) >> cl_shift) - col_begin(x); }
     __device__ __forceinline__ int total(int x) const { return rows(x) * cols(x); }
     // tile t of list x: R = its row tile in the arrival-ordered sequence, tn = its column tile
     __device__ __forceinline__ void position(int x, int t, int &R, int &tn) const
@@ -510,28 +515,31 @@ struct ListGrid {
         const int per_group = group * my_cols;
         const int g = t / per_group, first = g * group;
         const int gsz = min(my_rows - first, group);
-        R = (first + (t % per_group) % gsz) * classes() + x % classes();
+        R = ((first + (t % per_group) % gsz) << class_shift()) + row_class(x);
         tn = col_begin(x) + (t % per_group) / gsz;
     }
 };
+static_assert(kTicketLists == 8, "ListGrid shifts assume 8 lists");
 
-template <class T>
+// STREAM_OUT: the GEMM -> reduce-scatter form (r.done_count set), a separate instantiation so that its
+// epilogue and bookkeeping cost the all-gather form no registers.
+template <class T, bool STREAM_OUT>
 __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ TileWalk s_walk;
-    __shared__ int s_ok;
+    __shared__ int s_ok, s_chunk;
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt_per_chunk = (a.rows_per_block + T::BM - 1) / T::BM;
     const int row_tiles = r.n_chunks * rt_per_chunk;
-    const ListGrid lists{row_tiles, tiles_n, r.col_lists, r.group};
+    const ListGrid lists(row_tiles, tiles_n, r.col_lists, r.group);
     auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
     uint32_t drawn = 0;
-    // Output streaming (done_count set): a copy engine reads a piece of C while the kernel runs on, so
+    // Output streaming: a copy engine reads a piece of C while the kernel runs on, so
     // the tiles are written through the caches, and a tile is counted for its piece once every thread's
     // stores have been performed; whoever completes a piece lets its copy go. Ordering is by hand
     // (stores, their completion, barrier, counter, signal): a release fence would write back the whole
@@ -539,7 +547,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
     // first k-step, or after the loop if it was the workgroup's last.
     int stored_chunk = -1;                 // thread 0: piece of the tile stored last and not yet counted
     auto count_stored = [&]() {
-        if (threadIdx.x == 0 && stored_chunk >= 0) {
+        if (STREAM_OUT && threadIdx.x == 0 && stored_chunk >= 0) {
             const uint32_t before = __hip_atomic_fetch_add(r.done_count + stored_chunk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((before + 1u) % (uint32_t)r.tiles_per_chunk == 0u)
                 __hip_atomic_store(reinterpret_cast<int64_t *>(r.done_sig[stored_chunk]), (int64_t)0, __ATOMIC_RELAXED,
@@ -558,6 +566,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
                 lists.position(w.x, w.t, R, tn);
                 const int chunk = r.arrival[R / rt_per_chunk];
                 if (chunk < r.local_chunk_begin || chunk >= r.local_chunk_end) ok = wait_ready(a.gate, chunk);
+                s_chunk = chunk;           // the others take it from here instead of the table in memory
             }
             s_walk = w;
             s_ok = ok;
@@ -568,28 +577,31 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         if (s_ok) {
             int R, tn;
             lists.position(x, t, R, tn);
-            const int p = R / rt_per_chunk, rt = R % rt_per_chunk;
-            const int chunk = r.arrival[p];
+            const int rt = R % rt_per_chunk;
+            const int chunk = s_chunk;
             const int64_t row0 = (int64_t)chunk * a.rows_per_block + (int64_t)rt * T::BM;
             const int rows_valid = min(T::BM, a.rows_per_block - rt * T::BM);
             const int col0 = tn * T::BN;
             const int cols_valid = min(T::BN, a.N - col0);
             TileAcc<T> ta;
             tile_zero(ta);
-            tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem,
-                               count_stored);
+            if constexpr (STREAM_OUT)
+                tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem,
+                                   count_stored);
+            else
+                tile_accumulate<T>(ta, a.A + row0 * a.lda, rows_valid, a.Wt + (int64_t)col0 * a.K, cols_valid, a.lda, a.K, a.K, smem);
             // the next ticket's round trip runs under the epilogue
             if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
-            if (!r.done_count) {
-                tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
-            } else {
+            if constexpr (STREAM_OUT) {
                 tile_store_rows_through<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc, smem);
                 stored_chunk = chunk;
+            } else {
+                tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
             }
         }
         __syncthreads();                   // s_walk / s_ok / LDS stages are reused
     }
-    if (r.done_count) {
+    if constexpr (STREAM_OUT) {
         wait_vmem<0>();
         __syncthreads();
         count_stored();
@@ -608,7 +620,7 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int row_tiles = (r.M + T::BM - 1) / T::BM;
-    const ListGrid lists{row_tiles, tiles_n, r.col_lists, r.group};
+    const ListGrid lists(row_tiles, tiles_n, r.col_lists, r.group);
     auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
@@ -668,7 +680,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
     __shared__ int s_ok;
     const GemmLaunch &a = r.g;
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
-    const ListGrid lists{r.n_row_tiles, tiles_n, r.col_lists, r.group};
+    const ListGrid lists(r.n_row_tiles, tiles_n, r.col_lists, r.group);
     auto total_of = [&](int x) { return lists.total(x); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
@@ -817,10 +829,15 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
 template <class T>
 static hipError_t launch_resident_t(const ResidentLaunch &r, hipStream_t s)
 {
-    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T>));
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T, false>));
+    static hipError_t once_out = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T, true>));
     if (once != hipSuccess) return once;
+    if (once_out != hipSuccess) return once_out;
     if (r.grid <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_resident_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    if (r.done_count)
+        hipLaunchKernelGGL((gemm_resident_kernel<T, true>), dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    else
+        hipLaunchKernelGGL((gemm_resident_kernel<T, false>), dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }
 
@@ -869,10 +886,11 @@ static int grouped_grid_t(int device)
 template <class T>
 static int resident_grid_t(int device)
 {
-    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T>));
+    static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T, false>));
     (void)once;
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident_kernel<T>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    // (the output-streaming form may need more registers, but every tile shape is limited by LDS first)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident_kernel<T, false>, 256, T::LDS_BYTES) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return per_cu * cus;
 }
