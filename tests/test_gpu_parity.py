@@ -301,6 +301,42 @@ def test_gemm_rs_streams_row_blocks_to_peers(gpu):
             assert st.copy_bytes == M * N * 2 and st.n_copies == G * c
 
 
+@pytest.mark.parametrize("tile", [ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128,
+                                  ficco.FICCO_TILE_128x256, ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256,
+                                  ficco.FICCO_TILE_128x128_DEEP, ficco.FICCO_TILE_128x192, ficco.FICCO_TILE_256x192])
+def test_gemm_rs_resident_every_tile_shape_ragged(gpu, tile):
+    # the resident kernel's own epilogue (row segments through LDS, written through the caches) on pieces
+    # of 88 rows and 328 columns: no tile height or width divides them
+    dev = gpu["dev"]
+    G, c, m, K, N = 3, 2, 88, 192, 328
+    M = G * c * m
+    A = fi.normal_bf16(31, fi.TENSOR_A, M, K)
+    W = fi.make_weight(31, K, N)
+    blocks = og.gemm_rs_blocks(A, W, G)
+    outs = []
+    for sched in (ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
+        A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+        C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+        peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16, device=dev) for _ in range(G)]
+        torch.cuda.synchronize()
+        plan = ficco.ficco_plan(M, K, N, G, c, sched)
+        try:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_TILE, tile)
+            for _ in range(2):
+                ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
+                ficco.ficco_query_stats(plan)
+        finally:
+            ficco.ficco_destroy(plan)
+        torch.cuda.synchronize()
+        got = np.concatenate([p.cpu().numpy().view(np.uint16) for p in peers], 0)
+        for j in range(G):
+            check(got[j * c * m:(j + 1) * c * m], blocks[j], f"peer {j} tile {tile} sched {sched}")
+        assert np.array_equal(got, C_dev.cpu().numpy().view(np.uint16))
+        outs.append(got)
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_resident_kernel_gives_up_when_flags_never_arrive(gpu):
     # host-forced: the transfers are issued but the ready flags are withheld; the kernel's bounded
     # wait must expire, every workgroup must drain, and the run must report a timeout
