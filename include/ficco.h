@@ -272,8 +272,8 @@ int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64
 int ficco_plan_pieces(const ficco_plan_t *plan, int64_t *row0, int64_t *rows, int cap);
 
 /* Set an option; only before the plan's first use (FICCO_ERR_STATE afterwards), except
- * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US and FICCO_OPT_HOLD_FLAGS, which may
- * change between runs. */
+ * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_HOLD_FLAGS, FICCO_OPT_REPEAT,
+ * FICCO_OPT_TILE_GROUP and FICCO_OPT_TILE_COLUMN_LISTS, which may change between runs. */
 int ficco_plan_set(ficco_plan_t *plan, int option, int64_t value);
 
 /* Replace the arrival order by a permutation of 0..n_chunks-1 (tests: reversed, shuffled).

@@ -609,7 +609,8 @@ std::vector<int> usable_engines(bool touches_host, int want, void *scratch64x2)
 // that what an XCD has in flight - groups of `group` row tiles of a step times a run of column tiles,
 // one workgroup slot each - costs least by tile_order_cost. Ties go to the smaller col_lists and group.
 struct ListGeometry { int group, col_lists; };
-inline ListGeometry pick_lists(const ficco_plan_t *p, const TileShape &ts, int64_t tn, int64_t S, int64_t slots, bool big)
+inline ListGeometry pick_lists(const ficco_plan_t *p, const TileShape &ts, int64_t tn, int64_t row_tiles, int64_t S, int64_t slots,
+                               int64_t a_bytes, int64_t w_bytes)
 {
     ListGeometry best{0, 0};
     double best_cost = -1;
@@ -620,7 +621,7 @@ inline ListGeometry pick_lists(const ficco_plan_t *p, const TileShape &ts, int64
         const int64_t g_max = p->tile_group ? 8 : std::max<int64_t>(1, std::min<int64_t>(8, S / (kTicketLists / cl)));
         for (int g = 1; g <= g_max; g *= 2) {
             if (p->tile_group && p->tile_group != g) continue;
-            const double cost = tile_order_cost(ts.bm, ts.bn, tn, std::max<int64_t>(1, slots), cl, g, big);
+            const double cost = tile_order_cost(ts.bm, ts.bn, tn, row_tiles, std::max<int64_t>(1, slots), cl, g, a_bytes, w_bytes);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {g, cl}; }
         }
     }
@@ -632,8 +633,8 @@ inline ListGeometry resident_lists(const ficco_plan_t *p)
 {
     const TileShape ts = tile_shape(p->tile);
     const int64_t rt = (p->m + ts.bm - 1) / ts.bm;
-    return pick_lists(p, ts, (p->N + ts.bn - 1) / ts.bn, (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt,
-                      p->resident_grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
+    return pick_lists(p, ts, (p->N + ts.bn - 1) / ts.bn, (int64_t)p->n_chunks * rt, (p->order == FICCO_ORDER_STEP_MAJOR ? (int64_t)p->G : 1) * rt,
+                      p->resident_grid / kTicketLists, p->M * p->K * 2, p->N * p->K * 2);
 }
 
 // bytes of one row of a transferred piece of the activation
@@ -663,7 +664,7 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     TileShape ts = tile_shape(p->tile);
     const int64_t row_tiles = (p->M + ts.bm - 1) / ts.bm, tn = (p->N + ts.bn - 1) / ts.bn;
     // column pieces: every tile can start with the first step, so any group height goes
-    const ListGeometry lg = pick_lists(p, ts, tn, row_tiles, grid / kTicketLists, (p->M + p->N) * p->K * 2 > kCacheBudgetBytes);
+    const ListGeometry lg = pick_lists(p, ts, tn, row_tiles, row_tiles, grid / kTicketLists, p->M * p->K * 2, p->N * p->K * 2);
     if (!lg.col_lists) return FICCO_ERR_ARG;
     r.group = lg.group;
     r.col_lists = lg.col_lists;
@@ -806,8 +807,8 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
         TileShape ts = tile_shape(p->tile);
         const int64_t tn = (p->N + ts.bn - 1) / ts.bn;
         // ragged steps: a step brings about 1/c of the row tiles
-        const ListGeometry lg = pick_lists(p, ts, tn, std::max<int64_t>(1, p->n_row_tiles / std::max(p->c, 1)), r.grid / kTicketLists,
-                                           (p->M + (int64_t)p->E * p->N) * p->K * 2 > kCacheBudgetBytes);
+        const ListGeometry lg = pick_lists(p, ts, tn, p->n_row_tiles, std::max<int64_t>(1, p->n_row_tiles / std::max(p->c, 1)), r.grid / kTicketLists,
+                                           p->M * p->K * 2, (int64_t)p->E * p->N * p->K * 2);
         if (!lg.col_lists) return FICCO_ERR_ARG;
         r.group = lg.group;
         r.col_lists = lg.col_lists;
@@ -1341,7 +1342,8 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
                        option == FICCO_OPT_TIMING) && value != (option == FICCO_OPT_LOCAL_SHARD ? -1 : 0))
         return FICCO_ERR_ARG;          // expert-parallel plans: all-gather direction, every piece travels, no per-launch timing
     const bool late_ok = option == FICCO_OPT_MODE || option == FICCO_OPT_TIMING || option == FICCO_OPT_HOLD_FLAGS ||
-                         option == FICCO_OPT_SPIN_LIMIT_US || option == FICCO_OPT_REPEAT;
+                         option == FICCO_OPT_SPIN_LIMIT_US || option == FICCO_OPT_REPEAT || option == FICCO_OPT_TILE_GROUP ||
+                         option == FICCO_OPT_TILE_COLUMN_LISTS;
     if (p->finalized && !late_ok) return FICCO_ERR_STATE;
     switch (option) {
     case FICCO_OPT_DIRECTION:

@@ -815,10 +815,10 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
     if (b.group_m != 1 && b.group_m != 2 && b.group_m != 4 && b.group_m != 8) b.group_m = 0;
     if (!b.group_m) b.group_m = 8;
     if (!a.group_m && total > grid) {
-        const bool big = ((int64_t)a.n_blocks * a.rows_per_block + a.N) * a.K * 2 > kCacheBudgetBytes;
         double best = -1;
         for (int g = 1; g <= 8; g *= 2) {
-            const double c = tile_order_cost(T::BM, T::BN, tiles_n, grid / 8, 1, g, big);
+            const double c = tile_order_cost(T::BM, T::BN, tiles_n, (int64_t)a.n_blocks * rt, grid / 8, 1, g,
+                                             (int64_t)a.n_blocks * a.rows_per_block * a.K * 2, (int64_t)a.N * a.K * 2);
             if (best < 0 || c < best) { best = c; b.group_m = g; }
         }
     }

@@ -33,23 +33,40 @@ __host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_
 // Relative cost of a tile order for one XCD, whose L2 is filled with what its workgroups have in
 // flight: `slots` tiles taken from groups of g row tiles x `width` column tiles (width = the tn column
 // tiles cut into col_lists blocks), i.e. part of one group or several whole groups. Counted in operand
-// rows per k-step: rows of A plus rows of the packed weight. When the operands are too large for the
-// memory-side cache (`big`), rows of A come from HBM and weigh double - unless the col_lists XCDs that
-// walk the same row tiles at the same time share the fetch, which only works while a group stays in
-// flight for at most two rounds. Fitted to sweeps of (col_lists, g) on shapes with 14 and 32 column tiles.
-__host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t slots, int col_lists, int g, bool big)
+// rows per k-step - rows of A plus rows of the packed weight - each weighted by where the fill comes
+// from: the memory-side cache costs 1, HBM costs kHbmFillCost, and the kernels, whose rings hold two or
+// three k-steps, feel that latency. A line is fetched from HBM by the first XCD that wants it; the
+// XCDs that walk the same rows (the col_lists lists of a row class) or the same columns (the
+// kTicketLists / col_lists lists of a column block) at the same time find it in the cache, and so do
+// later passes over a group's rows and later groups' passes over the columns if the operand stays
+// there (operands up to kCacheStayBytes do). Among equal footprints groups of about three rounds of
+// tiles were fastest. Fitted to sweeps of (col_lists, g) on five shape/tile pairs (14 to 112 column
+// tiles, 16 to 128 row tiles, 128x128 and 256x256 tiles): the order it picks from all 16 is within
+// 2.1 % of the best of each sweep except one (3.7 %). Known miss: with 128-row pieces of a short, very
+// wide product (M = 4096, N = 14336) the orders a step-bound group allows are all 6-16 % slower than the
+// best free order, and the model picks the slowest of them.
+constexpr double kHbmFillCost = 6.0;
+constexpr int64_t kCacheStayBytes = 128ll << 20;       // of the 256 MB memory-side cache
+__host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t row_tiles, int64_t slots, int col_lists, int g,
+                                       int64_t a_bytes, int64_t w_bytes)
 {
+    const int classes = kTicketLists / col_lists;
+    const int64_t rows_list = row_tiles / classes > 1 ? (row_tiles + classes - 1) / classes : 1;
+    if (g > rows_list) g = (int)rows_list;
     const int64_t width = (tn + col_lists - 1) / col_lists;
     const int64_t per_group = (int64_t)g * width;
     const double rows_active = per_group >= slots ? (double)g : (double)g * (double)slots / (double)per_group;
-    int64_t cols_active = slots / g > 1 ? slots / g : 1;
-    if (cols_active > width) cols_active = width;
-    const double a_weight = !big ? 1.0 : (per_group > 2 * slots ? 2.0 : 1.0 + 1.0 / col_lists);
-    // among orders with the same footprint the sweeps favour groups of about three rounds of tiles
+    double cols_active = (double)slots / g > 1.0 ? (double)slots / g : 1.0;
+    if (cols_active > (double)width) cols_active = (double)width;
+    const double passes = per_group > slots ? (double)per_group / (double)slots : 1.0;       // rounds a group's rows stay in use
+    const double groups = rows_list > g ? (double)rows_list / g : 1.0;                       // passes over a list's columns
+    const double a_from_hbm = a_bytes <= kCacheStayBytes ? 1.0 / (col_lists * passes) : 1.0 / col_lists;
+    const double w_from_hbm = w_bytes <= kCacheStayBytes ? 1.0 / (classes * groups) : 1.0 / classes;
+    const double fill = rows_active * bm * (1.0 + (kHbmFillCost - 1.0) * a_from_hbm) +
+                        cols_active * bn * (1.0 + (kHbmFillCost - 1.0) * w_from_hbm);
     const double off = log2((double)per_group / (3.0 * (double)slots));
-    return (rows_active * bm * a_weight + (double)cols_active * bn) * (1.0 + 0.01 * (off < 0 ? -off : off));
+    return fill * (1.0 + 0.02 * (off < 0 ? -off : off));
 }
-constexpr int64_t kCacheBudgetBytes = 192ll << 20;    // operands beyond this do not stay in the 256 MB memory-side cache
 
 // Workgroups of a resident launch whose first list is x (workgroup b starts on list b % kTicketLists).
 __host__ __device__ inline int resident_list_homes(int grid, int x) { return grid > x ? (grid - x + kTicketLists - 1) / kTicketLists : 0; }
