@@ -40,12 +40,12 @@ HBM_PEAK_GBPS = 8000.0
 # read, and the factors by which a 256 MiB device copy's true traffic exceeds what they read for it.
 PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131086.7, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
-    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57468.6, "WRITE_SIZE": 12288.8},
+    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57468.6, "WRITE_SIZE": 12288.9},
     ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57449.0, "WRITE_SIZE": 12288.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 962294.1, "WRITE_SIZE": 116608.4},
-    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 836503.2, "WRITE_SIZE": 117167.0},
-    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 424925.8, "WRITE_SIZE": 32787.7},
-    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 520643.8, "WRITE_SIZE": 33798.7},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 929503.3, "WRITE_SIZE": 116573.6},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 849699.1, "WRITE_SIZE": 117399.7},
+    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 394133.5, "WRITE_SIZE": 32967.9},
+    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 527743.5, "WRITE_SIZE": 33697.0},
     ("cfg4_gemm_rs", "rs_reduce_kernel"): {"FETCH_SIZE": 131151.5, "WRITE_SIZE": 32768.0},      # profiles/rs_reduce_cfg4_gemm_rs.md
 }
 

@@ -792,9 +792,8 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
     if (total <= 0 || total > 0x7FFFFFFF) return hipErrorInvalidValue;
     // at most as many workgroups as run at once (a multiple of 8, one share per XCD); the rest of the tiles
     // are taken by the kernel's loop
-    static const bool loop = !(getenv("FICCO_BLOCKS_LOOP") && atoi(getenv("FICCO_BLOCKS_LOOP")) == 0);
     int64_t grid = total;
-    if (loop) {
+    {
         static int fit_of[64];                       // per device: 0 = not asked yet, -1 = could not be asked
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();

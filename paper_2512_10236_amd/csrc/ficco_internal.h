@@ -39,13 +39,15 @@ __host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_
 // XCDs that walk the same rows (the col_lists lists of a row class) or the same columns (the
 // kTicketLists / col_lists lists of a column block) at the same time find it in the cache, and so do
 // later passes over a group's rows and later groups' passes over the columns if the operand stays
-// there (operands up to kCacheStayBytes do). Among equal footprints groups of about three rounds of
-// tiles were fastest. Fitted to sweeps of (col_lists, g) on five shape/tile pairs (14 to 112 column
-// tiles, 16 to 128 row tiles, 128x128 and 256x256 tiles): the order it picks from all 16 is within
-// 2.1 % of the best of each sweep except one (3.7 %). Known miss: with 128-row pieces of a short, very
-// wide product (M = 4096, N = 14336) the orders a step-bound group allows are all 6-16 % slower than the
-// best free order, and the model picks the slowest of them.
-constexpr double kHbmFillCost = 6.0;
+// there (operands up to kCacheStayBytes do; a group's rows also do between its own rounds when the
+// rows all row classes hold at that time fit). Among equal footprints groups of about three rounds of
+// tiles were fastest. Fitted to sweeps of all 16 (col_lists, g) pairs on five shape/tile combinations
+// (14 to 112 column tiles, 16 to 128 row tiles, 128x128 and 256x256 tiles) and checked against such
+// sweeps on 8 shapes x 3 launch kinds: the pick is within 2 % of the best order in 23 of 24 cases.
+// Known miss: with 128-row pieces of a short, very wide product (M = 4096, N = 14336) the orders a
+// step-bound group allows are all 6-16 % slower than the best free order, and the model picks the
+// slowest of them.
+constexpr double kHbmFillCost = 3.0;
 constexpr int64_t kCacheStayBytes = 128ll << 20;       // of the 256 MB memory-side cache
 __host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t row_tiles, int64_t slots, int col_lists, int g,
                                        int64_t a_bytes, int64_t w_bytes)
@@ -60,7 +62,10 @@ __host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t row_t
     if (cols_active > (double)width) cols_active = (double)width;
     const double passes = per_group > slots ? (double)per_group / (double)slots : 1.0;       // rounds a group's rows stay in use
     const double groups = rows_list > g ? (double)rows_list / g : 1.0;                       // passes over a list's columns
-    const double a_from_hbm = a_bytes <= kCacheStayBytes ? 1.0 / (col_lists * passes) : 1.0 / col_lists;
+    // a group's rows are needed for `passes` rounds in a row: the later ones find them cached if the rows that
+    // all row classes hold at that time fit, even when the whole of A does not
+    const int64_t group_rows_bytes = row_tiles > 0 ? a_bytes / row_tiles * g * classes : a_bytes;
+    const double a_from_hbm = (a_bytes <= kCacheStayBytes || group_rows_bytes <= kCacheStayBytes) ? 1.0 / (col_lists * passes) : 1.0 / col_lists;
     const double w_from_hbm = w_bytes <= kCacheStayBytes ? 1.0 / (classes * groups) : 1.0 / classes;
     const double fill = rows_active * bm * (1.0 + (kHbmFillCost - 1.0) * a_from_hbm) +
                         cols_active * bn * (1.0 + (kHbmFillCost - 1.0) * w_from_hbm);
