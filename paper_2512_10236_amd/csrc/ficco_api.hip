@@ -319,14 +319,17 @@ LaunchShape launch_shape(const ficco_plan_t *p, const Group &g)
 // Tile choice. Estimated time of a launch = k-steps x [full rounds over the machine x step(1) +
 // step(fill of the last, partial round)], where step(f) = base + slope * f is the time of one k-step
 // of that tile shape when a fraction f of the machine's workgroup slots is occupied (microseconds,
-// fitted to a sweep of launch sizes on MI355X); padded (masked) rows and columns are paid in full.
+// fitted to a sweep of launch sizes on MI355X; the full-machine cost base + slope of the mid-size
+// tiles re-fitted to multi-round resident launches after the tile order changed: 128x256 and 256x128
+// run at 0.87-0.95 of the 256x256 tile's throughput there, 128x128 at 0.84-0.88); padded (masked)
+// rows and columns are paid in full.
 int choose_tile(const ficco_plan_t *p, int cus)
 {
     static const struct { int id; double base, slope; int occ; } cand[] = {
-        {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.80, 0.35, 1}, {TILE_256x128, 0.80, 0.40, 1},
-        {TILE_128x128, 0.60, 0.50, 2}, {TILE_128x128D, 0.48, 0.08, 1},
+        {TILE_256x256, 1.40, 0.45, 1}, {TILE_128x256, 0.80, 0.25, 1}, {TILE_256x128, 0.80, 0.27, 1},
+        {TILE_128x128, 0.60, 0.48, 2}, {TILE_128x128D, 0.48, 0.08, 1},
         {TILE_64x256, 0.57, 0.15, 1},  {TILE_32x256, 0.45, 0.05, 1},
-        {TILE_128x192, 0.72, 0.24, 1}, {TILE_256x192, 1.10, 0.50, 1},
+        {TILE_128x192, 0.72, 0.12, 1}, {TILE_256x192, 1.10, 0.45, 1},
     };
     double best = 1e300;
     int best_id = TILE_128x128;

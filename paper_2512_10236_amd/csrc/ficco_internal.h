@@ -44,9 +44,9 @@ __host__ __device__ inline int64_t resident_list_tiles(int64_t row_tiles, int64_
 // tiles were fastest. Fitted to sweeps of all 16 (col_lists, g) pairs on five shape/tile combinations
 // (14 to 112 column tiles, 16 to 128 row tiles, 128x128 and 256x256 tiles) and checked against such
 // sweeps on 8 shapes x 3 launch kinds: the pick is within 2 % of the best order in 23 of 24 cases.
-// Known miss: with 128-row pieces of a short, very wide product (M = 4096, N = 14336) the orders a
-// step-bound group allows are all 6-16 % slower than the best free order, and the model picks the
-// slowest of them.
+// Known miss: with 128-row pieces of a short, very wide product (M = 4096, N = 14336) and the
+// 128x128 tile (no longer chosen for it) the orders a step-bound group allows are all 6-16 % slower
+// than the best free order, and the model picks the slowest of them.
 constexpr double kHbmFillCost = 3.0;
 constexpr int64_t kCacheStayBytes = 128ll << 20;       // of the 256 MB memory-side cache
 __host__ inline double tile_order_cost(int bm, int bn, int64_t tn, int64_t row_tiles, int64_t slots, int col_lists, int g,
