@@ -41,6 +41,7 @@ HBM_PEAK_GBPS = 8000.0
 PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131086.7, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
     ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57468.6, "WRITE_SIZE": 12288.9},
+    ("cfg2_qkv8b", "gemm_resident2d_kernel<128x192>"): {"FETCH_SIZE": 57485.1, "WRITE_SIZE": 12288.7},
     ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57449.0, "WRITE_SIZE": 12288.0},
     ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 929503.3, "WRITE_SIZE": 116573.6},
     ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 849699.1, "WRITE_SIZE": 117399.7},
@@ -299,6 +300,14 @@ def main() -> int:
         best = min(screen, key=screen.get)
         plan = make(*best)
         ms = timed_steps(plan, source(tag, *best), args.steps, args.warmup)
+        # when column pieces (2D) win, the best row-piece schedule is timed in full as well
+        rows_best, ms_rows = None, None
+        if best[0] % PACKED == F.FICCO_FINE_2D:
+            rows_best = min((k for k in screen if k[0] % PACKED != F.FICCO_FINE_2D), key=screen.get, default=None)
+            if rows_best is not None:
+                p_rows = make(*rows_best)
+                ms_rows = timed_steps(p_rows, source(tag, *rows_best), args.steps, args.warmup)
+                F.ficco_destroy(p_rows)
         info = F.ficco_plan_info(plan)
         st = F.ficco_query_stats(plan)
         F.ficco_destroy(plan)
@@ -326,6 +335,7 @@ def main() -> int:
                    speedup_vs_serial=ms_ser / ms, speedup_vs_shard_level=ms_sh / ms,
                    copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
                    ms_local_shard_resident=ms_het,
+                   best_row_pieces=(f"{sched_name(rows_best[0])}:{rows_best[1]}" if rows_best else None), ms_best_row_pieces=ms_rows,
                    screen={f"{sched_name(s)}:{c}": round(v, 4) for (s, c), v in screen.items()})
         return res, best
 

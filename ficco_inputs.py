@@ -101,8 +101,9 @@ CONFIGS = {
     # tiny case the oracle finishes in well under a second
     "cfg1_tiny": dict(M=512, K=1024, N=1024, shards=4, chunk_rows=[128, 32], seed=0,
                       direction="ag_gemm"),
-    # Llama-3-8B QKV share at TP=8
-    "cfg2_qkv8b": dict(M=8192, K=4096, N=768, shards=8, chunk_rows=[1024, 512, 256], seed=1,
+    # Llama-3-8B QKV share at TP=8 (``k_slices``: the 2D decomposition is screened too; it needs no more
+    # than a K-sliced staging layout on the sending side)
+    "cfg2_qkv8b": dict(M=8192, K=4096, N=768, shards=8, chunk_rows=[1024, 512, 256], k_slices=[2, 4], seed=1,
                        direction="ag_gemm"),
     # 70B-class FFN-up share
     "cfg3_ffn70b": dict(M=16384, K=8192, N=3584, shards=8, chunk_rows=[2048, 1024, 512], seed=2,
