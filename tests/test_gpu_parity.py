@@ -380,8 +380,11 @@ def test_cfg2_full_compare(gpu):
     for rows in cfg["chunk_rows"]:
         for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
             cases.append((sched, ms // rows))
+    cases += [(ficco.FICCO_FINE_2D, c) for c in cfg["k_slices"]]       # the bench screens column pieces here too
     for sched, c in cases:
-        bits, st, _ = run_ag(gpu, shards, W, sched, c)
+        # device staging source for the resident schedules, as the bench times them
+        src = "device" if sched in (ficco.FICCO_FINE_PERSISTENT, ficco.FICCO_FINE_2D) else "pinned"
+        bits, st, _ = run_ag(gpu, shards, W, sched, c, src=src)
         if base is None:
             check(bits, ref, "cfg2 serial")
             base = bits
