@@ -401,6 +401,12 @@ def main() -> int:
                            "monolithic_us": round(float(np.mean(whole)), 3),
                            "monolithic_tflops": round(flops / float(np.mean(whole)) * 1e-6, 2),
                            "monolithic_tile": f"{winfo.tile_m}x{winfo.tile_n}"}
+        if "pair" in out and traffic:
+            # memory side of the overlapped pair: what the GEMM moves beyond its L2s (counters above) plus what the
+            # copy engines read and write (the staging buffer and A_dev both live in HBM), over the step time
+            step_bytes = traffic + 2 * (M * N * 2 if rs else M * K * 2)
+            out["pair"]["hbm_side_bytes_per_step"] = step_bytes
+            out["pair"]["hbm_side_frac_of_peak"] = round(step_bytes / (out["ms_per_step"] * 1e-3) / (HBM_PEAK_GBPS * 1e9), 4)
 
     if "losses" in legs and not rs:
         s, c = best if best else (F.FICCO_FINE_FUSED, 2)
