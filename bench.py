@@ -229,9 +229,13 @@ def main() -> int:
             F.ficco_run(plan, src, A_dev, W_dev, C_dev, None, cs, xs)
         return F.ficco_query_stats(plan)                  # the step's last stage; blocks until the step is done
 
-    def timed_steps(plan, src, steps, warmup):
-        """ms per step over `steps` back-to-back steps, synchronize on both sides."""
+    def timed_steps(plan, src, steps, warmup, warm_seconds=0.0):
+        """ms per step over `steps` back-to-back steps, synchronize on both sides. `warm_seconds`: keep
+        warming up (untimed) until that much time has passed."""
+        t_warm = time.perf_counter()
         for _ in range(warmup):
+            run_once(plan, src)
+        while time.perf_counter() - t_warm < warm_seconds:
             run_once(plan, src)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -285,17 +289,13 @@ def main() -> int:
     def leg_pair(tag):
         res = {}
         A_src = source(tag, F.FICCO_SERIAL, 1)
-        # bring the clocks up first (the first candidates of a cold screen read up to 15 % slow otherwise)
-        p_warm = make(F.FICCO_SERIAL, 1)
-        t_warm = time.perf_counter()
-        while time.perf_counter() - t_warm < 0.05:
-            run_once(p_warm, A_src)
-        F.ficco_destroy(p_warm)
-        # short screening of the candidates, then the full timed run of the winner
+        # short screening of the candidates, then the full timed run of the winner. The first plan of a
+        # process reads 5-10 % slow for its first 30 ms or so (clocks, first use of everything), so the first
+        # candidate warms up that long before it is timed.
         screen = {}
-        for s, c in cands:
+        for i, (s, c) in enumerate(cands):
             plan = make(s, c)
-            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3)
+            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.0)
             F.ficco_destroy(plan)
         best = min(screen, key=screen.get)
         plan = make(*best)
