@@ -158,10 +158,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2_qkv8b")
     ap.add_argument("--legs", default="pair,pcie,roofline,losses,cpu")
-    ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4 (default: a small sweep)")
+    ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4,5:3072+1024 (default: a small sweep)")
     ap.add_argument("--backend", default="auto", choices=["auto", "stream", "engines"],
                     help="transfer backend for every plan (default: the library's choice)")
-    ap.add_argument("--roofline-plan", default="", help="schedule:chunks for the roofline leg when the pair leg is not run")
+    ap.add_argument("--roofline-plan", default="", help="schedule:chunks (or schedule:w1+w2+... for column pieces of those widths) for the roofline leg when the pair leg is not run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box here has one); "
@@ -216,7 +216,11 @@ def main() -> int:
         if sched != F.FICCO_FINE_2D:
             return base
         if (tag, c) not in sliced:
-            t = base.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
+            if isinstance(c, tuple):                      # slices of unequal width, block after block
+                edges = [sum(c[:i]) for i in range(len(c) + 1)]
+                t = torch.cat([base[:, edges[i]:edges[i + 1]].reshape(-1) for i in range(len(c))]).view(M, K)
+            else:
+                t = base.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
             sliced[(tag, c)] = t if tag == "hbm" else t.pin_memory()
             torch.cuda.synchronize()
         return sliced[(tag, c)]
@@ -250,7 +254,9 @@ def main() -> int:
     def make(sched, c, opts=()):
         if sched >= PACKED:
             sched, opts = sched - PACKED, list(opts) + [(F.FICCO_OPT_PACKING, 1)]
-        plan = F.ficco_plan(M, K, N, G, c, sched)
+        plan = F.ficco_plan(M, K, N, G, len(c) if isinstance(c, tuple) else c, sched)
+        if isinstance(c, tuple):
+            F.ficco_plan_set_slice_widths(plan, c)
         if rs:
             F.ficco_plan_set(plan, F.FICCO_OPT_DIRECTION, F.FICCO_DIR_GEMM_RS)
         for o, v in opts:
@@ -261,13 +267,19 @@ def main() -> int:
         return plan
 
     # a candidate is (schedule, pieces per shard); the fused schedule with explicit Gather/Scatter copies
-    # ("3p:4" on the command line) is schedule FICCO_FINE_FUSED + PACKED
+    # ("3p:4" on the command line) is schedule FICCO_FINE_FUSED + PACKED; column pieces of unequal width
+    # ("5:3072+1024") carry the tuple of widths in place of the count
     PACKED = 1000
+    def pieces_of(c):
+        return len(c) if isinstance(c, tuple) else c
+    def label(sc):
+        return f"{sched_name(sc[0])}:" + ("+".join(str(w) for w in sc[1]) if isinstance(sc[1], tuple) else str(sc[1]))
+    def parse_plan(t):
+        a, b = t.split(":")
+        b = tuple(int(w) for w in b.split("+")) if "+" in b else int(b)
+        return (int(a[:-1]) + PACKED, b) if a.endswith("p") else (int(a), b)
     if args.candidates:
-        cands = []
-        for t in args.candidates.split(","):
-            a, b = t.split(":")
-            cands.append((int(a[:-1]) + PACKED, int(b)) if a.endswith("p") else (int(a), int(b)))
+        cands = [parse_plan(t) for t in args.candidates.split(",")]
     else:
         cands = []
         for rows in cfg["chunk_rows"]:
@@ -277,6 +289,7 @@ def main() -> int:
                 if (s, c) not in cands:
                     cands.append((s, c))
         cands += [(F.FICCO_FINE_2D, c) for c in cfg.get("k_slices", [])]
+        cands += [(F.FICCO_FINE_2D, tuple(w)) for w in cfg.get("k_widths", [])]
 
     out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
                      + " effective TFLOP/s (overlapped pair, best finer-grain schedule)",
@@ -330,13 +343,15 @@ def main() -> int:
             F.ficco_destroy(p_het)
         res.update(copy_backend={1: "stream", 2: "engines"}.get(info.copy_backend), links=info.links,
                    ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
-                   schedule=sched_name(best[0]), chunks_per_shard=best[1], chunk_rows=ms_shard // best[1],
+                   schedule=sched_name(best[0]), chunks_per_shard=pieces_of(best[1]),
+                   chunk_rows=ms_shard if best[0] % PACKED == F.FICCO_FINE_2D else ms_shard // best[1],
+                   slice_widths=(list(best[1]) if isinstance(best[1], tuple) else None),
                    tile=f"{info.tile_m}x{info.tile_n}", ms_serial=ms_ser, ms_shard_level=ms_sh,
                    speedup_vs_serial=ms_ser / ms, speedup_vs_shard_level=ms_sh / ms,
                    copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
                    ms_local_shard_resident=ms_het,
-                   best_row_pieces=(f"{sched_name(rows_best[0])}:{rows_best[1]}" if rows_best else None), ms_best_row_pieces=ms_rows,
-                   screen={f"{sched_name(s)}:{c}": round(v, 4) for (s, c), v in screen.items()})
+                   best_row_pieces=(label(rows_best) if rows_best else None), ms_best_row_pieces=ms_rows,
+                   screen={label(k): round(v, 4) for k, v in screen.items()})
         return res, best
 
     best = None
@@ -346,6 +361,8 @@ def main() -> int:
         out["ms_per_step"] = round(res["ms_per_step"], 5)
         out["pair"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
         out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"])
+        if res["slice_widths"]:
+            out["config"]["slice_widths"] = res["slice_widths"]
     if "pcie" in legs:
         res, _ = leg_pair("pcie")
         out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
@@ -354,7 +371,7 @@ def main() -> int:
         if best:
             s, c = best
         elif args.roofline_plan:
-            s, c = (int(x) for x in args.roofline_plan.split(":"))
+            s, c = parse_plan(args.roofline_plan)
         else:
             s, c = F.ficco_pick_schedule(M, K, N, G)
         s %= PACKED                                    # Gather/Scatter only exists in the overlapped pair

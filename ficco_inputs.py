@@ -102,9 +102,9 @@ CONFIGS = {
     "cfg1_tiny": dict(M=512, K=1024, N=1024, shards=4, chunk_rows=[128, 32], seed=0,
                       direction="ag_gemm"),
     # Llama-3-8B QKV share at TP=8 (``k_slices``: the 2D decomposition is screened too; it needs no more
-    # than a K-sliced staging layout on the sending side)
-    "cfg2_qkv8b": dict(M=8192, K=4096, N=768, shards=8, chunk_rows=[1024, 512, 256], k_slices=[2, 4], seed=1,
-                       direction="ag_gemm"),
+    # than a K-sliced staging layout on the sending side; ``k_widths``: column pieces of unequal width)
+    "cfg2_qkv8b": dict(M=8192, K=4096, N=768, shards=8, chunk_rows=[1024, 512, 256], k_slices=[2, 4],
+                       k_widths=[[3072, 1024]], seed=1, direction="ag_gemm"),
     # 70B-class FFN-up share
     "cfg3_ffn70b": dict(M=16384, K=8192, N=3584, shards=8, chunk_rows=[2048, 1024, 512], seed=2,
                         direction="ag_gemm"),
@@ -150,6 +150,17 @@ def to_k_sliced(A: np.ndarray, slices: int) -> np.ndarray:
     M, K = A.shape
     assert K % slices == 0
     return np.ascontiguousarray(A.reshape(M, slices, K // slices).transpose(1, 0, 2))
+
+
+def to_k_pieces(A: np.ndarray, widths) -> list[np.ndarray]:
+    """Layout change only, for slices of unequal width: the list of ``[M, widths[s]]`` contiguous blocks,
+    block s holding columns ``[sum(widths[:s]), sum(widths[:s+1]))`` of every row. Laid end to end
+    (``np.concatenate([b.ravel() for b in blocks])``) they are the layout in which such pieces travel; with
+    equal widths that is :func:`to_k_sliced`'s array."""
+    M, K = A.shape
+    assert sum(int(w) for w in widths) == K and all(int(w) > 0 for w in widths)
+    edges = np.concatenate([[0], np.cumsum(np.asarray(widths, dtype=np.int64))])
+    return [np.ascontiguousarray(A[:, edges[s]:edges[s + 1]]) for s in range(len(widths))]
 
 
 def config_inputs(name: str):

@@ -24,7 +24,10 @@
  *   - All matrices are row-major bf16 (1-8-7). "device" = hipMalloc'ed memory of the current
  *     device; "host" = ordinary host memory; "pinned" = hipHostMalloc'ed host memory.
  *   - Streams are hipStream_t passed as void*. Every call uses the device that is current on the
- *     calling thread; a plan must be used on the device it was created on.
+ *     calling thread; a plan must be used on the device it was created on. The copy-engine
+ *     backend keeps one process-wide context, set up by the first run that uses it: runs on
+ *     another device of the same process return FICCO_ERR_ARG, and that first run must not race
+ *     with another thread's.
  *   - Every function returns 0 (FICCO_OK) or a negative ficco_status; nothing throws or aborts.
  *     On failure output arguments are left untouched.
  *   - The caller owns every data buffer and both streams. The plan owns its flags, events,
@@ -240,7 +243,9 @@ typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this p
  * (ficco_pack_weight or ficco_run), after which most options are frozen.
  * Shape rules (FICCO_ERR_SHAPE otherwise): M, K, N >= 1; shards >= 1; chunks >= 1;
  * M % (shards*chunks) == 0; K % 64 == 0; N % 8 == 0; chunks == 1 for SERIAL and SHARD;
- * shards*chunks <= 4096. FICCO_FINE_2D instead needs M % shards == 0 and K % (64*chunks) == 0.
+ * shards*chunks <= 4096. FICCO_FINE_2D instead needs M % shards == 0 and chunks <= K/64; its
+ * slices are as equal as whole k-tiles of 64 columns allow (the first (K/64) mod chunks slices
+ * one k-tile wider) unless ficco_plan_set_slice_widths gives other widths.
  * With FICCO_AUTO, `chunks` is ignored and chosen by the heuristic.
  */
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule,
@@ -270,6 +275,23 @@ int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64
 /* First row and row count of every piece, by piece id (host arrays of at least n_chunks entries,
  * either may be NULL). For ordinary plans all pieces have chunk_rows rows. */
 int ficco_plan_pieces(const ficco_plan_t *plan, int64_t *row0, int64_t *rows, int cap);
+
+/*
+ * Column pieces of unequal width for a FICCO_FINE_2D plan (Sec. V-A cuts the k range evenly; with
+ * the overlap model of Sec. IV-A what stays exposed is the wait for the first piece when the GEMM
+ * is the longer side and the GEMM of the last piece when the transfers are, so a narrow first or
+ * last slice shortens it at no cost in transfer count). widths[s] = columns of slice s, s < n;
+ * n must equal the plan's `chunks`, every width a positive multiple of 64, their sum K
+ * (FICCO_ERR_SHAPE otherwise). Slice s then holds columns [k0_s, k0_s + widths[s]) of every row
+ * as an [M][widths[s]] row-major block, the blocks following each other in A_src and A_dev.
+ * widths == NULL (n ignored) restores equal slices. Only before the plan's first use
+ * (FICCO_ERR_STATE afterwards); FICCO_ERR_ARG for other schedules. The result bits do not change.
+ */
+int ficco_plan_set_slice_widths(ficco_plan_t *plan, const int64_t *widths, int n);
+
+/* First column and width of every slice of a FICCO_FINE_2D plan (host arrays of at least `chunks`
+ * entries, either may be NULL; `cap` is their length). FICCO_ERR_ARG for other schedules. */
+int ficco_plan_slices(const ficco_plan_t *plan, int64_t *k0, int64_t *widths, int cap);
 
 /* Set an option; only before the plan's first use (FICCO_ERR_STATE afterwards), except
  * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_HOLD_FLAGS, FICCO_OPT_REPEAT,
@@ -304,11 +326,12 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
  *             A_dev  - [M,K] device; written by the transfers, read by the GEMM.
  *             C_dev  - [M,N] device; written by the GEMM.
  *             peer_out must be NULL.
- *             FICCO_FINE_2D: A_src and A_dev are K-sliced, [chunks][M][K/chunks] bf16 (slice s holds
- *             columns [s*K/chunks, (s+1)*K/chunks) of every row, rows contiguous), so that piece
- *             s*shards + j (slice s of shard j) is one contiguous block, as a sender that owns
- *             shard j would lay its slices out for DMA. C is bitwise what FICCO_SERIAL computes
- *             from the same matrix in row-major layout.
+ *             FICCO_FINE_2D: A_src and A_dev are K-sliced: slice s holds its columns of every
+ *             row as an [M][width_s] row-major block, block after block ([chunks][M][K/chunks]
+ *             when K/64 is a multiple of chunks; ficco_plan_slices reports the slices), so that
+ *             piece s*shards + j (slice s of shard j) is one contiguous block, as a sender that
+ *             owns shard j would lay its slices out for DMA. C is bitwise what FICCO_SERIAL
+ *             computes from the same matrix in row-major layout.
  *   GEMM_RS : A_src must be NULL; A_dev is read; C_dev is written by the GEMM and its row block
  *             p (rows [p*M/G, (p+1)*M/G)) is then copied (on copy_stream, or by the engines) to
  *             peer_out[p] ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces

@@ -91,17 +91,21 @@ def gemm_rs_blocks(A, W, peers: int):
 
 def ag_gemm_2d(A_sliced, W, shards: int) -> np.ndarray:
     """The 2D decomposition carried out step by step (Sec. V-A/B): ``A_sliced`` is
-    ``[c, M, K/c]`` (bf16 bits), step s gathers slice s of every shard and its partial product with
-    rows ``[s*K/c, (s+1)*K/c)`` of W is accumulated into the output. fp64 throughout."""
-    A_sliced = np.ascontiguousarray(A_sliced, dtype=np.uint16)
+    ``[c, M, K/c]`` (bf16 bits), or a list of c blocks ``[M, k_s]`` when the slices differ in width;
+    step s gathers slice s of every shard and its partial product with the matching rows
+    ``[k0_s, k0_s + k_s)`` of W is accumulated into the output. fp64 throughout."""
+    blocks = [np.ascontiguousarray(b, dtype=np.uint16) for b in A_sliced]
     W = np.ascontiguousarray(W, dtype=np.uint16)
-    c, M, kc = A_sliced.shape
-    assert W.shape[0] == c * kc and M % shards == 0
+    M = blocks[0].shape[0]
+    assert all(b.ndim == 2 and b.shape[0] == M for b in blocks)
+    assert W.shape[0] == sum(b.shape[1] for b in blocks) and M % shards == 0
     ms = M // shards
     acc = np.zeros((M, W.shape[1]), dtype=np.float64)
-    for s in range(c):
-        pieces = [A_sliced[s, j * ms:(j + 1) * ms] for j in range(shards)]
-        acc += ag_gemm(pieces, W[s * kc:(s + 1) * kc])
+    k0 = 0
+    for blk in blocks:
+        pieces = [blk[j * ms:(j + 1) * ms] for j in range(shards)]
+        acc += ag_gemm(pieces, W[k0:k0 + blk.shape[1]])
+        k0 += blk.shape[1]
     return acc
 
 

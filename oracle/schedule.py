@@ -29,12 +29,17 @@ def chunk_span(M: int, G: int, c: int, i: int) -> tuple[int, int]:
     return i * m, m
 
 
-def piece_span_2d(M: int, K: int, G: int, c: int, i: int) -> tuple[int, int, int, int]:
+def piece_span_2d(M: int, K: int, G: int, c: int, i: int, widths=None) -> tuple[int, int, int, int]:
     """(first row, rows, first column, columns) of column piece ``i = s*G + j``: k slice ``s`` of
-    shard ``j`` (Sec. V-A: 2D decomposition cuts the shard along the contraction dimension)."""
-    assert M % G == 0 and K % c == 0 and 0 <= i < G * c
+    shard ``j`` (Sec. V-A: 2D decomposition cuts the shard along the contraction dimension).
+    ``widths``: the c slice widths when they differ (they partition K in order); equal otherwise."""
+    assert M % G == 0 and 0 <= i < G * c
     s, j = divmod(i, G)
-    return j * (M // G), M // G, s * (K // c), K // c
+    if widths is None:
+        assert K % c == 0
+        return j * (M // G), M // G, s * (K // c), K // c
+    assert len(widths) == c and sum(widths) == K and min(widths) > 0
+    return j * (M // G), M // G, sum(widths[:s]), widths[s]
 
 
 def arrival_order_2d(G: int, c: int, order: int) -> list[int]:

@@ -42,6 +42,7 @@ constexpr int kEpochSlots = 65536;   // pinned source words for flag writes; epo
 struct EngineCtx {
     bool ready = false;
     int status = FICCO_OK;
+    int device = -1;                                  // HIP device the context was set up for (one per process)
     hsa_agent_t gpu{}, cpu{};
     uint32_t mask_dd = 0, mask_hd = 0, mask_dh = 0;   // engine-status hints: device->device, host->device, device->host
     uint32_t validated = 0, failed = 0;               // engines that passed / failed the one-time self test
@@ -72,8 +73,9 @@ hsa_status_t pick_agents(hsa_agent_t a, void *data)
 int engines_init(int hip_device)
 {
     EngineCtx &c = g_engines;
-    if (c.ready) return c.status;
+    if (c.ready) return c.device == hip_device ? c.status : FICCO_ERR_ARG;   // one device per process drives the engines
     c.ready = true;
+    c.device = hip_device;
     c.status = FICCO_ERR_HIP;
     const bool dbg = getenv("FICCO_DEBUG") != nullptr;
     hsa_status_t hs = hsa_init();
@@ -138,6 +140,8 @@ struct ficco_plan_s {
     int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
     int repeat = 1;                      // GEMM-only runs: launches enqueued this many times inside one bracket
     int tile_group = 0, tile_col_lists = 0;   // forced tile order (0 = chosen from the shape)
+    std::vector<int64_t> slice_k0;       // column pieces: first column of each slice, then K (c + 1 entries)
+    bool own_widths = false;             // slice_k0 was given by the caller (ficco_plan_set_slice_widths)
     // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
     bool grouped = false;
     int E = 1;
@@ -164,6 +168,7 @@ struct ficco_plan_s {
     int32_t *d_tables = nullptr;         // arrival | block_row0 (by arrival position)
     int32_t *d_arrival = nullptr, *d_block_row0 = nullptr;
     int32_t *d_gather_idx = nullptr, *d_scatter_idx = nullptr;   // by arrival position: n + chunk, 2n + chunk
+    int32_t *d_slice_k0 = nullptr;       // column pieces: slice_k0 on the device (behind the other tables)
     uint16_t *d_pack_a = nullptr, *d_pack_c = nullptr;            // packing: step inputs [M,K] and step outputs [M,N], arrival order
     uint32_t *h_epochs = nullptr;        // pinned
     volatile uint32_t *h_status = nullptr;   // pinned, behind h_epochs
@@ -258,6 +263,12 @@ int build_lists(ficco_plan_t *p)
     const int G = p->G, c = p->c, n = G * c;
     p->n_chunks = n;
     p->m = is_2d(p) ? p->M / p->G : p->M / n;      // rows of one piece (column pieces keep the shard's rows)
+    if (is_2d(p) && !p->own_widths) {
+        // as equal as whole k-tiles allow: the first (K/64) mod c slices are one k-tile wider
+        const int64_t kt = p->K / kBK, base = kt / c, extra = kt % c;
+        p->slice_k0.assign((size_t)c + 1, 0);
+        for (int sl = 0; sl < c; ++sl) p->slice_k0[sl + 1] = p->slice_k0[sl] + kBK * (base + (sl < extra ? 1 : 0));
+    }
     if (p->order != FICCO_ORDER_CUSTOM) {
         p->arrival.clear();
         if (is_2d(p)) {
@@ -440,12 +451,15 @@ int finalize(ficco_plan_t *p)
     p->d_flags = p->d_words;
     p->d_ticket = p->d_ticket_mem;
     p->d_status = p->d_words + (size_t)n * kFlagStrideWords + kFlagStrideWords;
-    if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * 4 * (size_t)n) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    const size_t n_k0 = is_2d(p) ? p->slice_k0.size() : 0;
+    if (hipMalloc((void **)&p->d_tables, sizeof(int32_t) * (4 * (size_t)n + n_k0)) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     p->d_arrival = p->d_tables;
     p->d_block_row0 = p->d_tables + n;
     p->d_gather_idx = p->d_tables + 2 * (size_t)n;
     p->d_scatter_idx = p->d_tables + 3 * (size_t)n;
-    std::vector<int32_t> host(4 * (size_t)n);
+    p->d_slice_k0 = n_k0 ? p->d_tables + 4 * (size_t)n : nullptr;
+    std::vector<int32_t> host(4 * (size_t)n + n_k0);
+    for (size_t sl = 0; sl < n_k0; ++sl) host[4 * (size_t)n + sl] = (int32_t)p->slice_k0[sl];
     for (int q = 0; q < n; ++q) {
         host[q] = p->arrival[q];
         host[n + q] = (int32_t)(p->arrival[q] * p->m);
@@ -640,8 +654,17 @@ inline ListGeometry resident_lists(const ficco_plan_t *p)
                       p->resident_grid / kTicketLists, p->M * p->K * 2, p->N * p->K * 2);
 }
 
-// bytes of one row of a transferred piece of the activation
-inline size_t piece_row_bytes(const ficco_plan_t *p) { return (size_t)(is_2d(p) ? p->K / p->c : p->K) * 2; }
+// Where a transferred piece of the activation sits (byte offset, the same in the source and in A_dev) and
+// how long it is. Row pieces: m whole rows. Column pieces: the shard's rows of slice s, which are contiguous
+// in the K-sliced layout.
+struct Extent { size_t off, bytes; };
+inline Extent piece_extent(const ficco_plan_t *p, int chunk)
+{
+    if (!is_2d(p)) return {(size_t)chunk * p->m * p->K * 2, (size_t)p->m * p->K * 2};
+    const int sl = chunk / p->G, j = chunk % p->G;
+    const size_t kb = (size_t)p->slice_k0[sl], kw = (size_t)p->slice_k0[sl + 1] - kb;
+    return {((size_t)p->M * kb + (size_t)j * p->m * kw) * 2, (size_t)p->m * kw * 2};
+}
 
 // One resident launch of the K-sliced schedule: every tile owns its part of C for the whole k range
 // and waits, slice by slice, for the column pieces of the shards its rows come from.
@@ -651,7 +674,7 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     r.g.A = (const uint16_t *)A_dev;
     r.g.Wt = p->d_wt;
     r.g.C = (uint16_t *)C_dev;
-    r.g.lda = p->K / p->c;
+    r.g.lda = 0;                         // per slice: its width
     r.g.ldc = p->N;
     r.g.N = (int32_t)p->N;
     r.g.K = (int32_t)p->K;
@@ -660,7 +683,7 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
     r.slices = p->c;
     r.shards = p->G;
     r.rows_per_shard = (int32_t)(p->M / p->G);
-    r.k_per_slice = (int32_t)(p->K / p->c);
+    r.k0 = p->d_slice_k0;
     r.ticket = p->d_ticket;
     r.grid = grid;
     r.gated = gated ? 1 : 0;
@@ -909,7 +932,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     p->run_index += 1;
     const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
     const uint64_t spin_ticks = (uint64_t)p->spin_limit_us * (uint64_t)p->wall_clock_khz / 1000u;
-    const size_t row_bytes_a = piece_row_bytes(p), row_bytes_c = (size_t)p->N * 2;
+    const size_t row_bytes_a = (size_t)p->K * 2, row_bytes_c = (size_t)p->N * 2;
     auto is_local = [&](int chunk) { return !rs && p->local_shard >= 0 && shard_of(p, chunk) == p->local_shard; };
     // transfers are chained one after the other (peer-to-peer pattern) or run side by side (all-to-all)
     const bool chained = p->schedule == FICCO_SHARD ||
@@ -941,10 +964,10 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         hsa_agent_t dst_agent = ctx.gpu, src_agent = ctx.gpu;
         bool force = true;
         if (!rs) {
-            const size_t off = (size_t)chunk * p->m * row_bytes_a;
-            bytes = (size_t)p->m * row_bytes_a;
-            dst = (char *)A_dev + off;
-            src = (const char *)A_src + off;
+            const Extent ex = piece_extent(p, chunk);
+            bytes = ex.bytes;
+            dst = (char *)A_dev + ex.off;
+            src = (const char *)A_src + ex.off;
             if (!src_dev) { src_agent = ctx.cpu; force = false; }
         } else {
             const int peer = chunk / c;
@@ -1281,7 +1304,7 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
     if ((int64_t)shards * chunks > 4096) return FICCO_ERR_SHAPE;
     if (schedule == FICCO_FINE_2D) {
         // column pieces: every shard keeps its rows, k is cut into `chunks` slices of whole k-tiles
-        if (M % shards || K % ((int64_t)64 * chunks)) return FICCO_ERR_SHAPE;
+        if (M % shards || K % kBK || chunks > K / kBK) return FICCO_ERR_SHAPE;
     } else if (M % ((int64_t)shards * chunks)) {
         return FICCO_ERR_SHAPE;
     }
@@ -1334,6 +1357,36 @@ int ficco_plan_pieces(const ficco_plan_t *p, int64_t *row0, int64_t *rows, int c
         const int64_t nr = p->grouped ? p->piece_nrows[i] : p->m;
         if (row0) row0[i] = r0;
         if (rows) rows[i] = nr;
+    }
+    return FICCO_OK;
+}
+
+int ficco_plan_set_slice_widths(ficco_plan_t *p, const int64_t *widths, int n)
+{
+    if (!p || !is_2d(p)) return FICCO_ERR_ARG;
+    if (p->finalized) return FICCO_ERR_STATE;
+    if (!widths) {
+        p->own_widths = false;
+        return build_lists(p);
+    }
+    if (n != p->c) return FICCO_ERR_SHAPE;
+    std::vector<int64_t> k0((size_t)n + 1, 0);
+    for (int sl = 0; sl < n; ++sl) {
+        if (widths[sl] < kBK || widths[sl] % kBK || widths[sl] > p->K) return FICCO_ERR_SHAPE;
+        k0[sl + 1] = k0[sl] + widths[sl];
+    }
+    if (k0[n] != p->K) return FICCO_ERR_SHAPE;
+    p->slice_k0 = k0;
+    p->own_widths = true;
+    return build_lists(p);
+}
+
+int ficco_plan_slices(const ficco_plan_t *p, int64_t *k0, int64_t *widths, int cap)
+{
+    if (!p || !is_2d(p) || cap < p->c) return FICCO_ERR_ARG;
+    for (int sl = 0; sl < p->c; ++sl) {
+        if (k0) k0[sl] = p->slice_k0[sl];
+        if (widths) widths[sl] = p->slice_k0[sl + 1] - p->slice_k0[sl];
     }
     return FICCO_OK;
 }
@@ -1578,7 +1631,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     const bool first = p->run_index == 0;
     p->run_index += 1;
     const uint32_t epoch = 1u + (p->run_index - 1u) % (uint32_t)(kEpochSlots - 1);
-    const size_t row_bytes_a = piece_row_bytes(p), row_bytes_c = (size_t)p->N * 2;
+    const size_t row_bytes_c = (size_t)p->N * 2;
     const int c = p->c;
 
     // Order this run after the previous one on both streams, then start the clock on the stream
@@ -1613,7 +1666,8 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
     auto issue_copy_ag = [&](int q) -> int {
         const int chunk = p->arrival[q];
         if (is_local(chunk)) return FICCO_OK;
-        const size_t off = (size_t)chunk * p->m * row_bytes_a, bytes = (size_t)p->m * row_bytes_a;
+        const Extent ex = piece_extent(p, chunk);
+        const size_t off = ex.off, bytes = ex.bytes;
         if (timing) HIP_TRY(hipEventRecord(p->ev_copy_b[q], xs));
         if (!copy_first_recorded) {
             if (timing) HIP_TRY(hipEventRecord(p->ev_copy_first, xs));

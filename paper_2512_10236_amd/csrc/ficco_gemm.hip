@@ -657,10 +657,11 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
                 ok = s_ok;
                 __syncthreads();
             }
-            if (ok)
-                tile_accumulate<T>(ta, a.A + ((int64_t)sl * r.M + row0) * r.k_per_slice, rows_valid,
-                                   a.Wt + (int64_t)col0 * a.K + (int64_t)sl * r.k_per_slice, cols_valid,
-                                   r.k_per_slice, a.K, r.k_per_slice, smem);
+            if (ok) {
+                const int kb = r.k0[sl], kw = r.k0[sl + 1] - kb;          // uniform loads: the slice's columns
+                tile_accumulate<T>(ta, a.A + (int64_t)r.M * kb + row0 * kw, rows_valid,
+                                   a.Wt + (int64_t)col0 * a.K + kb, cols_valid, kw, a.K, kw, smem);
+            }
         }
         if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
         if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
@@ -845,7 +846,7 @@ static hipError_t launch_resident2d_t(const Resident2DLaunch &r, hipStream_t s)
 {
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
     if (once != hipSuccess) return once;
-    if (r.grid <= 0) return hipErrorInvalidValue;
+    if (r.grid <= 0 || !r.k0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(gemm_resident2d_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }

@@ -140,13 +140,15 @@ struct ResidentLaunch {
     int32_t tiles_per_chunk;      // row tiles per piece x column tiles
 };
 
-// The resident kernel for column (K) pieces: A is kept in K-sliced layout [slices][M][K/slices]; piece
-// s*shards + j is slice s of shard j (rows [j*rows_per_shard, (j+1)*rows_per_shard)). A workgroup owns
-// one tile of C for all of K, keeps its accumulators in registers, and before each slice waits for
-// the pieces that cover its rows.
+// The resident kernel for column (K) pieces: A is kept in K-sliced layout, slice after slice, slice s
+// being the [M][k0[s+1] - k0[s]] row-major block of columns [k0[s], k0[s+1]) (equal widths unless the
+// plan was given its own); piece s*shards + j is slice s of shard j (rows [j*rows_per_shard,
+// (j+1)*rows_per_shard)). A workgroup owns one tile of C for all of K, keeps its accumulators in
+// registers, and before each slice waits for the pieces that cover its rows.
 struct Resident2DLaunch {
     GemmLaunch g;                 // A = K-sliced base, Wt, C, ldc, N, K (whole), gate; other fields unused
-    int32_t M, slices, shards, rows_per_shard, k_per_slice;
+    int32_t M, slices, shards, rows_per_shard;
+    const int32_t *k0;            // device, slices + 1 entries: first column of each slice, then K (multiples of the k-tile)
     uint32_t *ticket;
     uint32_t ticket_base[8];
     int32_t grid;

@@ -31,15 +31,25 @@ def widen(bits):
 
 
 def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, delay_copy=False,
-           timing=0, allow_timeout=False, runs=1, local_shard=None, backend=None):
-    """One all-gather -> GEMM through the C ABI; returns (C bits, stats)."""
+           timing=0, allow_timeout=False, runs=1, local_shard=None, backend=None, widths=None):
+    """One all-gather -> GEMM through the C ABI; returns (C bits, stats). ``widths``: column pieces of
+    these widths (FICCO_FINE_2D, ``c`` = their number) instead of equal ones."""
     dev = gpu["dev"]
     A = np.concatenate(shards, 0)
     M, K = A.shape
     N = W.shape[1]
     G = len(shards)
     if schedule == ficco.FICCO_FINE_2D:
-        A = fi.to_k_sliced(A, c).reshape(M, K)         # same bytes, column pieces contiguous
+        if widths is None and K % c == 0:
+            A = fi.to_k_sliced(A, c).reshape(M, K)         # same bytes, column pieces contiguous
+        else:
+            if widths is None:                             # the library's own cut into whole k-tiles
+                probe = ficco.ficco_plan(M, K, N, G, c, schedule)
+                widths = ficco.ficco_plan_slices(probe)[1]
+                ficco.ficco_destroy(probe)
+                assert sum(widths) == K and len(widths) == c and max(widths) - min(widths) <= 64
+            assert len(widths) == c
+            A = np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)
     A_src = as_i16(A).pin_memory() if src == "pinned" else as_i16(A).to(dev)
     W_dev = as_i16(W).to(dev)
     A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)     # poison: unread rows show up as NaN
@@ -60,6 +70,8 @@ def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, 
             ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
         for o, v in opts:
             ficco.ficco_plan_set(plan, o, v)
+        if widths is not None:
+            ficco.ficco_plan_set_slice_widths(plan, widths)
         if arrival is not None:
             ficco.ficco_plan_set_arrival(plan, arrival)
         ficco.ficco_plan_set(plan, ficco.FICCO_OPT_TIMING, timing)
@@ -381,10 +393,12 @@ def test_cfg2_full_compare(gpu):
         for sched in (ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT):
             cases.append((sched, ms // rows))
     cases += [(ficco.FICCO_FINE_2D, c) for c in cfg["k_slices"]]       # the bench screens column pieces here too
+    cases += [(ficco.FICCO_FINE_2D, tuple(w)) for w in cfg["k_widths"]]
     for sched, c in cases:
         # device staging source for the resident schedules, as the bench times them
         src = "device" if sched in (ficco.FICCO_FINE_PERSISTENT, ficco.FICCO_FINE_2D) else "pinned"
-        bits, st, _ = run_ag(gpu, shards, W, sched, c, src=src)
+        widths = list(c) if isinstance(c, tuple) else None
+        bits, st, _ = run_ag(gpu, shards, W, sched, len(c) if widths else c, src=src, widths=widths)
         if base is None:
             check(bits, ref, "cfg2 serial")
             base = bits
@@ -502,6 +516,36 @@ def test_2d_every_tile_shape_ragged(gpu, tile):
     assert np.array_equal(bits, base)
 
 
+def test_2d_unequal_slices_match_oracle_and_serial_bits(gpu):
+    """Column pieces of unequal width (narrow first, narrow last, one k-tile, the library's own cut of a k range
+    that the slice count does not divide): the bits are those of the serial schedule."""
+    G, ms, K, N = 4, 160, 1024, 328
+    shards = fi.make_shards(31, G * ms, K, G)
+    W = fi.make_weight(31, K, N)
+    A = np.concatenate(shards, 0)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    check(base, og.ag_gemm(shards, W), "serial")
+    for widths in ([768, 256], [64, 64, 128, 256, 512], [512, 448, 64], [64] * 16, [1024]):
+        ref = og.ag_gemm_2d(fi.to_k_pieces(A, widths), W, G)
+        for src, opts in [("pinned", [(ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_STREAM)]),
+                          ("device", [(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)]),
+                          ("device", [(ficco.FICCO_OPT_FLAG_WRITE, 2)]),
+                          ("device", [])]:
+            bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, len(widths), src=src, opts=opts, runs=2, widths=widths)
+            check(bits, ref, f"2D widths={widths} {src} {opts}")
+            assert np.array_equal(bits, base), f"2D widths={widths} {src} {opts}: differs bitwise from serial"
+            assert st.n_copies == G * len(widths) and st.copy_bytes == G * ms * K * 2
+    # 16 k-tiles in 3, 5 and 7 slices: the first slices are one k-tile wider
+    for c in (3, 5, 7):
+        bits, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device")
+        assert np.array_equal(bits, base), f"2D c={c}"
+        assert st.n_copies == G * c and st.copy_bytes == G * ms * K * 2
+    # reversed arrival with unequal widths: a tile still takes the slices in k order
+    rev = list(range(G * 3 - 1, -1, -1))
+    bits, _, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, 3, src="device", arrival=rev, widths=[128, 640, 256])
+    assert np.array_equal(bits, base)
+
+
 def test_2d_waits_for_late_and_reordered_slices(gpu):
     G, ms, K, N, c = 4, 256, 1024, 512, 4
     shards = fi.make_shards(24, G * ms, K, G)
@@ -531,8 +575,9 @@ def test_cfg6_2d_full_size_sampled_rows(gpu):
     ref = og.ag_gemm_rows(shards, W, rows)
     base, st0, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
     check(base[rows], ref, "cfg6 serial")
-    for c in cfg["k_slices"]:
-        bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", runs=2)
+    for c in cfg["k_slices"] + [(1024, 3072, 4096, 4096, 4096)]:      # equal slices, then a narrow first one
+        widths = list(c) if isinstance(c, tuple) else None
+        bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, len(c) if widths else c, src="device", runs=2, widths=widths)
         check(bits[rows], ref, f"cfg6 2D c={c}")
         assert np.array_equal(bits, base), f"cfg6 2D c={c} differs bitwise from serial"
 

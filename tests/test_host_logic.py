@@ -57,6 +57,48 @@ def test_plan_lists_match_oracle(G, c, lib_s, ora_s, order):
     assert info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
 
 
+def test_2d_default_slices_are_as_equal_as_whole_k_tiles_allow():
+    # 11 k-tiles in 4 slices: 3, 3, 3, 2 tiles
+    plan = ficco.ficco_plan(64, 64 * 11, 8, 4, 4, ficco.FICCO_FINE_2D)
+    try:
+        k0, w = ficco.ficco_plan_slices(plan)
+    finally:
+        ficco.ficco_destroy(plan)
+    assert w == [192, 192, 192, 128] and k0 == [0, 192, 384, 576]
+
+
+def test_2d_slice_widths_are_validated_and_reported():
+    M, K, G, c = 64, 64 * 8, 4, 4
+    plan = ficco.ficco_plan(M, K, 8, G, c, ficco.FICCO_FINE_2D)
+    rows = ficco.ficco_plan(M, K, 8, G, 2, ficco.FICCO_FINE_PERSISTENT)
+    try:
+        k0, w = ficco.ficco_plan_slices(plan)
+        assert w == [K // c] * c and k0 == [s * (K // c) for s in range(c)]
+        widths = [64 * 4, 64, 64 * 2, 64]
+        ficco.ficco_plan_set_slice_widths(plan, widths)
+        k0, w = ficco.ficco_plan_slices(plan)
+        assert w == widths and k0 == [sum(widths[:s]) for s in range(c)]
+        for s in range(c):
+            for j in range(G):
+                assert sch.piece_span_2d(M, K, G, c, s * G + j, widths)[2:] == (k0[s], w[s])
+        # the arrival list does not depend on the widths
+        assert ficco.ficco_plan_arrival(plan)[0] == sch.arrival_order_2d(G, c, sch.ORDER_STEP_MAJOR)
+        for bad in (widths[:-1], [w_ + 64 for w_ in widths], [widths[0] - 32, widths[1] + 32] + widths[2:],
+                    [0] + [widths[0] + widths[1]] + widths[2:]):
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_plan_set_slice_widths(plan, bad)
+        assert ficco.ficco_plan_slices(plan)[1] == widths          # a rejected list changes nothing
+        ficco.ficco_plan_set_slice_widths(plan, None)
+        assert ficco.ficco_plan_slices(plan)[1] == [K // c] * c
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set_slice_widths(rows, [K // 2, K // 2])     # row pieces have no slices
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_slices(rows)
+    finally:
+        ficco.ficco_destroy(plan)
+        ficco.ficco_destroy(rows)
+
+
 @pytest.mark.parametrize("G,c", [(4, 1), (4, 4), (8, 2), (3, 5)])
 @pytest.mark.parametrize("order", [ficco.FICCO_ORDER_STEP_MAJOR, ficco.FICCO_ORDER_SHARD_MAJOR])
 def test_2d_plan_lists_match_oracle(G, c, order):
@@ -138,7 +180,7 @@ def test_custom_arrival_and_local_shard():
     (512, 96, 8, 4, 1, 0), (512, 64, 12, 4, 1, 0),                          # K % 64, N % 8
     (512, 64, 8, 4, 2, 0), (512, 64, 8, 4, 2, 1),                           # pieces with serial / shard
     (1 << 20, 64, 8, 8192, 1, 2),                                           # too many pieces
-    (512, 192, 8, 4, 2, 5), (510, 128, 8, 4, 2, 5),                         # 2D: slices of whole k-tiles, M % shards
+    (512, 192, 8, 4, 4, 5), (510, 128, 8, 4, 2, 5),                         # 2D: more slices than k-tiles, M % shards
 ])
 def test_shape_rules(args):
     with pytest.raises(ficco.FiccoError) as e:

@@ -225,3 +225,43 @@ def test_2d_steps_equal_whole_product_on_random_inputs():
     # same terms, another association of the fp64 sums
     assert np.max(np.abs(whole - steps)) <= 1e-12 * K
     assert np.array_equal(og.ag_gemm_2d(fi.to_k_sliced(A, 1), W, G), whole)
+
+
+# ------------------------------------------------------------------ column pieces of unequal width
+def test_k_pieces_layout_partitions_the_columns_in_order():
+    A = np.arange(5 * 12, dtype=np.uint16).reshape(5, 12)
+    blocks = fi.to_k_pieces(A, [6, 2, 4])
+    assert [b.shape for b in blocks] == [(5, 6), (5, 2), (5, 4)]
+    assert np.array_equal(np.concatenate(blocks, 1), A)
+    assert all(b.flags["C_CONTIGUOUS"] for b in blocks)
+    # equal widths give the bytes of the [c, M, K/c] layout
+    flat = np.concatenate([b.ravel() for b in fi.to_k_pieces(A, [4, 4, 4])])
+    assert np.array_equal(flat, fi.to_k_sliced(A, 3).ravel())
+
+
+@pytest.mark.parametrize("G,ms,widths,N,seed", [(2, 2, [6, 2], 3, 0), (4, 1, [1, 8, 3], 5, 1), (1, 3, [2, 1, 1, 4], 2, 2)])
+def test_2d_unequal_steps_exact_rational_brute_force(G, ms, widths, N, seed):
+    """As the equal-width brute force: small integers, every partial sum exact, so the slice-by-slice
+    result must equal the rational sums over the unsliced matrix whatever the widths."""
+    K = sum(widths)
+    rng = np.random.default_rng(seed)
+    A = bits_of(rng.integers(-8, 9, size=(G * ms, K)).astype(np.float32))
+    W = bits_of(rng.integers(-8, 9, size=(K, N)).astype(np.float32))
+    out = og.ag_gemm_2d(fi.to_k_pieces(A, widths), W, G)
+    for i in range(G * ms):
+        for j in range(N):
+            s = sum(Fraction(float(widen(A[i, k]))) * Fraction(float(widen(W[k, j]))) for k in range(K))
+            assert Fraction(float(out[i, j])) == s, (i, j)
+
+
+def test_2d_unequal_steps_pick_the_matching_weight_rows():
+    """One 1 per row of A in a known column: the result row must be that row of W. A slice paired with
+    rows of W that start at the equal-width offset instead of the running sum of widths fails."""
+    K, N, M, G = 16, 5, 8, 4
+    widths = [2, 9, 1, 4]
+    W = fi.make_weight(7, K, N)
+    cols = [(5 * i + 3) % K for i in range(M)]
+    A = np.zeros((M, K), dtype=np.float32)
+    A[np.arange(M), cols] = 1.0
+    out = og.ag_gemm_2d(fi.to_k_pieces(bits_of(A), widths), W, G)
+    assert np.array_equal(out, widen(W)[cols])

@@ -137,3 +137,19 @@ def test_column_pieces_tile_the_activation(G, c):
     assert [sch.piece_span_2d(M, K, G, c, i)[0] for i in by_shard] == [j * (M // G) for j in range(G) for _ in range(c)]
     p = sch.plan(M, G, c, sch.FINE_2D)
     assert p["arrival"] == arr and p["groups"] == [arr] and p["m"] == M // G and p["n_chunks"] == G * c
+
+
+@pytest.mark.parametrize("G,widths", [(4, [7, 1, 2]), (2, [3, 3]), (3, [1, 2, 4, 8])])
+def test_column_pieces_of_unequal_width_tile_the_activation(G, widths):
+    # the slices partition k in order whatever their widths; rows are still the shard's
+    M, K, c = G * 5, sum(widths), len(widths)
+    cover = [[0] * K for _ in range(M)]
+    for i in range(G * c):
+        r0, nr, k0, nk = sch.piece_span_2d(M, K, G, c, i, widths)
+        assert (r0, nr) == ((i % G) * (M // G), M // G) and nk == widths[i // G] and k0 == sum(widths[:i // G])
+        for r in range(r0, r0 + nr):
+            for k in range(k0, k0 + nk):
+                cover[r][k] += 1
+    assert all(v == 1 for row in cover for v in row)
+    if len(set(widths)) == 1:
+        assert all(sch.piece_span_2d(M, K, G, c, i, widths) == sch.piece_span_2d(M, K, G, c, i) for i in range(G * c))
