@@ -546,6 +546,21 @@ def test_2d_unequal_slices_match_oracle_and_serial_bits(gpu):
     assert np.array_equal(bits, base)
 
 
+def test_2d_more_slices_than_the_kernels_slice_table_holds(gpu):
+    # 80 slices of one k-tile each, then 70 of unequal width: the kernel keeps 64 boundaries in LDS and reads the rest from memory
+    G, ms, N = 2, 96, 72
+    K = 64 * 80
+    shards = fi.make_shards(33, G * ms, K, G)
+    W = fi.make_weight(33, K, N)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    check(base, og.ag_gemm(shards, W), "serial")
+    bits, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, 80, src="device", runs=2)
+    assert np.array_equal(bits, base) and st.n_copies == G * 80
+    widths = [64] * 60 + [128] * 10
+    bits, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, len(widths), src="device", widths=widths)
+    assert np.array_equal(bits, base) and st.n_copies == G * 70
+
+
 def test_2d_waits_for_late_and_reordered_slices(gpu):
     G, ms, K, N, c = 4, 256, 1024, 512, 4
     shards = fi.make_shards(24, G * ms, K, G)
