@@ -293,6 +293,22 @@ int ficco_plan_set_slice_widths(ficco_plan_t *plan, const int64_t *widths, int n
  * entries, either may be NULL; `cap` is their length). FICCO_ERR_ARG for other schedules. */
 int ficco_plan_slices(const ficco_plan_t *plan, int64_t *k0, int64_t *widths, int cap);
 
+/*
+ * Chain `plan` behind `after` for callers that keep the GPU fed without waiting on the host between
+ * steps (layer after layer of a model, a serving loop): from now on the transfers of every
+ * ficco_run(plan) start only when the latest ficco_run(after) enqueued before it has finished on
+ * the device, so the two plans may share A_dev (and the peers' buffers) while the host runs one
+ * step ahead. Two plans chained behind each other and run in turn give back-to-back steps with no
+ * host round trip in between: a run of a plan only waits (on the host) for that same plan's
+ * previous run. Runs of `after` end with a one-thread kernel on the compute stream that releases
+ * the dependency, and both plans must run on the same compute stream and on the copy-engine backend
+ * (ficco_run returns FICCO_ERR_ARG on the stream backend). `after` == NULL removes the dependency.
+ * Not for grouped plans or for a plan behind itself (FICCO_ERR_ARG). Either plan may be destroyed
+ * first; transfers parked behind a destroyed plan are let go. ficco_rs_reduce and graph launches
+ * take no part in it.
+ */
+int ficco_plan_chain(ficco_plan_t *plan, ficco_plan_t *after);
+
 /* Set an option; only before the plan's first use (FICCO_ERR_STATE afterwards), except
  * FICCO_OPT_MODE, FICCO_OPT_TIMING, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_HOLD_FLAGS, FICCO_OPT_REPEAT,
  * FICCO_OPT_TILE_GROUP and FICCO_OPT_TILE_COLUMN_LISTS, which may change between runs. */

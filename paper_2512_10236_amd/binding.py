@@ -65,7 +65,7 @@ class ficco_losses_t(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
-EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
+EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_chain", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
            "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
            "ficco_pick_schedule", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
@@ -94,6 +94,7 @@ def load():
     lib.ficco_plan_pieces.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.c_int]
     lib.ficco_plan_set_slice_widths.argtypes = [vp, C.POINTER(i64), C.c_int]
     lib.ficco_plan_slices.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.c_int]
+    lib.ficco_plan_chain.argtypes = [vp, vp]
     lib.ficco_plan_set.argtypes = [vp, C.c_int, i64]
     lib.ficco_plan_set_arrival.argtypes = [vp, i32p, C.c_int]
     lib.ficco_plan_info.argtypes = [vp, C.POINTER(ficco_plan_info_t)]
@@ -185,6 +186,11 @@ def ficco_plan_slices(plan):
     k0, w = (C.c_int64 * n)(), (C.c_int64 * n)()
     _ok(load().ficco_plan_slices(plan, k0, w, n), "ficco_plan_slices")
     return list(k0), list(w)
+
+
+def ficco_plan_chain(plan, after):
+    """Transfers of ``plan``'s runs wait (on the device) for the latest run of ``after``; ``None`` unchains."""
+    return _ok(load().ficco_plan_chain(plan, after), "ficco_plan_chain")
 
 
 def ficco_plan_set(plan, option, value):

@@ -14,6 +14,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -128,6 +129,23 @@ bool wait_signal(hsa_signal_t sgn, double limit_s)
     }
 }
 
+// What a plan shares with the plans chained behind it (ficco_plan_chain): two signals used in turn, armed
+// by the host when a run of the owning plan starts and released by a one-thread kernel at the end of that
+// run on the compute stream. The owner re-arms a signal two of its runs later, by which time it has
+// waited for the run in between, whose transfers could only start after every consumer of the older
+// signal had finished. Outlives the owner while a dependent still holds it.
+struct ChainLink {
+    hsa_signal_t free_sig[2]{};
+    uint64_t addr[2] = {0, 0};        // device-visible addresses of the value words
+    bool made = false, alive = true;
+    int last = -1;                    // signal armed by the owner's latest run (-1: none yet)
+    ~ChainLink()
+    {
+        if (made)
+            for (auto &sg : free_sig) (void)hsa_signal_destroy(sg);
+    }
+};
+
 }  // namespace
 
 struct ficco_plan_s {
@@ -140,6 +158,8 @@ struct ficco_plan_s {
     int packing = 0;                     // fused schedule with explicit Gather / Scatter copies
     int repeat = 1;                      // GEMM-only runs: launches enqueued this many times inside one bracket
     int tile_group = 0, tile_col_lists = 0;   // forced tile order (0 = chosen from the shape)
+    std::shared_ptr<ChainLink> link;        // released at the end of this plan's runs (plans are chained behind it)
+    std::shared_ptr<ChainLink> chain_from;  // this plan's transfers wait for the latest run of that link's owner
     std::vector<int64_t> slice_k0;       // column pieces: first column of each slice, then K (c + 1 entries)
     bool own_widths = false;             // slice_k0 was given by the caller (ficco_plan_set_slice_widths)
     // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
@@ -948,6 +968,44 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         }
     }
 
+    // Chained plans (ficco_plan_chain). Behind another plan: every transfer of this run also waits for the
+    // signal that plan's latest run releases when it ends. In front of others: this run arms one of its
+    // two signals now and releases it from the compute stream when everything it enqueues there is done;
+    // a run that fails half-way releases it from the host, so that nothing stays parked behind it.
+    hsa_signal_t chain_dep{};
+    bool has_chain_dep = false;
+    if (p->chain_from && p->chain_from->alive && p->chain_from->made && p->chain_from->last >= 0) {
+        chain_dep = p->chain_from->free_sig[p->chain_from->last];
+        has_chain_dep = true;
+    }
+    struct Disarm {
+        hsa_signal_t sg{};
+        bool on = false;
+        ~Disarm() { if (on) hsa_signal_store_screlease(sg, 0); }
+    } disarm;
+    uint64_t release_addr = 0;
+    if (p->link) {
+        ChainLink &L = *p->link;
+        if (!L.made) {
+            for (int i = 0; i < 2; ++i) {
+                if (make_signal(&L.free_sig[i]) != HSA_STATUS_SUCCESS) {
+                    if (i) (void)hsa_signal_destroy(L.free_sig[0]);
+                    return FICCO_ERR_ALLOC;
+                }
+            }
+            L.made = true;
+            for (int i = 0; i < 2; ++i)
+                if (!(L.addr[i] = signal_value_address(L.free_sig[i]))) return FICCO_ERR_HIP;   // needs signals the GPU can write
+        }
+        if (!L.addr[0] || !L.addr[1]) return FICCO_ERR_HIP;
+        const int idx = (L.last + 1) & 1;
+        hsa_signal_store_relaxed(L.free_sig[idx], 1);
+        L.last = idx;
+        disarm.sg = L.free_sig[idx];
+        disarm.on = true;
+        release_addr = L.addr[idx];
+    }
+
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
     // one piece: data copy, then the 4-byte flag copy behind it on the same engine
@@ -976,10 +1034,11 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             dst = (char *)peer_out[peer] + (size_t)(chunk % c) * p->m * row_bytes_c;
             if (!peer_dev[peer]) { dst_agent = ctx.cpu; force = false; }
         }
-        hsa_signal_t dep[2];
+        hsa_signal_t dep[3];
         int ndep = 0;
         if (chained && prev_chunk >= 0) dep[ndep++] = p->sig_data[prev_chunk];
         if (extra_dep) dep[ndep++] = (*extra_dep)[chunk];
+        if (has_chain_dep) dep[ndep++] = chain_dep;
         hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? dep : nullptr,
                                                               p->sig_data[chunk], engine, force);
         if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
@@ -1224,6 +1283,10 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
             if (!p->hold_flags) HIP_TRY(launch_wait_ready(gate, p->d_arrival, n, cs));
         }
     }
+    if (release_addr) {
+        HIP_TRY(launch_release_signal(release_addr, cs));
+        disarm.on = false;                               // the stream releases it from here on
+    }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
 
     p->last_had_copies = n_copies > 0;
@@ -1358,6 +1421,21 @@ int ficco_plan_pieces(const ficco_plan_t *p, int64_t *row0, int64_t *rows, int c
         if (row0) row0[i] = r0;
         if (rows) rows[i] = nr;
     }
+    return FICCO_OK;
+}
+
+int ficco_plan_chain(ficco_plan_t *p, ficco_plan_t *after)
+{
+    if (!p || p == after || p->grouped || (after && after->grouped)) return FICCO_ERR_ARG;
+    if (!after) {
+        p->chain_from.reset();
+        return FICCO_OK;
+    }
+    if (!after->link) {
+        after->link = std::shared_ptr<ChainLink>(new (std::nothrow) ChainLink());
+        if (!after->link) return FICCO_ERR_ALLOC;
+    }
+    p->chain_from = after->link;
     return FICCO_OK;
 }
 
@@ -1616,6 +1694,7 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         if (p->flag_write == 1) return FICCO_ERR_ARG;     // stream writes belong to the stream backend
         return run_engines(p, A_src, A_dev, C_dev, peer_out, cs, src_dev, peer_dev);
     }
+    if (p->link || p->chain_from) return FICCO_ERR_ARG;   // chained plans run on the copy engines
     p->last_engines = false;
     p->links = 1;
 
@@ -2283,6 +2362,12 @@ void ficco_destroy(ficco_plan_t *p)
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
     for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);      // nothing may stay parked behind a piece that never completed
+    if (p->link) {
+        // plans chained behind this one keep the link alive; their transfers no longer wait for it
+        p->link->alive = false;
+        if (p->link->made)
+            for (auto &sg : p->link->free_sig) hsa_signal_store_screlease(sg, 0);
+    }
     // transfers still in flight must not outlive their signals; one bound for all of them (a run that
     // failed half-way may have armed signals whose transfers were never submitted)
     const auto deadline = std::chrono::steady_clock::now() + std::chrono::seconds(5);

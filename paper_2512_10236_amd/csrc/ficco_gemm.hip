@@ -739,6 +739,11 @@ __global__ __launch_bounds__(64) void wait_ready_kernel(Gate gate, const int32_t
             if (!wait_ready(gate, chunks[i])) break;
 }
 
+__global__ __launch_bounds__(64) void release_signal_kernel(int64_t *value)
+{
+    if (threadIdx.x == 0) __hip_atomic_store(value, (int64_t)0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // W[K,N] -> Wt[N,K] through a 64x64 LDS tile (padded), 256 threads.
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__restrict__ W, uint16_t *__restrict__ Wt,
                                                           int64_t K, int64_t N)
@@ -955,6 +960,13 @@ int resident_grid_size(int tile, int device)
 hipError_t launch_wait_ready(const Gate &gate, const int32_t *chunks, int n, hipStream_t s)
 {
     hipLaunchKernelGGL(wait_ready_kernel, dim3(1), dim3(64), 0, s, gate, chunks, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_release_signal(uint64_t value_addr, hipStream_t s)
+{
+    if (!value_addr) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(release_signal_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<int64_t *>(value_addr));
     return hipGetLastError();
 }
 

@@ -196,6 +196,9 @@ hipError_t launch_resident(int tile, const ResidentLaunch &a, hipStream_t s);
 // One wavefront that waits (bounded) until the pieces chunks[0..n) are ready; used to join the
 // compute stream with copy-engine transfers when no GEMM consumes them.
 hipError_t launch_wait_ready(const Gate &gate, const int32_t *chunks, int n, hipStream_t s);
+// One thread stores 0 into the value word of a completion signal (device-visible address) once everything
+// before it on the stream has finished: transfers submitted with that signal as a dependency may start.
+hipError_t launch_release_signal(uint64_t value_addr, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_t N, hipStream_t s);
 int resident_grid_size(int tile, int device);
 

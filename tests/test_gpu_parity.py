@@ -561,6 +561,72 @@ def test_2d_more_slices_than_the_kernels_slice_table_holds(gpu):
     assert np.array_equal(bits, base) and st.n_copies == G * 70
 
 
+def test_chained_plans_take_turns_on_one_a_dev_without_host_waits(gpu):
+    """Two plans chained behind each other run in turn, the host never waiting between steps: they share A_dev,
+    read different sources and write different outputs, so a transfer of the next step that started before
+    the previous step's kernel had finished would put the wrong rows under that kernel."""
+    dev = gpu["dev"]
+    G, ms, K, N = 4, 512, 2048, 4096
+    M = G * ms
+    sh1, sh2 = fi.make_shards(41, M, K, G), fi.make_shards(42, M, K, G)
+    W = fi.make_weight(41, K, N)
+    base1, _, _ = run_ag(gpu, sh1, W, ficco.FICCO_SERIAL, 1)
+    base2, _, _ = run_ag(gpu, sh2, W, ficco.FICCO_SERIAL, 1)
+    rows = np.arange(0, M, 37)
+    check(base1[rows], og.ag_gemm_rows(sh1, W, rows), "serial, first source")
+    check(base2[rows], og.ag_gemm_rows(sh2, W, rows), "serial, second source")
+    widths = [1536, 512]
+    A1 = np.concatenate(sh1, 0)
+    A2 = np.concatenate([b.ravel() for b in fi.to_k_pieces(np.concatenate(sh2, 0), widths)]).reshape(M, K)
+    src1, src2 = as_i16(A1).to(dev), as_i16(A2).to(dev)
+    W_dev = as_i16(W).to(dev)
+    A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+    C1 = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    C2 = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    pa = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_PERSISTENT)
+    pb = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_2D)
+    try:
+        ficco.ficco_plan_set_slice_widths(pb, widths)
+        ficco.ficco_plan_chain(pa, pb)
+        ficco.ficco_plan_chain(pb, pa)
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_chain(pa, pa)
+        for it in range(8):
+            ficco.ficco_run(pa, src1, A_dev, W_dev, C1, None, gpu["cs"], gpu["xs"])
+            ficco.ficco_run(pb, src2, A_dev, W_dev, C2, None, gpu["cs"], gpu["xs"])
+            if it in (2, 5):                              # outputs of a step in the middle, while later steps are queued
+                sa, sb = ficco.ficco_query_stats(pa), ficco.ficco_query_stats(pb)
+                assert np.array_equal(C1.cpu().numpy().view(np.uint16), base1), f"step {it}: first plan"
+                assert np.array_equal(C2.cpu().numpy().view(np.uint16), base2), f"step {it}: second plan"
+                assert sa.n_copies == 2 * G and sb.n_copies == 2 * G and sa.n_launches == 1
+                C1.fill_(0x7FFF); C2.fill_(0x7FFF); torch.cuda.synchronize()
+        ficco.ficco_query_stats(pa); ficco.ficco_query_stats(pb)
+        assert np.array_equal(C1.cpu().numpy().view(np.uint16), base1)
+        assert np.array_equal(C2.cpu().numpy().view(np.uint16), base2)
+        # the plan in front is destroyed first: the one behind it runs on, with nothing left to wait for
+        ficco.ficco_destroy(pa)
+        pa = None
+        C2.fill_(0x7FFF)
+        ficco.ficco_run(pb, src2, A_dev, W_dev, C2, None, gpu["cs"], gpu["xs"])
+        ficco.ficco_query_stats(pb)
+        assert np.array_equal(C2.cpu().numpy().view(np.uint16), base2)
+        # chained plans need the copy engines
+        pc = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_FUSED)
+        try:
+            ficco.ficco_plan_set(pc, ficco.FICCO_OPT_COPY_BACKEND, ficco.FICCO_COPY_STREAM)
+            ficco.ficco_plan_chain(pc, pb)
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_run(pc, as_i16(A1).pin_memory(), A_dev, W_dev, C1, None, gpu["cs"], gpu["xs"])
+            ficco.ficco_plan_chain(pc, None)
+        finally:
+            ficco.ficco_destroy(pc)
+    finally:
+        if pa is not None:
+            ficco.ficco_destroy(pa)
+        ficco.ficco_destroy(pb)
+    torch.cuda.synchronize()
+
+
 def test_2d_waits_for_late_and_reordered_slices(gpu):
     G, ms, K, N, c = 4, 256, 1024, 512, 4
     shards = fi.make_shards(24, G * ms, K, G)

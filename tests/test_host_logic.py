@@ -57,6 +57,23 @@ def test_plan_lists_match_oracle(G, c, lib_s, ora_s, order):
     assert info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
 
 
+def test_chaining_takes_two_different_dense_plans():
+    a = ficco.ficco_plan(512, 128, 8, 4, 2, ficco.FICCO_FINE_PERSISTENT)
+    b = ficco.ficco_plan(512, 128, 8, 4, 2, ficco.FICCO_FINE_2D)
+    g = ficco.ficco_plan_grouped(128, 8, [[3, 4], [5, 6]], 1, ficco.FICCO_FINE_PERSISTENT)
+    try:
+        ficco.ficco_plan_chain(a, b)
+        ficco.ficco_plan_chain(b, a)
+        ficco.ficco_plan_chain(a, None)
+        for plan, after in ((a, a), (a, g), (g, a)):
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_plan_chain(plan, after)
+    finally:
+        ficco.ficco_destroy(b)          # the plan in front goes first: the link outlives it
+        ficco.ficco_destroy(a)
+        ficco.ficco_destroy(g)
+
+
 def test_2d_default_slices_are_as_equal_as_whole_k_tiles_allow():
     # 11 k-tiles in 4 slices: 3, 3, 3, 2 tiles
     plan = ficco.ficco_plan(64, 64 * 11, 8, 4, 4, ficco.FICCO_FINE_2D)
