@@ -332,9 +332,16 @@ def main() -> int:
         screen = {}
         for i, (s, c) in enumerate(cands):
             plan = make(s, c)
-            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.0)
+            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.02)
             F.ficco_destroy(plan)
-        best = min(screen, key=screen.get)
+        # the two best of the screen are timed in full; the faster one is the schedule of this run
+        finalists = sorted(screen, key=screen.get)[:2]
+        full = {}
+        for sc in finalists:
+            p_f = make(*sc)
+            full[sc] = timed_steps(p_f, source(tag, *sc), args.steps, args.warmup)
+            F.ficco_destroy(p_f)
+        best = min(full, key=full.get)
         plan = make(*best)
         ms_synced = timed_steps(plan, source(tag, *best), args.steps, args.warmup)
         # The step time that counts has no host round trip between steps (all-gather direction, where the
@@ -389,7 +396,8 @@ def main() -> int:
                    copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
                    ms_local_shard_resident=ms_het,
                    best_row_pieces=(label(rows_best) if rows_best else None), ms_best_row_pieces=ms_rows,
-                   screen={label(k): round(v, 4) for k, v in screen.items()})
+                   screen={label(k): round(v, 4) for k, v in screen.items()},
+                   finalists={label(k): round(v, 4) for k, v in full.items()})
         return res, best
 
     best = None

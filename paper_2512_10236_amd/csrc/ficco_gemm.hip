@@ -622,13 +622,6 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
     const int row_tiles = (r.M + T::BM - 1) / T::BM;
     const ListGrid lists(row_tiles, tiles_n, r.col_lists, r.group);
     auto total_of = [&](int x) { return lists.total(x); };
-    // The slice boundaries are read once per workgroup into LDS (a load from memory per slice and tile would
-    // put its latency in front of every slice); plans with more slices than the table holds read the rest
-    // from memory.
-    constexpr int kK0Lds = 64;
-    __shared__ int32_t s_k0[kK0Lds + 1];
-    for (int i = threadIdx.x; i <= min(r.slices, kK0Lds); i += 256) s_k0[i] = r.k0[i];
-    auto k0_of = [&](int i) { return __builtin_amdgcn_readfirstlane(i <= kK0Lds ? s_k0[i] : r.k0[i]); };
 
     if (threadIdx.x == 0) s_walk = TileWalk{0, 1, 0, 0, -1, 0};
     int have_drawn = 0;
@@ -640,7 +633,7 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
             have_drawn = 0;
             s_walk = w;
         }
-        __syncthreads();                   // also publishes s_k0 before its first use
+        __syncthreads();
         const int x = s_walk.x, t = s_walk.t;
         if (x < 0) break;
         int tm, tn;
@@ -653,7 +646,9 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
         TileAcc<T> ta;
         tile_zero(ta);
         int ok = 1;
+        int kb = r.k0[0];                  // uniform (scalar) loads; the next boundary is fetched before the wait for the slice
         for (int sl = 0; sl < r.slices && ok; ++sl) {
+            const int ke = r.k0[sl + 1];
             if (r.gated) {
                 if (threadIdx.x == 0) {
                     int o = 1;
@@ -665,10 +660,11 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
                 __syncthreads();
             }
             if (ok) {
-                const int kb = k0_of(sl), kw = k0_of(sl + 1) - kb;        // the slice's columns
+                const int kw = ke - kb;                                   // the slice's columns: [kb, ke)
                 tile_accumulate<T>(ta, a.A + (int64_t)r.M * kb + row0 * kw, rows_valid,
                                    a.Wt + (int64_t)col0 * a.K + kb, cols_valid, kw, a.K, kw, smem);
             }
+            kb = ke;
         }
         if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
         if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
