@@ -2,8 +2,12 @@
 """Benchmark of the all-gather -> GEMM pair on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch of synthetic input: plan (built once),
-the piece transfers, the ready flags / events, the piece GEMMs and the statistics query.
-Prints ONE JSON line. Only one GPU is used; --gpus > 1 exits.
+the piece transfers, the ready flags / signals and the piece GEMMs. In the all-gather direction the K
+timed steps are taken in turn by two plans chained behind each other (ficco_plan_chain): a step's
+transfers start on the device when the previous step's kernel has finished, the host never blocks
+between steps, and both sides of the K steps are synchronised (the figure with a blocking statistics
+query after every step is reported beside it). Prints ONE JSON line. Only one GPU is used; --gpus > 1
+exits.
 
 Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192 K=4096 N=768):
   pair      - K timed steps of the best finer-grain schedule, source shards resident in HBM

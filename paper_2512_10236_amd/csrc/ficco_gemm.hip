@@ -735,9 +735,12 @@ __global__ __launch_bounds__(64) void wait_ready_kernel(Gate gate, const int32_t
             if (!wait_ready(gate, chunks[i])) break;
 }
 
+// Nothing is published through the signal: what it orders is that the kernels before this one on the
+// stream have finished reading A, which stream order has settled when this kernel starts. A relaxed store
+// therefore does, and spares the cache write-back a release at system scope would add.
 __global__ __launch_bounds__(64) void release_signal_kernel(int64_t *value)
 {
-    if (threadIdx.x == 0) __hip_atomic_store(value, (int64_t)0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (threadIdx.x == 0) __hip_atomic_store(value, (int64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // W[K,N] -> Wt[N,K] through a 64x64 LDS tile (padded), 256 threads.
