@@ -297,15 +297,15 @@ int ficco_plan_slices(const ficco_plan_t *plan, int64_t *k0, int64_t *widths, in
  * Chain `plan` behind `after` for callers that keep the GPU fed without waiting on the host between
  * steps (layer after layer of a model, a serving loop): from now on the transfers of every
  * ficco_run(plan) start only when the latest ficco_run(after) enqueued before it has finished on
- * the device, so the two plans may share A_dev (and the peers' buffers) while the host runs one
- * step ahead. Two plans chained behind each other and run in turn give back-to-back steps with no
- * host round trip in between: a run of a plan only waits (on the host) for that same plan's
- * previous run. Runs of `after` end with a one-thread kernel on the compute stream that releases
- * the dependency, and both plans must run on the same compute stream and on the copy-engine backend
- * (ficco_run returns FICCO_ERR_ARG on the stream backend). `after` == NULL removes the dependency.
- * Not for grouped plans or for a plan behind itself (FICCO_ERR_ARG). Either plan may be destroyed
- * first; transfers parked behind a destroyed plan are let go. ficco_rs_reduce and graph launches
- * take no part in it.
+ * the device, so the two plans may share A_dev while the host runs one step ahead. Two plans
+ * chained behind each other and run in turn give back-to-back steps with no host round trip in
+ * between: a run of a plan only waits (on the host) for that same plan's previous run. Runs of
+ * `after` end with a one-thread kernel on the compute stream that releases the dependency. Both
+ * plans must run on the same compute stream and on the copy-engine backend, and `plan` in the
+ * all-gather direction (ficco_run returns FICCO_ERR_ARG otherwise). `after` == NULL removes the
+ * dependency. Not for grouped plans or for a plan behind itself (FICCO_ERR_ARG). Either plan may
+ * be destroyed first; transfers parked behind a destroyed plan are let go. ficco_rs_reduce and
+ * graph launches take no part in it.
  */
 int ficco_plan_chain(ficco_plan_t *plan, ficco_plan_t *after);
 

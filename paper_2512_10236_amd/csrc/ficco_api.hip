@@ -973,6 +973,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     // a run that fails half-way releases it from the host, so that nothing stays parked behind it.
     hsa_signal_t chain_dep{};
     bool has_chain_dep = false;
+    if (rs && p->chain_from) return FICCO_ERR_ARG;       // defined for the transfers into A_dev only
     if (p->chain_from && p->chain_from->alive && p->chain_from->made && p->chain_from->last >= 0) {
         chain_dep = p->chain_from->free_sig[p->chain_from->last];
         has_chain_dep = true;

@@ -620,6 +620,16 @@ def test_chained_plans_take_turns_on_one_a_dev_without_host_waits(gpu):
             ficco.ficco_plan_chain(pc, None)
         finally:
             ficco.ficco_destroy(pc)
+        # ... and are defined for the transfers into A_dev only
+        pr = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_FUSED)
+        try:
+            ficco.ficco_plan_set(pr, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+            ficco.ficco_plan_chain(pr, pb)
+            peers = [torch.zeros((ms, N), dtype=torch.int16, device=dev) for _ in range(G)]
+            with pytest.raises(ficco.FiccoError):
+                ficco.ficco_run(pr, None, A_dev, W_dev, C1, peers, gpu["cs"], gpu["xs"])
+        finally:
+            ficco.ficco_destroy(pr)
     finally:
         if pa is not None:
             ficco.ficco_destroy(pa)
