@@ -300,7 +300,8 @@ int ficco_plan_slices(const ficco_plan_t *plan, int64_t *k0, int64_t *widths, in
  * the device, so the two plans may share A_dev while the host runs one step ahead. Two plans
  * chained behind each other and run in turn give back-to-back steps with no host round trip in
  * between: a run of a plan only waits (on the host) for that same plan's previous run. Runs of
- * `after` end with a one-thread kernel on the compute stream that releases the dependency. Both
+ * `after` release the dependency when they end (from the resident kernel's last workgroup, or from
+ * a one-thread kernel on the compute stream). Both
  * plans must run on the same compute stream and on the copy-engine backend, and `plan` in the
  * all-gather direction (ficco_run returns FICCO_ERR_ARG otherwise). `after` == NULL removes the
  * dependency. Not for grouped plans or for a plan behind itself (FICCO_ERR_ARG). Either plan may

@@ -224,6 +224,7 @@ struct ficco_plan_s {
     // run state
     uint32_t run_index = 0;
     uint32_t ticket_total[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // tickets drawn from each list by all resident runs so far
+    uint32_t exit_total = 0;                               // workgroups counted out by all runs that released a chain signal in the kernel
     bool last_had_copies = false, last_had_gemm = false, last_timing = false;
     int64_t last_copy_bytes = 0;
     int last_n_copies = 0, last_n_launches = 0;
@@ -465,8 +466,9 @@ int finalize(ficco_plan_t *p)
     // memory is coherent at kernel boundaries only).
     if (hipExtMallocWithFlags((void **)&p->d_words, words * 4, hipDeviceMallocFinegrained) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
     HIP_TRY(hipMemset(p->d_words, 0, words * 4));
-    if (hipMalloc((void **)&p->d_ticket_mem, kTicketLists * kFlagStrideWords * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
-    HIP_TRY(hipMemset(p->d_ticket_mem, 0, kTicketLists * kFlagStrideWords * 4));
+    // ticket counters of the lists, then the counter of workgroups that have left a run (chained plans)
+    if (hipMalloc((void **)&p->d_ticket_mem, (kTicketLists + 1) * kFlagStrideWords * 4) != hipSuccess) { release(p); return FICCO_ERR_ALLOC; }
+    HIP_TRY(hipMemset(p->d_ticket_mem, 0, (kTicketLists + 1) * kFlagStrideWords * 4));
     HIP_TRY(hipDeviceSynchronize());
     p->d_flags = p->d_words;
     p->d_ticket = p->d_ticket_mem;
@@ -688,9 +690,13 @@ inline Extent piece_extent(const ficco_plan_t *p, int chunk)
 
 // One resident launch of the K-sliced schedule: every tile owns its part of C for the whole k range
 // and waits, slice by slice, for the column pieces of the shards its rows come from.
-int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const void *A_dev, void *C_dev, hipStream_t cs)
+int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const void *A_dev, void *C_dev, hipStream_t cs,
+              uint64_t release_addr = 0)
 {
     Resident2DLaunch r{};
+    if (release_addr)
+        r.leave = RunExit{p->d_ticket_mem + (size_t)kTicketLists * kFlagStrideWords, p->exit_total + (uint32_t)grid,
+                          reinterpret_cast<int64_t *>(release_addr)};
     r.g.A = (const uint16_t *)A_dev;
     r.g.Wt = p->d_wt;
     r.g.C = (uint16_t *)C_dev;
@@ -719,6 +725,7 @@ int launch_2d(ficco_plan_t *p, const Gate &gate, bool gated, int grid, const voi
         p->ticket_total[x] += resident_list_draws(resident_list_tiles(row_tiles, tn, x, r.col_lists), grid, x);
     }
     HIP_TRY(launch_resident2d(p->tile, r, cs));
+    if (release_addr) p->exit_total += (uint32_t)grid;      // counted only once the workgroups are on their way
     return FICCO_OK;
 }
 
@@ -1078,6 +1085,9 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     // span, and a run that is one resident launch and nothing else (all-gather pair) ends its span with the
     // end event.
     const bool span_is_run = !rs && !packed && is_resident(p) && do_gemm && dependent && !timing;
+    // ... and in such a run the kernel itself lets the transfers of a plan chained behind this one go (its last
+    // workgroup out); otherwise a one-thread kernel at the end of the run does
+    const bool release_in_kernel = release_addr != 0 && span_is_run;
     HIP_TRY(hipEventRecord(p->ev_begin, cs));
     if (packed) {
         // ---- the fused schedule as the paper runs it with an unmodified GEMM (Sec. V-A): the G pieces of a
@@ -1169,11 +1179,14 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (do_gemm) {
             if (is_2d(p)) {
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
-                if ((rc = launch_2d(p, gate, dependent, p->resident_grid, A_dev, C_dev, cs))) return rc;
+                if ((rc = launch_2d(p, gate, dependent, p->resident_grid, A_dev, C_dev, cs, release_in_kernel ? release_addr : 0))) return rc;
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
                 ++n_launches;
             } else if (p->schedule == FICCO_FINE_PERSISTENT) {
                 ResidentLaunch r{};
+                if (release_in_kernel)
+                    r.leave = RunExit{p->d_ticket_mem + (size_t)kTicketLists * kFlagStrideWords, p->exit_total + (uint32_t)p->resident_grid,
+                                      reinterpret_cast<int64_t *>(release_addr)};
                 Group all{0, n};
                 r.g = make_launch(p, all, A_dev, C_dev);
                 r.g.block_row0 = nullptr; r.g.row0 = 0; r.g.n_blocks = n; r.g.rows_per_block = (int32_t)p->m;
@@ -1196,6 +1209,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
                 }
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));
                 HIP_TRY(launch_resident(p->tile, r, cs));
+                if (release_in_kernel) p->exit_total += (uint32_t)p->resident_grid;
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_e[0], cs));
                 ++n_launches;
             } else {
@@ -1288,7 +1302,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         }
     }
     if (release_addr) {
-        HIP_TRY(launch_release_signal(release_addr, cs));
+        if (!release_in_kernel) HIP_TRY(launch_release_signal(release_addr, cs));
         disarm.on = false;                               // the stream releases it from here on
     }
     HIP_TRY(hipEventRecord(p->ev_end, cs));

@@ -521,6 +521,18 @@ struct ListGrid {
 };
 static_assert(kTicketLists == 8, "ListGrid shifts assume 8 lists");
 
+// A workgroup of a resident kernel has read everything it will read of A when it gets here (the data went
+// through the MFMAs before its last tile was stored), so the last one out may let the next run's transfers
+// into A start.
+__device__ __forceinline__ void leave_run(const RunExit &e)
+{
+    if (e.release_value && threadIdx.x == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(e.count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (before + 1u == e.target)
+            __hip_atomic_store(e.release_value, (int64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
 // STREAM_OUT: the GEMM -> reduce-scatter form (r.done_count set), a separate instantiation so that its
 // epilogue and bookkeeping cost the all-gather form no registers.
 template <class T, bool STREAM_OUT>
@@ -606,6 +618,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
         __syncthreads();
         count_stored();
     }
+    leave_run(r.leave);
 }
 
 // Column-piece variant of the resident kernel (the 2D communication shape of Sec. V-A, chosen when
@@ -670,6 +683,7 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
         if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
         __syncthreads();                   // s_walk / s_ok / LDS stages are reused
     }
+    leave_run(r.leave);
 }
 
 // Expert-parallel variant of the resident kernel (all-to-all token dispatch before the expert layers,

@@ -121,6 +121,16 @@ struct GemmLaunch {
     int32_t n_wait;
 };
 
+// What a resident kernel does on its way out when other plans' transfers wait for the end of this run
+// (chained plans): every workgroup counts itself out, and the one that brings the counter (device,
+// never reset) to `target` stores 0 into the value word of the signal those transfers depend on.
+// release_value == nullptr: nothing to do.
+struct RunExit {
+    uint32_t *count;
+    uint32_t target;
+    int64_t *release_value;
+};
+
 // The resident kernel: tiles are taken from a ticket counter in arrival order; the tiles of the
 // piece issued p-th wait until that piece is ready (g.gate).
 struct ResidentLaunch {
@@ -138,6 +148,7 @@ struct ResidentLaunch {
     uint32_t *done_count;         // device, one counter per chunk id, never reset: a run adds tiles_per_chunk to each
     const uint64_t *done_sig;     // device table: address of the value word of each chunk's dependency signal
     int32_t tiles_per_chunk;      // row tiles per piece x column tiles
+    RunExit leave;
 };
 
 // The resident kernel for column (K) pieces: A is kept in K-sliced layout, slice after slice, slice s
@@ -154,6 +165,7 @@ struct Resident2DLaunch {
     int32_t grid;
     int32_t gated;                // 0: operands resident, no waiting
     int32_t group, col_lists;     // tile order, as in ResidentLaunch
+    RunExit leave;
 };
 
 // One receiver-side reduction (see ficco_reduce.hip): `in` is the landing buffer [G][rows][N] of the
