@@ -637,6 +637,40 @@ def test_chained_plans_take_turns_on_one_a_dev_without_host_waits(gpu):
     torch.cuda.synchronize()
 
 
+def test_chained_plan_is_let_go_when_the_run_in_front_gives_up(gpu):
+    """The plan in front never sees its flags (forced from the host) and its kernel gives up after the spin
+    limit; the run still ends by releasing the plan behind it, whose result must be complete and right."""
+    dev = gpu["dev"]
+    shards, W = fi.config_inputs("cfg1_tiny")
+    A = np.concatenate(shards, 0)
+    M, K = A.shape
+    N, G = W.shape[1], len(shards)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    src, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+    A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+    C1 = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    C2 = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+    for sched in (ficco.FICCO_FINE_PERSISTENT, ficco.FICCO_FINE_FUSED):     # released by the kernel itself / by the release kernel
+        pa = ficco.ficco_plan(M, K, N, G, 2, sched)
+        pb = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_PERSISTENT)
+        try:
+            ficco.ficco_plan_set(pa, ficco.FICCO_OPT_HOLD_FLAGS, 1)
+            ficco.ficco_plan_set(pa, ficco.FICCO_OPT_SPIN_LIMIT_US, 2000)
+            ficco.ficco_plan_chain(pb, pa)
+            C2.fill_(0x7FFF)
+            torch.cuda.synchronize()
+            ficco.ficco_run(pa, src, A_dev, W_dev, C1, None, gpu["cs"], gpu["xs"])
+            ficco.ficco_run(pb, src, A_dev, W_dev, C2, None, gpu["cs"], gpu["xs"])
+            sa = ficco.ficco_query_stats(pa, allow_timeout=True)
+            sb = ficco.ficco_query_stats(pb)
+            assert sa.timed_out == 1 and sb.timed_out == 0
+            assert np.array_equal(C2.cpu().numpy().view(np.uint16), base), f"plan behind a run that gave up (schedule {sched})"
+        finally:
+            ficco.ficco_destroy(pa)
+            ficco.ficco_destroy(pb)
+    torch.cuda.synchronize()
+
+
 def test_2d_waits_for_late_and_reordered_slices(gpu):
     G, ms, K, N, c = 4, 256, 1024, 512, 4
     shards = fi.make_shards(24, G * ms, K, G)
