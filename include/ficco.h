@@ -304,8 +304,8 @@ int ficco_plan_slices(const ficco_plan_t *plan, int64_t *k0, int64_t *widths, in
  * a one-thread kernel on the compute stream). Both
  * plans must run on the same compute stream and on the copy-engine backend, and `plan` in the
  * all-gather direction (ficco_run returns FICCO_ERR_ARG otherwise). `after` == NULL removes the
- * dependency. Not for grouped plans or for a plan behind itself (FICCO_ERR_ARG). Either plan may
- * be destroyed first; transfers parked behind a destroyed plan are let go. ficco_rs_reduce and
+ * dependency. A plan cannot be chained behind itself (FICCO_ERR_ARG). Either plan may be
+ * destroyed first; transfers parked behind a destroyed plan are let go. ficco_rs_reduce and
  * graph launches take no part in it.
  */
 int ficco_plan_chain(ficco_plan_t *plan, ficco_plan_t *after);

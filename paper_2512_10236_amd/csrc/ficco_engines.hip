@@ -219,6 +219,48 @@ int engines_prepare(ficco_plan_t *p, bool touches_host, std::vector<int> &eng, i
     return FICCO_OK;
 }
 
+// Chained plans (ficco_plan_chain), one run's share. Behind another plan: every transfer of this run also
+// waits for the signal (dep) that plan's latest run releases when it ends. In front of others: the run
+// arms one of its two signals now and has it released from the compute stream (release_addr) when
+// everything it enqueues there is done; until the run has handed that over, a return - a run that fails
+// half-way - releases the signal from the host, so that nothing stays parked behind it.
+struct ChainScope {
+    hsa_signal_t dep{};
+    bool has_dep = false;
+    uint64_t release_addr = 0;
+    hsa_signal_t armed{};
+    bool on = false;
+    int begin(ficco_plan_t *p)
+    {
+        if (p->chain_from && p->chain_from->alive && p->chain_from->made && p->chain_from->last >= 0) {
+            dep = p->chain_from->free_sig[p->chain_from->last];
+            has_dep = true;
+        }
+        if (!p->link) return FICCO_OK;
+        ChainLink &L = *p->link;
+        if (!L.made) {
+            for (int i = 0; i < 2; ++i) {
+                if (make_signal(&L.free_sig[i]) != HSA_STATUS_SUCCESS) {
+                    if (i) (void)hsa_signal_destroy(L.free_sig[0]);
+                    return FICCO_ERR_ALLOC;
+                }
+            }
+            L.made = true;
+            for (int i = 0; i < 2; ++i) L.addr[i] = signal_value_address(L.free_sig[i]);
+        }
+        if (!L.addr[0] || !L.addr[1]) return FICCO_ERR_HIP;      // needs signals the GPU can write
+        const int idx = (L.last + 1) & 1;
+        hsa_signal_store_relaxed(L.free_sig[idx], 1);
+        L.last = idx;
+        armed = L.free_sig[idx];
+        on = true;
+        release_addr = L.addr[idx];
+        return FICCO_OK;
+    }
+    void handed_over() { on = false; }
+    ~ChainScope() { if (on) hsa_signal_store_screlease(armed, 0); }
+};
+
 // One run of an expert-parallel plan: the grouped kernel is enqueued first and waits per tile for the
 // pieces that cover its rows; piece (e, s, j) travels on peer j's link.
 int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hipStream_t cs, bool src_dev)
@@ -248,6 +290,8 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
         hsa_signal_store_relaxed(p->sig_data[i], (do_copy && p->piece_nrows[i] > 0) ? 1 : 0);
         hsa_signal_store_relaxed(p->sig_flag[i], 0);
     }
+    ChainScope chain;
+    if ((rc = chain.begin(p))) return rc;
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
     HIP_TRY(hipEventRecord(p->ev_begin, cs));          // also the start of the GEMM span on this backend
@@ -281,6 +325,10 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
     HIP_TRY(hipEventRecord(p->ev_gemm_last, cs));
     if (do_copy && (!dependent || !do_gemm) && !p->hold_flags)
         HIP_TRY(launch_wait_ready(gate, p->d_arrival, n, cs));       // nothing else on the stream consumes the flags
+    if (chain.release_addr) {
+        HIP_TRY(launch_release_signal(chain.release_addr, cs));
+        chain.handed_over();                             // the stream releases it from here on
+    }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
 
     const bool chained = p->schedule == FICCO_SHARD || (p->schedule != FICCO_SERIAL && p->order == FICCO_ORDER_SHARD_MAJOR);
@@ -291,11 +339,12 @@ int run_grouped(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, hi
         const size_t off = (size_t)p->piece_row0[chunk] * p->K * 2, bytes = (size_t)p->piece_nrows[chunk] * p->K * 2;
         hsa_status_t st;
         if (bytes) {
-            hsa_signal_t dep{};
+            hsa_signal_t dep[2];
             int ndep = 0;
-            if (chained && prev_chunk >= 0) { dep = p->sig_data[prev_chunk]; ndep = 1; }
+            if (chained && prev_chunk >= 0) dep[ndep++] = p->sig_data[prev_chunk];
+            if (chain.has_dep) dep[ndep++] = chain.dep;
             st = hsa_amd_memory_async_copy_on_engine((char *)A_dev + off, ctx.gpu, (const char *)A_src + off, src_dev ? ctx.gpu : ctx.cpu, bytes,
-                                                     ndep, ndep ? &dep : nullptr, p->sig_data[chunk], engine, src_dev);
+                                                     ndep, ndep ? dep : nullptr, p->sig_data[chunk], engine, src_dev);
             if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
             prev_chunk = chunk;
             ++n_copies;
@@ -381,44 +430,12 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         }
     }
 
-    // Chained plans (ficco_plan_chain). Behind another plan: every transfer of this run also waits for the
-    // signal that plan's latest run releases when it ends. In front of others: this run arms one of its
-    // two signals now and releases it from the compute stream when everything it enqueues there is done;
-    // a run that fails half-way releases it from the host, so that nothing stays parked behind it.
-    hsa_signal_t chain_dep{};
-    bool has_chain_dep = false;
-    if (rs && p->chain_from) return FICCO_ERR_ARG;       // defined for the transfers into A_dev only
-    if (p->chain_from && p->chain_from->alive && p->chain_from->made && p->chain_from->last >= 0) {
-        chain_dep = p->chain_from->free_sig[p->chain_from->last];
-        has_chain_dep = true;
-    }
-    struct Disarm {
-        hsa_signal_t sg{};
-        bool on = false;
-        ~Disarm() { if (on) hsa_signal_store_screlease(sg, 0); }
-    } disarm;
-    uint64_t release_addr = 0;
-    if (p->link) {
-        ChainLink &L = *p->link;
-        if (!L.made) {
-            for (int i = 0; i < 2; ++i) {
-                if (make_signal(&L.free_sig[i]) != HSA_STATUS_SUCCESS) {
-                    if (i) (void)hsa_signal_destroy(L.free_sig[0]);
-                    return FICCO_ERR_ALLOC;
-                }
-            }
-            L.made = true;
-            for (int i = 0; i < 2; ++i)
-                if (!(L.addr[i] = signal_value_address(L.free_sig[i]))) return FICCO_ERR_HIP;   // needs signals the GPU can write
-        }
-        if (!L.addr[0] || !L.addr[1]) return FICCO_ERR_HIP;
-        const int idx = (L.last + 1) & 1;
-        hsa_signal_store_relaxed(L.free_sig[idx], 1);
-        L.last = idx;
-        disarm.sg = L.free_sig[idx];
-        disarm.on = true;
-        release_addr = L.addr[idx];
-    }
+    if (rs && p->chain_from) return FICCO_ERR_ARG;       // chaining is defined for the transfers into A_dev only
+    ChainScope chain;
+    if ((rc = chain.begin(p))) return rc;
+    const hsa_signal_t chain_dep = chain.dep;
+    const bool has_chain_dep = chain.has_dep;
+    const uint64_t release_addr = chain.release_addr;
 
     int n_copies = 0, n_launches = 0;
     int64_t copy_bytes = 0;
@@ -710,7 +727,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     }
     if (release_addr) {
         if (!release_in_kernel) HIP_TRY(launch_release_signal(release_addr, cs));
-        disarm.on = false;                               // the stream releases it from here on
+        chain.handed_over();                             // the stream releases it from here on
     }
     HIP_TRY(hipEventRecord(p->ev_end, cs));
 

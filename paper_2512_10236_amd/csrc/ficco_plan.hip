@@ -559,7 +559,7 @@ int ficco_plan_pieces(const ficco_plan_t *p, int64_t *row0, int64_t *rows, int c
 
 int ficco_plan_chain(ficco_plan_t *p, ficco_plan_t *after)
 {
-    if (!p || p == after || p->grouped || (after && after->grouped)) return FICCO_ERR_ARG;
+    if (!p || p == after) return FICCO_ERR_ARG;
     if (!after) {
         p->chain_from.reset();
         return FICCO_OK;

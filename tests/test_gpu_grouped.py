@@ -91,6 +91,44 @@ def test_grouped_matches_oracle_in_every_schedule(gpu, rows):
             assert st.flops == 2 * A.shape[0] * N * K
 
 
+def test_chained_grouped_plans_take_turns_on_one_a_dev(gpu):
+    """Two expert-parallel plans with different token tables, sources and outputs, chained behind each other on
+    one A_dev (sized for the larger), run in turn without host waits: the dispatch of the next step may only
+    start when the previous step's kernel has finished."""
+    dev = gpu["dev"]
+    K, N = 1024, 2048
+    rows1 = [[300, 211], [512, 40], [0, 700], [129, 256]]
+    rows2 = [[700, 5], [64, 333], [257, 1], [90, 402]]
+    A1, W, en1 = make_case(51, rows1, K, N)
+    A2, _, en2 = make_case(52, rows2, K, N)
+    ref1, ref2 = ogr.grouped_gemm(A1, W, en1), ogr.grouped_gemm(A2, W, en2)
+    base1, _, _ = run_grouped(gpu, A1, W, rows1, 1, ficco.FICCO_SERIAL)
+    base2, _, _ = run_grouped(gpu, A2, W, rows2, 1, ficco.FICCO_SERIAL)
+    check(base1, ref1, "serial, first table")
+    check(base2, ref2, "serial, second table")
+    M1, M2 = A1.shape[0], A2.shape[0]
+    src1, src2, W_dev = as_i16(A1).to(dev), as_i16(A2).to(dev), as_i16(W).to(dev)
+    A_dev = torch.full((max(M1, M2), K), NAN_BF16, dtype=torch.int16, device=dev)
+    C1 = torch.full((M1, N), 0x7FFF, dtype=torch.int16, device=dev)
+    C2 = torch.full((M2, N), 0x7FFF, dtype=torch.int16, device=dev)
+    pa = ficco.ficco_plan_grouped(K, N, rows1, 2, ficco.FICCO_FINE_PERSISTENT)
+    pb = ficco.ficco_plan_grouped(K, N, rows2, 3, ficco.FICCO_FINE_PERSISTENT)
+    try:
+        ficco.ficco_plan_chain(pa, pb)
+        ficco.ficco_plan_chain(pb, pa)
+        for it in range(6):
+            ficco.ficco_run(pa, src1, A_dev, W_dev, C1, None, gpu["cs"], gpu["xs"])
+            ficco.ficco_run(pb, src2, A_dev, W_dev, C2, None, gpu["cs"], gpu["xs"])
+        ficco.ficco_query_stats(pa)
+        ficco.ficco_query_stats(pb)
+        assert np.array_equal(C1.cpu().numpy().view(np.uint16), base1)
+        assert np.array_equal(C2.cpu().numpy().view(np.uint16), base2)
+    finally:
+        ficco.ficco_destroy(pa)
+        ficco.ficco_destroy(pb)
+    torch.cuda.synchronize()
+
+
 def test_grouped_experts_use_their_own_weights(gpu):
     # W_e = (e + 1) * identity: every output row is its input row times its expert's factor, exactly
     K = N = 128

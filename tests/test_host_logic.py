@@ -57,7 +57,7 @@ def test_plan_lists_match_oracle(G, c, lib_s, ora_s, order):
     assert info.chunk_rows == ref["m"] and info.n_chunks == ref["n_chunks"]
 
 
-def test_chaining_takes_two_different_dense_plans():
+def test_chaining_takes_two_different_plans():
     a = ficco.ficco_plan(512, 128, 8, 4, 2, ficco.FICCO_FINE_PERSISTENT)
     b = ficco.ficco_plan(512, 128, 8, 4, 2, ficco.FICCO_FINE_2D)
     g = ficco.ficco_plan_grouped(128, 8, [[3, 4], [5, 6]], 1, ficco.FICCO_FINE_PERSISTENT)
@@ -65,9 +65,11 @@ def test_chaining_takes_two_different_dense_plans():
         ficco.ficco_plan_chain(a, b)
         ficco.ficco_plan_chain(b, a)
         ficco.ficco_plan_chain(a, None)
-        for plan, after in ((a, a), (a, g), (g, a)):
+        ficco.ficco_plan_chain(g, a)          # grouped plans chain like the others
+        ficco.ficco_plan_chain(g, None)
+        for plan in (a, g):
             with pytest.raises(ficco.FiccoError):
-                ficco.ficco_plan_chain(plan, after)
+                ficco.ficco_plan_chain(plan, plan)
     finally:
         ficco.ficco_destroy(b)          # the plan in front goes first: the link outlives it
         ficco.ficco_destroy(a)
