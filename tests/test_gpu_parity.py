@@ -403,6 +403,32 @@ def test_cfg2_full_compare(gpu):
             check(bits, ref, "cfg2 serial")
             base = bits
         assert np.array_equal(bits, base), (sched, c)
+    # the configuration the bench times: two plans of the unequal column cut chained behind each other, taking
+    # steps in turn from the device staging source
+    dev = gpu["dev"]
+    widths = cfg["k_widths"][0]
+    A = np.concatenate(shards, 0)
+    M, K, N, G = cfg["M"], cfg["K"], cfg["N"], cfg["shards"]
+    src = as_i16(np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)).to(dev)
+    W_dev = as_i16(W).to(dev)
+    A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+    outs = [torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev) for _ in range(2)]
+    plans = [ficco.ficco_plan(M, K, N, G, len(widths), ficco.FICCO_FINE_2D) for _ in range(2)]
+    try:
+        for p_ in plans:
+            ficco.ficco_plan_set_slice_widths(p_, widths)
+        ficco.ficco_plan_chain(plans[0], plans[1])
+        ficco.ficco_plan_chain(plans[1], plans[0])
+        for i in range(10):
+            ficco.ficco_run(plans[i % 2], src, A_dev, W_dev, outs[i % 2], None, gpu["cs"], gpu["xs"])
+        for p_ in plans:
+            ficco.ficco_query_stats(p_)
+        for o in outs:
+            assert np.array_equal(o.cpu().numpy().view(np.uint16), base), "cfg2, chained plans"
+    finally:
+        for p_ in plans:
+            ficco.ficco_destroy(p_)
+    torch.cuda.synchronize()
 
 
 def test_cfg3_sampled_rows(gpu):
