@@ -336,7 +336,12 @@ int ficco_plan_arrival(const ficco_plan_t *plan, int32_t *chunk_ids, int32_t *gr
 int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
 
 /*
- * Enqueue one run of the plan; returns without waiting for the device.
+ * Enqueue one run of the plan. The stream backend only enqueues. On the engine backend the call
+ * first waits for this plan's previous run, whose signals the host re-arms (ficco_plan_chain gives
+ * back-to-back steps without that wait), and then returns without waiting for the device, with
+ * two exceptions in which the host relays kernel completions to the engines and the call returns
+ * when the last launch has finished: GEMM_RS with the per-launch schedules, and
+ * FICCO_OPT_PACKING (GEMM_RS with FICCO_FINE_PERSISTENT keeps the host out of the loop).
  *   AG_GEMM : A_src  - the G shards, contiguous ([M,K] bf16), pinned host or device memory;
  *                      piece i is copied to the same rows of A_dev on copy_stream (may be NULL in
  *                      FICCO_MODE_GEMM_ONLY).
