@@ -336,6 +336,7 @@ int ficco_graph_capture(ficco_plan_t *p, const void *A_src, void *A_dev, const v
     if (!p || !A_dev || !W_dev || !C_dev) return FICCO_ERR_ARG;
     if (is_resident(p) || p->grouped || p->timing || p->packing || p->mode != FICCO_MODE_PAIR) return FICCO_ERR_ARG;
     if (p->backend_opt == FICCO_COPY_ENGINES) return FICCO_ERR_ARG;      // engine submissions are host calls, not stream work
+    if (p->link || p->chain_from) return FICCO_ERR_ARG;                  // chained plans run on the engines
     const bool rs = p->direction == FICCO_DIR_GEMM_RS;
     if (rs ? (A_src || !peer_out) : (!A_src || peer_out)) return FICCO_ERR_ARG;
     int rc = finalize(p);
