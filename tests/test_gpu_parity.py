@@ -139,6 +139,50 @@ def test_every_tile_shape_ragged(gpu, tile):
     assert np.array_equal(test_every_tile_shape_ragged.results[0], outs[0])
 
 
+@pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
+def test_seeded_random_shapes_schedules_and_options(gpu, seed):
+    """Shapes, piece counts, schedules, tiles, tile orders, sources, backends, arrival orders and slice widths
+    drawn from a seeded generator (the same cases every run): whatever the combination, the result is within
+    tolerance of the oracle and bitwise that of the serial schedule."""
+    rng = np.random.default_rng(seed)
+    tiles = [ficco.FICCO_TILE_AUTO, ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128, ficco.FICCO_TILE_128x256,
+             ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256, ficco.FICCO_TILE_128x128_DEEP, ficco.FICCO_TILE_128x192, ficco.FICCO_TILE_256x192]
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    c = int(rng.choice([1, 2, 3, 4, 6]))
+    m = int(rng.choice([8, 24, 40, 72, 136, 264]))            # rows of a piece: below, across and above the tile heights
+    kt = int(rng.integers(1, 9))                              # k-tiles of 64
+    K, N = 64 * kt, 8 * int(rng.integers(1, 90))
+    shards = fi.make_shards(seed, G * c * m, K, G)
+    W = fi.make_weight(seed, K, N)
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    check(base, ref, f"serial G={G} c={c} m={m} K={K} N={N}")
+    for case in range(5):
+        sched = int(rng.choice([ficco.FICCO_SHARD, ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT, ficco.FICCO_FINE_2D]))
+        opts = [(ficco.FICCO_OPT_TILE, int(rng.choice(tiles)))]
+        if rng.random() < 0.5:
+            opts.append((ficco.FICCO_OPT_TILE_GROUP, int(rng.choice([1, 2, 4, 8]))))
+        src = "device" if rng.random() < 0.5 else "pinned"
+        backend = None if sched == ficco.FICCO_FINE_2D or rng.random() < 0.6 else int(rng.choice([STREAM, ENGINES]))
+        kw = {}
+        cc = 1 if sched == ficco.FICCO_SHARD else c
+        if sched == ficco.FICCO_FINE_2D:
+            n_sl = int(rng.integers(1, min(kt, 5) + 1))
+            cuts = np.sort(rng.choice(np.arange(1, kt), size=n_sl - 1, replace=False)) if n_sl > 1 else np.array([], dtype=int)
+            edges = np.concatenate([[0], cuts, [kt]])
+            kw["widths"] = [int(64 * (edges[i + 1] - edges[i])) for i in range(n_sl)]
+            cc = n_sl
+        elif rng.random() < 0.4:
+            opts.append((ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR))
+        if rng.random() < 0.3 and sched != ficco.FICCO_SHARD:
+            n_pieces = G * cc
+            kw["arrival"] = [int(i) for i in rng.permutation(n_pieces)]
+        what = f"seed {seed} case {case}: G={G} c={cc} m={m} K={K} N={N} sched={sched} opts={opts} src={src} backend={backend} {kw}"
+        bits, st, _ = run_ag(gpu, shards, W, sched, cc, src=src, opts=opts, backend=backend, runs=2, **kw)
+        assert np.array_equal(bits, base), what
+        assert st.copy_bytes == G * c * m * K * 2, what
+
+
 def test_every_tile_order_gives_the_same_bits(gpu):
     # 42 row tiles x 9 column tiles of 32x256 (both ragged): more tiles than workgroups that fit, so the
     # resident kernels draw tickets and steal, and the one-launch kernel loops
