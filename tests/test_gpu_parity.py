@@ -183,6 +183,68 @@ def test_seeded_random_shapes_schedules_and_options(gpu, seed):
         assert st.copy_bytes == G * c * m * K * 2, what
 
 
+@pytest.mark.parametrize("seed", [111, 112, 113, 114])
+def test_seeded_random_gemm_rs(gpu, seed):
+    """GEMM -> reduce-scatter (data movement half) over shapes, piece counts, schedules, tiles, tile orders, peer
+    kinds and backends drawn from a seeded generator: every peer receives its row block of the oracle's
+    product, bitwise what the serial schedule delivers."""
+    dev = gpu["dev"]
+    rng = np.random.default_rng(seed)
+    tiles = [ficco.FICCO_TILE_AUTO, ficco.FICCO_TILE_256x256, ficco.FICCO_TILE_128x128, ficco.FICCO_TILE_256x128, ficco.FICCO_TILE_128x256,
+             ficco.FICCO_TILE_64x256, ficco.FICCO_TILE_32x256, ficco.FICCO_TILE_128x128_DEEP, ficco.FICCO_TILE_128x192, ficco.FICCO_TILE_256x192]
+    G = int(rng.choice([1, 2, 4, 8]))
+    c = int(rng.choice([1, 2, 3, 4]))
+    m = int(rng.choice([8, 24, 72, 136, 264]))
+    K, N = 64 * int(rng.integers(1, 7)), 8 * int(rng.integers(1, 90))
+    M = G * c * m
+    A = fi.normal_bf16(seed, fi.TENSOR_A, M, K)
+    W = fi.make_weight(seed, K, N)
+    blocks = og.gemm_rs_blocks(A, W, G)
+    A_dev, W_dev = as_i16(A).to(dev), as_i16(W).to(dev)
+    base = None
+    cases = [(ficco.FICCO_SERIAL, 1, "device", None, [])]
+    for _ in range(5):
+        sched = int(rng.choice([ficco.FICCO_SHARD, ficco.FICCO_FINE_UNFUSED, ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT]))
+        kind = "device" if rng.random() < 0.6 else "pinned"
+        backend = None if rng.random() < 0.5 else int(rng.choice([STREAM, ENGINES]))
+        if sched == ficco.FICCO_FINE_PERSISTENT and backend == STREAM:
+            backend = ENGINES                                  # the kernel releases copy-engine transfers
+        opts = [(ficco.FICCO_OPT_TILE, int(rng.choice(tiles)))]
+        if rng.random() < 0.5:
+            opts.append((ficco.FICCO_OPT_TILE_GROUP, int(rng.choice([1, 2, 4, 8]))))
+        cases.append((sched, 1 if sched == ficco.FICCO_SHARD else c, kind, backend, opts))
+    for sched, cc, kind, backend, opts in cases:
+        what = f"seed {seed}: G={G} c={cc} m={m} K={K} N={N} sched={sched} peers={kind} backend={backend} opts={opts}"
+        C_dev = torch.zeros((M, N), dtype=torch.int16, device=dev)
+        peers = [torch.full((M // G, N), NAN_BF16, dtype=torch.int16, device=dev) if kind == "device"
+                 else torch.full((M // G, N), NAN_BF16, dtype=torch.int16).pin_memory() for _ in range(G)]
+        torch.cuda.synchronize()
+        plan = ficco.ficco_plan(M, K, N, G, cc, sched)
+        try:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_DIRECTION, ficco.FICCO_DIR_GEMM_RS)
+            if backend is not None:
+                ficco.ficco_plan_set(plan, ficco.FICCO_OPT_COPY_BACKEND, backend)
+            for o, v in opts:
+                ficco.ficco_plan_set(plan, o, v)
+            for rep_ in range(2):
+                for p_ in peers:
+                    p_.fill_(NAN_BF16)
+                torch.cuda.synchronize()
+                ficco.ficco_run(plan, None, A_dev, W_dev, C_dev, peers, gpu["cs"], gpu["xs"])
+                st = ficco.ficco_query_stats(plan)
+        finally:
+            ficco.ficco_destroy(plan)
+        torch.cuda.synchronize()
+        got = np.concatenate([p_.cpu().numpy().view(np.uint16) for p_ in peers], 0)
+        if base is None:
+            for j in range(G):
+                check(got[j * (M // G):(j + 1) * (M // G)], blocks[j], what)
+            base = got
+        assert np.array_equal(got, base), what
+        assert np.array_equal(got, C_dev.cpu().numpy().view(np.uint16)), what
+        assert st.copy_bytes == M * N * 2, what
+
+
 def test_every_tile_order_gives_the_same_bits(gpu):
     # 42 row tiles x 9 column tiles of 32x256 (both ragged): more tiles than workgroups that fit, so the
     # resident kernels draw tickets and steal, and the one-launch kernel loops
