@@ -371,7 +371,7 @@ int ficco_run(ficco_plan_t *plan, const void *A_src, void *A_dev, const void *W_
 
 /*
  * Receiver side of a true reduce-scatter (the paper leaves it out because a DMA engine cannot add,
- * Sec. V): this GPU owns row block `block` of the output; every other GPU j sends its partial block.
+ * Sec. IV-E): this GPU owns row block `block` of the output; every other GPU j sends its partial block.
  *   P_src  - [shards][M/shards][N] bf16, the peers' partial blocks where they come from (device
  *            staging or pinned host memory; slot `block` is never read)
  *   P_dev  - [shards][M/shards][N] bf16 device landing buffer, written by the transfers (slot `block`
@@ -393,7 +393,7 @@ int ficco_rs_reduce(ficco_plan_t *plan, int block, const void *P_src, void *P_de
 
 /*
  * Capture one run of the plan into a HIP graph (the paper notes the cost of enqueueing many small
- * operations, Sec. IV-B; a graph replays the whole run with one call). For the per-launch schedules
+ * operations, Sec. IV-A; a graph replays the whole run with one call). For the per-launch schedules
  * (SERIAL, SHARD, FINE_UNFUSED, FINE_FUSED) in FICCO_MODE_PAIR on the stream backend, with the far
  * side (A_src, or every peer_out[j]) in pinned host memory; FICCO_OPT_TIMING must be 0 and
  * FICCO_OPT_COPY_BACKEND must not be ENGINES (FICCO_ERR_ARG otherwise). Arguments as in ficco_run();

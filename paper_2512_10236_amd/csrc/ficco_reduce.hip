@@ -1,8 +1,8 @@
 // Receiver side of a reduce-scatter: out[rows, N] = sum over the G GPUs of their partial row block,
 // bf16 in, fp32 accumulate in ascending GPU order, one round-to-nearest-even to bf16.
 //
-// The paper leaves reduce-scatter out because a DMA engine cannot add (Sec. V, the GEMM ->
-// reduce-scatter pair); this kernel is the adding half, built so that it overlaps with the incoming
+// The paper leaves reduce-scatter out because a DMA engine cannot add (Sec. IV-E, the scenarios it
+// studies); this kernel is the adding half, built so that it overlaps with the incoming
 // transfers the way the GEMM overlaps with an all-gather: a block is cut into `pieces` row pieces,
 // piece s of every peer's partial block arrives in step s, and one launch per reduction walks the
 // pieces in step order, each tile waiting (bounded) until the G-1 incoming copies of its piece have
