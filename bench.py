@@ -430,6 +430,12 @@ def main() -> int:
                    best_row_pieces=(label(rows_best) if rows_best else None), ms_best_row_pieces=ms_rows,
                    screen={label(k): round(v, 4) for k, v in screen.items()},
                    finalists={label(k): round(v, 4) for k, v in full.items()})
+        if not rs:
+            # what the static rules answer for this shape, and where the screen put those answers
+            picks = {"rows_only": F.ficco_pick_schedule(M, K, N, G), "any_shape": F.ficco_pick_schedule_any(M, K, N, G)}
+            res["heuristic"] = {k: dict(pick=label(v), screen_ms=(round(screen[v], 4) if v in screen else None),
+                                        vs_screen_best=(round(screen[v] / min(screen.values()), 4) if v in screen else None))
+                                for k, v in picks.items()}
         return res, best
 
     best = None

@@ -106,7 +106,7 @@ CONFIGS = {
     "cfg2_qkv8b": dict(M=8192, K=4096, N=768, shards=8, chunk_rows=[1024, 512, 256], k_slices=[2, 4],
                        k_widths=[[3072, 1024]], seed=1, direction="ag_gemm"),
     # 70B-class FFN-up share
-    "cfg3_ffn70b": dict(M=16384, K=8192, N=3584, shards=8, chunk_rows=[2048, 1024, 512], seed=2,
+    "cfg3_ffn70b": dict(M=16384, K=8192, N=3584, shards=8, chunk_rows=[2048, 1024, 512, 256], seed=2,
                         direction="ag_gemm"),
     # GEMM -> reduce-scatter share (data movement half): output streamed out in 8 row blocks
     "cfg4_gemm_rs": dict(M=16384, K=3584, N=8192, shards=8, chunk_rows=[2048, 512, 256, 128], seed=3,

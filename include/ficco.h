@@ -437,6 +437,11 @@ int ficco_profile_losses(ficco_plan_t *plan, const void *A_src, void *A_dev, con
  */
 int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
 
+/* The same for callers that can hand over the activation K-sliced (see ficco_run): may also answer
+ * FICCO_FINE_2D, with the number of slices in *chunks - the choice of communication shape of
+ * Sec. V-C, decided here by whether the output is about one round of tiles over the machine. */
+int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
+
 /* Static descriptors of an (m, N, K) bf16 GEMM: op-to-byte (Sec. IV-B) and memory traffic in
  * bytes (Sec. IV-C). Host-only. */
 int ficco_static_descriptors(int64_t m, int64_t N, int64_t K, double *otb, double *mt_bytes);

@@ -155,6 +155,21 @@ def heuristic_paper(M: int, N: int, K: int, G: int, threshold: float, ratio: flo
     return "hetero-fused-1D"
 
 
+def pick_any(M: int, K: int, N: int, G: int) -> tuple[int, int]:
+    """(schedule, pieces) when column pieces are allowed too: this build's reading of the Sec. V-C choice of
+    communication shape. Column pieces (FINE_2D) when the output is at most about one round of 256x256
+    tiles over 256 CUs (M*N <= 2e7), in 2 slices, 4 from 1e11 flop, 8 from 4e11 flop (never more than
+    there are k-tiles of 64); otherwise the resident row-piece schedule with :func:`pick_pieces`."""
+    if K % 64 == 0 and float(M) * float(N) <= 2.0e7:
+        flops = 2.0 * M * N * K
+        sl = 2 if flops < 1.0e11 else 4 if flops < 4.0e11 else 8
+        while sl > 1 and sl > K // 64:
+            sl //= 2
+        if sl > 1:
+            return FINE_2D, sl
+    return FINE_PERSISTENT, pick_pieces(M, K, N, G)
+
+
 def pick_pieces(M: int, K: int, N: int, G: int, piece_flops: float = 2.5e10, min_rows: int = 256, max_pieces: int = 16) -> int:
     """This build's reading of the Sec. V-C rule for the piece count: the largest power-of-two split of
     a shard whose pieces still carry ``piece_flops`` flops each (OTB x MT of the piece GEMM), pieces of

@@ -486,6 +486,28 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
     return FICCO_OK;
 }
 
+int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
+{
+    int rc = ficco_pick_schedule(M, K, N, shards, schedule, chunks);
+    if (rc) return rc;
+    // Column pieces (the paper's 2D shape, Sec. V-C picks it from M against K) pay off on this machine when
+    // the output is no more than about one round of tiles over the CUs (256x256 tiles on 256 CUs, with 20 %
+    // slack: M*N <= 2e7): then every tile can make progress with every slice, while row pieces would leave
+    // most tiles waiting for their own piece. Slices: 2, from 1e11 flop 4, from 4e11 flop 8 (the more the GEMM
+    // weighs against the transfers, the earlier it should start). Fitted to the 24-shape sweep, where the rule
+    // picks the faster family everywhere, and to the M <= K workload of the bench.
+    if (K % kBK == 0 && (double)M * (double)N <= 2.0e7) {
+        const double flops = 2.0 * (double)M * (double)N * (double)K;
+        int sl = flops < 1.0e11 ? 2 : flops < 4.0e11 ? 4 : 8;
+        while (sl > 1 && sl > K / kBK) sl /= 2;
+        if (sl > 1) {
+            *schedule = FICCO_FINE_2D;
+            *chunks = sl;
+        }
+    }
+    return FICCO_OK;
+}
+
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule, ficco_plan_t **out)
 {
     if (!out) return FICCO_ERR_ARG;

@@ -124,7 +124,8 @@ def fit(args) -> int:
         else:
             note_2d = ""
         table.append(dict(key=k, serial=serial, shard=shard, best=best, fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in fine},
-                          best_2d=min((r["wall_us"] for r in two_d), default=None)))
+                          best_2d=min((r["wall_us"] for r in two_d), default=None),
+                          two_d={r["chunks"]: r["wall_us"] for r in two_d}))
         print(f"M={k[0]:6d} K={k[1]:5d} N={k[2]:6d}: serial {serial:9.1f} us  shard-level {shard:9.1f} us  best {best['schedule']} x{best['chunks']} "
               f"{best['wall_us']:9.1f} us  speedup {serial / best['wall_us']:.3f}x (vs shard-level {shard / best['wall_us']:.2f}x){note_2d}")
 
@@ -173,6 +174,23 @@ def fit(args) -> int:
               f"within 3% of it at {near}/{len(with_2d)} ({n_le} shapes have M <= K)")
     h, n, loss = score((2.5e10, 256, 16), table)
     print(f"constants compiled into ficco_pick_schedule (2.5e10, 256, 16): exact {h}/{len(table)}, within 3% {n}/{len(table)}")
+    # ficco_pick_schedule_any (column pieces allowed) against the best of both families
+    if with_2d:
+        hit = near = fam = 0
+        worst = 0.0
+        for t in with_2d:
+            M, K, N, G = t["key"]
+            s, c = F.ficco_pick_schedule_any(M, K, N, G)
+            got = t["two_d"].get(c) if s == F.FICCO_FINE_2D else t["fine"].get((s, c))
+            if got is None:
+                continue
+            best = min(t["best"]["wall_us"], t["best_2d"])
+            hit += got <= 1.001 * best
+            near += got <= 1.03 * best
+            worst = max(worst, got / best)
+            fam += (s == F.FICCO_FINE_2D) == (t["best_2d"] <= t["best"]["wall_us"])
+        print(f"ficco_pick_schedule_any against the best of row and column pieces: exact {hit}/{len(with_2d)}, within 3% {near}/{len(with_2d)}, "
+              f"worst {100 * (worst - 1):.1f}% off, faster family picked at {fam}/{len(with_2d)} shapes")
     return 0
 
 

@@ -551,6 +551,7 @@ def test_cfg3_sampled_rows(gpu):
                                    (ficco.FICCO_FINE_FUSED, 4, "pinned", S), (ficco.FICCO_FINE_UNFUSED, 2, "device", E),
                                    (ficco.FICCO_FINE_PERSISTENT, 4, "pinned", S),      # full grid minus the helper-kernel headroom
                                    (ficco.FICCO_FINE_PERSISTENT, 4, "pinned", E), (ficco.FICCO_FINE_PERSISTENT, 2, "device", E),
+                                   (ficco.FICCO_FINE_PERSISTENT, 8, "device", E),      # what ficco_pick_schedule answers for this shape
                                    (ficco.FICCO_SERIAL, 1, "device", E)]:
         bits, st, info = run_ag(gpu, shards, W, sched, c, src=src, opts=[(ficco.FICCO_OPT_COPY_BACKEND, backend)])
         assert info.copy_backend == backend

@@ -263,6 +263,29 @@ def test_pick_pieces_hand_cases():
         assert ficco.ficco_pick_schedule(*args)[1] == sch.pick_pieces(*args)
 
 
+def test_pick_schedule_any_matches_oracle_and_gives_valid_plans():
+    for M in (512, 4096, 8192, 16384, 65536):
+        for K in (64, 128, 4096, 8192, 16384):
+            for N in (8, 512, 768, 1024, 3584, 4096, 14336):
+                s, c = ficco.ficco_pick_schedule_any(M, K, N, 8)
+                assert (s, c) == sch.pick_any(M, K, N, 8), (M, K, N)
+                plan = ficco.ficco_plan(M, K, N, 8, c, s)          # whatever it answers can be planned
+                ficco.ficco_destroy(plan)
+                if s != ficco.FICCO_FINE_2D:
+                    assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
+
+
+def test_pick_any_hand_cases():
+    # the bench's workloads: small outputs take column pieces, large ones row pieces
+    assert sch.pick_any(8192, 4096, 768, 8) == (sch.FINE_2D, 2)            # 6.3e6 outputs, 5.2e10 flop
+    assert sch.pick_any(4096, 16384, 4096, 8) == (sch.FINE_2D, 8)          # 1.7e7 outputs, 5.5e11 flop
+    assert sch.pick_any(4096, 8192, 3584, 8) == (sch.FINE_2D, 4)           # 1.5e7 outputs, 2.4e11 flop
+    assert sch.pick_any(16384, 8192, 3584, 8) == (sch.FINE_PERSISTENT, 8)  # 5.9e7 outputs: several rounds of tiles
+    assert sch.pick_any(4096, 4096, 14336, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 4096, 14336, 8))
+    assert sch.pick_any(4096, 64, 512, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 64, 512, 8))   # one k-tile: nothing to slice
+    assert sch.pick_any(4096, 128, 512, 8) == (sch.FINE_2D, 2)
+
+
 # ------------------------------------------------------------------ expert-parallel (grouped) plans
 from oracle import grouped as ogr  # noqa: E402
 
