@@ -80,7 +80,10 @@ typedef enum ficco_schedule {
                                     activation travels and is stored K-sliced (see ficco_run).
                                     AG_GEMM only, no FICCO_OPT_LOCAL_SHARD, never picked by AUTO
                                     because it changes the caller's layout                          */
-    FICCO_AUTO            = 100  /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
+    FICCO_AUTO            = 100, /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
+    FICCO_AUTO_ANY        = 101  /* ficco_pick_schedule_any() decides: the answer may be FICCO_FINE_2D,
+                                    whose layout the caller then has to provide (ficco_plan_info() and
+                                    ficco_plan_slices() say what was chosen)                         */
 } ficco_schedule;
 
 typedef enum ficco_direction {
@@ -246,7 +249,7 @@ typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this p
  * shards*chunks <= 4096. FICCO_FINE_2D instead needs M % shards == 0 and chunks <= K/64; its
  * slices are as equal as whole k-tiles of 64 columns allow (the first (K/64) mod chunks slices
  * one k-tile wider) unless ficco_plan_set_slice_widths gives other widths.
- * With FICCO_AUTO, `chunks` is ignored and chosen by the heuristic.
+ * With FICCO_AUTO and FICCO_AUTO_ANY, `chunks` is ignored and chosen by the heuristic.
  */
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule,
                ficco_plan_t **out);

@@ -15,6 +15,7 @@ FICCO_OK, FICCO_ERR_ARG, FICCO_ERR_SHAPE, FICCO_ERR_ALLOC = 0, -1, -2, -3
 FICCO_ERR_HIP, FICCO_ERR_TIMEOUT, FICCO_ERR_STATE = -4, -5, -6
 FICCO_SERIAL, FICCO_SHARD, FICCO_FINE_UNFUSED, FICCO_FINE_FUSED, FICCO_FINE_PERSISTENT, FICCO_FINE_2D = 0, 1, 2, 3, 4, 5
 FICCO_AUTO = 100
+FICCO_AUTO_ANY = 101
 FICCO_DIR_AG_GEMM, FICCO_DIR_GEMM_RS = 0, 1
 FICCO_ORDER_STEP_MAJOR, FICCO_ORDER_SHARD_MAJOR, FICCO_ORDER_CUSTOM = 0, 1, 2
 FICCO_MODE_PAIR, FICCO_MODE_GEMM_ONLY, FICCO_MODE_COPY_ONLY, FICCO_MODE_INDEPENDENT = 0, 1, 2, 3

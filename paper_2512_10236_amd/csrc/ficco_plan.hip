@@ -512,8 +512,9 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
 {
     if (!out) return FICCO_ERR_ARG;
     if (M < 1 || K < 1 || N < 1 || shards < 1) return FICCO_ERR_SHAPE;
-    if (schedule == FICCO_AUTO) {
-        int rc = ficco_pick_schedule(M, K, N, shards, &schedule, &chunks);
+    if (schedule == FICCO_AUTO || schedule == FICCO_AUTO_ANY) {
+        int rc = schedule == FICCO_AUTO ? ficco_pick_schedule(M, K, N, shards, &schedule, &chunks)
+                                        : ficco_pick_schedule_any(M, K, N, shards, &schedule, &chunks);
         if (rc) return rc;
     }
     if (schedule < FICCO_SERIAL || schedule > FICCO_FINE_2D) return FICCO_ERR_ARG;

@@ -271,6 +271,10 @@ def test_pick_schedule_any_matches_oracle_and_gives_valid_plans():
                 assert (s, c) == sch.pick_any(M, K, N, 8), (M, K, N)
                 plan = ficco.ficco_plan(M, K, N, 8, c, s)          # whatever it answers can be planned
                 ficco.ficco_destroy(plan)
+                plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO_ANY)
+                info = ficco.ficco_plan_info(plan)
+                ficco.ficco_destroy(plan)
+                assert (info.schedule, info.chunks) == (s, c)
                 if s != ficco.FICCO_FINE_2D:
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
 
