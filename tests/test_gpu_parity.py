@@ -804,6 +804,31 @@ def test_chained_plan_is_let_go_when_the_run_in_front_gives_up(gpu):
     torch.cuda.synchronize()
 
 
+def test_auto_any_plan_runs_in_the_layout_it_reports(gpu):
+    """FICCO_AUTO_ANY may answer with column pieces; the caller learns the layout from the plan and provides it."""
+    dev = gpu["dev"]
+    shards, W = fi.config_inputs("cfg1_tiny")
+    A = np.concatenate(shards, 0)
+    M, K = A.shape
+    N, G = W.shape[1], len(shards)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    plan = ficco.ficco_plan(M, K, N, G, 1, ficco.FICCO_AUTO_ANY)
+    try:
+        info = ficco.ficco_plan_info(plan)
+        assert (info.schedule, info.chunks) == ficco.ficco_pick_schedule_any(M, K, N, G) == (ficco.FICCO_FINE_2D, 2)
+        _, widths = ficco.ficco_plan_slices(plan)
+        src = as_i16(np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)).to(dev)
+        W_dev = as_i16(W).to(dev)
+        A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+        C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+        ficco.ficco_run(plan, src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
+        ficco.ficco_query_stats(plan)
+        assert np.array_equal(C_dev.cpu().numpy().view(np.uint16), base)
+    finally:
+        ficco.ficco_destroy(plan)
+    torch.cuda.synchronize()
+
+
 def test_2d_waits_for_late_and_reordered_slices(gpu):
     G, ms, K, N, c = 4, 256, 1024, 512, 4
     shards = fi.make_shards(24, G * ms, K, G)
