@@ -82,8 +82,9 @@ typedef enum ficco_schedule {
                                     because it changes the caller's layout                          */
     FICCO_AUTO            = 100, /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
     FICCO_AUTO_ANY        = 101  /* ficco_pick_schedule_any() decides: the answer may be FICCO_FINE_2D,
-                                    whose layout the caller then has to provide (ficco_plan_info() and
-                                    ficco_plan_slices() say what was chosen)                         */
+                                    cut by ficco_pick_slice_widths(), whose layout the caller then has
+                                    to provide (ficco_plan_info() and ficco_plan_slices() say what was
+                                    chosen)                                                          */
 } ficco_schedule;
 
 typedef enum ficco_direction {
@@ -444,6 +445,14 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
  * FICCO_FINE_2D, with the number of slices in *chunks - the choice of communication shape of
  * Sec. V-C, decided here by whether the output is about one round of tiles over the machine. */
 int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
+
+/* The cut of the k range that goes with a FICCO_FINE_2D answer: widths[0..slices) for
+ * ficco_plan_set_slice_widths (a FICCO_AUTO_ANY plan has them applied already). Two slices of a
+ * transfer-bound shape (N*shards <= 8192) are cut three quarters to one quarter, in whole k-tiles,
+ * so that little GEMM is left when the last byte lands (the overlap model of Sec. IV-A); everything
+ * else is cut as evenly as k-tiles allow. FICCO_ERR_ARG unless K is a multiple of 64 with at least
+ * `slices` k-tiles. */
+int ficco_pick_slice_widths(int64_t M, int64_t K, int64_t N, int shards, int slices, int64_t *widths);
 
 /* Static descriptors of an (m, N, K) bf16 GEMM: op-to-byte (Sec. IV-B) and memory traffic in
  * bytes (Sec. IV-C). Host-only. */

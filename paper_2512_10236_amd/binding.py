@@ -68,7 +68,7 @@ class ficco_losses_t(C.Structure):
 
 EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_chain", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
            "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
-           "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
+           "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
 _lib = None
@@ -110,6 +110,7 @@ def load():
     lib.ficco_profile_losses.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(ficco_losses_t)]
     lib.ficco_pick_schedule.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_schedule_any.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.ficco_pick_slice_widths.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.POINTER(i64)]
     lib.ficco_static_descriptors.argtypes = [i64, i64, i64, dp, dp]
     lib.ficco_ideal_overlap_us.argtypes = [C.c_double, C.c_double, C.c_int]
     lib.ficco_ideal_overlap_us.restype = C.c_double
@@ -276,6 +277,12 @@ def ficco_pick_schedule(M, K, N, shards):
     s, c = C.c_int(), C.c_int()
     _ok(load().ficco_pick_schedule(M, K, N, shards, C.byref(s), C.byref(c)), "ficco_pick_schedule")
     return s.value, c.value
+
+
+def ficco_pick_slice_widths(M, K, N, shards, slices):
+    w = (C.c_int64 * max(int(slices), 1))()
+    _ok(load().ficco_pick_slice_widths(M, K, N, shards, slices, w), "ficco_pick_slice_widths")
+    return list(w)[:slices]
 
 
 def ficco_pick_schedule_any(M, K, N, shards):

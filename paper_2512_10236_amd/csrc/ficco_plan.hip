@@ -493,12 +493,14 @@ int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *sc
     // Column pieces (the paper's 2D shape, Sec. V-C picks it from M against K) pay off on this machine when
     // the output is no more than about one round of tiles over the CUs (256x256 tiles on 256 CUs, with 20 %
     // slack: M*N <= 2e7): then every tile can make progress with every slice, while row pieces would leave
-    // most tiles waiting for their own piece. Slices: 2, from 1e11 flop 4, from 4e11 flop 8 (the more the GEMM
-    // weighs against the transfers, the earlier it should start). Fitted to the 24-shape sweep, where the rule
-    // picks the faster family everywhere, and to the M <= K workload of the bench.
+    // most tiles waiting for their own piece. Slices: two when the transfers are the longer side (GEMM time
+    // over transfer time grows with N*shards; up to 8192 the transfers dominate: see ficco_pick_slice_widths
+    // for their cut), else 2, from 1e11 flop 4, from 4e11 flop 8 (the more the GEMM weighs, the earlier it
+    // should start). Fitted to the 24-shape sweep, where the rule picks the faster family everywhere, and to
+    // the M <= K workload of the bench.
     if (K % kBK == 0 && (double)M * (double)N <= 2.0e7) {
         const double flops = 2.0 * (double)M * (double)N * (double)K;
-        int sl = flops < 1.0e11 ? 2 : flops < 4.0e11 ? 4 : 8;
+        int sl = (double)N * shards <= 8192.0 ? 2 : flops < 1.0e11 ? 2 : flops < 4.0e11 ? 4 : 8;
         while (sl > 1 && sl > K / kBK) sl /= 2;
         if (sl > 1) {
             *schedule = FICCO_FINE_2D;
@@ -508,10 +510,29 @@ int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *sc
     return FICCO_OK;
 }
 
+int ficco_pick_slice_widths(int64_t M, int64_t K, int64_t N, int shards, int slices, int64_t *widths)
+{
+    if (M < 1 || K < kBK || K % kBK || N < 1 || shards < 1 || slices < 1 || slices > K / kBK || !widths) return FICCO_ERR_ARG;
+    const int64_t kt = K / kBK;
+    if (slices == 2 && (double)N * shards <= 8192.0) {
+        // Transfers are the longer side: what stays exposed is the GEMM of the last slice, so the first slice is
+        // as wide as the GEMM can digest while the second one travels. Three quarters of K was the best cut, by
+        // 2-7 % over two equal slices, at every transfer-bound shape tried (N 512-1024, K 4096-8192, M 4096-16384).
+        int64_t first = (3 * kt + 2) / 4;
+        first = std::max<int64_t>(1, std::min(first, kt - 1));
+        widths[0] = first * kBK;
+        widths[1] = (kt - first) * kBK;
+        return FICCO_OK;
+    }
+    for (int sl = 0; sl < slices; ++sl) widths[sl] = kBK * (kt / slices + (sl < kt % slices ? 1 : 0));
+    return FICCO_OK;
+}
+
 int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int schedule, ficco_plan_t **out)
 {
     if (!out) return FICCO_ERR_ARG;
     if (M < 1 || K < 1 || N < 1 || shards < 1) return FICCO_ERR_SHAPE;
+    const bool any_shape = schedule == FICCO_AUTO_ANY;
     if (schedule == FICCO_AUTO || schedule == FICCO_AUTO_ANY) {
         int rc = schedule == FICCO_AUTO ? ficco_pick_schedule(M, K, N, shards, &schedule, &chunks)
                                         : ficco_pick_schedule_any(M, K, N, shards, &schedule, &chunks);
@@ -536,6 +557,13 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
     p->order = (schedule == FICCO_SERIAL || schedule == FICCO_SHARD) ? FICCO_ORDER_SHARD_MAJOR : FICCO_ORDER_STEP_MAJOR;
     int rc = build_lists(p);
     if (rc) { delete p; return rc; }
+    if (any_shape && schedule == FICCO_FINE_2D) {
+        // the rule's cut of the k range comes with its answer
+        std::vector<int64_t> w((size_t)chunks);
+        rc = ficco_pick_slice_widths(M, K, N, shards, chunks, w.data());
+        if (!rc) rc = ficco_plan_set_slice_widths(p, w.data(), chunks);
+        if (rc) { delete p; return rc; }
+    }
     *out = p;
     return FICCO_OK;
 }

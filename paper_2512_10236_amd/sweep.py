@@ -42,17 +42,29 @@ def measure(args) -> int:
                 W = (torch.randn((K, N), device=dev, generator=gen) * K ** -0.5).to(torch.bfloat16).view(torch.int16)
                 C = torch.zeros((M, N), dtype=torch.int16, device=dev)
                 C_ref = None
-                cases = [(F.FICCO_SERIAL, 1), (F.FICCO_SHARD, 1)]
-                cases += [(s, c) for c in args.chunks for s in FINE if (M // G) % c == 0 and c * G <= 4096]
+                cases = [(F.FICCO_SERIAL, 1, None), (F.FICCO_SHARD, 1, None)]
+                cases += [(s, c, None) for c in args.chunks for s in FINE if (M // G) % c == 0 and c * G <= 4096]
                 # the 2D schedule (k slices) wherever the slices are whole k-tiles; its source is the K-sliced copy
-                cases += [(F.FICCO_FINE_2D, c) for c in args.chunks if c > 1 and K % (64 * c) == 0 and c * G <= 4096]
-                for sched, c in cases:
+                cases += [(F.FICCO_FINE_2D, c, None) for c in args.chunks if c > 1 and K % (64 * c) == 0 and c * G <= 4096]
+                # what ficco_pick_schedule_any answers, when that is column pieces in a cut of its own
+                ps, pc = F.ficco_pick_schedule_any(M, K, N, G)
+                if ps == F.FICCO_FINE_2D:
+                    pw = F.ficco_pick_slice_widths(M, K, N, G, pc)
+                    if len(set(pw)) > 1:
+                        cases.append((ps, pc, pw))
+                for sched, c, widths in cases:
                     src = A_stage
-                    if sched == F.FICCO_FINE_2D:
+                    if widths is not None:
+                        edges = [sum(widths[:i]) for i in range(len(widths) + 1)]
+                        src = torch.cat([A_stage[:, edges[i]:edges[i + 1]].reshape(-1) for i in range(len(widths))]).view(M, K)
+                        torch.cuda.synchronize()
+                    elif sched == F.FICCO_FINE_2D:
                         src = A_stage.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
                         torch.cuda.synchronize()
                     plan = F.ficco_plan(M, K, N, G, c, sched)
                     try:
+                        if widths is not None:
+                            F.ficco_plan_set_slice_widths(plan, widths)
                         F.ficco_pack_weight(plan, W, cs)
                         ts, cps = [], []
                         for it in range(args.warmup + args.iters):
@@ -77,6 +89,8 @@ def measure(args) -> int:
                                wall_us=round(sum(ts) / len(ts), 2), min_us=round(min(ts), 2),
                                copy_span_us=round(sum(cps) / len(cps), 2), tile=f"{info.tile_m}x{info.tile_n}",
                                bits_equal_serial=same)
+                    if widths is not None:
+                        row["widths"] = widths
                     out.write(json.dumps(row) + "\n")
                     out.flush()
                     print(json.dumps(row), flush=True)
@@ -117,7 +131,8 @@ def fit(args) -> int:
         shard = next(r for r in rs if r["schedule"] == "shard")["wall_us"]
         fine = [r for r in rs if r["sched_id"] in FINE]
         best = min(fine, key=lambda r: r["wall_us"])
-        two_d = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D]
+        two_d = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D and "widths" not in r]
+        cut = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D and "widths" in r]
         if two_d:
             b2 = min(two_d, key=lambda r: r["wall_us"])
             note_2d = f"  best 2D x{b2['chunks']} {b2['wall_us']:9.1f} us ({best['wall_us'] / b2['wall_us']:.3f}x of best 1D)"
@@ -125,7 +140,8 @@ def fit(args) -> int:
             note_2d = ""
         table.append(dict(key=k, serial=serial, shard=shard, best=best, fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in fine},
                           best_2d=min((r["wall_us"] for r in two_d), default=None),
-                          two_d={r["chunks"]: r["wall_us"] for r in two_d}))
+                          two_d={r["chunks"]: r["wall_us"] for r in two_d},
+                          rule_cut={(r["chunks"], tuple(r["widths"])): r["wall_us"] for r in cut}))
         print(f"M={k[0]:6d} K={k[1]:5d} N={k[2]:6d}: serial {serial:9.1f} us  shard-level {shard:9.1f} us  best {best['schedule']} x{best['chunks']} "
               f"{best['wall_us']:9.1f} us  speedup {serial / best['wall_us']:.3f}x (vs shard-level {shard / best['wall_us']:.2f}x){note_2d}")
 
@@ -182,13 +198,17 @@ def fit(args) -> int:
             M, K, N, G = t["key"]
             s, c = F.ficco_pick_schedule_any(M, K, N, G)
             got = t["two_d"].get(c) if s == F.FICCO_FINE_2D else t["fine"].get((s, c))
+            if s == F.FICCO_FINE_2D:           # the rule's own cut, where the sweep measured it
+                got = t["rule_cut"].get((c, tuple(F.ficco_pick_slice_widths(M, K, N, G, c))), got)
             if got is None:
                 continue
-            best = min(t["best"]["wall_us"], t["best_2d"])
+            best = min([t["best"]["wall_us"], t["best_2d"]] + list(t["rule_cut"].values()))
             hit += got <= 1.001 * best
             near += got <= 1.03 * best
             worst = max(worst, got / best)
             fam += (s == F.FICCO_FINE_2D) == (t["best_2d"] <= t["best"]["wall_us"])
+        n_cut = sum(1 for t in with_2d if t["rule_cut"])
+        print(f"(column pieces in the rule's own unequal cut were measured at {n_cut} shapes and count among the candidates)")
         print(f"ficco_pick_schedule_any against the best of row and column pieces: exact {hit}/{len(with_2d)}, within 3% {near}/{len(with_2d)}, "
               f"worst {100 * (worst - 1):.1f}% off, faster family picked at {fam}/{len(with_2d)} shapes")
     return 0

@@ -273,8 +273,12 @@ def test_pick_schedule_any_matches_oracle_and_gives_valid_plans():
                 ficco.ficco_destroy(plan)
                 plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO_ANY)
                 info = ficco.ficco_plan_info(plan)
+                widths = ficco.ficco_plan_slices(plan)[1] if s == ficco.FICCO_FINE_2D else None
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
+                if s == ficco.FICCO_FINE_2D:
+                    assert widths == ficco.ficco_pick_slice_widths(M, K, N, 8, c) == sch.pick_widths(M, K, N, 8, c)
+                    assert sum(widths) == K and all(w > 0 and w % 64 == 0 for w in widths)
                 if s != ficco.FICCO_FINE_2D:
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
 
@@ -288,6 +292,17 @@ def test_pick_any_hand_cases():
     assert sch.pick_any(4096, 4096, 14336, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 4096, 14336, 8))
     assert sch.pick_any(4096, 64, 512, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 64, 512, 8))   # one k-tile: nothing to slice
     assert sch.pick_any(4096, 128, 512, 8) == (sch.FINE_2D, 2)
+    assert sch.pick_any(16384, 4096, 1024, 8) == (sch.FINE_2D, 2)          # 1.4e11 flop, but the transfers are the longer side
+    # the cut: transfer-bound pairs of slices three to one, the rest even
+    assert sch.pick_widths(8192, 4096, 768, 8, 2) == [3072, 1024]          # what the bench found by screening
+    assert sch.pick_widths(4096, 128, 512, 8, 2) == [64, 64]
+    assert sch.pick_widths(4096, 192, 512, 8, 2) == [128, 64]
+    assert sch.pick_widths(4096, 4096, 3584, 8, 4) == [1024] * 4
+    assert sch.pick_widths(4096, 4096, 3584, 8, 2) == [2048, 2048]         # N*G = 28672: not transfer-bound
+    assert sch.pick_widths(64, 704, 8, 8, 4) == [192, 192, 192, 128]
+    for bad in ((4096, 4096, 512, 8, 0), (4096, 100, 512, 8, 1), (4096, 128, 512, 8, 3)):
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_pick_slice_widths(*bad)
 
 
 # ------------------------------------------------------------------ expert-parallel (grouped) plans
