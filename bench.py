@@ -346,6 +346,14 @@ def main() -> int:
                     cands.append((s, c))
         cands += [(F.FICCO_FINE_2D, c) for c in cfg.get("k_slices", [])]
         cands += [(F.FICCO_FINE_2D, tuple(w)) for w in cfg.get("k_widths", [])]
+        if not rs:
+            # what the any-shape rule answers, in the rule's own cut of the k range
+            ps, pc = F.ficco_pick_schedule_any(M, K, N, G)
+            if ps == F.FICCO_FINE_2D:
+                pw = tuple(F.ficco_pick_slice_widths(M, K, N, G, pc))
+                cand = (ps, pw) if len(set(pw)) > 1 else (ps, pc)
+                if cand not in cands:
+                    cands.append(cand)
 
     out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
                      + " effective TFLOP/s (overlapped pair, best finer-grain schedule)",
@@ -433,6 +441,10 @@ def main() -> int:
         if not rs:
             # what the static rules answer for this shape, and where the screen put those answers
             picks = {"rows_only": F.ficco_pick_schedule(M, K, N, G), "any_shape": F.ficco_pick_schedule_any(M, K, N, G)}
+            if picks["any_shape"][0] == F.FICCO_FINE_2D:
+                pw = tuple(F.ficco_pick_slice_widths(M, K, N, G, picks["any_shape"][1]))
+                if len(set(pw)) > 1:
+                    picks["any_shape"] = (F.FICCO_FINE_2D, pw)
             res["heuristic"] = {k: dict(pick=label(v), screen_ms=(round(screen[v], 4) if v in screen else None),
                                         vs_screen_best=(round(screen[v] / min(screen.values()), 4) if v in screen else None))
                                 for k, v in picks.items()}
