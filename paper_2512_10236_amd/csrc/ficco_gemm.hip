@@ -104,11 +104,66 @@ struct NoHook {
 // `after_first_wait` runs once, right after the first k-step's wait and barrier: vector memory
 // operations complete in issue order, so by then every store that any wavefront of the workgroup
 // issued before this call has been performed.
-template <class T, class Hook = NoHook>
-static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uint16_t *__restrict__ a_tile, int rows_valid,
-                                                       const uint16_t *__restrict__ wt_tile, int cols_valid,
-                                                       int64_t lda, int64_t ldw, int K, unsigned char *smem,
-                                                       Hook after_first_wait = Hook())
+// Where the loader finds its part of k-tile kt of A. PlainA: one row-major block [rows, K] with row stride lda
+// (a per-lane pointer per load, advanced by whole k-tiles).
+template <class T>
+struct PlainA {
+    const uint16_t *ga[T::AB];
+    __device__ __forceinline__ PlainA(const uint16_t *a_tile, int rows_valid, int64_t lda, int wave, int lane)
+    {
+#pragma unroll
+        for (int i = 0; i < T::AB; ++i) {
+            const int row = (wave * T::AB + i) * 8 + (lane >> 3);
+            const int kc = (lane & 7) ^ ((row >> 1) & 7);
+            const int rr = row < rows_valid ? row : rows_valid - 1;
+            ga[i] = a_tile + (int64_t)rr * lda + kc * 8;
+        }
+    }
+    __device__ __forceinline__ void seek(int) {}
+    __device__ __forceinline__ const uint16_t *at(int i, int kt) const { return ga[i] + (int64_t)kt * kBK; }
+};
+
+// SlicedA: a run of consecutive k slices of the K-sliced layout (slice s = the [M][k0[s+1]-k0[s]] block that
+// starts at element M*k0[s]), read as one k range. The issue stream walks the k-tiles in ascending order;
+// `seek` moves to the slice a k-tile lies in and only then rebuilds the per-lane pointers for that slice's
+// base and row stride, so that inside a slice a load costs what it costs with PlainA.
+template <class T>
+struct SlicedA {
+    const uint16_t *ga[T::AB];
+    const uint16_t *A;
+    const int32_t *k0;
+    int64_t M, row0;
+    int sl, kt_begin, kt_end, rows_valid, wave, lane;
+    __device__ __forceinline__ SlicedA(const uint16_t *A_, const int32_t *k0_, int64_t M_, int64_t row0_, int first_slice, int rows_valid_,
+                                       int wave_, int lane_)
+        : A(A_), k0(k0_), M(M_), row0(row0_), sl(first_slice - 1), kt_begin(0), kt_end(0), rows_valid(rows_valid_), wave(wave_), lane(lane_)
+    {
+    }
+    __device__ __forceinline__ void seek(int kt)
+    {
+        while (kt >= kt_end) {               // uniform: every lane takes the same steps
+            ++sl;
+            const int kb = k0[sl], kw = k0[sl + 1] - kb;
+            kt_begin = kt_end;
+            kt_end += kw / kBK;
+            const uint16_t *base = A + M * kb + row0 * kw;
+#pragma unroll
+            for (int i = 0; i < T::AB; ++i) {
+                const int row = (wave * T::AB + i) * 8 + (lane >> 3);
+                const int kc = (lane & 7) ^ ((row >> 1) & 7);
+                const int rr = row < rows_valid ? row : rows_valid - 1;
+                ga[i] = base + (int64_t)rr * kw + kc * 8;
+            }
+        }
+    }
+    __device__ __forceinline__ const uint16_t *at(int i, int kt) const { return ga[i] + (int64_t)(kt - kt_begin) * kBK; }
+};
+
+template <class T, class Hook = NoHook, class AddrA = PlainA<T>>
+static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, AddrA &pa,
+                                                            const uint16_t *__restrict__ wt_tile, int cols_valid,
+                                                            int64_t ldw, int K, unsigned char *smem,
+                                                            Hook after_first_wait = Hook())
 {
     f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
     const int tid = threadIdx.x;
@@ -117,15 +172,7 @@ static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uin
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
-    const uint16_t *ga[T::AB];
     const uint16_t *gb[T::BB];
-#pragma unroll
-    for (int i = 0; i < T::AB; ++i) {
-        const int row = (wave * T::AB + i) * 8 + (lane >> 3);
-        const int kc = (lane & 7) ^ ((row >> 1) & 7);
-        const int rr = row < rows_valid ? row : rows_valid - 1;
-        ga[i] = a_tile + (int64_t)rr * lda + kc * 8;
-    }
 #pragma unroll
     for (int i = 0; i < T::BB; ++i) {
         const int row = (wave * T::BB + i) * 8 + (lane >> 3);
@@ -133,13 +180,14 @@ static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uin
         const int rr = row < cols_valid ? row : cols_valid - 1;
         gb[i] = wt_tile + (int64_t)rr * ldw + kc * 8;
     }
-    // quarter q of the loads of k-tile kt into `stage`
+    // quarter q of the loads of k-tile kt into `stage` (k-tiles are issued in ascending order)
     auto issue_part = [&](int stage, int kt, int q) {
         const uint32_t sa = lds0 + stage * T::STAGE + wave * T::AB * 1024;
         const uint32_t sb = lds0 + stage * T::STAGE + T::A_STAGE + wave * T::BB * 1024;
+        if (q == 0) pa.seek(kt);
 #pragma unroll
         for (int i = 0; i < T::AB; ++i)
-            if ((i & 3) == q || (T::AB < 4 && q == 0)) load_to_lds_16(ga[i] + (int64_t)kt * kBK, sa + i * 1024);
+            if ((i & 3) == q || (T::AB < 4 && q == 0)) load_to_lds_16(pa.at(i, kt), sa + i * 1024);
 #pragma unroll
         for (int i = 0; i < T::BB; ++i)
             if ((i & 3) == q || (T::BB < 4 && q == 0)) load_to_lds_16(gb[i] + (int64_t)kt * kBK, sb + i * 1024);
@@ -215,6 +263,16 @@ static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uin
     }
 
     wg_barrier();                          // every wavefront is done with the ring before it is refilled
+}
+
+template <class T, class Hook = NoHook>
+static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uint16_t *__restrict__ a_tile, int rows_valid,
+                                                       const uint16_t *__restrict__ wt_tile, int cols_valid,
+                                                       int64_t lda, int64_t ldw, int K, unsigned char *smem,
+                                                       Hook after_first_wait = Hook())
+{
+    PlainA<T> pa(a_tile, rows_valid, lda, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63);
+    tile_accumulate_from<T, Hook, PlainA<T>>(ta, pa, wt_tile, cols_valid, ldw, K, smem, after_first_wait);
 }
 
 // Rounds the accumulators to bf16 (nearest even) and stores the valid part of the tile.
@@ -337,6 +395,13 @@ static __device__ __forceinline__ int wait_ready(const Gate &g, int chunk)
         }
         __builtin_amdgcn_s_sleep(8);
     }
+}
+
+// One look at a piece, without waiting: has it landed?
+static __device__ __forceinline__ int peek_ready(const Gate &g, int chunk)
+{
+    if (g.sig_value) return __hip_atomic_load(reinterpret_cast<const int64_t *>(g.sig_value[chunk]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) <= 0;
+    return __hip_atomic_load(g.flags + (size_t)chunk * kFlagStrideWords, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == g.epoch;
 }
 
 // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2). The tiles are cut
@@ -659,25 +724,34 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
         TileAcc<T> ta;
         tile_zero(ta);
         int ok = 1;
-        int kb = r.k0[0];                  // uniform (scalar) loads; the next boundary is fetched before the wait for the slice
-        for (int sl = 0; sl < r.slices && ok; ++sl) {
-            const int ke = r.k0[sl + 1];
+        // The k loop takes runs of slices: it waits for the next slice, then looks (without waiting) how many of
+        // the following ones have landed as well, and multiplies the whole run as one k range, so that the load
+        // pipeline is only drained where the kernel has to wait anyway. With operands resident the run is all of K.
+        for (int sl = 0; sl < r.slices && ok;) {
+            int run_end = r.slices;
             if (r.gated) {
                 if (threadIdx.x == 0) {
                     int o = 1;
                     for (int j = j0; j <= j1 && o; ++j) o = wait_ready(a.gate, sl * r.shards + j);
-                    s_ok = o;
+                    int e = sl + 1;
+                    for (; o && e < r.slices; ++e) {
+                        int landed = 1;
+                        for (int j = j0; j <= j1 && landed; ++j) landed = peek_ready(a.gate, e * r.shards + j);
+                        if (!landed) break;
+                    }
+                    s_ok = o ? e : 0;      // 0: gave up; else the slice after the run
                 }
-                __syncthreads();           // also orders the slice's loads after the flag reads
-                ok = s_ok;
+                __syncthreads();           // also orders the run's loads after the flag reads
+                run_end = s_ok;
+                ok = run_end != 0;
                 __syncthreads();
             }
             if (ok) {
-                const int kw = ke - kb;                                   // the slice's columns: [kb, ke)
-                tile_accumulate<T>(ta, a.A + (int64_t)r.M * kb + row0 * kw, rows_valid,
-                                   a.Wt + (int64_t)col0 * a.K + kb, cols_valid, kw, a.K, kw, smem);
+                const int kb = r.k0[sl], ke = r.k0[run_end];              // the run's columns: [kb, ke)
+                SlicedA<T> pa(a.A, r.k0, r.M, row0, sl, rows_valid, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63);
+                tile_accumulate_from<T, NoHook, SlicedA<T>>(ta, pa, a.Wt + (int64_t)col0 * a.K + kb, cols_valid, a.K, ke - kb, smem);
+                sl = run_end;
             }
-            kb = ke;
         }
         if (threadIdx.x == 0) have_drawn = tile_walk_predraw(s_walk, r.ticket, r.grid, total_of, drawn);
         if (ok) tile_store<T>(ta, a.C + row0 * a.ldc + col0, rows_valid, cols_valid, a.ldc);
