@@ -45,12 +45,12 @@ HBM_PEAK_GBPS = 8000.0
 PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131086.7, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
     ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57468.6, "WRITE_SIZE": 12288.9},
-    ("cfg2_qkv8b", "gemm_resident2d_kernel<128x192>"): {"FETCH_SIZE": 57489.1, "WRITE_SIZE": 12448.2},
+    ("cfg2_qkv8b", "gemm_resident2d_kernel<128x192>"): {"FETCH_SIZE": 57499.1, "WRITE_SIZE": 12288.9},
     ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57449.0, "WRITE_SIZE": 12288.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 933880.8, "WRITE_SIZE": 116488.9},
-    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 838954.6, "WRITE_SIZE": 117349.1},
-    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 394091.1, "WRITE_SIZE": 33043.1},
-    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 500209.9, "WRITE_SIZE": 33658.0},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 937152.7, "WRITE_SIZE": 116594.3},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 848429.0, "WRITE_SIZE": 117460.9},
+    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 394321.3, "WRITE_SIZE": 32998.0},
+    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 478520.6, "WRITE_SIZE": 33602.3},
     ("cfg4_gemm_rs", "rs_reduce_kernel"): {"FETCH_SIZE": 131151.5, "WRITE_SIZE": 32768.0},      # profiles/rs_reduce_cfg4_gemm_rs.md
 }
 
