@@ -18,6 +18,8 @@ depend on how the tensor is blocked.
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 TENSOR_A = 0
@@ -69,16 +71,29 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def normal_bf16(seed: int, tensor_id: int, rows: int, cols: int, std: float = 1.0,
-                row0: int = 0, block_rows: int = 0) -> np.ndarray:
+                row0: int = 0, block_rows: int = 0, workers: int = 0) -> np.ndarray:
     """bf16 bits ``[rows, cols]`` of rows ``row0 .. row0+rows-1`` of an iid N(0, std^2) tensor
-    whose row length is ``cols``. Generated in row blocks to bound temporaries."""
+    whose row length is ``cols``. Generated in row blocks to bound temporaries; big tensors spread
+    their blocks over a few threads (the generator has no state, so the values do not change)."""
     out = np.empty((rows, cols), dtype=np.uint16)
     if block_rows <= 0:
-        block_rows = max(1, (1 << 22) // max(cols, 1))
-    for r in range(0, rows, block_rows):
+        block_rows = max(1, (1 << 18) // max(cols, 1))      # blocks that stay in the caches
+
+    def fill(r):
         nr = min(block_rows, rows - r)
         z = standard_normal_f64(seed, tensor_id, (row0 + r) * cols, nr * cols)
         out[r:r + nr] = f32_to_bf16_bits((z * std).astype(np.float32)).reshape(nr, cols)
+
+    starts = range(0, rows, block_rows)
+    if workers <= 0:
+        workers = min(8, os.cpu_count() or 1) if rows * cols >= (1 << 24) else 1
+    if workers > 1 and len(starts) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            list(pool.map(fill, starts))
+    else:
+        for r in starts:
+            fill(r)
     return out
 
 

@@ -2,7 +2,9 @@
 
 TEST INFRASTRUCTURE ONLY (see the package docstring). Everything here is integer bookkeeping or a
 one-line ratio taken from the paper's definitions; the HIP library has its own implementation
-and the tests compare the two.
+and the tests compare the two. The library's fitted schedule rules (piece count, communication
+shape, slice cut) have no counterpart here: their constants are timing fits of one machine, not
+something the paper defines, so the tests pin them by hand-worked cases instead.
 
 Notation: G shards of ``ms = M/G`` rows; each shard cut into ``c`` sub-chunks of ``m = ms/c`` rows
 (Sec. III-A: communication is decomposed one level below the shard); chunk id ``i = j*c + s`` is
@@ -153,47 +155,3 @@ def heuristic_paper(M: int, N: int, K: int, G: int, threshold: float, ratio: flo
     if x > ratio * threshold:
         return "hetero-unfused-1D"
     return "hetero-fused-1D"
-
-
-def pick_any(M: int, K: int, N: int, G: int) -> tuple[int, int]:
-    """(schedule, pieces) when column pieces are allowed too: this build's reading of the Sec. V-C choice of
-    communication shape. Column pieces (FINE_2D) when the output is at most about one round of 256x256
-    tiles over 256 CUs (M*N <= 2e7): 2 slices when the transfers are the longer side (N*G <= 8192), else 2,
-    4 from 1e11 flop, 8 from 4e11 flop (never more than there are k-tiles of 64); otherwise the resident row-piece schedule with :func:`pick_pieces`."""
-    if K % 64 == 0 and float(M) * float(N) <= 2.0e7:
-        flops = 2.0 * M * N * K
-        sl = 2 if N * G <= 8192 else 2 if flops < 1.0e11 else 4 if flops < 4.0e11 else 8
-        while sl > 1 and sl > K // 64:
-            sl //= 2
-        if sl > 1:
-            return FINE_2D, sl
-    return FINE_PERSISTENT, pick_pieces(M, K, N, G)
-
-
-def pick_widths(M: int, K: int, N: int, G: int, slices: int) -> list[int]:
-    """The k cut that goes with a column-piece answer (Sec. IV-A's overlap model read for unequal pieces: with the
-    transfers the longer side, what stays exposed is the last piece's GEMM): two slices of a transfer-bound
-    shape (N*G <= 8192) take three quarters and one quarter of the k-tiles (first = (3*kt + 2) // 4, at least one
-    tile each); anything else is as even as whole k-tiles allow, the first kt mod slices one tile wider."""
-    kt = K // 64
-    assert K % 64 == 0 and 1 <= slices <= kt
-    if slices == 2 and N * G <= 8192:
-        first = max(1, min((3 * kt + 2) // 4, kt - 1))
-        return [64 * first, 64 * (kt - first)]
-    return [64 * (kt // slices + (1 if s < kt % slices else 0)) for s in range(slices)]
-
-
-def pick_pieces(M: int, K: int, N: int, G: int, piece_flops: float = 2.5e10, min_rows: int = 256, max_pieces: int = 16) -> int:
-    """This build's reading of the Sec. V-C rule for the piece count: the largest power-of-two split of
-    a shard whose pieces still carry ``piece_flops`` flops each (OTB x MT of the piece GEMM), pieces of
-    at least ``min_rows`` rows, at most ``max_pieces`` pieces per shard."""
-    ms = M // G
-    t = piece_flops / (2.0 * N * K)
-    m = 1
-    while m * 2 <= t:
-        m *= 2
-    m = max(min_rows, min(m, ms))
-    c = max(1, min(max_pieces, ms // m))
-    while c > 1 and ms % c:
-        c //= 2
-    return c

@@ -38,10 +38,11 @@ static __device__ __forceinline__ uint32_t pack2_bf16_rne(float lo, float hi)
 
 // 64 lanes x 16 B from per-lane global addresses straight into 1 KiB of LDS starting at the
 // wave-uniform byte address lds_base (lane l lands at lds_base + 16 l). Issued through inline
-// assembly so that the waits are placed by hand (s_waitcnt vmcnt) and not widened by the compiler.
+// assembly so that the waits are placed by hand (s_waitcnt vmcnt) and not widened by the compiler;
+// M0 is declared clobbered, so the compiler keeps nothing of its own in it across the load.
 static __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 template <int N>
 static __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }

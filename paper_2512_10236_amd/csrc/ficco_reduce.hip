@@ -66,21 +66,29 @@ __global__ __launch_bounds__(256) void rs_reduce_kernel(ReduceLaunch r)
         const int s = t / tiles_per_piece, tt = t % tiles_per_piece;
         if (r.gated) {
             if (threadIdx.x == 0) {
-                // Only the first tile of a piece watches the G-1 transfers (their signals live in host
-                // memory: thousands of workgroups polling them would swamp the host link). It then raises
-                // the piece's word in device memory - the flag slot of the receiver's own piece, which no
-                // transfer ever uses - and the piece's other tiles wait on that word.
+                // The first tile of a piece watches the G-1 transfers (their signals live in host memory:
+                // thousands of workgroups polling them would swamp the host link). It then raises the
+                // piece's word in device memory - the flag slot of the receiver's own piece, which no
+                // transfer ever uses - and the piece's other tiles watch that word. No tile depends on
+                // another workgroup being resident: a tile that has not seen the word after a quarter of
+                // the wait limit (far longer than any piece takes to land; the watcher may never have
+                // been dispatched if other work holds CUs) watches the transfers itself and raises the
+                // word as well, so such a launch ends late instead of giving up.
                 const int mine = r.block * r.pieces + s;
-                int ok = 1;
-                if (tt == 0) {
+                uint32_t *word = const_cast<uint32_t *>(r.gate.flags) + (size_t)mine * kFlagStrideWords;
+                int ok = 1, watch = tt == 0;
+                if (!watch) {
+                    const uint64_t t0 = wall_clock64();
+                    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != r.gate.epoch) {
+                        if (__hip_atomic_load(r.gate.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) { ok = 0; break; }
+                        if (wall_clock64() - t0 > r.gate.spin_limit_ticks / 4) { watch = 1; break; }
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+                }
+                if (watch && ok) {
                     for (int p = 0; p < r.G && ok; ++p)
                         if (p != r.block) ok = piece_ready(r.gate, p * r.pieces + s);
-                    if (ok) __hip_atomic_store(const_cast<uint32_t *>(r.gate.flags) + (size_t)mine * kFlagStrideWords, r.gate.epoch,
-                                               __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-                } else {
-                    Gate word = r.gate;
-                    word.sig_value = nullptr;          // wait on the flag word, whatever the transfers are watched through
-                    ok = piece_ready(word, mine);
+                    if (ok) __hip_atomic_store(word, r.gate.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
                 }
                 s_ok = ok;
             }

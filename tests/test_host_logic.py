@@ -238,37 +238,115 @@ def test_ideal_overlap_matches_oracle(tc, tg, n):
     assert ficco.ficco_ideal_overlap_us(tc, tg, n) == pytest.approx(sch.ideal_overlap_time(tc, tg, n), rel=1e-14)
 
 
+# The fitted rules of the library (Sec. V-C read for this machine) are pinned by cases worked out by hand
+# from the rule as the header states it; no second implementation is consulted.
+#
+# Row pieces (ficco_pick_schedule): the resident schedule; piece rows m = the largest power of two with
+# 2*m*N*K <= 2.5e10 flop, at least 256 and at most one shard (M/shards rows); pieces per shard
+# c = shard rows / m, at most 16, halved until it divides the shard.
+ROW_PIECE_CASES = [
+    # 2NK = 58 720 256 -> 2.5e10 / 2NK = 425.7 -> m = 256; shard 2048 rows -> 8 pieces
+    ((16384, 8192, 3584, 8), 8),
+    # 2NK = 4 194 304 -> 5960 -> m = 4096, more than the 512-row shard -> 1 piece
+    ((4096, 4096, 512, 8), 1),
+    # 2NK = 234 881 024 -> 106 -> 64, raised to the 256-row minimum; shard 8192 rows -> 32, capped at 16
+    ((65536, 8192, 14336, 8), 16),
+    # the 128-row shard is below the 256-row minimum -> 1 piece
+    ((512, 1024, 1024, 4), 1),
+    # 2NK = 8 388 608 -> 2980 -> m = 2048; shard 3072 rows -> 3072 / 2048 = 1 piece
+    ((24576, 4096, 1024, 8), 1),
+    # 2NK = 6 291 456 -> 3973 -> m = 2048, more than the 1024-row shard -> 1 piece
+    ((8192, 4096, 768, 8), 1),
+    # 2NK = 29 360 128 -> 851 -> m = 512; shard 2048 rows -> 4 pieces
+    ((16384, 4096, 3584, 8), 4),
+    # 2NK = 117 440 512 -> 212.9 -> 128, raised to 256; shard 512 rows -> 2 pieces
+    ((4096, 4096, 14336, 8), 2),
+]
+
+
+@pytest.mark.parametrize("shape,pieces", ROW_PIECE_CASES)
+def test_pick_schedule_hand_cases(shape, pieces):
+    assert ficco.ficco_pick_schedule(*shape) == (ficco.FICCO_FINE_PERSISTENT, pieces)
+
+
 def test_pick_schedule_returns_a_valid_plan():
     for M in (4096, 16384, 65536):
         for K in (4096, 8192):
             for N in (512, 1024, 3584, 14336):
                 s, c = ficco.ficco_pick_schedule(M, K, N, 8)
-                assert s in (ficco.FICCO_SERIAL, ficco.FICCO_SHARD, ficco.FICCO_FINE_UNFUSED,
-                             ficco.FICCO_FINE_FUSED, ficco.FICCO_FINE_PERSISTENT)
-                assert c >= 1 and (M // 8) % c == 0
-                assert s == ficco.FICCO_FINE_PERSISTENT and c == sch.pick_pieces(M, K, N, 8)
+                assert s == ficco.FICCO_FINE_PERSISTENT
+                assert 1 <= c <= 16 and (M // 8) % c == 0 and (c == 1 or M // 8 // c >= 256)
                 plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO)
                 info = ficco.ficco_plan_info(plan)
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
 
 
-def test_pick_pieces_hand_cases():
-    # 2.5e10 flop per piece at N=3584, K=8192 is 426 rows; the power of two below it is 256
-    assert sch.pick_pieces(16384, 8192, 3584, 8) == 8          # 2048-row shards in 256-row pieces
-    assert sch.pick_pieces(4096, 4096, 512, 8) == 1            # threshold (5960 rows) exceeds the shard
-    assert sch.pick_pieces(65536, 8192, 14336, 8) == 16        # capped at 16 pieces
-    assert sch.pick_pieces(512, 1024, 1024, 4) == 1            # shard smaller than the minimum piece
-    for args in [(16384, 8192, 3584, 8), (4096, 4096, 512, 8), (65536, 8192, 14336, 8), (512, 1024, 1024, 4), (24576, 4096, 1024, 8)]:
-        assert ficco.ficco_pick_schedule(*args)[1] == sch.pick_pieces(*args)
+# Communication shape (ficco_pick_schedule_any): column pieces when the output has at most 2e7 elements
+# (about one round of 256x256 tiles over 256 CUs) and K has at least two k-tiles of 64; slices: 2 when
+# N*shards <= 8192 (the transfers are the longer side), else 2 below 1e11 flop, 4 below 4e11, 8 from
+# there, never more than K/64; otherwise the row-piece answer.
+ANY_SHAPE_CASES = [
+    # 8192*768 = 6.3e6 outputs; N*G = 6144 -> 2 slices
+    ((8192, 4096, 768, 8), (ficco.FICCO_FINE_2D, 2)),
+    # 4096*4096 = 1.7e7 outputs; N*G = 32768; 2*4096*4096*16384 = 5.5e11 flop -> 8 slices
+    ((4096, 16384, 4096, 8), (ficco.FICCO_FINE_2D, 8)),
+    # 4096*3584 = 1.5e7 outputs; 2*4096*3584*8192 = 2.4e11 flop -> 4 slices
+    ((4096, 8192, 3584, 8), (ficco.FICCO_FINE_2D, 4)),
+    # 16384*3584 = 5.9e7 outputs: several rounds of tiles -> row pieces, 8 per shard (worked above)
+    ((16384, 8192, 3584, 8), (ficco.FICCO_FINE_PERSISTENT, 8)),
+    # 4096*14336 = 5.9e7 outputs -> row pieces, 2 per shard (worked above)
+    ((4096, 4096, 14336, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # one k-tile: nothing to slice; 2NK = 65 536 -> m far above the 512-row shard -> 1 piece
+    ((4096, 64, 512, 8), (ficco.FICCO_FINE_PERSISTENT, 1)),
+    # two k-tiles, N*G = 4096 -> 2 slices
+    ((4096, 128, 512, 8), (ficco.FICCO_FINE_2D, 2)),
+    # 1.7e7 outputs, 1.4e11 flop, but N*G = 8192: the transfers are the longer side -> 2 slices
+    ((16384, 4096, 1024, 8), (ficco.FICCO_FINE_2D, 2)),
+    # 4096*4096 outputs, N*G = 32768, 2*4096*4096*2048 = 6.9e10 flop -> 2 slices
+    ((4096, 2048, 4096, 8), (ficco.FICCO_FINE_2D, 2)),
+    # either side of the limit: 4096*4880 = 19 988 480 outputs, 2*4096*4880*8192 = 3.3e11 flop -> 4 slices ...
+    ((4096, 8192, 4880, 8), (ficco.FICCO_FINE_2D, 4)),
+    # ... 4096*4888 = 20 021 248 outputs -> row pieces; 2NK = 80 084 992 -> 312 -> m = 256; shard 512 rows -> 2
+    ((4096, 8192, 4888, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+]
 
 
-def test_pick_schedule_any_matches_oracle_and_gives_valid_plans():
+@pytest.mark.parametrize("shape,answer", ANY_SHAPE_CASES)
+def test_pick_schedule_any_hand_cases(shape, answer):
+    assert ficco.ficco_pick_schedule_any(*shape) == answer
+
+
+# The cut of the k range (ficco_pick_slice_widths): two slices of a transfer-bound shape (N*shards <= 8192)
+# take three quarters and one quarter of the k-tiles (first = (3*kt + 2) // 4 k-tiles, at least one tile
+# each); everything else as even as whole k-tiles allow, the first kt mod slices one tile wider.
+SLICE_WIDTH_CASES = [
+    ((8192, 4096, 768, 8, 2), [3072, 1024]),               # kt = 64 -> 48 + 16 tiles
+    ((4096, 128, 512, 8, 2), [64, 64]),                    # kt = 2 -> (6+2)//4 = 2, capped at kt-1 = 1 tile
+    ((4096, 192, 512, 8, 2), [128, 64]),                   # kt = 3 -> (9+2)//4 = 2 tiles + 1
+    ((4096, 4096, 3584, 8, 4), [1024] * 4),
+    ((4096, 4096, 3584, 8, 2), [2048, 2048]),              # N*G = 28672: not transfer-bound
+    ((64, 704, 8, 8, 4), [192, 192, 192, 128]),            # kt = 11 = 4*2 + 3: three slices of 3 tiles, one of 2
+    ((4096, 8192, 1024, 8, 2), [6144, 2048]),              # N*G = 8192 counts as transfer-bound; kt = 128 -> 96 + 32
+]
+
+
+@pytest.mark.parametrize("args,widths", SLICE_WIDTH_CASES)
+def test_pick_slice_widths_hand_cases(args, widths):
+    assert ficco.ficco_pick_slice_widths(*args) == widths
+
+
+def test_pick_slice_widths_rejects_bad_arguments():
+    for bad in ((4096, 4096, 512, 8, 0), (4096, 100, 512, 8, 1), (4096, 128, 512, 8, 3)):
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_pick_slice_widths(*bad)
+
+
+def test_pick_schedule_any_gives_valid_plans_with_its_own_cut():
     for M in (512, 4096, 8192, 16384, 65536):
         for K in (64, 128, 4096, 8192, 16384):
             for N in (8, 512, 768, 1024, 3584, 4096, 14336):
                 s, c = ficco.ficco_pick_schedule_any(M, K, N, 8)
-                assert (s, c) == sch.pick_any(M, K, N, 8), (M, K, N)
                 plan = ficco.ficco_plan(M, K, N, 8, c, s)          # whatever it answers can be planned
                 ficco.ficco_destroy(plan)
                 plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO_ANY)
@@ -277,32 +355,11 @@ def test_pick_schedule_any_matches_oracle_and_gives_valid_plans():
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
                 if s == ficco.FICCO_FINE_2D:
-                    assert widths == ficco.ficco_pick_slice_widths(M, K, N, 8, c) == sch.pick_widths(M, K, N, 8, c)
-                    assert sum(widths) == K and all(w > 0 and w % 64 == 0 for w in widths)
-                if s != ficco.FICCO_FINE_2D:
+                    assert M * N <= 2e7 and 2 <= c <= K // 64
+                    assert widths == ficco.ficco_pick_slice_widths(M, K, N, 8, c)
+                    assert len(widths) == c and sum(widths) == K and all(w > 0 and w % 64 == 0 for w in widths)
+                else:
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
-
-
-def test_pick_any_hand_cases():
-    # the bench's workloads: small outputs take column pieces, large ones row pieces
-    assert sch.pick_any(8192, 4096, 768, 8) == (sch.FINE_2D, 2)            # 6.3e6 outputs, 5.2e10 flop
-    assert sch.pick_any(4096, 16384, 4096, 8) == (sch.FINE_2D, 8)          # 1.7e7 outputs, 5.5e11 flop
-    assert sch.pick_any(4096, 8192, 3584, 8) == (sch.FINE_2D, 4)           # 1.5e7 outputs, 2.4e11 flop
-    assert sch.pick_any(16384, 8192, 3584, 8) == (sch.FINE_PERSISTENT, 8)  # 5.9e7 outputs: several rounds of tiles
-    assert sch.pick_any(4096, 4096, 14336, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 4096, 14336, 8))
-    assert sch.pick_any(4096, 64, 512, 8) == (sch.FINE_PERSISTENT, sch.pick_pieces(4096, 64, 512, 8))   # one k-tile: nothing to slice
-    assert sch.pick_any(4096, 128, 512, 8) == (sch.FINE_2D, 2)
-    assert sch.pick_any(16384, 4096, 1024, 8) == (sch.FINE_2D, 2)          # 1.4e11 flop, but the transfers are the longer side
-    # the cut: transfer-bound pairs of slices three to one, the rest even
-    assert sch.pick_widths(8192, 4096, 768, 8, 2) == [3072, 1024]          # what the bench found by screening
-    assert sch.pick_widths(4096, 128, 512, 8, 2) == [64, 64]
-    assert sch.pick_widths(4096, 192, 512, 8, 2) == [128, 64]
-    assert sch.pick_widths(4096, 4096, 3584, 8, 4) == [1024] * 4
-    assert sch.pick_widths(4096, 4096, 3584, 8, 2) == [2048, 2048]         # N*G = 28672: not transfer-bound
-    assert sch.pick_widths(64, 704, 8, 8, 4) == [192, 192, 192, 128]
-    for bad in ((4096, 4096, 512, 8, 0), (4096, 100, 512, 8, 1), (4096, 128, 512, 8, 3)):
-        with pytest.raises(ficco.FiccoError):
-            ficco.ficco_pick_slice_widths(*bad)
 
 
 # ------------------------------------------------------------------ expert-parallel (grouped) plans

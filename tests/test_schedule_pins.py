@@ -105,9 +105,11 @@ def test_heuristic_rule_structure():
     T = 1e9
     assert sch.heuristic_paper(4096, 1024, 8192, 8, T) == "uniform-fused-2D"     # M <= K
     assert sch.heuristic_paper(8192, 1024, 8192, 8, T) == "uniform-fused-2D"
-    # step GEMM flops = 2*(M/8)*N*K
-    M, N, K = 16384, 512, 4096                      # 2*2048*512*4096 = 8.6e9
-    x = 2 * (M // 8) * N * K
+    # Sec. IV-B/C by hand for the step GEMM (2048 x 512 x 4096, bf16): ops 2*2048*512*4096 = 8 589 934 592;
+    # bytes 2*(2048*4096 + 512*4096 + 2048*512) = 23 068 672; OTB = 372.36...; OTB x MT = the op count
+    M, N, K = 16384, 512, 4096
+    x = 8589934592
+    assert sch.mt_bytes(M // 8, N, K) == 23068672 and sch.otb(M // 8, N, K) == pytest.approx(372.3636, rel=1e-6)
     assert sch.heuristic_paper(M, N, K, 8, x * 1.01) == "uniform-fused-1D"
     assert sch.heuristic_paper(M, N, K, 8, x / 2) == "hetero-fused-1D"
     assert sch.heuristic_paper(M, N, K, 8, x / 5.01) == "hetero-unfused-1D"
