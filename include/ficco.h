@@ -461,6 +461,28 @@ int ficco_static_descriptors(int64_t m, int64_t N, int64_t K, double *otb, doubl
 /* Ideal-overlap time (Sec. IV-A): n pieces, times scale exactly with the split. Host-only. */
 double ficco_ideal_overlap_us(double t_comm_us, double t_gemm_us, int n);
 
+/*
+ * For callers that cannot allocate device memory - code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: C_dev[M,N] = A_dev[M,K] * W_dev[K,N] with every operand already in
+ * device memory, by the resident kernel, enqueued on `stream` (hipStream_t). It is what ficco_run()
+ * does for a FICCO_FINE_PERSISTENT plan of one shard and one piece in FICCO_MODE_GEMM_ONLY, with the
+ * same tile and tile order, so the result is the same bit for bit; but no plan is needed and the call
+ * makes no device allocation, now or later: the kernel's ticket counters, its status word, its arrival
+ * table and the packed copy of the weight ([N,K], rewritten by every call) live in one fixed array in
+ * the library's device image, of FICCO_STATIC_MAX_WEIGHT_BYTES + 4096 bytes, which every GPU the
+ * library runs on holds until the process ends. The call clears what must start at zero with a small
+ * kernel (no memset node is recorded if the stream is being captured), packs the weight and launches
+ * the GEMM, three kernels on `stream`, and returns without waiting.
+ * Shape rules: M, K, N >= 1, K % 64 == 0, N % 8 == 0, each below 2^31, and K*N*2 bytes at most
+ * FICCO_STATIC_MAX_WEIGHT_BYTES (FICCO_ERR_SHAPE otherwise; e.g. K = 4096 with N up to 1024).
+ * All calls on one GPU share that GPU's array: two calls whose kernels overlap on one GPU (different
+ * streams, or the same call from two threads) race; calls on one stream are ordered and safe. The
+ * caller owns A_dev, W_dev and C_dev. FICCO_ERR_ARG for a null or non-device pointer.
+ */
+#define FICCO_STATIC_MAX_WEIGHT_BYTES (8u << 20)
+int ficco_gemm_static(int64_t M, int64_t K, int64_t N, const void *A_dev, const void *W_dev, void *C_dev,
+                      void *stream);
+
 void ficco_destroy(ficco_plan_t *plan);      /* waits for the plan's runs, frees what it owns */
 
 const char *ficco_strerror(int status);

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libficco.so")
-SOURCES = ["ficco_gemm.hip", "ficco_reduce.hip", "ficco_plan.hip", "ficco_engines.hip", "ficco_api.hip"]
+SOURCES = ["ficco_gemm.hip", "ficco_reduce.hip", "ficco_plan.hip", "ficco_engines.hip", "ficco_api.hip", "ficco_static.hip"]
 HEADERS = ["ficco_internal.h", "ficco_plan.h", os.path.join("..", "..", "include", "ficco.h")]
 
 # packed fp32 instructions are switched off for all device code (they have misbehaved on the test machines)

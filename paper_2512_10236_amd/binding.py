@@ -16,6 +16,7 @@ FICCO_ERR_HIP, FICCO_ERR_TIMEOUT, FICCO_ERR_STATE = -4, -5, -6
 FICCO_SERIAL, FICCO_SHARD, FICCO_FINE_UNFUSED, FICCO_FINE_FUSED, FICCO_FINE_PERSISTENT, FICCO_FINE_2D = 0, 1, 2, 3, 4, 5
 FICCO_AUTO = 100
 FICCO_AUTO_ANY = 101
+FICCO_STATIC_MAX_WEIGHT_BYTES = 8 << 20
 FICCO_DIR_AG_GEMM, FICCO_DIR_GEMM_RS = 0, 1
 FICCO_ORDER_STEP_MAJOR, FICCO_ORDER_SHARD_MAJOR, FICCO_ORDER_CUSTOM = 0, 1, 2
 FICCO_MODE_PAIR, FICCO_MODE_GEMM_ONLY, FICCO_MODE_COPY_ONLY, FICCO_MODE_INDEPENDENT = 0, 1, 2, 3
@@ -67,7 +68,7 @@ class ficco_losses_t(C.Structure):
 
 
 EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_chain", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
-           "ficco_pack_weight", "ficco_run", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
+           "ficco_pack_weight", "ficco_run", "ficco_gemm_static", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
            "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
@@ -102,6 +103,7 @@ def load():
     lib.ficco_plan_arrival.argtypes = [vp, i32p, i32p, C.c_int]
     lib.ficco_pack_weight.argtypes = [vp, vp, vp]
     lib.ficco_run.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp]
+    lib.ficco_gemm_static.argtypes = [i64, i64, i64, vp, vp, vp, vp]
     lib.ficco_graph_capture.argtypes = [vp, vp, vp, vp, vp, C.POINTER(vp)]
     lib.ficco_graph_launch.argtypes = [vp, vp]
     lib.ficco_rs_reduce.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
@@ -228,6 +230,11 @@ def ficco_run(plan, A_src, A_dev, W_dev, C_dev, peer_out, compute_stream, copy_s
         peers = (C.c_void_p * len(peer_out))(*[_ptr(p) for p in peer_out])
     return _ok(load().ficco_run(plan, _ptr(A_src), _ptr(A_dev), _ptr(W_dev), _ptr(C_dev), peers,
                                 _ptr(compute_stream), _ptr(copy_stream)), "ficco_run")
+
+
+def ficco_gemm_static(M, K, N, A_dev, W_dev, C_dev, stream):
+    """The resident GEMM over operands in place, without any device allocation (see include/ficco.h)."""
+    return _ok(load().ficco_gemm_static(M, K, N, _ptr(A_dev), _ptr(W_dev), _ptr(C_dev), _ptr(stream)), "ficco_gemm_static")
 
 
 def ficco_graph_capture(plan, A_src, A_dev, W_dev, C_dev, peer_out):

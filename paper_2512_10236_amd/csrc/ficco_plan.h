@@ -175,6 +175,7 @@ inline Extent piece_extent(const ficco_plan_t *p, int chunk)
 
 // ---- plan construction and launches (ficco_plan.hip)
 int build_lists(ficco_plan_t *p);
+int choose_tile(const ficco_plan_t *p, int cus);
 int finalize(ficco_plan_t *p);
 void release(ficco_plan_t *p);
 int make_events(std::vector<hipEvent_t> &v, size_t n);
