@@ -17,8 +17,16 @@
 // schedules.
 #include "ficco_internal.h"
 #include <stdlib.h>
+#include <type_traits>
 
 namespace ficco {
+
+#ifdef FICCO_PROBE
+// profiling build only: per-wavefront-slot sums of {cycles waiting for loads, cycles at the barrier, cycles per k-step, k-steps}
+__device__ unsigned long long g_probe[4][4];
+__device__ unsigned long long g_probe_lgkm[4];
+#define PROBE_T() clock64()
+#endif
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -36,13 +44,21 @@ static __device__ __forceinline__ uint32_t pack2_bf16_rne(float lo, float hi)
     return (ra & 0xFFFFu) | (rb << 16);
 }
 
-// 64 lanes x 16 B from per-lane global addresses straight into 1 KiB of LDS starting at the
-// wave-uniform byte address lds_base (lane l lands at lds_base + 16 l). Issued through inline
-// assembly so that the waits are placed by hand (s_waitcnt vmcnt) and not widened by the compiler;
-// M0 is declared clobbered, so the compiler keeps nothing of its own in it across the load.
-static __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_base)
+// 64 lanes x 16 B from global memory straight into 1 KiB of LDS starting at the wave-uniform byte address
+// lds_base (lane l lands at lds_base + 16 l). The global address is a wave-uniform 64-bit base (scalar
+// registers) plus a per-lane 32-bit byte offset, so that stepping along k costs scalar additions only and a
+// load needs one vector register. Issued through inline assembly so that the waits are placed by hand
+// (s_waitcnt vmcnt) and not widened by the compiler; M0 is declared clobbered, so the compiler keeps nothing
+// of its own in it across the load.
+static __device__ __forceinline__ void load_to_lds_16(const void *base, uint32_t lane_off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+    // (the base is the same in every lane by construction; the compiler cannot always see that - where it
+    // comes out of a table in memory, say - and is told so, half by half)
+    const uint64_t b = (uint64_t)base;
+    const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_off), "s"(ub), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory", "m0");
 }
 template <int N>
 static __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
@@ -74,11 +90,10 @@ struct TileCfg {
 // LDS holds a ring of NSTAGE stages; a stage is BM + BN rows of 128 B (64 k values), the 16-byte
 // slot kc of row r stored at slot kc ^ ((r >> 1) & 7) so that the 16 lanes of a ds_read_b128 phase
 // hit 64 different banks. Loads go global -> LDS directly (no staging registers): a wavefront
-// instruction fills 8 rows, lane l fetching the slot that belongs at position l. One barrier per
-// k-step: after it, the loads of k-tile kt+NSTAGE-1 are issued into the stage that k-tile kt-1 just
-// left (spread over the first half of the step so that they do not hold up MFMA issue). The big
-// tile only has room for two stages; the smaller tiles use three or four, which is what keeps
-// launches with few workgroups (small pieces) from being bound by load latency.
+// instruction fills 8 rows, lane l fetching the slot that belongs at position l. The big tile only
+// has room for two stages; the smaller tiles use three or four, which is what keeps launches with
+// few workgroups (small pieces) from being bound by load latency. The loop itself is described in
+// tile_accumulate_from.
 template <class T>
 struct TileAcc {
     f32x16_t acc[T::FN][T::FM];
@@ -99,45 +114,48 @@ struct NoHook {
     __device__ __forceinline__ void operator()() const {}
 };
 
-// Adds A[rows, k0 .. k0+K) * W[k0 .. k0+K, cols) to the tile's accumulators; a_tile / wt_tile point
-// at column k0 of the tile's first row of A / Wt. Calling it for consecutive k ranges in ascending
-// order gives exactly the accumulation sequence of one call over the whole range.
-// `after_first_wait` runs once, right after the first k-step's wait and barrier: vector memory
-// operations complete in issue order, so by then every store that any wavefront of the workgroup
-// issued before this call has been performed.
-// Where the loader finds its part of k-tile kt of A. PlainA: one row-major block [rows, K] with row stride lda
-// (a per-lane pointer per load, advanced by whole k-tiles).
+// Byte offset, from the first row of the tile, of what lane `lane` fetches for 8-row block `blk` of a stage:
+// row blk*8 + lane/8 (clamped to the last row that exists), 16-byte slot (lane%8) ^ ((row>>1)&7) of its k-tile.
+static __device__ __forceinline__ uint32_t lane_offset(int blk, int lane, int rows_valid, int64_t row_stride_elems)
+{
+    const int row = blk * 8 + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    const int rr = row < rows_valid ? row : rows_valid - 1;
+    return (uint32_t)(((int64_t)rr * row_stride_elems + kc * 8) * 2);
+}
+
+// Where the loader finds its part of k-tile kt of A. PlainA: one row-major block [rows, K] with row stride lda:
+// a wave-uniform base that moves along k, and one per-lane byte offset per load (the tile's rows must span less
+// than 4 GiB, which the shape rules guarantee: at most 256 rows of at most 2^31 elements... of 2 bytes - the
+// launchers refuse K >= 2^23).
 template <class T>
 struct PlainA {
-    const uint16_t *ga[T::AB];
-    __device__ __forceinline__ PlainA(const uint16_t *a_tile, int rows_valid, int64_t lda, int wave, int lane)
+    uint32_t off[T::AB];
+    const uint16_t *base;
+    __device__ __forceinline__ PlainA(const uint16_t *a_tile, int rows_valid, int64_t lda, int wave, int lane) : base(a_tile)
     {
 #pragma unroll
-        for (int i = 0; i < T::AB; ++i) {
-            const int row = (wave * T::AB + i) * 8 + (lane >> 3);
-            const int kc = (lane & 7) ^ ((row >> 1) & 7);
-            const int rr = row < rows_valid ? row : rows_valid - 1;
-            ga[i] = a_tile + (int64_t)rr * lda + kc * 8;
-        }
+        for (int i = 0; i < T::AB; ++i) off[i] = lane_offset(wave * T::AB + i, lane, rows_valid, lda);
     }
     __device__ __forceinline__ void seek(int) {}
-    __device__ __forceinline__ const uint16_t *at(int i, int kt) const { return ga[i] + (int64_t)kt * kBK; }
+    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)kt * kBK; }
 };
 
 // SlicedA: a run of consecutive k slices of the K-sliced layout (slice s = the [M][k0[s+1]-k0[s]] block that
 // starts at element M*k0[s]), read as one k range. The issue stream walks the k-tiles in ascending order;
-// `seek` moves to the slice a k-tile lies in and only then rebuilds the per-lane pointers for that slice's
-// base and row stride, so that inside a slice a load costs what it costs with PlainA.
+// `seek` moves to the slice a k-tile lies in and only then rebuilds the base and the per-lane offsets for that
+// slice's row stride, so that inside a slice a load costs what it costs with PlainA.
 template <class T>
 struct SlicedA {
-    const uint16_t *ga[T::AB];
+    uint32_t off[T::AB];
+    const uint16_t *base;
     const uint16_t *A;
     const int32_t *k0;
     int64_t M, row0;
     int sl, kt_begin, kt_end, rows_valid, wave, lane;
     __device__ __forceinline__ SlicedA(const uint16_t *A_, const int32_t *k0_, int64_t M_, int64_t row0_, int first_slice, int rows_valid_,
                                        int wave_, int lane_)
-        : A(A_), k0(k0_), M(M_), row0(row0_), sl(first_slice - 1), kt_begin(0), kt_end(0), rows_valid(rows_valid_), wave(wave_), lane(lane_)
+        : base(A_), A(A_), k0(k0_), M(M_), row0(row0_), sl(first_slice - 1), kt_begin(0), kt_end(0), rows_valid(rows_valid_), wave(wave_), lane(lane_)
     {
     }
     __device__ __forceinline__ void seek(int kt)
@@ -147,18 +165,23 @@ struct SlicedA {
             const int kb = k0[sl], kw = k0[sl + 1] - kb;
             kt_begin = kt_end;
             kt_end += kw / kBK;
-            const uint16_t *base = A + M * kb + row0 * kw;
+            base = A + M * kb + row0 * kw;
 #pragma unroll
-            for (int i = 0; i < T::AB; ++i) {
-                const int row = (wave * T::AB + i) * 8 + (lane >> 3);
-                const int kc = (lane & 7) ^ ((row >> 1) & 7);
-                const int rr = row < rows_valid ? row : rows_valid - 1;
-                ga[i] = base + (int64_t)rr * kw + kc * 8;
-            }
+            for (int i = 0; i < T::AB; ++i) off[i] = lane_offset(wave * T::AB + i, lane, rows_valid, kw);
         }
     }
-    __device__ __forceinline__ const uint16_t *at(int i, int kt) const { return ga[i] + (int64_t)(kt - kt_begin) * kBK; }
+    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)(kt - kt_begin) * kBK; }
 };
+
+// Waits until at most `load_groups` k-tiles' worth of this wavefront's loads are outstanding (the counter wants
+// a constant, hence the ladder; load_groups <= 2 with rings of at most four stages).
+template <class T>
+static __device__ __forceinline__ void wait_issued_after(int load_groups)
+{
+    if (load_groups >= 2) wait_vmem<2 * T::LOADS>();
+    else if (load_groups == 1) wait_vmem<T::LOADS>();
+    else wait_vmem<0>();
+}
 
 template <class T, class Hook = NoHook, class AddrA = PlainA<T>>
 static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, AddrA &pa,
@@ -173,25 +196,15 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
-    const uint16_t *gb[T::BB];
+    uint32_t offb[T::BB];                  // per-lane byte offsets of the W loads from the tile's first row
 #pragma unroll
-    for (int i = 0; i < T::BB; ++i) {
-        const int row = (wave * T::BB + i) * 8 + (lane >> 3);
-        const int kc = (lane & 7) ^ ((row >> 1) & 7);
-        const int rr = row < cols_valid ? row : cols_valid - 1;
-        gb[i] = wt_tile + (int64_t)rr * ldw + kc * 8;
-    }
-    // quarter q of the loads of k-tile kt into `stage` (k-tiles are issued in ascending order)
-    auto issue_part = [&](int stage, int kt, int q) {
-        const uint32_t sa = lds0 + stage * T::STAGE + wave * T::AB * 1024;
-        const uint32_t sb = lds0 + stage * T::STAGE + T::A_STAGE + wave * T::BB * 1024;
-        if (q == 0) pa.seek(kt);
-#pragma unroll
-        for (int i = 0; i < T::AB; ++i)
-            if ((i & 3) == q || (T::AB < 4 && q == 0)) load_to_lds_16(pa.at(i, kt), sa + i * 1024);
-#pragma unroll
-        for (int i = 0; i < T::BB; ++i)
-            if ((i & 3) == q || (T::BB < 4 && q == 0)) load_to_lds_16(gb[i] + (int64_t)kt * kBK, sb + i * 1024);
+    for (int i = 0; i < T::BB; ++i) offb[i] = lane_offset(wave * T::BB + i, lane, cols_valid, ldw);
+    // load l of the wavefront's LOADS loads of k-tile kt into `stage`: first the AB blocks of A, then the BB blocks
+    // of W (k-tiles are issued in ascending order; load 0 of a k-tile comes first)
+    auto issue_load = [&](int stage, int kt, int l) {
+        if (l == 0) pa.seek(kt);
+        if (l < T::AB) load_to_lds_16(pa.at(kt), pa.off[l], lds0 + stage * T::STAGE + (wave * T::AB + l) * 1024);
+        else load_to_lds_16(wt_tile + (int64_t)kt * kBK, offb[l - T::AB], lds0 + stage * T::STAGE + T::A_STAGE + (wave * T::BB + (l - T::AB)) * 1024);
     };
 
     // LDS -> fragment addresses: lane reads row (lane%32) of a 32-row block, k-slot 2*kk + lane/32,
@@ -202,69 +215,134 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
 
     const int KT = K / kBK;
     constexpr int D = T::NSTAGE - 1;      // prefetch distance in k-tiles
+    bf16x8_t fa[2][T::FM], fb[2][T::FN];
+    // fragment q of the FM + FN fragments of sub-step kk of the k-tile in the stage at `base`, into buffer n.
+    // Order of arrival = order of first use by the MFMAs below (row block 0, then every column block, then the
+    // other row blocks).
+    auto read_frag = [&](const unsigned char *base, int kk, int n, int q) {
+        const int slot = ((2 * kk + fh) ^ fs) << 4;
+        if (q == 0) fa[n][0] = *reinterpret_cast<const bf16x8_t *>(base + a_base + slot);
+        else if (q <= T::FN) fb[n][q - 1] = *reinterpret_cast<const bf16x8_t *>(base + b_base + (q - 1) * 4096 + slot);
+        else fa[n][q - T::FN] = *reinterpret_cast<const bf16x8_t *>(base + a_base + (q - T::FN) * 4096 + slot);
+    };
+    constexpr int NM = T::FM * T::FN;           // MFMAs per sub-step
+    constexpr int NR = T::FM + T::FN;           // fragment reads per sub-step
+    constexpr int H1 = T::LOADS / 2, H2 = T::LOADS - H1;      // the two halves of a k-tile's loads
+
+    // ---- prologue: the first D k-tiles' loads, the first barrier, the first fragments
 #pragma unroll
     for (int d = 0; d < D; ++d)
         if (d < KT) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) issue_part(d, d, q);
+            for (int l = 0; l < T::LOADS; ++l) issue_load(d, d, l);
         }
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt % T::NSTAGE;
-        // This wavefront's part of k-tile kt must have landed; the k-tiles kt+1 .. kt+D-1 that exist may
-        // still be in flight (loads complete in order, so a count is enough) ...
-        {
-            const int inflight = min(D - 1, KT - 1 - kt);
-            if (D >= 3 && inflight == 2) wait_vmem<2 * T::LOADS>();
-            else if (D >= 2 && inflight == 1) wait_vmem<T::LOADS>();
-            else wait_vmem<0>();
-        }
-        wg_barrier();                      // ... and so has everyone else's; the stage of k-tile kt-1 is free again
-        if (kt == 0) after_first_wait();
-        const bool more = kt + D < KT;
-        const int nxt = (kt + D) % T::NSTAGE;
-        const unsigned char *base = smem + cur * T::STAGE;
-        bf16x8_t fa[2][T::FM], fb[2][T::FN];
-        {
-            const int slot = ((0 + fh) ^ fs) << 4;
+    wait_issued_after<T>(min(D - 1, KT - 1));
+    wg_barrier();                          // B_0: k-tile 0 has landed for everyone
+    after_first_wait();
+    if (D < KT) {
 #pragma unroll
-            for (int i = 0; i < T::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t *>(base + a_base + i * 4096 + slot);
-#pragma unroll
-            for (int j = 0; j < T::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t *>(base + b_base + j * 4096 + slot);
-        }
-#pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            const int c = kk & 1, n = c ^ 1;
-            if (more && kk < 2) {
-                issue_part(nxt, kt + D, 2 * kk);
-                issue_part(nxt, kt + D, 2 * kk + 1);
-            }
-            if (kk < 3) {
-                const int slot = ((2 * (kk + 1) + fh) ^ fs) << 4;
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i) fa[n][i] = *reinterpret_cast<const bf16x8_t *>(base + a_base + i * 4096 + slot);
-#pragma unroll
-                for (int j = 0; j < T::FN; ++j) fb[n][j] = *reinterpret_cast<const bf16x8_t *>(base + b_base + j * 4096 + slot);
-            }
-            // operands swapped on purpose: D[n][m], so each lane ends up with 4 consecutive
-            // columns of one C row (8-byte stores in the epilogue)
-#pragma unroll
-            for (int j = 0; j < T::FN; ++j)
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][j], fa[c][i], acc[j][i], 0, 0, 0);
-            if (kk < 3) {
-                // one LDS read, then a few MFMAs: the next fragments arrive under the current MFMAs
-#pragma unroll
-                for (int q = 0; q < T::FM + T::FN; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, (T::FM * T::FN) / (T::FM + T::FN) > 0 ? (T::FM * T::FN) / (T::FM + T::FN) : 1, 0);
-                }
-            }
-        }
+        for (int l = 0; l < H1; ++l) issue_load(D % T::NSTAGE, D, l);
     }
+#pragma unroll
+    for (int q = 0; q < NR; ++q) read_frag(smem, 0, 0, q);
 
-    wg_barrier();                          // every wavefront is done with the ring before it is refilled
+    // ---- the loop, one k-tile per turn, rotated by one sub-step: a turn runs sub-steps 0..2 of k-tile k out of
+    // the fragments read one sub-step earlier, then waits for k-tile k+1 and for its own LDS reads and meets the
+    // others at barrier B_{k+1} (k-tile k+1 has landed for everyone; everyone is done with the stage of k-tile k,
+    // which the loads of k-tile k+1+D may now overwrite), and only then runs sub-step 3, whose 16 MFMAs need
+    // registers only: under them go the first half of the loads of k-tile k+1+D and the reads of the first
+    // fragments of k-tile k+1, so that neither the barrier nor the LDS latency behind it leaves the MFMA pipe
+    // empty. The second half of those loads follows under sub-step 0 of the next turn. Every MFMA of the big
+    // tiles is followed by at most one load or one read, and the order is pinned (sched_barrier), so that a
+    // wavefront never issues a burst of loads: the four wavefronts share one address path, which takes about 16
+    // cycles per load, and whatever a wavefront issues between two MFMAs beyond the 32 cycles one of them takes
+    // leaves the MFMA pipe empty.
+#ifdef FICCO_PROBE
+    long long probe_vm = 0, probe_bar = 0, probe_step = 0, probe_last = 0, probe_n = 0, probe_lgkm = 0;
+#endif
+    // (A turn is compiled in two forms: the steady state, where every condition is known and the body has no
+    // branch, and a general one for the first and last turns of a tile.)
+    auto turn = [&](int k, auto l1st, auto l2nd, auto rn, auto steady_c) __attribute__((always_inline)) {
+        constexpr bool steady = decltype(steady_c)::value;
+        const unsigned char *cur = smem + (k % T::NSTAGE) * T::STAGE;
+        const unsigned char *nxt = smem + ((k + 1) % T::NSTAGE) * T::STAGE;
+        const int free_stage = k % T::NSTAGE;           // after B_{k+1}
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int c = kk & 1, n = c ^ 1;
+            if (kk == 3) {
+                // everything this wavefront reads from the stage of k-tile k has arrived in registers
+#ifdef FICCO_PROBE
+                const long long pt0 = PROBE_T();
+#endif
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#ifdef FICCO_PROBE
+                const long long pt1 = PROBE_T();
+#endif
+                // ... and k-tile k+1 has landed: what may still be in flight are the loads issued after its own,
+                // those of the k-tiles k+2 .. k+D that exist (memory operations complete in issue order)
+                if constexpr (steady) wait_vmem<(D - 1) * T::LOADS>();
+                else if (rn) wait_issued_after<T>(min(D - 1, KT - 2 - k));
+#ifdef FICCO_PROBE
+                const long long pt2 = PROBE_T();
+#endif
+                wg_barrier();
+#ifdef FICCO_PROBE
+                const long long pt3 = PROBE_T();
+                if (lane == 0) {
+                    probe_vm += pt2 - pt1; probe_bar += pt3 - pt2; probe_lgkm += pt1 - pt0;
+                    if (probe_last) probe_step += pt0 - probe_last;
+                    probe_last = pt0; ++probe_n;
+                }
+#endif
+            }
+#pragma unroll
+            for (int t = 0; t < NM; ++t) {
+                const int i = t / T::FN, j = t % T::FN;
+                // operands swapped on purpose: D[n][m], so each lane ends up with 4 consecutive
+                // columns of one C row (8-byte stores in the epilogue)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][j], fa[c][i], acc[j][i], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // under this MFMA: the reads and loads whose turn it is. Reads of the next sub-step's fragments go
+                // behind the even MFMAs, loads behind the odd ones, where there are enough MFMAs to keep them apart.
+#pragma unroll
+                for (int q = 0; q < NR; ++q)
+                    if (q * NM / NR == t) {
+                        if (kk < 3) read_frag(cur, kk + 1, n, q);
+                        else if (rn) read_frag(nxt, 0, n, q);
+                    }
+                if (kk == 3 && l1st) {
+#pragma unroll
+                    for (int l = 0; l < H1; ++l)
+                        if (min(NM - 1, l * NM / H1 + NM / H1 / 2) == t) issue_load(free_stage, k + 1 + D, l);
+                }
+                if (kk == 0 && l2nd) {
+#pragma unroll
+                    for (int l = 0; l < H2; ++l)
+                        if (min(NM - 1, l * NM / H2 + NM / H2 / 2) == t) issue_load((k + D) % T::NSTAGE, k + D, H1 + l);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    int k = 0;
+    for (; k + 1 < D && k + 1 + D < KT; ++k) turn(k, true, true, true, no);    // (rings of three or four stages only)
+    for (; k + 1 + D < KT; ++k) turn(k, yes, yes, yes, yes);
+    for (; k < KT; ++k) turn(k, false, k + D < KT, k + 1 < KT, no);
+    // (the barrier before the last sub-step was the last one: every wavefront had finished reading the ring)
+#ifdef FICCO_PROBE
+    if (lane == 0) {
+        atomicAdd(&g_probe[wave][0], (unsigned long long)probe_vm);
+        atomicAdd(&g_probe[wave][1], (unsigned long long)probe_bar);
+        atomicAdd(&g_probe[wave][2], (unsigned long long)probe_step);
+        atomicAdd(&g_probe[wave][3], (unsigned long long)probe_n);
+        atomicAdd(&g_probe_lgkm[wave], (unsigned long long)probe_lgkm);
+    }
+#endif
 }
+
 
 template <class T, class Hook = NoHook>
 static __device__ __forceinline__ void tile_accumulate(TileAcc<T> &ta, const uint16_t *__restrict__ a_tile, int rows_valid,
@@ -994,6 +1072,20 @@ static int resident_grid_t(int device)
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return per_cu * cus;
 }
+
+#ifdef FICCO_PROBE
+extern "C" int ficco_probe_read(unsigned long long *out16, int clear)
+{
+    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_probe), sizeof(unsigned long long) * 16) != hipSuccess) return -1;
+    if (hipMemcpyFromSymbol(out16 + 16, HIP_SYMBOL(g_probe_lgkm), sizeof(unsigned long long) * 4) != hipSuccess) return -1;
+    if (clear) {
+        unsigned long long z[16] = {0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_probe), z, sizeof(z)) != hipSuccess) return -1;
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_probe_lgkm), z, sizeof(unsigned long long) * 4) != hipSuccess) return -1;
+    }
+    return 0;
+}
+#endif
 
 hipError_t launch_gemm(int tile, const GemmLaunch &a, hipStream_t s)
 {
