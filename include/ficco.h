@@ -77,14 +77,15 @@ typedef enum ficco_schedule {
                                     step s moves slice s of every shard, and one resident kernel adds
                                     slice s into its accumulators as it lands, so the partial products
                                     of the paper's accumulating GEMMs never leave the registers. The
-                                    activation travels and is stored K-sliced (see ficco_run).
-                                    AG_GEMM only, no FICCO_OPT_LOCAL_SHARD, never picked by AUTO
-                                    because it changes the caller's layout                          */
+                                    activation lands K-sliced in A_dev (see ficco_run); A_src is the
+                                    caller's row-major matrix unless FICCO_OPT_SOURCE_LAYOUT says the
+                                    sender holds it K-sliced already. AG_GEMM only, no
+                                    FICCO_OPT_LOCAL_SHARD; FICCO_AUTO keeps to row pieces             */
     FICCO_AUTO            = 100, /* ficco_pick_schedule() decides schedule and chunks (Sec. V-C)        */
     FICCO_AUTO_ANY        = 101  /* ficco_pick_schedule_any() decides: the answer may be FICCO_FINE_2D,
-                                    cut by ficco_pick_slice_widths(), whose layout the caller then has
-                                    to provide (ficco_plan_info() and ficco_plan_slices() say what was
-                                    chosen)                                                          */
+                                    cut by ficco_pick_slice_widths() (ficco_plan_info() and
+                                    ficco_plan_slices() say what was chosen). A_src stays row-major; the
+                                    landing buffer A_dev is then K-sliced                            */
 } ficco_schedule;
 
 typedef enum ficco_direction {
@@ -145,10 +146,32 @@ typedef enum ficco_option {
     FICCO_OPT_TILE_GROUP  = 13,  /* tile order, row tiles per group: 0 (default) = chosen per launch from the
                                     shape, else 1, 2, 4 or 8. The order decides which tiles share an XCD's L2
                                     at a time; it never changes a result bit.                         */
-    FICCO_OPT_TILE_COLUMN_LISTS = 14 /* resident kernels: column blocks their eight tile lists are split into:
+    FICCO_OPT_TILE_COLUMN_LISTS = 14, /* resident kernels: column blocks their eight tile lists are split into:
                                     0 (default) = chosen from the shape, else 1, 2, 4 or 8 (at most the
                                     number of column tiles, otherwise the run fails with FICCO_ERR_ARG)   */
+    FICCO_OPT_SOURCE_LAYOUT = 15 /* ficco_source_layout of A_src for FICCO_FINE_2D plans; default ROW_MAJOR       */
 } ficco_option;
+
+/*
+ * How the far side holds the activation when column pieces travel (FICCO_FINE_2D; Sec. V-A/B, 2D decomposition).
+ *   ROW_MAJOR - A_src is the caller's ordinary [M,K] row-major matrix, shard after shard, as for every other
+ *               schedule. A column piece is then a strided rectangle ([M/G rows] x [width] at pitch K). From
+ *               pinned host memory it is moved as such by a copy engine (a rectangular engine copy; measured
+ *               47-53 GB/s for rows of 2-6 KB, the rate of the host link). From device memory the runtime
+ *               puts every rectangular copy on one engine (56 GB/s in total, no links side by side), so the
+ *               sending side re-lays its shards out instead, inside the run: a kernel on the compute stream
+ *               writes each column piece as one contiguous block into a staging buffer the plan owns (M*K
+ *               elements) and, piece by piece, releases that piece's transfer, which then travels on its
+ *               link's engine like any other piece. On a real node every GPU would do this for the one shard
+ *               it sends; here the one GPU does it for all G senders, and the step pays for all of it.
+ *   K_SLICED  - the sender already holds its slices as DMA-ready blocks: A_src is K-sliced like A_dev (see
+ *               ficco_run). Nothing is re-laid out.
+ * A_dev is K-sliced in both cases.
+ */
+typedef enum ficco_source_layout {
+    FICCO_LAYOUT_ROW_MAJOR = 0,
+    FICCO_LAYOUT_K_SLICED  = 1
+} ficco_source_layout;
 
 /*
  * How transfers are issued.
@@ -352,12 +375,15 @@ int ficco_pack_weight(ficco_plan_t *plan, const void *W_dev, void *stream);
  *             A_dev  - [M,K] device; written by the transfers, read by the GEMM.
  *             C_dev  - [M,N] device; written by the GEMM.
  *             peer_out must be NULL.
- *             FICCO_FINE_2D: A_src and A_dev are K-sliced: slice s holds its columns of every
- *             row as an [M][width_s] row-major block, block after block ([chunks][M][K/chunks]
- *             when K/64 is a multiple of chunks; ficco_plan_slices reports the slices), so that
- *             piece s*shards + j (slice s of shard j) is one contiguous block, as a sender that
- *             owns shard j would lay its slices out for DMA. C is bitwise what FICCO_SERIAL
- *             computes from the same matrix in row-major layout.
+ *             FICCO_FINE_2D: A_dev is K-sliced: slice s holds its columns of every row as an
+ *             [M][width_s] row-major block, block after block ([chunks][M][K/chunks] when K/64 is a
+ *             multiple of chunks; ficco_plan_slices reports the slices), so that piece s*shards + j
+ *             (slice s of shard j) lands as one contiguous block. A_src is row-major like for every
+ *             other schedule, or K-sliced like A_dev with FICCO_OPT_SOURCE_LAYOUT = K_SLICED (see
+ *             ficco_source_layout for how the pieces leave a row-major source; on the stream
+ *             backend only K_SLICED sources are accepted). In FICCO_MODE_GEMM_ONLY A_dev must
+ *             already hold the K-sliced matrix. C is bitwise what FICCO_SERIAL computes from the
+ *             same matrix.
  *   GEMM_RS : A_src must be NULL; A_dev is read; C_dev is written by the GEMM and its row block
  *             p (rows [p*M/G, (p+1)*M/G)) is then copied (on copy_stream, or by the engines) to
  *             peer_out[p] ([M/G, N] bf16 each, device or pinned host), piece by piece as pieces

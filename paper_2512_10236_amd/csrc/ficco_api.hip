@@ -90,6 +90,9 @@ int ficco_run(ficco_plan_t *p, const void *A_src, void *A_dev, const void *W_dev
         return run_engines(p, A_src, A_dev, C_dev, peer_out, cs, src_dev, peer_dev);
     }
     if (p->link || p->chain_from) return FICCO_ERR_ARG;   // chained plans run on the copy engines
+    // column pieces leave a row-major source as rectangular engine copies or through the re-layout kernel, both on
+    // the engine backend; the stream backend moves K-sliced sources only
+    if (is_2d(p) && do_copy && p->src_layout == FICCO_LAYOUT_ROW_MAJOR) return FICCO_ERR_ARG;
     p->last_engines = false;
     p->links = 1;
 
@@ -532,6 +535,7 @@ int ficco_query_stats(ficco_plan_t *p, ficco_stats_t *out)
             }
             s.timed_out = 1;
             for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);   // let parked copies go
+            for (auto &sg : p->sig_packed) hsa_signal_store_screlease(sg, 0);
             HIP_TRY(hipMemset(p->d_status, 0, 4));
             p->h_status[0] = 0;
         }

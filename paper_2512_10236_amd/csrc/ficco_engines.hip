@@ -442,6 +442,52 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
     // one piece: data copy, then the 4-byte flag copy behind it on the same engine
     int prev_chunk = -1;
     std::vector<hsa_signal_t> *extra_dep = nullptr;      // per chunk id: one more signal every transfer waits for
+    // Column pieces out of a row-major matrix (ficco_source_layout): rectangular engine copies from pinned host
+    // memory; from device memory the sender-side re-layout kernel, which releases each piece's transfer.
+    const bool row_src = !rs && is_2d(p) && p->src_layout == FICCO_LAYOUT_ROW_MAJOR && do_copy;
+    const bool relayout = row_src && src_dev;
+    if (relayout) {
+        if (!p->d_slice_src && hipMalloc((void **)&p->d_slice_src, (size_t)p->M * p->K * 2) != hipSuccess) return FICCO_ERR_ALLOC;
+        while ((int)p->sig_packed.size() < n) {
+            hsa_signal_t a;
+            if (make_signal(&a) != HSA_STATUS_SUCCESS) return FICCO_ERR_ALLOC;
+            p->sig_packed.push_back(a);
+        }
+        if (!p->d_packed_value) {
+            std::vector<uint64_t> addr(n);
+            for (int i = 0; i < n; ++i)
+                if (!(addr[i] = signal_value_address(p->sig_packed[i]))) return FICCO_ERR_HIP;   // needs signals the GPU can write
+            if (hipMalloc((void **)&p->d_packed_value, sizeof(uint64_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemcpy(p->d_packed_value, addr.data(), sizeof(uint64_t) * (size_t)n, hipMemcpyHostToDevice));
+            if (hipMalloc((void **)&p->d_packed_count, sizeof(uint32_t) * (size_t)n) != hipSuccess) return FICCO_ERR_ALLOC;
+            HIP_TRY(hipMemset(p->d_packed_count, 0, sizeof(uint32_t) * (size_t)n));
+        }
+        for (int i = 0; i < n; ++i) hsa_signal_store_relaxed(p->sig_packed[i], 1);
+        extra_dep = &p->sig_packed;
+    }
+    // the re-layout kernel goes onto the compute stream in front of the GEMM (a resident GEMM kernel would
+    // otherwise hold every CU while it waits for transfers that wait for this kernel)
+    auto launch_relayout = [&]() -> int {
+        if (!relayout) return FICCO_OK;
+        SliceLaunch sl{};
+        sl.src = (const uint16_t *)A_src;
+        sl.dst = p->d_slice_src;
+        sl.M = p->M; sl.K = p->K;
+        sl.shards = p->G;
+        sl.rows_per_shard = (int32_t)p->m;
+        sl.k0 = p->d_slice_k0;
+        sl.arrival = p->d_arrival;
+        sl.n_pieces = n;
+        // blocks of about 256 KiB of the widest slice: many more blocks than CUs, few enough to keep the counters quiet
+        int64_t widest = 0;
+        for (int q = 0; q < c; ++q) widest = std::max<int64_t>(widest, p->slice_k0[q + 1] - p->slice_k0[q]);
+        sl.rows_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(p->m, (256 << 10) / (widest * 2)));
+        sl.blocks_per_piece = (int32_t)((p->m + sl.rows_per_block - 1) / sl.rows_per_block);
+        sl.done_count = p->d_packed_count;
+        sl.done_sig = p->d_packed_value;
+        HIP_TRY(launch_slice_source(sl, cs));
+        return FICCO_OK;
+    };
     auto submit = [&](int q) -> int {
         const int chunk = p->arrival[q];
         if (is_local(chunk)) return FICCO_OK;
@@ -452,11 +498,14 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         size_t bytes;
         hsa_agent_t dst_agent = ctx.gpu, src_agent = ctx.gpu;
         bool force = true;
+        bool rect = false;
         if (!rs) {
             const Extent ex = piece_extent(p, chunk);
             bytes = ex.bytes;
             dst = (char *)A_dev + ex.off;
             src = (const char *)A_src + ex.off;
+            if (relayout) src = (const char *)p->d_slice_src + ex.off;       // the sender-side staging copy, K-sliced like A_dev
+            rect = row_src && !src_dev;                                      // a strided rectangle out of the row-major host matrix
             if (!src_dev) { src_agent = ctx.cpu; force = false; }
         } else {
             const int peer = chunk / c;
@@ -470,8 +519,21 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (chained && prev_chunk >= 0) dep[ndep++] = p->sig_data[prev_chunk];
         if (extra_dep) dep[ndep++] = (*extra_dep)[chunk];
         if (has_chain_dep) dep[ndep++] = chain_dep;
-        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? dep : nullptr,
-                                                              p->sig_data[chunk], engine, force);
+        hsa_status_t st;
+        if (rect) {
+            // rows [j*m, (j+1)*m) x columns [kb, kb+kw) at pitch K -> the piece's contiguous block of A_dev; the
+            // runtime picks the engine for rectangular copies itself (its host-to-device one)
+            const int sl = chunk / p->G, j = chunk % p->G;
+            const size_t kb = (size_t)p->slice_k0[sl], kw = (size_t)p->slice_k0[sl + 1] - kb;
+            hsa_pitched_ptr_t ps{(void *)((const char *)A_src + ((size_t)j * p->m * p->K + kb) * 2), (size_t)p->K * 2, 0};
+            hsa_pitched_ptr_t pd{dst, kw * 2, 0};
+            const hsa_dim3_t zero{0, 0, 0}, range{(uint32_t)(kw * 2), (uint32_t)p->m, 1};
+            st = hsa_amd_memory_async_copy_rect(&pd, &zero, &ps, &zero, &range, ctx.gpu, hsaHostToDevice, ndep, ndep ? dep : nullptr,
+                                                p->sig_data[chunk]);
+        } else {
+            st = hsa_amd_memory_async_copy_on_engine(dst, dst_agent, src, src_agent, bytes, ndep, ndep ? dep : nullptr,
+                                                     p->sig_data[chunk], engine, force);
+        }
         if (st != HSA_STATUS_SUCCESS) { g_last_hip = (int)st; return FICCO_ERR_HIP; }
         prev_chunk = chunk;
         ++n_copies;
@@ -600,6 +662,7 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         if (copies_first)
             for (int q = 0; q < n; ++q)
                 if ((rc = submit(q))) return rc;
+        if ((rc = launch_relayout())) return rc;
         if (do_gemm) {
             if (is_2d(p)) {
                 if (timing) HIP_TRY(hipEventRecord(p->ev_gemm_b[0], cs));

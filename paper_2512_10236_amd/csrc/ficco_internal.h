@@ -211,6 +211,24 @@ hipError_t launch_wait_ready(const Gate &gate, const int32_t *chunks, int n, hip
 // One thread stores 0 into the value word of a completion signal (device-visible address) once everything
 // before it on the stream has finished: transfers submitted with that signal as a dependency may start.
 hipError_t launch_release_signal(uint64_t value_addr, hipStream_t s);
+// Sender-side re-layout for column pieces out of a row-major matrix: piece (slice sl, shard j) = rows
+// [j*rows_per_shard, (j+1)*rows_per_shard) x columns [k0[sl], k0[sl+1]) of src [M,K] is written as one
+// contiguous block at element M*k0[sl] + j*rows_per_shard*width of dst (the K-sliced layout). Workgroups
+// take blocks of rows_per_block rows of a piece, pieces in arrival order; stores go through the caches (a copy
+// engine reads them next), and the workgroup that completes a piece (counter never reset: blocks_per_piece
+// more per run) stores 0 into the value word of that piece's signal, which lets its transfer go.
+struct SliceLaunch {
+    const uint16_t *src;
+    uint16_t *dst;
+    int64_t M, K;
+    int32_t shards, rows_per_shard;
+    const int32_t *k0;            // device, slices + 1 entries
+    const int32_t *arrival;       // device, piece ids (sl*shards + j) in arrival order
+    int32_t n_pieces, rows_per_block, blocks_per_piece;
+    uint32_t *done_count;         // device, per piece id
+    const uint64_t *done_sig;     // device, per piece id: address of the signal's value word
+};
+hipError_t launch_slice_source(const SliceLaunch &a, hipStream_t s);
 hipError_t launch_pack_weight(const uint16_t *W, uint16_t *Wt, int64_t K, int64_t N, hipStream_t s);
 int resident_grid_size(int tile, int device);
 

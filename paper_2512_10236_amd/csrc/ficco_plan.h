@@ -72,6 +72,13 @@ struct ficco_plan_s {
     std::shared_ptr<ficco::ChainLink> chain_from;  // this plan's transfers wait for the latest run of that link's owner
     std::vector<int64_t> slice_k0;       // column pieces: first column of each slice, then K (c + 1 entries)
     bool own_widths = false;             // slice_k0 was given by the caller (ficco_plan_set_slice_widths)
+    int src_layout = FICCO_LAYOUT_ROW_MAJOR;   // column pieces: how A_src holds the activation
+    // column pieces out of a row-major device source: the sender-side staging copy (K-sliced), one dependency signal
+    // per piece that the re-layout kernel releases, their value-word addresses and the kernel's block counters
+    uint16_t *d_slice_src = nullptr;
+    std::vector<hsa_signal_t> sig_packed;
+    uint64_t *d_packed_value = nullptr;
+    uint32_t *d_packed_count = nullptr;
     // expert-parallel (grouped) plans: E experts, ragged pieces, piece id (e*c + s)*G + j
     bool grouped = false;
     int E = 1;

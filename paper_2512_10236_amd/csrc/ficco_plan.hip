@@ -171,7 +171,7 @@ void release(ficco_plan_t *p)
         for (auto &e : *v) ev(e);
         v->clear();
     }
-    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter, &p->sig_done}) {
+    for (auto *v : {&p->sig_data, &p->sig_flag, &p->sig_gather, &p->sig_scatter, &p->sig_done, &p->sig_packed}) {
         for (auto &sg : *v) (void)hsa_signal_destroy(sg);
         v->clear();
     }
@@ -180,6 +180,10 @@ void release(ficco_plan_t *p)
     if (p->d_sig_value) (void)hipFree(p->d_sig_value);
     if (p->d_done_value) (void)hipFree(p->d_done_value);
     if (p->d_done_count) (void)hipFree(p->d_done_count);
+    if (p->d_slice_src) (void)hipFree(p->d_slice_src);
+    if (p->d_packed_value) (void)hipFree(p->d_packed_value);
+    if (p->d_packed_count) (void)hipFree(p->d_packed_count);
+    p->d_slice_src = nullptr; p->d_packed_value = nullptr; p->d_packed_count = nullptr;
     p->d_done_value = nullptr;
     p->d_done_count = nullptr;
     p->d_sig_value = nullptr;
@@ -722,6 +726,11 @@ int ficco_plan_set(ficco_plan_t *p, int option, int64_t value)
     case FICCO_OPT_TILE_COLUMN_LISTS:
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return FICCO_ERR_ARG;
         p->tile_col_lists = (int)value;
+        break;
+    case FICCO_OPT_SOURCE_LAYOUT:
+        if (value != FICCO_LAYOUT_ROW_MAJOR && value != FICCO_LAYOUT_K_SLICED) return FICCO_ERR_ARG;
+        if (!is_2d(p) && value != FICCO_LAYOUT_ROW_MAJOR) return FICCO_ERR_ARG;      // row pieces leave a row-major source as they are
+        p->src_layout = (int)value;
         break;
     case FICCO_OPT_PACKING:
         if (value != 0 && value != 1) return FICCO_ERR_ARG;

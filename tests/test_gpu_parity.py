@@ -31,15 +31,17 @@ def widen(bits):
 
 
 def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, delay_copy=False,
-           timing=0, allow_timeout=False, runs=1, local_shard=None, backend=None, widths=None):
+           timing=0, allow_timeout=False, runs=1, local_shard=None, backend=None, widths=None, row_major=False):
     """One all-gather -> GEMM through the C ABI; returns (C bits, stats). ``widths``: column pieces of
-    these widths (FICCO_FINE_2D, ``c`` = their number) instead of equal ones."""
+    these widths (FICCO_FINE_2D, ``c`` = their number) instead of equal ones. Column pieces travel out of a
+    K-sliced source (FICCO_LAYOUT_K_SLICED) unless ``row_major`` asks for the caller's own layout."""
     dev = gpu["dev"]
     A = np.concatenate(shards, 0)
     M, K = A.shape
     N = W.shape[1]
     G = len(shards)
-    if schedule == ficco.FICCO_FINE_2D:
+    k_sliced = schedule == ficco.FICCO_FINE_2D and not row_major
+    if k_sliced:
         if widths is None and K % c == 0:
             A = fi.to_k_sliced(A, c).reshape(M, K)         # same bytes, column pieces contiguous
         else:
@@ -72,6 +74,8 @@ def run_ag(gpu, shards, W, schedule, c, *, src="pinned", opts=(), arrival=None, 
             ficco.ficco_plan_set(plan, o, v)
         if widths is not None:
             ficco.ficco_plan_set_slice_widths(plan, widths)
+        if k_sliced:
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
         if arrival is not None:
             ficco.ficco_plan_set_arrival(plan, arrival)
         ficco.ficco_plan_set(plan, ficco.FICCO_OPT_TIMING, timing)
@@ -523,6 +527,7 @@ def test_cfg2_full_compare(gpu):
     try:
         for p_ in plans:
             ficco.ficco_plan_set_slice_widths(p_, widths)
+            ficco.ficco_plan_set(p_, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
         ficco.ficco_plan_chain(plans[0], plans[1])
         ficco.ficco_plan_chain(plans[1], plans[0])
         for i in range(10):
@@ -720,6 +725,7 @@ def test_chained_plans_take_turns_on_one_a_dev_without_host_waits(gpu):
     pb = ficco.ficco_plan(M, K, N, G, 2, ficco.FICCO_FINE_2D)
     try:
         ficco.ficco_plan_set_slice_widths(pb, widths)
+        ficco.ficco_plan_set(pb, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
         ficco.ficco_plan_chain(pa, pb)
         ficco.ficco_plan_chain(pb, pa)
         with pytest.raises(ficco.FiccoError):
@@ -804,29 +810,80 @@ def test_chained_plan_is_let_go_when_the_run_in_front_gives_up(gpu):
     torch.cuda.synchronize()
 
 
-def test_auto_any_plan_runs_in_the_layout_it_reports(gpu):
-    """FICCO_AUTO_ANY may answer with column pieces; the caller learns the layout from the plan and provides it."""
+def test_auto_any_plan_runs_from_the_callers_row_major_matrix(gpu):
+    """FICCO_AUTO_ANY may answer with column pieces; A_src stays the caller's row-major matrix, in device memory
+    (the sender-side re-layout kernel releases each piece's transfer) and in pinned host memory (rectangular
+    engine copies), and a sender that holds its slices K-sliced already can say so."""
     dev = gpu["dev"]
     shards, W = fi.config_inputs("cfg1_tiny")
     A = np.concatenate(shards, 0)
     M, K = A.shape
     N, G = W.shape[1], len(shards)
     base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
-    plan = ficco.ficco_plan(M, K, N, G, 1, ficco.FICCO_AUTO_ANY)
-    try:
-        info = ficco.ficco_plan_info(plan)
-        assert (info.schedule, info.chunks) == ficco.ficco_pick_schedule_any(M, K, N, G) == (ficco.FICCO_FINE_2D, 2)
-        _, widths = ficco.ficco_plan_slices(plan)
-        src = as_i16(np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)).to(dev)
-        W_dev = as_i16(W).to(dev)
-        A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
-        C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
-        ficco.ficco_run(plan, src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
-        ficco.ficco_query_stats(plan)
-        assert np.array_equal(C_dev.cpu().numpy().view(np.uint16), base)
-    finally:
-        ficco.ficco_destroy(plan)
+    W_dev = as_i16(W).to(dev)
+    for kind in ("device", "pinned", "k_sliced"):
+        plan = ficco.ficco_plan(M, K, N, G, 1, ficco.FICCO_AUTO_ANY)
+        try:
+            info = ficco.ficco_plan_info(plan)
+            assert (info.schedule, info.chunks) == ficco.ficco_pick_schedule_any(M, K, N, G) == (ficco.FICCO_FINE_2D, 2)
+            _, widths = ficco.ficco_plan_slices(plan)
+            if kind == "k_sliced":
+                ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
+                src = as_i16(np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)).to(dev)
+            else:
+                src = as_i16(A).to(dev) if kind == "device" else as_i16(A).pin_memory()
+            for run in range(3):                              # signals, counters and the staging copy are reused
+                A_dev = torch.full((M, K), NAN_BF16, dtype=torch.int16, device=dev)
+                C_dev = torch.full((M, N), 0x7FFF, dtype=torch.int16, device=dev)
+                torch.cuda.synchronize()
+                ficco.ficco_run(plan, src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
+                st = ficco.ficco_query_stats(plan)
+                assert st.n_copies == 2 * G and st.copy_bytes == M * K * 2
+                assert np.array_equal(C_dev.cpu().numpy().view(np.uint16), base), (kind, run)
+                # the landing buffer holds the K-sliced matrix
+                want = np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)])
+                assert np.array_equal(A_dev.cpu().numpy().view(np.uint16).ravel(), want), (kind, run)
+        finally:
+            ficco.ficco_destroy(plan)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("src", ["device", "pinned"])
+def test_2d_from_row_major_source_ragged_and_unequal(gpu, src):
+    # 3 shards of 88 rows (no tile height divides it), K = 5 k-tiles cut 128 + 64 + 128, N not a tile width;
+    # then equal slices, reversed arrival, shard-major order (transfers one after the other)
+    G, ms, K, N = 3, 88, 320, 328
+    shards = fi.make_shards(33, G * ms, K, G)
+    W = fi.make_weight(33, K, N)
+    ref = og.ag_gemm(shards, W)
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    check(base, ref, "serial")
+    for widths, arrival, opts in [([128, 64, 128], None, ()), (None, None, ()), ([64, 192, 64], list(range(3 * G))[::-1], ()),
+                                  (None, None, [(ficco.FICCO_OPT_ORDER, ficco.FICCO_ORDER_SHARD_MAJOR)])]:
+        c = len(widths) if widths else 5
+        bits, st, info = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src=src, widths=widths, arrival=arrival, opts=opts,
+                                runs=2, row_major=True)
+        assert info.copy_backend == ENGINES and st.n_copies == c * G
+        assert np.array_equal(bits, base), (src, widths, arrival, opts)
+
+
+def test_2d_row_major_source_is_refused_on_the_stream_backend(gpu):
+    shards, W = fi.config_inputs("cfg1_tiny")
+    with pytest.raises(ficco.FiccoError) as e:
+        run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, 2, backend=STREAM, row_major=True)
+    assert e.value.status == ficco.FICCO_ERR_ARG
+
+
+def test_cfg2_and_cfg6_2d_from_row_major_device_source(gpu):
+    for name, c, widths in [("cfg2_qkv8b", 2, [3072, 1024]), ("cfg6_2d_proj", 8, None)]:
+        cfg = fi.CONFIGS[name]
+        shards, W = fi.config_inputs(name)
+        rows = np.unique(np.concatenate([np.arange(0, cfg["M"], 257), [0, cfg["M"] // 8 - 1, cfg["M"] // 8, cfg["M"] - 1]]))
+        ref = og.ag_gemm_rows(shards, W, rows)
+        base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
+        check(base[rows], ref, f"{name} serial")
+        bits, st, _ = run_ag(gpu, shards, W, ficco.FICCO_FINE_2D, c, src="device", widths=widths, runs=2, row_major=True)
+        assert np.array_equal(bits, base), f"{name}: column pieces out of the row-major source differ bitwise from serial"
 
 
 def test_2d_waits_for_late_and_reordered_slices(gpu):

@@ -362,6 +362,24 @@ def test_pick_schedule_any_gives_valid_plans_with_its_own_cut():
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
 
 
+def test_source_layout_option_belongs_to_column_pieces():
+    plan = ficco.ficco_plan(512, 1024, 1024, 4, 2, ficco.FICCO_FINE_2D)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_ROW_MAJOR)
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, 2)
+    finally:
+        ficco.ficco_destroy(plan)
+    plan = ficco.ficco_plan(512, 1024, 1024, 4, 2, ficco.FICCO_FINE_PERSISTENT)
+    try:
+        ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_ROW_MAJOR)
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
+    finally:
+        ficco.ficco_destroy(plan)
+
+
 # ------------------------------------------------------------------ expert-parallel (grouped) plans
 from oracle import grouped as ogr  # noqa: E402
 
