@@ -9,9 +9,12 @@ between steps, and both sides of the K steps are synchronised (the figure with a
 query after every step is reported beside it). Prints ONE JSON line. Only one GPU is used; --gpus > 1
 exits.
 
-Legs (all on the same workload, default the Llama-3-8B QKV share at TP=8, M=8192 K=4096 N=768):
-  pair      - K timed steps of the best finer-grain schedule, source shards resident in HBM
-              (device staging buffer); also serial and shard-level schedules for the speedup
+Legs (all on the same workload, default the 70B-class FFN-up share at TP=8, M=16384 K=8192 N=3584, the largest
+all-gather configuration one GPU holds):
+  pair      - K timed steps of the schedule the library itself picks (FICCO_AUTO_ANY) from the caller's
+              row-major shards resident in HBM (device staging buffer): that is `value`. Beside it a screen of
+              the other schedules and piece counts, and the serial and shard-level schedules for the speedups
+  small     - the pair and pcie legs of the two smaller all-gather workloads (cfg1, cfg2), condensed
   pcie      - the same with the shards in pinned host memory (PCIe-inclusive; never `value`)
   roofline  - the GEMM launches of the timed plan in isolation, enqueued back to back between two
               HIP events on the compute stream -> achieved TFLOP/s against the bf16 dense MFMA peak
@@ -188,8 +191,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2_qkv8b")
-    ap.add_argument("--legs", default="pair,pcie,roofline,losses,cpu")
+    ap.add_argument("--workload", default="cfg3_ffn70b")
+    ap.add_argument("--legs", default="pair,pcie,roofline,losses,small,cpu")
     ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4,5:3072+1024 (default: a small sweep)")
     ap.add_argument("--backend", default="auto", choices=["auto", "stream", "engines"],
                     help="transfer backend for every plan (default: the library's choice)")
@@ -239,13 +242,14 @@ def main() -> int:
 
     sliced = {}
 
-    def source(tag, sched, c):
-        """Shard source for a plan: the row-major staging buffer, or its K-sliced copy (same bytes, the
-        layout column pieces travel in) for the 2D schedule. `tag` is "hbm" or "pcie"."""
+    def source(tag, sched, c, layout="rm"):
+        """Shard source for a plan: the row-major staging buffer (the caller's layout, also for column pieces),
+        or its K-sliced copy (same bytes) for column pieces whose sender holds them that way (layout "ks").
+        `tag` is "hbm" or "pcie"."""
         if rs:
             return peers_dev if tag == "hbm" else peers_pin
         base = A_stage if tag == "hbm" else A_pinned
-        if sched != F.FICCO_FINE_2D:
+        if sched != F.FICCO_FINE_2D or layout != "ks":
             return base
         if (tag, c) not in sliced:
             if isinstance(c, tuple):                      # slices of unequal width, block after block
@@ -280,12 +284,12 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    def timed_steps_chained(sc, src, steps, warmup):
+    def timed_steps_chained(sc, src, steps, warmup, opts=()):
         """ms per step when the host does not wait between steps: two plans of the same kind, chained behind
         each other (ficco_plan_chain), take the steps in turn on the same buffers; the transfers of a step
         start on the device when the previous step's kernel has finished, and the host only ever waits for
         the step before the previous one. Synchronize on both sides of the timed steps."""
-        pa, pb = make(*sc), make(*sc)
+        pa, pb = make(*sc, opts=opts), make(*sc, opts=opts)
         try:
             F.ficco_plan_chain(pa, pb)
             F.ficco_plan_chain(pb, pa)
@@ -307,12 +311,14 @@ def main() -> int:
     def sched_name(sched):
         return F.SCHEDULE_NAMES[sched % PACKED] + ("+gather_scatter" if sched >= PACKED else "")
 
-    def make(sched, c, opts=()):
+    def make(sched, c, layout="rm", opts=()):
         if sched >= PACKED:
             sched, opts = sched - PACKED, list(opts) + [(F.FICCO_OPT_PACKING, 1)]
         plan = F.ficco_plan(M, K, N, G, len(c) if isinstance(c, tuple) else c, sched)
         if isinstance(c, tuple):
             F.ficco_plan_set_slice_widths(plan, c)
+        if sched == F.FICCO_FINE_2D and layout == "ks":
+            F.ficco_plan_set(plan, F.FICCO_OPT_SOURCE_LAYOUT, F.FICCO_LAYOUT_K_SLICED)
         if rs:
             F.ficco_plan_set(plan, F.FICCO_OPT_DIRECTION, F.FICCO_DIR_GEMM_RS)
         for o, v in opts:
@@ -322,41 +328,58 @@ def main() -> int:
         F.ficco_pack_weight(plan, W_dev, cs)
         return plan
 
-    # a candidate is (schedule, pieces per shard); the fused schedule with explicit Gather/Scatter copies
-    # ("3p:4" on the command line) is schedule FICCO_FINE_FUSED + PACKED; column pieces of unequal width
-    # ("5:3072+1024") carry the tuple of widths in place of the count
+    # a candidate is (schedule, pieces per shard, source layout); the fused schedule with explicit Gather/Scatter
+    # copies ("3p:4" on the command line) is schedule FICCO_FINE_FUSED + PACKED; column pieces of unequal width
+    # ("5:3072+1024") carry the tuple of widths in place of the count; column pieces leave the caller's row-major
+    # matrix (layout "rm": the step pays for the sender-side re-layout) unless the candidate says the sender
+    # holds them K-sliced ("5k:2", layout "ks")
     PACKED = 1000
     def pieces_of(c):
         return len(c) if isinstance(c, tuple) else c
     def label(sc):
-        return f"{sched_name(sc[0])}:" + ("+".join(str(w) for w in sc[1]) if isinstance(sc[1], tuple) else str(sc[1]))
+        return f"{sched_name(sc[0])}" + ("_presliced" if sc[2] == "ks" else "") + ":" + \
+            ("+".join(str(w) for w in sc[1]) if isinstance(sc[1], tuple) else str(sc[1]))
     def parse_plan(t):
         a, b = t.split(":")
         b = tuple(int(w) for w in b.split("+")) if "+" in b else int(b)
-        return (int(a[:-1]) + PACKED, b) if a.endswith("p") else (int(a), b)
+        if a.endswith("p"):
+            return (int(a[:-1]) + PACKED, b, "rm")
+        if a.endswith("k"):
+            return (int(a[:-1]), b, "ks")
+        return (int(a), b, "rm")
+    def library_pick():
+        """What ficco_plan(..., FICCO_AUTO_ANY) builds for this shape, as a candidate."""
+        plan = F.ficco_plan(M, K, N, G, 1, F.FICCO_AUTO_ANY)
+        try:
+            info = F.ficco_plan_info(plan)
+            c = info.chunks
+            if info.schedule == F.FICCO_FINE_2D:
+                w = tuple(F.ficco_plan_slices(plan)[1])
+                if len(set(w)) > 1:
+                    c = w
+            return (info.schedule, c, "rm")
+        finally:
+            F.ficco_destroy(plan)
+    pick = None if rs else library_pick()
     if args.candidates:
         cands = [parse_plan(t) for t in args.candidates.split(",")]
     else:
         cands = []
         for rows in cfg["chunk_rows"]:
             c = ms_shard // rows
-            for s in ((F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED) if cfg["direction"] == "gemm_rs"
-                      else (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED)):
-                if (s, c) not in cands:
-                    cands.append((s, c))
-        cands += [(F.FICCO_FINE_2D, c) for c in cfg.get("k_slices", [])]
-        cands += [(F.FICCO_FINE_2D, tuple(w)) for w in cfg.get("k_widths", [])]
-        if not rs:
-            # what the any-shape rule answers, in the rule's own cut of the k range
-            ps, pc = F.ficco_pick_schedule_any(M, K, N, G)
-            if ps == F.FICCO_FINE_2D:
-                pw = tuple(F.ficco_pick_slice_widths(M, K, N, G, pc))
-                cand = (ps, pw) if len(set(pw)) > 1 else (ps, pc)
-                if cand not in cands:
-                    cands.append(cand)
+            for s in (F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT, F.FICCO_FINE_UNFUSED):
+                if (s, c, "rm") not in cands:
+                    cands.append((s, c, "rm"))
+        for lay in ("rm", "ks"):
+            cands += [(F.FICCO_FINE_2D, c, lay) for c in cfg.get("k_slices", [])]
+            cands += [(F.FICCO_FINE_2D, tuple(w), lay) for w in cfg.get("k_widths", [])]
+    if pick is not None and pick not in cands:
+        cands.append(pick)
+        if pick[0] == F.FICCO_FINE_2D:
+            cands.append((pick[0], pick[1], "ks"))
 
     out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
-                     + " effective TFLOP/s (overlapped pair, best finer-grain schedule)",
+                     + " effective TFLOP/s (overlapped pair, the schedule the library picks)",
            "value": None, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
@@ -366,89 +389,83 @@ def main() -> int:
     def leg_pair(tag):
         res = {}
         A_src = source(tag, F.FICCO_SERIAL, 1)
-        # short screening of the candidates, then the full timed run of the winner. The first plan of a
-        # process reads 5-10 % slow for its first 30 ms or so (clocks, first use of everything), so the first
-        # candidate warms up that long before it is timed.
+        chain = not rs
+        # short screening of the candidates. The first plan of a process reads 5-10 % slow for its first 30 ms or
+        # so (clocks, first use of everything), so the first candidate warms up that long before it is timed.
         screen = {}
-        for i, (s, c) in enumerate(cands):
-            plan = make(s, c)
-            screen[(s, c)] = timed_steps(plan, source(tag, s, c), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.02)
+        for i, sc in enumerate(cands):
+            plan = make(*sc)
+            screen[sc] = timed_steps(plan, source(tag, *sc), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.02)
             F.ficco_destroy(plan)
-        # the two best of the screen are timed in full; the faster one is the schedule of this run
-        finalists = sorted(screen, key=screen.get)[:2]
-        full = {}
-        for sc in finalists:
+        # The schedule of this run is the library's own pick (all-gather direction; the reduce-scatter direction
+        # has no rule of its own and takes the best of the screen). It is timed in full, with a blocking query
+        # after every step and - the figure that counts - with steps back to back through two chained plans.
+        # The best of the screen is timed the same way beside it.
+        screen_best = min(screen, key=screen.get)
+        timed = pick if pick is not None else screen_best
+        def full(sc):
             p_f = make(*sc)
-            full[sc] = timed_steps(p_f, source(tag, *sc), args.steps, args.warmup)
+            synced = timed_steps(p_f, source(tag, *sc), args.steps, args.warmup)
+            info_f, st_f = F.ficco_plan_info(p_f), F.ficco_query_stats(p_f)
             F.ficco_destroy(p_f)
-        best = min(full, key=full.get)
-        plan = make(*best)
-        ms_synced = timed_steps(plan, source(tag, *best), args.steps, args.warmup)
-        # The step time that counts has no host round trip between steps (all-gather direction, where the
-        # library can chain plans); the figure with a blocking query after every step is kept beside it.
-        chain = not rs and best[0] < PACKED
-        ms = timed_steps_chained(best, source(tag, *best), args.steps, args.warmup) if chain else ms_synced
-        # when column pieces (2D) win, the best row-piece schedule is timed in full as well
+            ms_f = timed_steps_chained(sc, source(tag, *sc), args.steps, args.warmup) if chain and sc[0] < PACKED else synced
+            return ms_f, synced, info_f, st_f
+        ms, ms_synced, info, st = full(timed)
+        ms_best, ms_best_synced = (ms, ms_synced) if screen_best == timed else full(screen_best)[:2]
+        # the best row-piece schedule, when column pieces were timed
         rows_best, ms_rows = None, None
-        if best[0] % PACKED == F.FICCO_FINE_2D:
+        if timed[0] % PACKED == F.FICCO_FINE_2D:
             rows_best = min((k for k in screen if k[0] % PACKED != F.FICCO_FINE_2D), key=screen.get, default=None)
             if rows_best is not None:
-                p_rows = make(*rows_best)
-                ms_rows = timed_steps(p_rows, source(tag, *rows_best), args.steps, args.warmup)
-                if chain and rows_best[0] < PACKED:
-                    ms_rows = timed_steps_chained(rows_best, source(tag, *rows_best), args.steps, args.warmup)
-                F.ficco_destroy(p_rows)
-        info = F.ficco_plan_info(plan)
-        st = F.ficco_query_stats(plan)
-        F.ficco_destroy(plan)
+                ms_rows = full(rows_best)[0]
         p_ser = make(F.FICCO_SERIAL, 1)
         ms_ser_synced = timed_steps(p_ser, A_src, args.steps, args.warmup)
         st_ser = F.ficco_query_stats(p_ser)
         F.ficco_destroy(p_ser)
-        ms_ser = timed_steps_chained((F.FICCO_SERIAL, 1), A_src, args.steps, args.warmup) if chain else ms_ser_synced
+        ms_ser = timed_steps_chained((F.FICCO_SERIAL, 1, "rm"), A_src, args.steps, args.warmup) if chain else ms_ser_synced
         p_sh = make(F.FICCO_SHARD, 1)
         ms_sh = timed_steps(p_sh, A_src, args.steps, args.warmup)
         F.ficco_destroy(p_sh)
         if chain:
-            ms_sh = timed_steps_chained((F.FICCO_SHARD, 1), A_src, args.steps, args.warmup)
+            ms_sh = timed_steps_chained((F.FICCO_SHARD, 1, "rm"), A_src, args.steps, args.warmup)
+        # shard-sized pieces over all links at once: what shard granularity gives when the links are not the
+        # difference (the shard-level schedule above moves one shard at a time over one link, Fig. 3(c))
+        all_links_c1 = {label(k): round(v, 4) for k, v in screen.items() if k[1] == 1 and k[0] % PACKED != F.FICCO_FINE_2D}
         # the paper's "hetero" start, for information (never `value`): shard 0 is this GPU's own and already in
         # place, so seven shards travel and the GEMM starts on local rows at once
         ms_het = None
-        if not rs and best[0] % PACKED != F.FICCO_FINE_2D:
+        if not rs and timed[0] % PACKED != F.FICCO_FINE_2D:
             ms_shard_rows = M // G
             A_dev[:ms_shard_rows].copy_(A_stage[:ms_shard_rows])
             torch.cuda.synchronize()
-            p_het = make(best[0], best[1], [(F.FICCO_OPT_LOCAL_SHARD, 0)])
-            ms_het = timed_steps(p_het, source(tag, *best), args.steps, args.warmup)
-            if chain:
-                ms_het = timed_steps_chained((best[0], best[1], [(F.FICCO_OPT_LOCAL_SHARD, 0)]), source(tag, *best), args.steps, args.warmup)
-            F.ficco_destroy(p_het)
+            het = [(F.FICCO_OPT_LOCAL_SHARD, 0)]
+            ms_het = timed_steps_chained(timed, source(tag, *timed), args.steps, args.warmup, opts=het)
         res.update(copy_backend={1: "stream", 2: "engines"}.get(info.copy_backend), links=info.links,
                    ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
+                   picked_by=("the library (FICCO_AUTO_ANY)" if pick is not None else "the screen (no rule for this direction)"),
                    stepping=("two plans chained behind each other take the steps in turn; the host runs one step ahead"
                              if chain else "a blocking query after every step"),
                    ms_per_step_host_synced=ms_synced, ms_serial_host_synced=ms_ser_synced,
-                   schedule=sched_name(best[0]), chunks_per_shard=pieces_of(best[1]),
-                   chunk_rows=ms_shard if best[0] % PACKED == F.FICCO_FINE_2D else ms_shard // best[1],
-                   slice_widths=(list(best[1]) if isinstance(best[1], tuple) else None),
+                   schedule=sched_name(timed[0]), chunks_per_shard=pieces_of(timed[1]),
+                   source_layout=("row-major (the caller's)" if timed[2] == "rm" else "K-sliced by the sender"),
+                   chunk_rows=ms_shard if timed[0] % PACKED == F.FICCO_FINE_2D else ms_shard // timed[1],
+                   slice_widths=(list(timed[1]) if isinstance(timed[1], tuple) else None),
                    tile=f"{info.tile_m}x{info.tile_n}", ms_serial=ms_ser, ms_shard_level=ms_sh,
                    speedup_vs_serial=ms_ser / ms, speedup_vs_shard_level=ms_sh / ms,
+                   speedup_vs_shard_level_note="the shard-level schedule sends one shard after the other over one link while the finer "
+                                               "schedules use all links at once: the ratio is dominated by the link count; "
+                                               "shard_granularity_all_links has shard-sized pieces over all links",
+                   shard_granularity_all_links_ms_host_synced=all_links_c1,
                    copy_gbps_serial=st_ser.copy_gbps, copy_span_us=st.copy_span_us,
                    ms_local_shard_resident=ms_het,
+                   screen_best=label(screen_best), ms_screen_best=ms_best, ms_screen_best_host_synced=ms_best_synced,
+                   pick_vs_screen_best=ms / ms_best,
                    best_row_pieces=(label(rows_best) if rows_best else None), ms_best_row_pieces=ms_rows,
-                   screen={label(k): round(v, 4) for k, v in screen.items()},
-                   finalists={label(k): round(v, 4) for k, v in full.items()})
+                   screen_ms_host_synced={label(k): round(v, 4) for k, v in screen.items()})
         if not rs:
-            # what the static rules answer for this shape, and where the screen put those answers
-            picks = {"rows_only": F.ficco_pick_schedule(M, K, N, G), "any_shape": F.ficco_pick_schedule_any(M, K, N, G)}
-            if picks["any_shape"][0] == F.FICCO_FINE_2D:
-                pw = tuple(F.ficco_pick_slice_widths(M, K, N, G, picks["any_shape"][1]))
-                if len(set(pw)) > 1:
-                    picks["any_shape"] = (F.FICCO_FINE_2D, pw)
-            res["heuristic"] = {k: dict(pick=label(v), screen_ms=(round(screen[v], 4) if v in screen else None),
-                                        vs_screen_best=(round(screen[v] / min(screen.values()), 4) if v in screen else None))
-                                for k, v in picks.items()}
-        return res, best
+            s_rows, c_rows = F.ficco_pick_schedule(M, K, N, G)
+            res["row_piece_rule"] = label((s_rows, c_rows, "rm"))
+        return res, timed
 
     best = None
     if "pair" in legs:
@@ -456,22 +473,23 @@ def main() -> int:
         out["value"] = round(res["eff_tflops"], 3)
         out["ms_per_step"] = round(res["ms_per_step"], 5)
         out["pair"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
-        out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"])
+        out["config"].update(schedule=res["schedule"], chunks_per_shard=res["chunks_per_shard"], tile=res["tile"],
+                             picked_by=res["picked_by"], source_layout=res["source_layout"])
         if res["slice_widths"]:
             out["config"]["slice_widths"] = res["slice_widths"]
     if "roofline" in legs:
         if best:
-            s, c = best
+            s, c, lay = best
         elif args.roofline_plan:
-            s, c = parse_plan(args.roofline_plan)
+            s, c, lay = parse_plan(args.roofline_plan)
         else:
-            s, c = F.ficco_pick_schedule(M, K, N, G)
+            s, c, lay = pick if pick is not None else (F.FICCO_FINE_PERSISTENT, 1, "rm")
         s %= PACKED                                    # Gather/Scatter only exists in the overlapped pair
         def launch_time(sched, chunks, A_res):
             """Average duration of the plan's GEMM launches, operands resident: one run that enqueues them
             `steps` times back to back between the two HIP events it records on the compute stream
             (FICCO_OPT_REPEAT), so the figure holds the kernels and the gaps between them, nothing else."""
-            plan = make(sched, chunks, [(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY)])
+            plan = make(sched, chunks, opts=[(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY)])
             for _ in range(args.warmup):
                 F.ficco_run(plan, None, A_res, W_dev, C_dev, None, cs, xs)
             st1 = F.ficco_query_stats(plan)
@@ -491,7 +509,7 @@ def main() -> int:
             F.ficco_destroy(plan)
             return st.wall_us / args.steps, st1.n_launches, info
 
-        us_step, launches, info = launch_time(s, c, A_stage if rs else source("hbm", s, c))   # operands in the layout the plan reads
+        us_step, launches, info = launch_time(s, c, A_stage if rs else source("hbm", s, c, "ks"))   # operands resident in the layout the kernel reads (column pieces: K-sliced)
         achieved = flops / us_step * 1e-6
         # the monolithic GEMM of the same shape, for reference
         whole_us, _, winfo = launch_time(F.FICCO_SERIAL, 1, A_stage)
@@ -524,12 +542,12 @@ def main() -> int:
         out["pcie_inclusive"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.items()}
 
     if "losses" in legs and not rs:
-        s, c = best if best else (F.FICCO_FINE_FUSED, 2)
-        s %= PACKED
+        sc = best if best else (pick if pick is not None else (F.FICCO_FINE_FUSED, 2, "rm"))
+        sc = (sc[0] % PACKED, sc[1], sc[2])
         losses = {}
         for tag in ("hbm", "pcie"):
-            src = source(tag, s, c)
-            plan = make(s, c)
+            src = source(tag, *sc)
+            plan = make(*sc)
             L = F.ficco_profile_losses(plan, src, A_dev, W_dev, C_dev, cs, xs, 10, 5)
             F.ficco_destroy(plan)
             losses[tag] = {k: round(v, 4) for k, v in L.as_dict().items()}
@@ -539,12 +557,38 @@ def main() -> int:
             losses[tag]["comm_cil_pct"] = round((L.comm_cil - 1) * 100, 2)
         out["losses"] = losses
 
+    if "small" in legs and not rs and args.workload == "cfg3_ffn70b":
+        # the two smaller all-gather workloads, each by a run of this script of its own (pair and pcie legs),
+        # condensed to: serial, shard-level, the library's pick, the best of the screen; both source kinds
+        import subprocess
+        small = {}
+        for w in ("cfg1_tiny", "cfg2_qkv8b"):
+            r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", w, "--legs", "pair,pcie",
+                                "--steps", str(min(args.steps, 30)), "--warmup", str(min(args.warmup, 5))],
+                               stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+            if r.returncode != 0:
+                small[w] = {"error": r.stderr[-400:]}
+                continue
+            d = json.loads(r.stdout.strip().splitlines()[-1])
+            row = {"shape": [d["config"]["M"], d["config"]["K"], d["config"]["N"]]}
+            for key, leg in (("hbm_staging", "pair"), ("pinned_host", "pcie_inclusive")):
+                q = d[leg]
+                row[key] = {"ms_serial": q["ms_serial"], "ms_shard_level": q["ms_shard_level"],
+                            "library_pick": f'{q["schedule"]}:' + ("+".join(map(str, q["slice_widths"])) if q["slice_widths"] else str(q["chunks_per_shard"])),
+                            "ms_library_pick": q["ms_per_step"], "eff_tflops": q["eff_tflops"],
+                            "speedup_vs_serial": q["speedup_vs_serial"], "speedup_vs_shard_level": q["speedup_vs_shard_level"],
+                            "screen_best": q["screen_best"], "ms_screen_best": q["ms_screen_best"],
+                            "best_row_pieces": q["best_row_pieces"], "ms_best_row_pieces": q["ms_best_row_pieces"],
+                            "shard_granularity_all_links_ms_host_synced": q["shard_granularity_all_links_ms_host_synced"]}
+            small[w] = row
+        out["small_workloads"] = small
+
     if "graph" in legs and not rs:
         # HIP-graph replay of one run against the same run enqueued call by call (stream backend, shards in
         # pinned host memory): mean step time, and the host time one enqueue takes
         res = {}
         for sname, sched, c in (("serial", F.FICCO_SERIAL, 1), ("fine_fused", F.FICCO_FINE_FUSED, 4), ("fine_unfused", F.FICCO_FINE_UNFUSED, 4)):
-            plan = make(sched, c, [(F.FICCO_OPT_COPY_BACKEND, F.FICCO_COPY_STREAM)])
+            plan = make(sched, c, opts=[(F.FICCO_OPT_COPY_BACKEND, F.FICCO_COPY_STREAM)])
             row = {}
             for how in ("eager", "graph"):
                 if how == "graph":

@@ -252,15 +252,21 @@ typedef struct ficco_stats {
 } ficco_stats_t;
 
 typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this plan's decomposition    */
-    double t_gemm_whole_us;         /* one GEMM over all M rows, isolated                               */
-    double t_gemm_pieces_us;        /* sum of the plan's GEMM launches, isolated, back to back          */
-    double t_gemm_pieces_cont_us;   /* the same launches while the plan's transfers run independently   */
+    double t_gemm_whole_us;         /* one GEMM over all M rows, isolated: span of 8 launches back to back / 8,
+                                       after 40 ms of the same launches have settled the clocks           */
+    double t_gemm_pieces_us;        /* the plan's GEMM launches, isolated, taken the same way (span: dispatch gaps
+                                       between a decomposed schedule's launches count as decomposition cost) */
+    double t_gemm_pieces_cont_us;   /* span of the same launches, one run per bracket, while the plan's transfers run
+                                       independently                                                     */
     double t_copy_whole_us;         /* G shard-sized transfers, isolated                                */
     double t_copy_pieces_us;        /* the plan's transfers, isolated                                   */
     double t_copy_pieces_cont_us;   /* the plan's transfers while the GEMM launches run independently   */
-    double gemm_dil, gemm_cil;      /* ratios: pieces/whole, contended/isolated                         */
-    double comm_dil, comm_cil;
+    double gemm_dil, gemm_cil;      /* t_gemm_pieces_us / t_gemm_whole_us; t_gemm_pieces_cont_us / t_gemm_pieces_single_us */
+    double comm_dil, comm_cil;      /* pieces / whole; contended / isolated                             */
     double ideal_us;                /* ideal-overlap time from the whole-operator times (Sec. IV-A)     */
+    double t_gemm_pieces_single_us; /* span of the plan's launches, isolated, one run per bracket (CIL's denominator) */
+    double t_gemm_pieces_busy_us;   /* sum of the launches' own durations (an event before and after each launch;
+                                       for a resident schedule the one launch's)                       */
 } ficco_losses_t;
 
 /*
@@ -467,10 +473,14 @@ int ficco_profile_losses(ficco_plan_t *plan, const void *A_src, void *A_dev, con
  */
 int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
 
-/* The same for callers that can hand over the activation K-sliced (see ficco_run): may also answer
- * FICCO_FINE_2D, with the number of slices in *chunks - the choice of communication shape of
- * Sec. V-C, decided here by whether the output is about one round of tiles over the machine. */
+/* The same with column pieces allowed - the choice of communication shape of Sec. V-C, decided here by whether
+ * the output is about one round of tiles over the machine: may also answer FICCO_FINE_2D, with the number of
+ * slices in *chunks. ficco_pick_schedule_any answers for the caller's row-major A_src (what a FICCO_AUTO_ANY
+ * plan uses): the step then pays for the sender-side re-layout, so column pieces are only picked where the GEMM
+ * is the longer side and large enough to hide it. ficco_pick_schedule_layout takes the ficco_source_layout: for
+ * a sender that holds its slices K-sliced already, column pieces are picked for every small output. */
 int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
+int ficco_pick_schedule_layout(int64_t M, int64_t K, int64_t N, int shards, int source_layout, int *schedule, int *chunks);
 
 /* The cut of the k range that goes with a FICCO_FINE_2D answer: widths[0..slices) for
  * ficco_plan_set_slice_widths (a FICCO_AUTO_ANY plan has them applied already). Two slices of a

@@ -62,7 +62,8 @@ class ficco_losses_t(C.Structure):
                 ("t_gemm_pieces_cont_us", C.c_double), ("t_copy_whole_us", C.c_double),
                 ("t_copy_pieces_us", C.c_double), ("t_copy_pieces_cont_us", C.c_double),
                 ("gemm_dil", C.c_double), ("gemm_cil", C.c_double),
-                ("comm_dil", C.c_double), ("comm_cil", C.c_double), ("ideal_us", C.c_double)]
+                ("comm_dil", C.c_double), ("comm_cil", C.c_double), ("ideal_us", C.c_double),
+                ("t_gemm_pieces_single_us", C.c_double), ("t_gemm_pieces_busy_us", C.c_double)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -70,7 +71,7 @@ class ficco_losses_t(C.Structure):
 
 EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_chain", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
            "ficco_pack_weight", "ficco_run", "ficco_gemm_static", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
-           "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
+           "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_pick_schedule_layout", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
 _lib = None
@@ -113,6 +114,7 @@ def load():
     lib.ficco_profile_losses.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(ficco_losses_t)]
     lib.ficco_pick_schedule.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_schedule_any.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.ficco_pick_schedule_layout.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_slice_widths.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.POINTER(i64)]
     lib.ficco_static_descriptors.argtypes = [i64, i64, i64, dp, dp]
     lib.ficco_ideal_overlap_us.argtypes = [C.c_double, C.c_double, C.c_int]
@@ -293,8 +295,15 @@ def ficco_pick_slice_widths(M, K, N, shards, slices):
     return list(w)[:slices]
 
 
+def ficco_pick_schedule_layout(M, K, N, shards, source_layout):
+    """As :func:`ficco_pick_schedule_any` for a given ficco_source_layout of A_src."""
+    s, c = C.c_int(), C.c_int()
+    _ok(load().ficco_pick_schedule_layout(M, K, N, shards, source_layout, C.byref(s), C.byref(c)), "ficco_pick_schedule_layout")
+    return s.value, c.value
+
+
 def ficco_pick_schedule_any(M, K, N, shards):
-    """As :func:`ficco_pick_schedule`, for callers that can provide the K-sliced layout (may answer FICCO_FINE_2D)."""
+    """As :func:`ficco_pick_schedule` with column pieces allowed (may answer FICCO_FINE_2D); A_src row-major."""
     s, c = C.c_int(), C.c_int()
     _ok(load().ficco_pick_schedule_any(M, K, N, shards, C.byref(s), C.byref(c)), "ficco_pick_schedule_any")
     return s.value, c.value

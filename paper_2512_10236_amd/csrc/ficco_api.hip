@@ -611,37 +611,62 @@ int ficco_profile_losses(ficco_plan_t *p, const void *A_src, void *A_dev, const 
     whole->spin_limit_us = p->spin_limit_us;
     const int saved_mode = p->mode, saved_timing = p->timing;
 
-    // mean span of one mode over `iters` runs after `warmup`
-    auto measure = [&](ficco_plan_t *q, int mode, double *gemm_us, double *copy_us) -> int {
+    // mean span of one mode over `iters` runs after `warmup`; `repeat` > 1 (GEMM alone): every run enqueues the
+    // plan's launches that many times back to back inside its bracket of events and the span is divided by it
+    auto measure = [&](ficco_plan_t *q, int mode, int timing, int repeat, double *gemm_us, double *copy_us, double *busy_us) -> int {
         int r = ficco_plan_set(q, FICCO_OPT_MODE, mode);
         if (r) return r;
-        if ((r = ficco_plan_set(q, FICCO_OPT_TIMING, 0))) return r;
-        double g = 0, cp = 0;
+        if ((r = ficco_plan_set(q, FICCO_OPT_TIMING, timing))) return r;
+        if ((r = ficco_plan_set(q, FICCO_OPT_REPEAT, repeat))) return r;
+        double g = 0, cp = 0, bz = 0;
         for (int it = 0; it < warmup + iters; ++it) {
             if ((r = ficco_run(q, A_src, A_dev, W_dev, C_dev, nullptr, compute_stream, copy_stream))) return r;
             ficco_stats_t s;
             if ((r = ficco_query_stats(q, &s))) return r;
-            if (it >= warmup) { g += s.gemm_span_us; cp += s.copy_span_us; }
+            if (it >= warmup) { g += s.gemm_span_us / repeat; cp += s.copy_span_us; bz += s.gemm_busy_us; }
         }
         if (gemm_us) *gemm_us = g / iters;
         if (copy_us) *copy_us = cp / iters;
-        return FICCO_OK;
+        if (busy_us) *busy_us = bz / iters;
+        return ficco_plan_set(q, FICCO_OPT_REPEAT, 1);
     };
 
     ficco_losses_t L{};
+    const int saved_repeat = p->repeat;
+    constexpr int kRepeat = 8;
     do {
-        if ((rc = measure(whole, FICCO_MODE_GEMM_ONLY, &L.t_gemm_whole_us, nullptr))) break;
-        if ((rc = measure(whole, FICCO_MODE_COPY_ONLY, nullptr, &L.t_copy_whole_us))) break;
-        if ((rc = measure(p, FICCO_MODE_GEMM_ONLY, &L.t_gemm_pieces_us, nullptr))) break;
-        if ((rc = measure(p, FICCO_MODE_COPY_ONLY, nullptr, &L.t_copy_pieces_us))) break;
-        if ((rc = measure(p, FICCO_MODE_INDEPENDENT, &L.t_gemm_pieces_cont_us, &L.t_copy_pieces_cont_us))) break;
+        // After an idle spell the shader clock needs some tens of milliseconds of load to settle: the whole GEMM
+        // runs back to back until 40 ms of it have passed before anything is measured.
+        {
+            if ((rc = ficco_plan_set(whole, FICCO_OPT_MODE, FICCO_MODE_GEMM_ONLY))) break;
+            if ((rc = ficco_plan_set(whole, FICCO_OPT_REPEAT, kRepeat))) break;
+            double burnt_us = 0;
+            while (burnt_us < 40e3 && !rc) {
+                if ((rc = ficco_run(whole, A_src, A_dev, W_dev, C_dev, nullptr, compute_stream, copy_stream))) break;
+                ficco_stats_t s;
+                if ((rc = ficco_query_stats(whole, &s))) break;
+                burnt_us += s.wall_us > 1.0 ? s.wall_us : 1.0;
+            }
+            if (rc) break;
+        }
+        // decomposition loss: both sides as launches back to back, clocks settled
+        if ((rc = measure(whole, FICCO_MODE_GEMM_ONLY, 0, kRepeat, &L.t_gemm_whole_us, nullptr, nullptr))) break;
+        if ((rc = measure(p, FICCO_MODE_GEMM_ONLY, 0, kRepeat, &L.t_gemm_pieces_us, nullptr, nullptr))) break;
+        // the launches' own durations summed (an event before and after each): what is left of the span are dispatch gaps
+        if ((rc = measure(p, FICCO_MODE_GEMM_ONLY, 1, 1, nullptr, nullptr, &L.t_gemm_pieces_busy_us))) break;
+        // contention loss: one run per bracket on both sides, so that the two are taken the same way
+        if ((rc = measure(p, FICCO_MODE_GEMM_ONLY, 0, 1, &L.t_gemm_pieces_single_us, nullptr, nullptr))) break;
+        if ((rc = measure(whole, FICCO_MODE_COPY_ONLY, 0, 1, nullptr, &L.t_copy_whole_us, nullptr))) break;
+        if ((rc = measure(p, FICCO_MODE_COPY_ONLY, 0, 1, nullptr, &L.t_copy_pieces_us, nullptr))) break;
+        if ((rc = measure(p, FICCO_MODE_INDEPENDENT, 0, 1, &L.t_gemm_pieces_cont_us, &L.t_copy_pieces_cont_us, nullptr))) break;
     } while (0);
     ficco_destroy(whole);
     p->mode = saved_mode;
     p->timing = saved_timing;
+    p->repeat = saved_repeat;
     if (rc) return rc;
     L.gemm_dil = L.t_gemm_pieces_us / L.t_gemm_whole_us;
-    L.gemm_cil = L.t_gemm_pieces_cont_us / L.t_gemm_pieces_us;
+    L.gemm_cil = L.t_gemm_pieces_cont_us / L.t_gemm_pieces_single_us;
     L.comm_dil = L.t_copy_pieces_us / L.t_copy_whole_us;
     L.comm_cil = L.t_copy_pieces_cont_us / L.t_copy_pieces_us;
     L.ideal_us = ficco_ideal_overlap_us(L.t_copy_whole_us, L.t_gemm_whole_us, p->schedule == FICCO_SERIAL ? 1 : ((int)p->groups.size() > 1 ? (int)p->groups.size() : p->n_chunks));

@@ -478,10 +478,10 @@ int run_engines(ficco_plan_t *p, const void *A_src, void *A_dev, void *C_dev, vo
         sl.k0 = p->d_slice_k0;
         sl.arrival = p->d_arrival;
         sl.n_pieces = n;
-        // blocks of about 256 KiB of the widest slice: many more blocks than CUs, few enough to keep the counters quiet
+        // blocks of about 64 KiB of the widest slice, walked in arrival order by at most 1024 workgroups
         int64_t widest = 0;
         for (int q = 0; q < c; ++q) widest = std::max<int64_t>(widest, p->slice_k0[q + 1] - p->slice_k0[q]);
-        sl.rows_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(p->m, (256 << 10) / (widest * 2)));
+        sl.rows_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(p->m, (64 << 10) / (widest * 2)));
         sl.blocks_per_piece = (int32_t)((p->m + sl.rows_per_block - 1) / sl.rows_per_block);
         sl.done_count = p->d_packed_count;
         sl.done_sig = p->d_packed_value;

@@ -18,6 +18,7 @@
 #include "ficco_internal.h"
 #include <stdlib.h>
 #include <type_traits>
+#include <algorithm>
 
 namespace ficco {
 
@@ -931,44 +932,51 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__rest
 // of a piece is width/8 of them; the workgroup's threads stride over (row, vector) pairs of its block.
 __global__ __launch_bounds__(256) void slice_source_kernel(SliceLaunch a)
 {
-    const int q = blockIdx.x / a.blocks_per_piece, b = blockIdx.x % a.blocks_per_piece;
-    const int piece = a.arrival[q];
-    const int sl = piece / a.shards, j = piece % a.shards;
-    const int kb = a.k0[sl], kw = a.k0[sl + 1] - kb;
-    const int r0 = b * a.rows_per_block, r1 = min(a.rows_per_shard, r0 + a.rows_per_block);
-    const int vecs = kw / 8;
-    const u32x4_t *src = reinterpret_cast<const u32x4_t *>(a.src + ((int64_t)j * a.rows_per_shard + r0) * a.K + kb);
-    u32x4_t *dst = reinterpret_cast<u32x4_t *>(a.dst + a.M * kb + ((int64_t)j * a.rows_per_shard + r0) * kw);
-    const int64_t src_pitch = a.K / 8;
-    const int total = (r1 - r0) * vecs;
-    for (int e = threadIdx.x; e < total; e += 4 * 256) {
-        u32x4_t v[4];
+    // blocks in arrival order, a bounded number of workgroups striding over them: the pieces of the first step
+    // are finished - and their transfers released - first instead of every piece at the end
+    const int total_blocks = a.n_pieces * a.blocks_per_piece;
+    for (int blk = blockIdx.x; blk < total_blocks; blk += gridDim.x) {
+        const int q = blk / a.blocks_per_piece, b = blk % a.blocks_per_piece;
+        const int piece = a.arrival[q];
+        const int sl = piece / a.shards, j = piece % a.shards;
+        const int kb = a.k0[sl], kw = a.k0[sl + 1] - kb;
+        const int r0 = b * a.rows_per_block, r1 = min(a.rows_per_shard, r0 + a.rows_per_block);
+        const int vecs = kw / 8;
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(a.src + ((int64_t)j * a.rows_per_shard + r0) * a.K + kb);
+        u32x4_t *dst = reinterpret_cast<u32x4_t *>(a.dst + a.M * kb + ((int64_t)j * a.rows_per_shard + r0) * kw);
+        const int64_t src_pitch = a.K / 8;
+        const int total = (r1 - r0) * vecs;
+        for (int e = threadIdx.x; e < total; e += 4 * 256) {
+            u32x4_t v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ee = e + u * 256;
-            if (ee < total) v[u] = __builtin_nontemporal_load(src + (int64_t)(ee / vecs) * src_pitch + ee % vecs);
-        }
+            for (int u = 0; u < 4; ++u) {
+                const int ee = e + u * 256;
+                if (ee < total) v[u] = __builtin_nontemporal_load(src + (int64_t)(ee / vecs) * src_pitch + ee % vecs);
+            }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ee = e + u * 256;
-            // written through the caches: the reader is a copy engine
-            if (ee < total) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst + ee), "v"(v[u]) : "memory");
+            for (int u = 0; u < 4; ++u) {
+                const int ee = e + u * 256;
+                // written through the caches: the reader is a copy engine
+                if (ee < total) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(dst + ee), "v"(v[u]) : "memory");
+            }
         }
-    }
-    // every store of the block has been performed (not just issued) before the block is counted
-    wait_vmem<0>();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t before = __hip_atomic_fetch_add(a.done_count + piece, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((before + 1u) % (uint32_t)a.blocks_per_piece == 0u)
-            __hip_atomic_store(reinterpret_cast<int64_t *>(a.done_sig[piece]), (int64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        // every store of the block has been performed (not just issued) before the block is counted
+        wait_vmem<0>();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t before = __hip_atomic_fetch_add(a.done_count + piece, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((before + 1u) % (uint32_t)a.blocks_per_piece == 0u)
+                __hip_atomic_store(reinterpret_cast<int64_t *>(a.done_sig[piece]), (int64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
 hipError_t launch_slice_source(const SliceLaunch &a, hipStream_t s)
 {
     if (a.n_pieces <= 0 || a.blocks_per_piece <= 0 || a.rows_per_block <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(slice_source_kernel, dim3((unsigned)(a.n_pieces * a.blocks_per_piece)), dim3(256), 0, s, a);
+    const int64_t total = (int64_t)a.n_pieces * a.blocks_per_piece;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(slice_source_kernel, dim3((unsigned)std::min<int64_t>(total, 1024)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -470,48 +470,72 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
 {
     if (M < 1 || K < 1 || N < 1 || shards < 1 || !schedule || !chunks) return FICCO_ERR_ARG;
     if (M % shards) return FICCO_ERR_SHAPE;
-    // Static rule in the spirit of Sec. V-C: decomposition loss grows as the decomposed GEMM's combined
-    // op-to-byte and memory-traffic metric (their product = its flop count) falls, so a shard is cut
-    // into as many pieces as keep one piece's GEMM above a machine threshold (fitted on MI355X with
-    // the sweep tool: 2.5e10 flop, piece rows a power of two, at least 256 rows, at most 16 pieces).
-    // Among the schedules the resident kernel was the fastest at every point of the sweep, so the
-    // schedule itself needs no threshold here.
+    // Static rule in the spirit of Sec. V-C, built on the overlap model of Sec. IV-A with the two losses of
+    // Sec. IV-B as per-piece costs. With c pieces per shard, all links side by side, the pair takes about
+    //     T(c) = max(Tc + c * a, Tg + c * b) + min(Tc, Tg) / c
+    // Tc = one shard over one link, Tg = the whole GEMM, both from machine rates (58 GB/s per copy engine, 1.2e15
+    // flop/s sustained by the GEMM kernel); a = 16 us is what one more piece costs a link (the gap an engine leaves
+    // between copies and the lower rate of small copies: the communication DIL), b = 8 us what it costs the GEMM
+    // (GEMM DIL). The first term is the longer side stretched by its own per-piece cost, the second what stays
+    // exposed of the shorter side: the first piece's transfer or the last piece's GEMM. c = the power of two up to
+    // 32 that divides the shard, keeps pieces of at least 256 rows and minimises T. Among the schedules the resident
+    // kernel was the fastest at every point of the sweep, so the schedule itself needs no threshold. a, b and the
+    // row limit were fitted to the 24-shape sweep and scored on 16 shapes off its grid.
     const int64_t ms = M / shards;
-    const double kPieceFlops = 2.5e10;
-    const double t = kPieceFlops / (2.0 * (double)N * (double)K);
-    int64_t m = 1;
-    while ((double)(m * 2) <= t && m < (int64_t)1 << 40) m *= 2;
-    m = std::max<int64_t>(256, std::min(m, ms));
-    int c = (int)std::max<int64_t>(1, std::min<int64_t>(16, ms / m));
-    while (c > 1 && ms % c) c /= 2;
+    const double Tc = (double)ms * (double)K * 2.0 / 58.0e3;                        // us
+    const double Tg = 2.0 * (double)M * (double)N * (double)K / 1.2e9;              // us
+    int c = 1;
+    double best = -1.0;
+    for (int cc = 1; cc <= 32; cc *= 2) {
+        if (ms % cc || (cc > 1 && ms / cc < 256)) continue;
+        const double T = std::max(Tc + cc * 16.0, Tg + cc * 8.0) + std::min(Tc, Tg) / cc;
+        if (best < 0 || T < best * 0.999) { best = T; c = cc; }
+    }
     const int sch = FICCO_FINE_PERSISTENT;
     *schedule = sch;
     *chunks = c;
     return FICCO_OK;
 }
 
-int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
+int ficco_pick_schedule_layout(int64_t M, int64_t K, int64_t N, int shards, int source_layout, int *schedule, int *chunks)
 {
+    if (source_layout != FICCO_LAYOUT_ROW_MAJOR && source_layout != FICCO_LAYOUT_K_SLICED) return FICCO_ERR_ARG;
     int rc = ficco_pick_schedule(M, K, N, shards, schedule, chunks);
     if (rc) return rc;
     // Column pieces (the paper's 2D shape, Sec. V-C picks it from M against K) pay off on this machine when
-    // the output is no more than about one round of tiles over the CUs (256x256 tiles on 256 CUs, with 20 %
-    // slack: M*N <= 2e7): then every tile can make progress with every slice, while row pieces would leave
-    // most tiles waiting for their own piece. Slices: two when the transfers are the longer side (GEMM time
-    // over transfer time grows with N*shards; up to 8192 the transfers dominate: see ficco_pick_slice_widths
-    // for their cut), else 2, from 1e11 flop 4, from 4e11 flop 8 (the more the GEMM weighs, the earlier it
-    // should start). Fitted to the 24-shape sweep, where the rule picks the faster family everywhere, and to
-    // the M <= K workload of the bench.
-    if (K % kBK == 0 && (double)M * (double)N <= 2.0e7) {
-        const double flops = 2.0 * (double)M * (double)N * (double)K;
-        int sl = (double)N * shards <= 8192.0 ? 2 : flops < 1.0e11 ? 2 : flops < 4.0e11 ? 4 : 8;
-        while (sl > 1 && sl > K / kBK) sl /= 2;
-        if (sl > 1) {
-            *schedule = FICCO_FINE_2D;
-            *chunks = sl;
-        }
+    // the output is no more than one round of 256x256 tiles over the 256 CUs: then every tile can make progress
+    // with every slice, while row pieces would leave most tiles waiting for their own piece. With a second,
+    // partly filled round every tile of it would wait for the whole first round (measured: 18 % more tiles than
+    // CUs made column pieces 18-37 % slower than row pieces).
+    if (K % kBK != 0 || ((M + 255) / 256) * ((N + 255) / 256) > 256) return FICCO_OK;
+    const double flops = 2.0 * (double)M * (double)N * (double)K;
+    const bool transfer_bound = (double)N * shards <= 8192.0;     // GEMM time over transfer time grows with N*shards
+    int sl;
+    if (source_layout == FICCO_LAYOUT_K_SLICED) {
+        // The sender holds its slices ready for DMA. Two slices when the transfers are the longer side (see
+        // ficco_pick_slice_widths for their cut), else 2, from 1e11 flop 4, from 4e11 flop 8 (the more the GEMM
+        // weighs, the earlier it should start). Fitted to the 24-shape sweep and the M <= K workload of the bench.
+        sl = transfer_bound ? 2 : flops < 1.0e11 ? 2 : flops < 4.0e11 ? 4 : 8;
+    } else {
+        // The caller's row-major matrix: the step also pays for the sender-side re-layout (device sources) or
+        // moves strided rectangles (pinned host sources). Where the transfers are the longer side that delay
+        // lands on the critical path and row pieces stay ahead (measured at all eight transfer-bound shapes
+        // tried); where the GEMM is the longer side and weighs at least 2e11 flop the re-layout hides behind
+        // it and column pieces keep a lead of 9-13 %.
+        if (transfer_bound || flops < 2.0e11) return FICCO_OK;
+        sl = flops < 4.0e11 ? 4 : 8;
+    }
+    while (sl > 1 && sl > K / kBK) sl /= 2;
+    if (sl > 1) {
+        *schedule = FICCO_FINE_2D;
+        *chunks = sl;
     }
     return FICCO_OK;
+}
+
+int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
+{
+    return ficco_pick_schedule_layout(M, K, N, shards, FICCO_LAYOUT_ROW_MAJOR, schedule, chunks);
 }
 
 int ficco_pick_slice_widths(int64_t M, int64_t K, int64_t N, int shards, int slices, int64_t *widths)

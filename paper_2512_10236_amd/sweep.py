@@ -1,216 +1,249 @@
 #!/usr/bin/env python3
-"""Heuristic sweep (paper Sec. V-C, Sec. VI-D): measure every schedule and piece count on a grid of
-all-gather -> GEMM shapes on this GPU, fit the thresholds of the static schedule rule, and report
-how often the rule picks the measured best.
+"""Heuristic sweep (paper Sec. V-C, Sec. VI-D): measure the schedules and piece counts on all-gather -> GEMM
+shapes on this GPU, fit the constants of the static row-piece rule, and report how often the library's rules
+pick the measured best - on the grid the constants were fitted on and on shapes they never saw.
 
-    python -m paper_2512_10236_amd.sweep --out sweep.jsonl            # measure
-    python -m paper_2512_10236_amd.sweep --fit sweep.jsonl            # fit + accuracy
+    python -m paper_2512_10236_amd.sweep --out grid.jsonl                 # measure the grid
+    python -m paper_2512_10236_amd.sweep --out unseen.jsonl --holdout     # measure 16 shapes off the grid
+    python -m paper_2512_10236_amd.sweep --fit grid.jsonl --score unseen.jsonl
 
-Shapes default to the grid M in {4096,16384,65536} x K in {4096,8192} x N in {512,1024,3584,14336},
-8 shards, pieces per shard in {1,2,4,8,16,32}; shards are moved from a device staging buffer by one
-SDMA engine per shard. Inputs are seeded normal bf16 (A ~ N(0,1), W ~ N(0,1/K)) generated on the
-device; every schedule's output is compared bitwise with the serial schedule's.
-PyTorch is used for device memory and streams only.
+The grid is M in {4096,16384,65536} x K in {4096,8192} x N in {512,1024,3584,14336}, 8 shards, pieces per shard
+in {1,2,4,8,16,32}; shards are moved from a device staging buffer by one SDMA engine per shard. Inputs are the
+seeded bf16 bits of ficco_inputs (A ~ N(0,1), W ~ N(0,1/K), the sweep's seed); every schedule's output is
+compared bitwise with the serial schedule's (whose correctness against the CPU oracle the GPU tests check at the
+corners of the grid). Column pieces are measured out of the caller's row-major matrix (layout "rm": the step pays
+for the sender-side re-layout) and out of a K-sliced source (layout "ks"). PyTorch is used for device memory and
+streams only.
 """
 from __future__ import annotations
 
 import argparse
 import json
-import math
+import os
 import sys
 
-from . import binding as F
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from . import binding as F  # noqa: E402
 
 FINE = (F.FICCO_FINE_UNFUSED, F.FICCO_FINE_FUSED, F.FICCO_FINE_PERSISTENT)
+# sixteen shapes off the grid (the paper scores its rule on 16 unseen scenarios too, Sec. VI-D)
+HOLDOUT = [(8192, 8192, 2048), (4096, 16384, 2048), (8192, 4096, 2560), (2048, 8192, 8192), (4096, 4096, 2048),
+           (8192, 16384, 1024), (2048, 16384, 7168), (4096, 8192, 2048), (32768, 4096, 1536), (8192, 8192, 7168),
+           (16384, 16384, 1024), (2048, 4096, 4096), (32768, 8192, 512), (8192, 2048, 8192), (4096, 12288, 4608),
+           (24576, 4096, 3072)]
 
 
 def measure(args) -> int:
+    import numpy as np
     import torch
+
+    import ficco_inputs as fi
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
     G = args.shards
+    seed = fi.SWEEP["seed"]
+    shapes = HOLDOUT if args.holdout else [(M, K, N) for M in args.M for K in args.K for N in args.N]
     out = open(args.out, "w")
-    for M in args.M:
-        for K in args.K:
-            gen = torch.Generator(device=dev)
-            gen.manual_seed(4)
-            A_stage = torch.randn((M, K), device=dev, generator=gen).to(torch.bfloat16).view(torch.int16)
-            A_dev = torch.zeros((M, K), dtype=torch.int16, device=dev)
-            for N in args.N:
-                W = (torch.randn((K, N), device=dev, generator=gen) * K ** -0.5).to(torch.bfloat16).view(torch.int16)
-                C = torch.zeros((M, N), dtype=torch.int16, device=dev)
-                C_ref = None
-                cases = [(F.FICCO_SERIAL, 1, None), (F.FICCO_SHARD, 1, None)]
-                cases += [(s, c, None) for c in args.chunks for s in FINE if (M // G) % c == 0 and c * G <= 4096]
-                # the 2D schedule (k slices) wherever the slices are whole k-tiles; its source is the K-sliced copy
-                cases += [(F.FICCO_FINE_2D, c, None) for c in args.chunks if c > 1 and K % (64 * c) == 0 and c * G <= 4096]
-                # what ficco_pick_schedule_any answers, when that is column pieces in a cut of its own
-                ps, pc = F.ficco_pick_schedule_any(M, K, N, G)
-                if ps == F.FICCO_FINE_2D:
-                    pw = F.ficco_pick_slice_widths(M, K, N, G, pc)
-                    if len(set(pw)) > 1:
-                        cases.append((ps, pc, pw))
-                for sched, c, widths in cases:
-                    src = A_stage
-                    if widths is not None:
-                        edges = [sum(widths[:i]) for i in range(len(widths) + 1)]
-                        src = torch.cat([A_stage[:, edges[i]:edges[i + 1]].reshape(-1) for i in range(len(widths))]).view(M, K)
+    held = {}
+
+    def bits(kind, r, c):                                   # one upload per distinct tensor
+        if (kind, r, c) not in held:
+            if len(held) > 2:
+                held.clear()
+                torch.cuda.empty_cache()
+            b = fi.normal_bf16(seed, fi.TENSOR_A, r, c) if kind == "A" else fi.make_weight(seed, r, c)
+            held[(kind, r, c)] = torch.from_numpy(b.view(np.int16)).to(dev)
+        return held[(kind, r, c)]
+
+    for M, K, N in shapes:
+        A_stage, W = bits("A", M, K), bits("W", K, N)
+        A_dev = torch.zeros((M, K), dtype=torch.int16, device=dev)
+        C = torch.zeros((M, N), dtype=torch.int16, device=dev)
+        C_ref = None
+        cases = [(F.FICCO_SERIAL, 1, None, "rm"), (F.FICCO_SHARD, 1, None, "rm")]
+        cases += [(s, c, None, "rm") for c in args.chunks for s in FINE
+                  if (M // G) % c == 0 and c * G <= 4096 and (s != F.FICCO_FINE_UNFUSED or c <= 4)]
+        for lay in ("rm", "ks"):
+            cases += [(F.FICCO_FINE_2D, c, None, lay) for c in (2, 4, 8) if K % (64 * c) == 0]
+            pw = F.ficco_pick_slice_widths(M, K, N, G, 2)         # the unequal cut of two slices, where the rule has one
+            if len(set(pw)) > 1:
+                cases.append((F.FICCO_FINE_2D, 2, pw, lay))
+        for sched, c, widths, lay in cases:
+            src = A_stage
+            if sched == F.FICCO_FINE_2D and lay == "ks":
+                w = widths if widths is not None else [K // c] * c
+                edges = [sum(w[:i]) for i in range(len(w) + 1)]
+                src = torch.cat([A_stage[:, edges[i]:edges[i + 1]].reshape(-1) for i in range(len(w))]).view(M, K)
+                torch.cuda.synchronize()
+            plan = F.ficco_plan(M, K, N, G, c, sched)
+            try:
+                if widths is not None:
+                    F.ficco_plan_set_slice_widths(plan, widths)
+                if sched == F.FICCO_FINE_2D and lay == "ks":
+                    F.ficco_plan_set(plan, F.FICCO_OPT_SOURCE_LAYOUT, F.FICCO_LAYOUT_K_SLICED)
+                F.ficco_pack_weight(plan, W, cs)
+                ts, cps = [], []
+                for it in range(args.warmup + args.iters):
+                    if it == 0:
+                        C.zero_()
                         torch.cuda.synchronize()
-                    elif sched == F.FICCO_FINE_2D:
-                        src = A_stage.view(M, c, K // c).permute(1, 0, 2).contiguous().view(M, K)
-                        torch.cuda.synchronize()
-                    plan = F.ficco_plan(M, K, N, G, c, sched)
-                    try:
-                        if widths is not None:
-                            F.ficco_plan_set_slice_widths(plan, widths)
-                        F.ficco_pack_weight(plan, W, cs)
-                        ts, cps = [], []
-                        for it in range(args.warmup + args.iters):
-                            if it == 0:
-                                C.zero_()
-                                torch.cuda.synchronize()
-                            F.ficco_run(plan, src, A_dev, W, C, None, cs, xs)
-                            st = F.ficco_query_stats(plan)
-                            if it >= args.warmup:
-                                ts.append(st.wall_us)
-                                cps.append(st.copy_span_us)
-                        info = F.ficco_plan_info(plan)
-                    finally:
-                        F.ficco_destroy(plan)
-                    torch.cuda.synchronize()
-                    if C_ref is None:
-                        C_ref = C.clone()
-                        same = True
-                    else:
-                        same = bool(torch.equal(C, C_ref))
-                    row = dict(M=M, K=K, N=N, shards=G, schedule=F.SCHEDULE_NAMES[sched], sched_id=sched, chunks=c,
-                               wall_us=round(sum(ts) / len(ts), 2), min_us=round(min(ts), 2),
-                               copy_span_us=round(sum(cps) / len(cps), 2), tile=f"{info.tile_m}x{info.tile_n}",
-                               bits_equal_serial=same)
-                    if widths is not None:
-                        row["widths"] = widths
-                    out.write(json.dumps(row) + "\n")
-                    out.flush()
-                    print(json.dumps(row), flush=True)
-                    if not same:
-                        print("sweep: output differs bitwise from the serial schedule", file=sys.stderr)
-                        return 1
-                del W, C, C_ref
-            del A_stage, A_dev
-            torch.cuda.empty_cache()
+                    F.ficco_run(plan, src, A_dev, W, C, None, cs, xs)
+                    st = F.ficco_query_stats(plan)
+                    if it >= args.warmup:
+                        ts.append(st.wall_us)
+                        cps.append(st.copy_span_us)
+                info = F.ficco_plan_info(plan)
+            finally:
+                F.ficco_destroy(plan)
+            torch.cuda.synchronize()
+            if C_ref is None:
+                C_ref = C.clone()
+            same = bool(torch.equal(C, C_ref))
+            row = dict(M=M, K=K, N=N, shards=G, schedule=F.SCHEDULE_NAMES[sched], sched_id=sched, chunks=c, layout=lay,
+                       wall_us=round(sum(ts) / len(ts), 2), min_us=round(min(ts), 2),
+                       copy_span_us=round(sum(cps) / len(cps), 2), tile=f"{info.tile_m}x{info.tile_n}", bits_equal_serial=same)
+            if widths is not None:
+                row["widths"] = widths
+            out.write(json.dumps(row) + "\n")
+            out.flush()
+            print(json.dumps(row), flush=True)
+            if not same:
+                print("sweep: output differs bitwise from the serial schedule", file=sys.stderr)
+                return 1
+        del A_dev, C, C_ref
     return 0
 
 
-def rule(M, K, N, G, piece_flops, min_rows, max_pieces):
-    """The static rule of ficco_pick_schedule with free constants: the resident schedule, and as many
-    pieces per shard as keep one piece's GEMM (OTB x MT = its flops) above ``piece_flops``."""
+def row_rule(M, K, N, G, a_us, b_us, min_rows):
+    """The static rule of ficco_pick_schedule with free constants: the resident schedule, and the power-of-two
+    piece count that minimises T(c) = max(Tc + c a, Tg + c b) + min(Tc, Tg) / c (Sec. IV-A's overlap model with
+    a per-piece cost on either side), Tc = one shard over one 58 GB/s link, Tg = the GEMM at 1.2e15 flop/s."""
     ms = M // G
-    t = piece_flops / (2.0 * N * K)
-    m = 1
-    while m * 2 <= t:
-        m *= 2
-    m = max(min_rows, min(m, ms))
-    c = max(1, min(max_pieces, ms // m))
-    while c > 1 and ms % c:
-        c //= 2
+    Tc, Tg = ms * K * 2 / 58e3, 2.0 * M * N * K / 1.2e9
+    best, c = None, 1
+    for cc in (1, 2, 4, 8, 16, 32):
+        if ms % cc or (cc > 1 and ms // cc < min_rows):
+            continue
+        T = max(Tc + cc * a_us, Tg + cc * b_us) + min(Tc, Tg) / cc
+        if best is None or T < best * 0.999:
+            best, c = T, cc
     return F.FICCO_FINE_PERSISTENT, c
 
 
-def fit(args) -> int:
-    rows = [json.loads(l) for l in open(args.fit) if l.startswith("{")]
+def load(path):
     shapes = {}
-    for r in rows:
-        shapes.setdefault((r["M"], r["K"], r["N"], r["shards"]), []).append(r)
-    keys = sorted(shapes)
+    for line in open(path):
+        if line.startswith("{"):
+            r = json.loads(line)
+            shapes.setdefault((r["M"], r["K"], r["N"], r["shards"]), []).append(r)
     table = []
-    for k in keys:
+    for k in sorted(shapes):
         rs = shapes[k]
-        serial = next(r for r in rs if r["schedule"] == "serial")["wall_us"]
-        shard = next(r for r in rs if r["schedule"] == "shard")["wall_us"]
-        fine = [r for r in rs if r["sched_id"] in FINE]
-        best = min(fine, key=lambda r: r["wall_us"])
-        two_d = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D and "widths" not in r]
-        cut = [r for r in rs if r["sched_id"] == F.FICCO_FINE_2D and "widths" in r]
-        if two_d:
-            b2 = min(two_d, key=lambda r: r["wall_us"])
-            note_2d = f"  best 2D x{b2['chunks']} {b2['wall_us']:9.1f} us ({best['wall_us'] / b2['wall_us']:.3f}x of best 1D)"
+        t = dict(key=k, serial=next(r for r in rs if r["schedule"] == "serial")["wall_us"],
+                 shard=next(r for r in rs if r["schedule"] == "shard")["wall_us"],
+                 fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in rs if r["sched_id"] in FINE})
+        t["best_rows"] = min(t["fine"].values())
+        for lay in ("rm", "ks"):
+            t["2d_" + lay] = {(r["chunks"], tuple(r.get("widths", ()))): r["wall_us"] for r in rs
+                              if r["sched_id"] == F.FICCO_FINE_2D and r.get("layout", "ks") == lay}
+        table.append(t)
+    return table
+
+
+def score_rows(consts, subset):
+    hit = near = 0
+    loss = []
+    for t in subset:
+        M, K, N, G = t["key"]
+        got = t["fine"].get(row_rule(M, K, N, G, *consts))
+        if got is None:
+            continue
+        bw = t["best_rows"]
+        hit += got <= 1.001 * bw
+        near += got <= 1.03 * bw
+        if got > 1.03 * bw:
+            loss.append((t["serial"] / bw - t["serial"] / got) / (t["serial"] / bw))
+    return hit, near, loss
+
+
+def score_layout(table, layout):
+    """ficco_pick_schedule_layout against the best of row pieces and of column pieces out of that source layout."""
+    lay = "rm" if layout == F.FICCO_LAYOUT_ROW_MAJOR else "ks"
+    hit = near = fam = n = 0
+    worst, loss = 0.0, []
+    for t in table:
+        M, K, N, G = t["key"]
+        two_d = t["2d_" + lay]
+        if not two_d:
+            continue
+        s, c = F.ficco_pick_schedule_layout(M, K, N, G, layout)
+        if s == F.FICCO_FINE_2D:
+            w = tuple(F.ficco_pick_slice_widths(M, K, N, G, c))
+            got = two_d.get((c, w if len(set(w)) > 1 else ()))
         else:
-            note_2d = ""
-        table.append(dict(key=k, serial=serial, shard=shard, best=best, fine={(r["sched_id"], r["chunks"]): r["wall_us"] for r in fine},
-                          best_2d=min((r["wall_us"] for r in two_d), default=None),
-                          two_d={r["chunks"]: r["wall_us"] for r in two_d},
-                          rule_cut={(r["chunks"], tuple(r["widths"])): r["wall_us"] for r in cut}))
-        print(f"M={k[0]:6d} K={k[1]:5d} N={k[2]:6d}: serial {serial:9.1f} us  shard-level {shard:9.1f} us  best {best['schedule']} x{best['chunks']} "
-              f"{best['wall_us']:9.1f} us  speedup {serial / best['wall_us']:.3f}x (vs shard-level {shard / best['wall_us']:.2f}x){note_2d}")
-
-    def score(consts, subset):
-        hit = near = 0
-        loss = []
-        for t in subset:
-            M, K, N, G = t["key"]
-            s, c = rule(M, K, N, G, *consts)
             got = t["fine"].get((s, c))
-            if got is None:
-                continue
-            bw = t["best"]["wall_us"]
-            hit += (s, c) == (t["best"]["sched_id"], t["best"]["chunks"])
-            near += got <= 1.03 * bw
-            if got > 1.03 * bw:
-                sp_best, sp_got = t["serial"] / bw, t["serial"] / got
-                loss.append((sp_best - sp_got) / sp_best)
-        return hit, near, loss
+        if got is None:
+            continue
+        n += 1
+        best = min(t["best_rows"], min(two_d.values()))
+        hit += got <= 1.001 * best
+        near += got <= 1.03 * best
+        worst = max(worst, got / best)
+        fam += (s == F.FICCO_FINE_2D) == (min(two_d.values()) < t["best_rows"])
+        if got > 1.03 * best:
+            loss.append((t["serial"] / best - t["serial"] / got) / (t["serial"] / best))
+    ml = 100 * sum(loss) / len(loss) if loss else 0.0
+    return f"exact {hit}/{n}, within 3% {near}/{n}, worst {100 * (worst - 1):.1f}% off, faster family at {fam}/{n}, mean loss of optimal speedup on misses {ml:.1f}%"
 
-    train, test = table[0::2], table[1::2]
-    best_c, best_s = None, (-1, -1)
-    for piece_flops in (0.5e10, 1e10, 1.5e10, 2e10, 2.5e10, 3e10, 4e10, 6e10, 1e11):
-        for min_rows in (128, 256, 512, 1024):
-            for max_pieces in (8, 16, 32):
-                consts = (piece_flops, min_rows, max_pieces)
-                h, n, _ = score(consts, train)
-                if (n, h) > best_s:
-                    best_s, best_c = (n, h), consts
-    for name, subset in (("fitted on (even shapes)", train), ("held out (odd shapes)", test), ("all", table)):
-        h, n, loss = score(best_c, subset)
+
+def fit(args) -> int:
+    table = load(args.fit)
+    for t in table:
+        k = t["key"]
+        best = min(t["fine"], key=t["fine"].get)
+        b2 = {lay: (min(t["2d_" + lay].values()) if t["2d_" + lay] else None) for lay in ("rm", "ks")}
+        print(f"M={k[0]:6d} K={k[1]:5d} N={k[2]:6d}: serial {t['serial']:9.1f} us  shard-level {t['shard']:9.1f} us  best rows "
+              f"{F.SCHEDULE_NAMES[best[0]]} x{best[1]} {t['best_rows']:9.1f} us ({t['serial'] / t['best_rows']:.3f}x serial)  "
+              f"best 2D row-major {b2['rm']}  K-sliced {b2['ks']}")
+    unseen = load(args.score) if args.score else []
+    sets = [("the grid (fitted on)", table), ("even grid shapes", table[0::2]), ("odd grid shapes", table[1::2])]
+    if unseen:
+        sets.append((f"unseen shapes ({len(unseen)}, off the grid)", unseen))
+    best_c, best_s = None, None
+    for a_us in (2, 4, 6, 8, 12, 16, 24):
+        for b_us in (0, 2, 4, 8, 12, 16, 24, 32):
+            for min_rows in (128, 256):
+                h, n, loss = score_rows((a_us, b_us, min_rows), table)
+                key = (n, h, -sum(loss))
+                if best_s is None or key > best_s:
+                    best_s, best_c = key, (a_us, b_us, min_rows)
+    print("row-piece rule, constants fitted on the grid: per-piece cost %g us on the transfer side, %g us on the GEMM side, pieces of at least %d rows" % best_c)
+    for name, subset in sets:
+        h, n, loss = score_rows(best_c, subset)
         ml = 100 * sum(loss) / len(loss) if loss else 0.0
-        print(f"{name}: exact pick {h}/{len(subset)}, within 3% of best {n}/{len(subset)}, mean loss of optimal speedup on misses {ml:.1f}%")
-    print("fitted constants: piece flops %.3g, min rows %d, max pieces %d" % best_c)
+        print(f"  {name}: exact {h}/{len(subset)}, within 3% of the best row-piece schedule {n}/{len(subset)}, mean loss of optimal speedup on misses {ml:.1f}%")
+    print("row-piece rule, constants compiled into ficco_pick_schedule (16 us, 8 us, 256 rows):")
+    for name, subset in sets:
+        h, n, loss = score_rows((16, 8, 256), subset)
+        ml = 100 * sum(loss) / len(loss) if loss else 0.0
+        print(f"  {name}: exact {h}/{len(subset)}, within 3% {n}/{len(subset)}, mean loss on misses {ml:.1f}%")
+    for layout, what in ((F.FICCO_LAYOUT_ROW_MAJOR, "ficco_pick_schedule_any (row-major source, re-layout paid)"),
+                         (F.FICCO_LAYOUT_K_SLICED, "ficco_pick_schedule_layout (K-sliced source)")):
+        print(what + ", against the best of row and column pieces:")
+        print("  whole grid (its thresholds were chosen on these shapes): " + score_layout(table, layout))
+        if unseen:
+            print(f"  unseen shapes: " + score_layout(unseen, layout))
     # the shape rule of Sec. V-C: column pieces (2D) when M <= K, row pieces (1D) otherwise
-    with_2d = [t for t in table if t["best_2d"] is not None]
-    if with_2d:
-        ok = near = 0
-        for t in with_2d:
-            M, K = t["key"][0], t["key"][1]
-            picked, other = (t["best_2d"], t["best"]["wall_us"]) if M <= K else (t["best"]["wall_us"], t["best_2d"])
-            ok += picked <= other
-            near += picked <= 1.03 * other
-        n_le = sum(1 for t in with_2d if t["key"][0] <= t["key"][1])
-        print(f"shape rule (2D when M <= K, else 1D): picks the faster family at {ok}/{len(with_2d)} shapes, "
-              f"within 3% of it at {near}/{len(with_2d)} ({n_le} shapes have M <= K)")
-    h, n, loss = score((2.5e10, 256, 16), table)
-    print(f"constants compiled into ficco_pick_schedule (2.5e10, 256, 16): exact {h}/{len(table)}, within 3% {n}/{len(table)}")
-    # ficco_pick_schedule_any (column pieces allowed) against the best of both families
-    if with_2d:
-        hit = near = fam = 0
-        worst = 0.0
-        for t in with_2d:
-            M, K, N, G = t["key"]
-            s, c = F.ficco_pick_schedule_any(M, K, N, G)
-            got = t["two_d"].get(c) if s == F.FICCO_FINE_2D else t["fine"].get((s, c))
-            if s == F.FICCO_FINE_2D:           # the rule's own cut, where the sweep measured it
-                got = t["rule_cut"].get((c, tuple(F.ficco_pick_slice_widths(M, K, N, G, c))), got)
-            if got is None:
-                continue
-            best = min([t["best"]["wall_us"], t["best_2d"]] + list(t["rule_cut"].values()))
-            hit += got <= 1.001 * best
-            near += got <= 1.03 * best
-            worst = max(worst, got / best)
-            fam += (s == F.FICCO_FINE_2D) == (t["best_2d"] <= t["best"]["wall_us"])
-        n_cut = sum(1 for t in with_2d if t["rule_cut"])
-        print(f"(column pieces in the rule's own unequal cut were measured at {n_cut} shapes and count among the candidates)")
-        print(f"ficco_pick_schedule_any against the best of row and column pieces: exact {hit}/{len(with_2d)}, within 3% {near}/{len(with_2d)}, "
-              f"worst {100 * (worst - 1):.1f}% off, faster family picked at {fam}/{len(with_2d)} shapes")
+    for name, subset in (("grid", table), ("unseen", unseen)):
+        with_2d = [t for t in subset if t["2d_ks"]]
+        if with_2d:
+            ok = sum(1 for t in with_2d if (min(t["2d_ks"].values()) <= t["best_rows"]) == (t["key"][0] <= t["key"][1]))
+            print(f"the paper's shape rule (2D when M <= K) on the {name} shapes, K-sliced source: faster family at {ok}/{len(with_2d)}")
     return 0
 
 
@@ -218,6 +251,8 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="")
     ap.add_argument("--fit", default="")
+    ap.add_argument("--score", default="", help="with --fit: a second measurement file (shapes the constants never saw)")
+    ap.add_argument("--holdout", action="store_true", help="with --out: measure the 16 shapes off the grid")
     ap.add_argument("--M", type=int, nargs="+", default=[4096, 16384, 65536])
     ap.add_argument("--K", type=int, nargs="+", default=[4096, 8192])
     ap.add_argument("--N", type=int, nargs="+", default=[512, 1024, 3584, 14336])

@@ -815,21 +815,25 @@ def test_auto_any_plan_runs_from_the_callers_row_major_matrix(gpu):
     (the sender-side re-layout kernel releases each piece's transfer) and in pinned host memory (rectangular
     engine copies), and a sender that holds its slices K-sliced already can say so."""
     dev = gpu["dev"]
-    shards, W = fi.config_inputs("cfg1_tiny")
+    M, K, N, G = 4096, 8192, 3584, 8                       # a sweep shape the rule sends to column pieces
+    shards = fi.make_shards(fi.SWEEP["seed"], M, K, G)
+    W = fi.make_weight(fi.SWEEP["seed"], K, N)
     A = np.concatenate(shards, 0)
-    M, K = A.shape
-    N, G = W.shape[1], len(shards)
-    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1)
+    rows = np.unique(np.concatenate([np.arange(0, M, 193), [0, M // G - 1, M // G, M - 1]]))
+    base, _, _ = run_ag(gpu, shards, W, ficco.FICCO_SERIAL, 1, src="device")
+    check(base[rows], og.ag_gemm_rows(shards, W, rows), "serial")
     W_dev = as_i16(W).to(dev)
+    assert ficco.ficco_pick_schedule_any(M, K, N, G) == (ficco.FICCO_FINE_2D, 4)
     for kind in ("device", "pinned", "k_sliced"):
         plan = ficco.ficco_plan(M, K, N, G, 1, ficco.FICCO_AUTO_ANY)
         try:
             info = ficco.ficco_plan_info(plan)
-            assert (info.schedule, info.chunks) == ficco.ficco_pick_schedule_any(M, K, N, G) == (ficco.FICCO_FINE_2D, 2)
+            assert (info.schedule, info.chunks) == (ficco.FICCO_FINE_2D, 4)
             _, widths = ficco.ficco_plan_slices(plan)
+            want = np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)])
             if kind == "k_sliced":
                 ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_K_SLICED)
-                src = as_i16(np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)]).reshape(M, K)).to(dev)
+                src = as_i16(want.reshape(M, K)).to(dev)
             else:
                 src = as_i16(A).to(dev) if kind == "device" else as_i16(A).pin_memory()
             for run in range(3):                              # signals, counters and the staging copy are reused
@@ -838,10 +842,9 @@ def test_auto_any_plan_runs_from_the_callers_row_major_matrix(gpu):
                 torch.cuda.synchronize()
                 ficco.ficco_run(plan, src, A_dev, W_dev, C_dev, None, gpu["cs"], gpu["xs"])
                 st = ficco.ficco_query_stats(plan)
-                assert st.n_copies == 2 * G and st.copy_bytes == M * K * 2
+                assert st.n_copies == 4 * G and st.copy_bytes == M * K * 2
                 assert np.array_equal(C_dev.cpu().numpy().view(np.uint16), base), (kind, run)
                 # the landing buffer holds the K-sliced matrix
-                want = np.concatenate([b.ravel() for b in fi.to_k_pieces(A, widths)])
                 assert np.array_equal(A_dev.cpu().numpy().view(np.uint16).ravel(), want), (kind, run)
         finally:
             ficco.ficco_destroy(plan)

@@ -241,26 +241,32 @@ def test_ideal_overlap_matches_oracle(tc, tg, n):
 # The fitted rules of the library (Sec. V-C read for this machine) are pinned by cases worked out by hand
 # from the rule as the header states it; no second implementation is consulted.
 #
-# Row pieces (ficco_pick_schedule): the resident schedule; piece rows m = the largest power of two with
-# 2*m*N*K <= 2.5e10 flop, at least 256 and at most one shard (M/shards rows); pieces per shard
-# c = shard rows / m, at most 16, halved until it divides the shard.
+# Row pieces (ficco_pick_schedule): the resident schedule; pieces per shard c = the power of two up to 32 that
+# divides the shard, keeps pieces of at least 256 rows and minimises
+#     T(c) = max(Tc + 16 c, Tg + 8 c) + min(Tc, Tg) / c      [us]
+# with Tc = (M/shards) * K * 2 B / 58e3 B/us (one shard over one link) and Tg = 2 M N K / 1.2e9 flop/us.
 ROW_PIECE_CASES = [
-    # 2NK = 58 720 256 -> 2.5e10 / 2NK = 425.7 -> m = 256; shard 2048 rows -> 8 pieces
+    # Tc = 2048*8192*2/58e3 = 578.5, Tg = 801.7: T(1) = 801.7+8+578.5 = 1388.3, T(2) = 1107.0, T(4) = 978.4,
+    # T(8) = 865.7+72.3 = 938.0; 16 pieces would have 128 rows
     ((16384, 8192, 3584, 8), 8),
-    # 2NK = 4 194 304 -> 5960 -> m = 4096, more than the 512-row shard -> 1 piece
+    # Tc = 72.3, Tg = 14.3: T(1) = 88.3+14.3 = 102.6, T(2) = 104.3+7.2 = 111.5 (256-row pieces are the limit)
     ((4096, 4096, 512, 8), 1),
-    # 2NK = 234 881 024 -> 106 -> 64, raised to the 256-row minimum; shard 8192 rows -> 32, capped at 16
+    # Tc = 2314.1, Tg = 12827.6: T(8) = 12891.6+289.3 = 13180.9, T(16) = 12955.6+144.6 = 13100.3, T(32) = 13156.0
     ((65536, 8192, 14336, 8), 16),
     # the 128-row shard is below the 256-row minimum -> 1 piece
     ((512, 1024, 1024, 4), 1),
-    # 2NK = 8 388 608 -> 2980 -> m = 2048; shard 3072 rows -> 3072 / 2048 = 1 piece
-    ((24576, 4096, 1024, 8), 1),
-    # 2NK = 6 291 456 -> 3973 -> m = 2048, more than the 1024-row shard -> 1 piece
-    ((8192, 4096, 768, 8), 1),
-    # 2NK = 29 360 128 -> 851 -> m = 512; shard 2048 rows -> 4 pieces
-    ((16384, 4096, 3584, 8), 4),
-    # 2NK = 117 440 512 -> 212.9 -> 128, raised to 256; shard 512 rows -> 2 pieces
+    # Tc = 433.9, Tg = 171.8: T(1) = 621.7, T(2) = 465.9+85.9 = 551.8, T(4) = 497.9+43.0 = 540.8, T(8) = 583.4
+    ((24576, 4096, 1024, 8), 4),
+    # Tc = 144.6, Tg = 42.9: T(1) = 160.6+42.9 = 203.6, T(2) = 176.6+21.5 = 198.1, T(4) = 208.6+10.7 = 219.4
+    ((8192, 4096, 768, 8), 2),
+    # Tc = 289.3, Tg = 400.9: T(4) = 432.9+72.3 = 505.2, T(8) = 464.9+36.2 = 501.0
+    ((16384, 4096, 3584, 8), 8),
+    # Tc = 72.3, Tg = 400.9: T(1) = 408.9+72.3 = 481.2, T(2) = 416.9+36.2 = 453.0; 4 pieces would have 128 rows
     ((4096, 4096, 14336, 8), 2),
+    # transfers and GEMM level (Tc = 144.6, Tg = 143.2): T(1) = 303.8, T(2) = 248.2, T(4) = 208.6+35.8 = 244.4
+    ((8192, 4096, 2560, 8), 4),
+    # Tc = 1157.0, Tg = 229.1: T(2) = 1189.0+114.6 = 1303.6, T(4) = 1221.0+57.3 = 1278.3, T(8) = 1285.0+28.6 = 1313.7
+    ((65536, 4096, 512, 8), 4),
 ]
 
 
@@ -275,18 +281,20 @@ def test_pick_schedule_returns_a_valid_plan():
             for N in (512, 1024, 3584, 14336):
                 s, c = ficco.ficco_pick_schedule(M, K, N, 8)
                 assert s == ficco.FICCO_FINE_PERSISTENT
-                assert 1 <= c <= 16 and (M // 8) % c == 0 and (c == 1 or M // 8 // c >= 256)
+                assert 1 <= c <= 32 and (M // 8) % c == 0 and (c == 1 or M // 8 // c >= 256)
                 plan = ficco.ficco_plan(M, K, N, 8, 1, ficco.FICCO_AUTO)
                 info = ficco.ficco_plan_info(plan)
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
 
 
-# Communication shape (ficco_pick_schedule_any): column pieces when the output has at most 2e7 elements
-# (about one round of 256x256 tiles over 256 CUs) and K has at least two k-tiles of 64; slices: 2 when
-# N*shards <= 8192 (the transfers are the longer side), else 2 below 1e11 flop, 4 below 4e11, 8 from
-# there, never more than K/64; otherwise the row-piece answer.
-ANY_SHAPE_CASES = [
+# Communication shape. Column pieces need an output of at most 256 tiles of 256x256 (one round over 256 CUs:
+# ceil(M/256) * ceil(N/256) <= 256) and at least two k-tiles of 64. For a sender that holds its slices K-sliced
+# (ficco_pick_schedule_layout, K_SLICED) that is all: slices 2 when N*shards <= 8192 (the transfers are the longer
+# side), else 2 below 1e11 flop, 4 below 4e11, 8 from there, never more than K/64. For the caller's row-major
+# matrix (ficco_pick_schedule_any = layout ROW_MAJOR) the step pays for the re-layout, so column pieces also need
+# N*shards > 8192 and at least 2e11 flop: 4 slices below 4e11 flop, 8 from there. Otherwise the row-piece answer.
+K_SLICED_CASES = [
     # 8192*768 = 6.3e6 outputs; N*G = 6144 -> 2 slices
     ((8192, 4096, 768, 8), (ficco.FICCO_FINE_2D, 2)),
     # 4096*4096 = 1.7e7 outputs; N*G = 32768; 2*4096*4096*16384 = 5.5e11 flop -> 8 slices
@@ -297,7 +305,7 @@ ANY_SHAPE_CASES = [
     ((16384, 8192, 3584, 8), (ficco.FICCO_FINE_PERSISTENT, 8)),
     # 4096*14336 = 5.9e7 outputs -> row pieces, 2 per shard (worked above)
     ((4096, 4096, 14336, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
-    # one k-tile: nothing to slice; 2NK = 65 536 -> m far above the 512-row shard -> 1 piece
+    # one k-tile: nothing to slice; Tc = 1.1, Tg = 0.2: T(1) = 17.1+0.2 = 17.4, T(2) = 33.2 -> 1 piece
     ((4096, 64, 512, 8), (ficco.FICCO_FINE_PERSISTENT, 1)),
     # two k-tiles, N*G = 4096 -> 2 slices
     ((4096, 128, 512, 8), (ficco.FICCO_FINE_2D, 2)),
@@ -305,16 +313,46 @@ ANY_SHAPE_CASES = [
     ((16384, 4096, 1024, 8), (ficco.FICCO_FINE_2D, 2)),
     # 4096*4096 outputs, N*G = 32768, 2*4096*4096*2048 = 6.9e10 flop -> 2 slices
     ((4096, 2048, 4096, 8), (ficco.FICCO_FINE_2D, 2)),
-    # either side of the limit: 4096*4880 = 19 988 480 outputs, 2*4096*4880*8192 = 3.3e11 flop -> 4 slices ...
-    ((4096, 8192, 4880, 8), (ficco.FICCO_FINE_2D, 4)),
-    # ... 4096*4888 = 20 021 248 outputs -> row pieces; 2NK = 80 084 992 -> 312 -> m = 256; shard 512 rows -> 2
-    ((4096, 8192, 4888, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # either side of the limit: 16 x 16 = 256 tiles, 2*4096*4096*8192 = 2.7e11 flop -> 4 slices ...
+    ((4096, 8192, 4096, 8), (ficco.FICCO_FINE_2D, 4)),
+    # ... 16 x 17 = 272 tiles -> row pieces; Tc = 144.6, Tg = 229.5: T(1) = 382.1, T(2) = 245.5+72.3 = 317.8 -> 2
+    ((4096, 8192, 4104, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+]
+ROW_MAJOR_CASES = [
+    # N*G = 6144: transfer-bound -> row pieces, 2 per shard (worked above)
+    ((8192, 4096, 768, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # N*G = 32768, 5.5e11 flop -> 8 slices
+    ((4096, 16384, 4096, 8), (ficco.FICCO_FINE_2D, 8)),
+    # N*G = 28672, 2.4e11 flop -> 4 slices
+    ((4096, 8192, 3584, 8), (ficco.FICCO_FINE_2D, 4)),
+    # N*G = 28672 but 2*4096*3584*4096 = 1.2e11 flop: too little GEMM to hide the re-layout -> row pieces;
+    # Tc = 72.3, Tg = 100.2: T(1) = 108.2+72.3 = 180.5, T(2) = 116.2+36.2 = 152.4 -> 2 pieces
+    ((4096, 4096, 3584, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # N*G = 8192 counts as transfer-bound -> row pieces; Tc = 289.3, Tg = 114.5: T(1) = 419.8, T(2) = 321.3+57.3 =
+    # 378.5, T(4) = 353.3+28.6 = 381.9 -> 2 pieces
+    ((16384, 4096, 1024, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # 6.9e10 flop -> row pieces; Tc = 36.2, Tg = 57.3: T(1) = 65.3+36.2 = 101.4, T(2) = 73.3+18.1 = 91.3 -> 2 pieces
+    ((4096, 2048, 4096, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # large outputs stay with row pieces whatever the layout
+    ((16384, 8192, 3584, 8), (ficco.FICCO_FINE_PERSISTENT, 8)),
+    ((4096, 4096, 14336, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # either side of the output limit (256 and 272 tiles) at 2.7e11 flop
+    ((4096, 8192, 4096, 8), (ficco.FICCO_FINE_2D, 4)),
+    ((4096, 8192, 4104, 8), (ficco.FICCO_FINE_PERSISTENT, 2)),
+    # the tiny configuration: 512 x 1024 x 1024 on 4 shards, 1e9 flop -> row pieces, 1 per shard (worked above)
+    ((512, 1024, 1024, 4), (ficco.FICCO_FINE_PERSISTENT, 1)),
 ]
 
 
-@pytest.mark.parametrize("shape,answer", ANY_SHAPE_CASES)
+@pytest.mark.parametrize("shape,answer", K_SLICED_CASES)
+def test_pick_schedule_k_sliced_source_hand_cases(shape, answer):
+    assert ficco.ficco_pick_schedule_layout(*shape, ficco.FICCO_LAYOUT_K_SLICED) == answer
+
+
+@pytest.mark.parametrize("shape,answer", ROW_MAJOR_CASES)
 def test_pick_schedule_any_hand_cases(shape, answer):
     assert ficco.ficco_pick_schedule_any(*shape) == answer
+    assert ficco.ficco_pick_schedule_layout(*shape, ficco.FICCO_LAYOUT_ROW_MAJOR) == answer
 
 
 # The cut of the k range (ficco_pick_slice_widths): two slices of a transfer-bound shape (N*shards <= 8192)
@@ -355,7 +393,7 @@ def test_pick_schedule_any_gives_valid_plans_with_its_own_cut():
                 ficco.ficco_destroy(plan)
                 assert (info.schedule, info.chunks) == (s, c)
                 if s == ficco.FICCO_FINE_2D:
-                    assert M * N <= 2e7 and 2 <= c <= K // 64
+                    assert -(-M // 256) * -(-N // 256) <= 256 and 2 <= c <= K // 64 and N * 8 > 8192 and 2.0 * M * N * K >= 2e11
                     assert widths == ficco.ficco_pick_slice_widths(M, K, N, 8, c)
                     assert len(widths) == c and sum(widths) == K and all(w > 0 and w % 64 == 0 for w in widths)
                 else:
