@@ -14,6 +14,7 @@ all-gather configuration one GPU holds):
   pair      - K timed steps of the schedule the library itself picks (FICCO_AUTO_ANY) from the caller's
               row-major shards resident in HBM (device staging buffer): that is `value`. Beside it a screen of
               the other schedules and piece counts, and the serial and shard-level schedules for the speedups
+  contend   - (for counter runs) the plan's GEMM with its transfers beside it, no dependency between them
   small     - the pair and pcie legs of the two smaller all-gather workloads (cfg1, cfg2), condensed
   pcie      - the same with the shards in pinned host memory (PCIe-inclusive; never `value`)
   roofline  - the GEMM launches of the timed plan in isolation, enqueued back to back between two
@@ -534,6 +535,21 @@ def main() -> int:
             step_bytes = traffic + 2 * (M * N * 2 if rs else M * K * 2)
             out["pair"]["hbm_side_bytes_per_step"] = step_bytes
             out["pair"]["hbm_side_frac_of_peak"] = round(step_bytes / (out["ms_per_step"] * 1e-3) / (HBM_PEAK_GBPS * 1e9), 4)
+
+    if "contend" in legs and not rs:
+        # counter runs only: the plan's GEMM launches with the plan's transfers running beside them and no
+        # dependency between the two (FICCO_MODE_INDEPENDENT), so that rocprofv3 --pmc reads the kernel's
+        # counters under the copy engines' traffic; the roofline leg gives the same kernel alone
+        s, c, lay = parse_plan(args.roofline_plan) if args.roofline_plan else (pick if pick is not None else (F.FICCO_FINE_PERSISTENT, 1, "rm"))
+        s %= PACKED
+        plan = make(s, c, "ks", opts=[(F.FICCO_OPT_MODE, F.FICCO_MODE_INDEPENDENT)])
+        src = source("hbm", s, c, "ks")
+        A_dev.copy_(src if isinstance(src, torch.Tensor) else A_stage)     # the kernel reads resident operands
+        torch.cuda.synchronize()
+        ms = timed_steps(plan, src, args.steps, args.warmup)
+        st = F.ficco_query_stats(plan)
+        F.ficco_destroy(plan)
+        out["contend"] = {"ms_per_step": round(ms, 4), "gemm_span_us": round(st.gemm_span_us, 2), "copy_span_us": round(st.copy_span_us, 2)}
 
     # after the roofline leg: half a second of host-link-bound steps leaves the chip in a lower clock state than
     # the settling loop of that leg brings back (its launches read 5 % longer behind this leg than in front of it)

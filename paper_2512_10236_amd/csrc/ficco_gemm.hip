@@ -65,18 +65,25 @@ template <int N>
 static __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 static __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <int BM_, int BN_, int WGM_, int WGN_, int NSTAGE_>
+template <int BM_, int BN_, int WGM_, int WGN_, int NSTAGE_, int BK_ = kBK>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
     static constexpr int NSTAGE = NSTAGE_;                     // LDS stages in the ring; loads run NSTAGE-1 k-tiles ahead
+    static constexpr int BK = BK_;                             // k extent of one LDS stage: 64, or 32 (a deeper ring in the same LDS)
+    static constexpr int KSUB = BK / 16;                       // sub-steps (one MFMA's k extent each) per stage
+    static constexpr int ROWB = BK * 2;                        // bytes of a row of a stage
+    static constexpr int SLOTS = BK / 8;                       // 16-byte slots per row
+    static constexpr int RPL = 1024 / ROWB;                    // rows one load instruction (64 lanes x 16 B) fills
+    static constexpr int SWZ_SHIFT = BK == 64 ? 1 : 2;         // rows that share a 256-byte bank line
     static constexpr int THREADS = WGM * WGN * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
     static constexpr int FM = WTM / 32, FN = WTN / 32;         // 32x32 MFMA blocks per wavefront
-    static constexpr int A_STAGE = BM * kBK * 2, B_STAGE = BN * kBK * 2;   // bytes
+    static constexpr int A_STAGE = BM * ROWB, B_STAGE = BN * ROWB;   // bytes
     static constexpr int STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
-    static constexpr int AB = BM / 8 / 4, BB = BN / 8 / 4;     // 8-row (1 KiB) blocks loaded per wavefront per stage
+    static constexpr int AB = BM / RPL / 4, BB = BN / RPL / 4; // 1 KiB blocks loaded per wavefront per stage
     static constexpr int LOADS = AB + BB;                      // load instructions per wavefront per k-tile
+    static_assert(BK == 64 || BK == 32, "stages of 64 or 32 k values");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2 to 4 stages");
     static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS ring plus the kernels' few static words must fit one CU");
     static_assert(THREADS == 256, "loaders assume 4 wavefronts");
@@ -115,12 +122,16 @@ struct NoHook {
     __device__ __forceinline__ void operator()() const {}
 };
 
-// Byte offset, from the first row of the tile, of what lane `lane` fetches for 8-row block `blk` of a stage:
-// row blk*8 + lane/8 (clamped to the last row that exists), 16-byte slot (lane%8) ^ ((row>>1)&7) of its k-tile.
+// Byte offset, from the first row of the tile, of what lane `lane` fetches for 1 KiB block `blk` of a stage:
+// row blk*RPL + lane/SLOTS (clamped to the last row that exists), 16-byte slot (lane%SLOTS) ^ swizzle(row) of
+// its k-tile. The swizzle - (row>>1)&7 for rows of 128 B, (row>>2)&3 for rows of 64 B - spreads the rows that
+// share a 256-byte line of banks over different slots, so that the 16 lanes of a ds_read_b128 phase, which read
+// the same k slot of 16 consecutive rows, hit 64 different banks.
+template <class T>
 static __device__ __forceinline__ uint32_t lane_offset(int blk, int lane, int rows_valid, int64_t row_stride_elems)
 {
-    const int row = blk * 8 + (lane >> 3);
-    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    const int row = blk * T::RPL + lane / T::SLOTS;
+    const int kc = (lane % T::SLOTS) ^ ((row >> T::SWZ_SHIFT) & (T::SLOTS - 1));
     const int rr = row < rows_valid ? row : rows_valid - 1;
     return (uint32_t)(((int64_t)rr * row_stride_elems + kc * 8) * 2);
 }
@@ -136,10 +147,10 @@ struct PlainA {
     __device__ __forceinline__ PlainA(const uint16_t *a_tile, int rows_valid, int64_t lda, int wave, int lane) : base(a_tile)
     {
 #pragma unroll
-        for (int i = 0; i < T::AB; ++i) off[i] = lane_offset(wave * T::AB + i, lane, rows_valid, lda);
+        for (int i = 0; i < T::AB; ++i) off[i] = lane_offset<T>(wave * T::AB + i, lane, rows_valid, lda);
     }
     __device__ __forceinline__ void seek(int) {}
-    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)kt * kBK; }
+    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)kt * T::BK; }
 };
 
 // SlicedA: a run of consecutive k slices of the K-sliced layout (slice s = the [M][k0[s+1]-k0[s]] block that
@@ -165,13 +176,13 @@ struct SlicedA {
             ++sl;
             const int kb = k0[sl], kw = k0[sl + 1] - kb;
             kt_begin = kt_end;
-            kt_end += kw / kBK;
+            kt_end += kw / T::BK;
             base = A + M * kb + row0 * kw;
 #pragma unroll
-            for (int i = 0; i < T::AB; ++i) off[i] = lane_offset(wave * T::AB + i, lane, rows_valid, kw);
+            for (int i = 0; i < T::AB; ++i) off[i] = lane_offset<T>(wave * T::AB + i, lane, rows_valid, kw);
         }
     }
-    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)(kt - kt_begin) * kBK; }
+    __device__ __forceinline__ const uint16_t *at(int kt) const { return base + (int64_t)(kt - kt_begin) * T::BK; }
 };
 
 // Waits until at most `load_groups` k-tiles' worth of this wavefront's loads are outstanding (the counter wants
@@ -199,22 +210,22 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
 
     uint32_t offb[T::BB];                  // per-lane byte offsets of the W loads from the tile's first row
 #pragma unroll
-    for (int i = 0; i < T::BB; ++i) offb[i] = lane_offset(wave * T::BB + i, lane, cols_valid, ldw);
+    for (int i = 0; i < T::BB; ++i) offb[i] = lane_offset<T>(wave * T::BB + i, lane, cols_valid, ldw);
     // load l of the wavefront's LOADS loads of k-tile kt into `stage`: first the AB blocks of A, then the BB blocks
     // of W (k-tiles are issued in ascending order; load 0 of a k-tile comes first)
     auto issue_load = [&](int stage, int kt, int l) {
         if (l == 0) pa.seek(kt);
         if (l < T::AB) load_to_lds_16(pa.at(kt), pa.off[l], lds0 + stage * T::STAGE + (wave * T::AB + l) * 1024);
-        else load_to_lds_16(wt_tile + (int64_t)kt * kBK, offb[l - T::AB], lds0 + stage * T::STAGE + T::A_STAGE + (wave * T::BB + (l - T::AB)) * 1024);
+        else load_to_lds_16(wt_tile + (int64_t)kt * T::BK, offb[l - T::AB], lds0 + stage * T::STAGE + T::A_STAGE + (wave * T::BB + (l - T::AB)) * 1024);
     };
 
     // LDS -> fragment addresses: lane reads row (lane%32) of a 32-row block, k-slot 2*kk + lane/32,
-    // un-swizzled by ((row>>1)&7), which only depends on the lane
-    const int frow = lane & 31, fh = lane >> 5, fs = (lane >> 1) & 7;
-    const int a_base = (wm * T::WTM + frow) * 128;
-    const int b_base = T::A_STAGE + (wn * T::WTN + frow) * 128;
+    // un-swizzled by the row's swizzle, which only depends on the lane
+    const int frow = lane & 31, fh = lane >> 5, fs = (frow >> T::SWZ_SHIFT) & (T::SLOTS - 1);
+    const int a_base = (wm * T::WTM + frow) * T::ROWB;
+    const int b_base = T::A_STAGE + (wn * T::WTN + frow) * T::ROWB;
 
-    const int KT = K / kBK;
+    const int KT = K / T::BK;
     constexpr int D = T::NSTAGE - 1;      // prefetch distance in k-tiles
     bf16x8_t fa[2][T::FM], fb[2][T::FN];
     // fragment q of the FM + FN fragments of sub-step kk of the k-tile in the stage at `base`, into buffer n.
@@ -223,8 +234,8 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
     auto read_frag = [&](const unsigned char *base, int kk, int n, int q) {
         const int slot = ((2 * kk + fh) ^ fs) << 4;
         if (q == 0) fa[n][0] = *reinterpret_cast<const bf16x8_t *>(base + a_base + slot);
-        else if (q <= T::FN) fb[n][q - 1] = *reinterpret_cast<const bf16x8_t *>(base + b_base + (q - 1) * 4096 + slot);
-        else fa[n][q - T::FN] = *reinterpret_cast<const bf16x8_t *>(base + a_base + (q - T::FN) * 4096 + slot);
+        else if (q <= T::FN) fb[n][q - 1] = *reinterpret_cast<const bf16x8_t *>(base + b_base + (q - 1) * 32 * T::ROWB + slot);
+        else fa[n][q - T::FN] = *reinterpret_cast<const bf16x8_t *>(base + a_base + (q - T::FN) * 32 * T::ROWB + slot);
     };
     constexpr int NM = T::FM * T::FN;           // MFMAs per sub-step
     constexpr int NR = T::FM + T::FN;           // fragment reads per sub-step
@@ -247,11 +258,11 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
 #pragma unroll
     for (int q = 0; q < NR; ++q) read_frag(smem, 0, 0, q);
 
-    // ---- the loop, one k-tile per turn, rotated by one sub-step: a turn runs sub-steps 0..2 of k-tile k out of
-    // the fragments read one sub-step earlier, then waits for k-tile k+1 and for its own LDS reads and meets the
-    // others at barrier B_{k+1} (k-tile k+1 has landed for everyone; everyone is done with the stage of k-tile k,
-    // which the loads of k-tile k+1+D may now overwrite), and only then runs sub-step 3, whose 16 MFMAs need
-    // registers only: under them go the first half of the loads of k-tile k+1+D and the reads of the first
+    // ---- the loop, one k-tile (a stage of BK k values, KSUB sub-steps of one MFMA's k extent) per turn, rotated by
+    // one sub-step: a turn runs all but the last sub-step of k-tile k out of the fragments read one sub-step earlier,
+    // then waits for k-tile k+1 and for its own LDS reads and meets the others at barrier B_{k+1} (k-tile k+1 has
+    // landed for everyone; everyone is done with the stage of k-tile k, which the loads of k-tile k+1+D may now
+    // overwrite), and only then runs the last sub-step, whose MFMAs (16 in the big tiles) need registers only: under them go the first half of the loads of k-tile k+1+D and the reads of the first
     // fragments of k-tile k+1, so that neither the barrier nor the LDS latency behind it leaves the MFMA pipe
     // empty. The second half of those loads follows under sub-step 0 of the next turn. Every MFMA of the big
     // tiles is followed by at most one load or one read, and the order is pinned (sched_barrier), so that a
@@ -269,9 +280,9 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
         const unsigned char *nxt = smem + ((k + 1) % T::NSTAGE) * T::STAGE;
         const int free_stage = k % T::NSTAGE;           // after B_{k+1}
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < T::KSUB; ++kk) {
             const int c = kk & 1, n = c ^ 1;
-            if (kk == 3) {
+            if (kk == T::KSUB - 1) {
                 // everything this wavefront reads from the stage of k-tile k has arrived in registers
 #ifdef FICCO_PROBE
                 const long long pt0 = PROBE_T();
@@ -309,18 +320,18 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
 #pragma unroll
                 for (int q = 0; q < NR; ++q)
                     if (q * NM / NR == t) {
-                        if (kk < 3) read_frag(cur, kk + 1, n, q);
+                        if (kk < T::KSUB - 1) read_frag(cur, kk + 1, n, q);
                         else if (rn) read_frag(nxt, 0, n, q);
                     }
-                if (kk == 3 && l1st) {
+                if (kk == T::KSUB - 1 && l1st) {
 #pragma unroll
                     for (int l = 0; l < H1; ++l)
-                        if (min(NM - 1, l * NM / H1 + NM / H1 / 2) == t) issue_load(free_stage, k + 1 + D, l);
+                        if (min(NM - 1, l * NM / H1 + ((NM / H1 / 2) | 1)) == t) issue_load(free_stage, k + 1 + D, l);
                 }
                 if (kk == 0 && l2nd) {
 #pragma unroll
                     for (int l = 0; l < H2; ++l)
-                        if (min(NM - 1, l * NM / H2 + NM / H2 / 2) == t) issue_load((k + D) % T::NSTAGE, k + D, H1 + l);
+                        if (min(NM - 1, l * NM / H2 + ((NM / H2 / 2) | 1)) == t) issue_load((k + D) % T::NSTAGE, k + D, H1 + l);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -981,6 +992,9 @@ hipError_t launch_slice_source(const SliceLaunch &a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------ host
+// The big tile keeps two stages of 64 k values. Four stages of 32 (TileCfg<256, 256, 2, 2, 4, 32>) take the
+// memory wait out of the loop but run 6-8 % slower: rows of 64 bytes double the cache lines each load
+// instruction touches, and every 64 k values pay two barriers instead of one.
 typedef TileCfg<256, 256, 2, 2, 2> T256x256;
 typedef TileCfg<128, 128, 2, 2, 2> T128x128;       // two workgroups per CU: for launches that fill the machine
 typedef TileCfg<128, 128, 2, 2, 4> T128x128D;      // deep ring, one workgroup per CU: for launches that do not
