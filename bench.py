@@ -14,6 +14,8 @@ all-gather configuration one GPU holds):
   pair      - K timed steps of the schedule the library itself picks (FICCO_AUTO_ANY) from the caller's
               row-major shards resident in HBM (device staging buffer): that is `value`. Beside it a screen of
               the other schedules and piece counts, and the serial and shard-level schedules for the speedups
+  power     - (not run by default) board power and TFLOP/s of the timed plan's GEMM on the workload's data and on
+              zeros, with the vendor library's GEMM beside it
   contend   - (for counter runs) the plan's GEMM with its transfers beside it, no dependency between them
   small     - the pair and pcie legs of the two smaller all-gather workloads (cfg1, cfg2), condensed
   pcie      - the same with the shards in pinned host memory (PCIe-inclusive; never `value`)
@@ -48,13 +50,12 @@ HBM_PEAK_GBPS = 8000.0
 # read, and the factors by which a 256 MiB device copy's true traffic exceeds what they read for it.
 PMC_SCALE = {"FETCH_SIZE": 262144.0 / 131086.7, "WRITE_SIZE": 262144.0 / 262144.0}
 PMC_KIB = {
-    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57468.6, "WRITE_SIZE": 12288.9},
-    ("cfg2_qkv8b", "gemm_resident2d_kernel<128x192>"): {"FETCH_SIZE": 57499.1, "WRITE_SIZE": 12288.9},
-    ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57449.0, "WRITE_SIZE": 12288.0},
-    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 937152.7, "WRITE_SIZE": 116594.3},
-    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 848429.0, "WRITE_SIZE": 117460.9},
-    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 394321.3, "WRITE_SIZE": 32998.0},
-    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 478520.6, "WRITE_SIZE": 33602.3},
+    ("cfg2_qkv8b", "gemm_resident_kernel<128x192>"): {"FETCH_SIZE": 57491.0, "WRITE_SIZE": 12288.0},
+    ("cfg2_qkv8b", "gemm_blocks_kernel<128x192>"): {"FETCH_SIZE": 57458.0, "WRITE_SIZE": 12288.0},
+    ("cfg3_ffn70b", "gemm_resident_kernel<256x256>"): {"FETCH_SIZE": 908479.1, "WRITE_SIZE": 115327.7},
+    ("cfg3_ffn70b", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 825994.4, "WRITE_SIZE": 115201.6},
+    ("cfg6_2d_proj", "gemm_resident2d_kernel<256x256>"): {"FETCH_SIZE": 394542.8, "WRITE_SIZE": 33777.8},
+    ("cfg6_2d_proj", "gemm_blocks_kernel<256x256>"): {"FETCH_SIZE": 395433.1, "WRITE_SIZE": 33006.5},
     ("cfg4_gemm_rs", "rs_reduce_kernel"): {"FETCH_SIZE": 131151.5, "WRITE_SIZE": 32768.0},      # profiles/rs_reduce_cfg4_gemm_rs.md
 }
 
@@ -348,8 +349,12 @@ def main() -> int:
         if a.endswith("k"):
             return (int(a[:-1]), b, "ks")
         return (int(a), b, "rm")
-    def library_pick():
-        """What ficco_plan(..., FICCO_AUTO_ANY) builds for this shape, as a candidate."""
+    def library_pick(host_resident=False):
+        """What the library's rule builds for this shape, as a candidate: a FICCO_AUTO_ANY plan for shards in device
+        memory; for shards in pinned host memory the caller says so (ficco_pick_schedule_layout, ROW_MAJOR_HOST)."""
+        if host_resident:
+            s_h, c_h = F.ficco_pick_schedule_layout(M, K, N, G, F.FICCO_LAYOUT_ROW_MAJOR_HOST)
+            return (s_h, c_h, "rm")
         plan = F.ficco_plan(M, K, N, G, 1, F.FICCO_AUTO_ANY)
         try:
             info = F.ficco_plan_info(plan)
@@ -362,6 +367,7 @@ def main() -> int:
         finally:
             F.ficco_destroy(plan)
     pick = None if rs else library_pick()
+    pick_host = None if rs else library_pick(host_resident=True)
     if args.candidates:
         cands = [parse_plan(t) for t in args.candidates.split(",")]
     else:
@@ -374,10 +380,11 @@ def main() -> int:
         for lay in ("rm", "ks"):
             cands += [(F.FICCO_FINE_2D, c, lay) for c in cfg.get("k_slices", [])]
             cands += [(F.FICCO_FINE_2D, tuple(w), lay) for w in cfg.get("k_widths", [])]
-    if pick is not None and pick not in cands:
-        cands.append(pick)
-        if pick[0] == F.FICCO_FINE_2D:
-            cands.append((pick[0], pick[1], "ks"))
+    for pk in (pick, pick_host):
+        if pk is not None and pk not in cands:
+            cands.append(pk)
+            if pk[0] == F.FICCO_FINE_2D:
+                cands.append((pk[0], pk[1], "ks"))
 
     out = {"metric": ("GEMM+RS(data movement)" if cfg["direction"] == "gemm_rs" else "AG+GEMM")
                      + " effective TFLOP/s (overlapped pair, the schedule the library picks)",
@@ -403,7 +410,8 @@ def main() -> int:
         # after every step and - the figure that counts - with steps back to back through two chained plans.
         # The best of the screen is timed the same way beside it.
         screen_best = min(screen, key=screen.get)
-        timed = pick if pick is not None else screen_best
+        my_pick = pick_host if tag == "pcie" else pick
+        timed = my_pick if my_pick is not None else screen_best
         def full(sc):
             p_f = make(*sc)
             synced = timed_steps(p_f, source(tag, *sc), args.steps, args.warmup)
@@ -443,7 +451,9 @@ def main() -> int:
             ms_het = timed_steps_chained(timed, source(tag, *timed), args.steps, args.warmup, opts=het)
         res.update(copy_backend={1: "stream", 2: "engines"}.get(info.copy_backend), links=info.links,
                    ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
-                   picked_by=("the library (FICCO_AUTO_ANY)" if pick is not None else "the screen (no rule for this direction)"),
+                   picked_by=("the screen (no rule for this direction)" if my_pick is None else
+                              "the library (ficco_pick_schedule_layout, shards in pinned host memory)" if tag == "pcie" else
+                              "the library (FICCO_AUTO_ANY)"),
                    stepping=("two plans chained behind each other take the steps in turn; the host runs one step ahead"
                              if chain else "a blocking query after every step"),
                    ms_per_step_host_synced=ms_synced, ms_serial_host_synced=ms_ser_synced,
@@ -535,6 +545,70 @@ def main() -> int:
             step_bytes = traffic + 2 * (M * N * 2 if rs else M * K * 2)
             out["pair"]["hbm_side_bytes_per_step"] = step_bytes
             out["pair"]["hbm_side_frac_of_peak"] = round(step_bytes / (out["ms_per_step"] * 1e-3) / (HBM_PEAK_GBPS * 1e9), 4)
+
+    if "power" in legs and not rs:
+        # (not in the default set) board power while the timed plan's GEMM launches loop for about a second, on the
+        # workload's own data and on zeros: the chip holds its power limit by lowering the shader clock, and how
+        # far depends on how many bits toggle, so the same kernel is faster on zeros. Beside it the vendor
+        # library's GEMM (torch.matmul on the same operands, weight in the k-contiguous layout it is fastest in),
+        # as the practical ceiling of the machine at that power.
+        import glob
+        import threading
+        pw_files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or \
+            glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+
+        def looped(fn, seconds=1.2):
+            samples, stop = [], [False]
+
+            def sample():
+                while not stop[0]:
+                    try:
+                        samples.append(max(float(open(f).read()) for f in pw_files))
+                    except (OSError, ValueError):
+                        pass
+                    time.sleep(0.004)
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            th = threading.Thread(target=sample, daemon=True)
+            th.start()
+            t0, n = time.perf_counter(), 0
+            while time.perf_counter() - t0 < seconds:
+                fn()
+                n += 1
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            stop[0] = True
+            th.join()
+            tail = samples[len(samples) // 3:]
+            return dt / n, (sum(tail) / len(tail) * 1e-6 if tail else None)
+
+        s, c, lay = parse_plan(args.roofline_plan) if args.roofline_plan else (pick if pick is not None else (F.FICCO_FINE_PERSISTENT, 1, "rm"))
+        s %= PACKED
+        REP = 20
+        res = {}
+        for kind in ("workload", "zeros"):
+            A_k = source("hbm", s, c, "ks") if kind == "workload" else torch.zeros_like(A_stage)
+            W_k = W_dev if kind == "workload" else torch.zeros_like(W_dev)
+            plan = make(s, c, "ks", opts=[(F.FICCO_OPT_MODE, F.FICCO_MODE_GEMM_ONLY)])
+            F.ficco_pack_weight(plan, W_k, cs)
+            F.ficco_plan_set(plan, F.FICCO_OPT_REPEAT, REP)
+
+            def ours():
+                F.ficco_run(plan, None, A_k, W_k, C_dev, None, cs, xs)
+                F.ficco_query_stats(plan)
+            t, watts = looped(ours)
+            F.ficco_destroy(plan)
+            Ab = (A_stage if kind == "workload" else torch.zeros_like(A_stage)).view(torch.bfloat16)
+            Wt_b = W_k.view(torch.bfloat16).t().contiguous()
+
+            def vendor():
+                for _ in range(REP):
+                    torch.matmul(Ab, Wt_b.t())
+            tv, wv = looped(vendor)
+            res[kind] = {"tflops": round(flops / (t / REP) * 1e-12, 1), "watts": round(watts, 0) if watts else None,
+                         "vendor_library_tflops": round(flops / (tv / REP) * 1e-12, 1), "vendor_library_watts": round(wv, 0) if wv else None}
+        out["power"] = res
 
     if "contend" in legs and not rs:
         # counter runs only: the plan's GEMM launches with the plan's transfers running beside them and no

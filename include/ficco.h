@@ -170,7 +170,9 @@ typedef enum ficco_option {
  */
 typedef enum ficco_source_layout {
     FICCO_LAYOUT_ROW_MAJOR = 0,
-    FICCO_LAYOUT_K_SLICED  = 1
+    FICCO_LAYOUT_K_SLICED  = 1,
+    FICCO_LAYOUT_ROW_MAJOR_HOST = 2  /* for ficco_pick_schedule_layout only: ROW_MAJOR, and the caller says that the
+                                        shards lie in pinned host memory (ficco_run itself sees where A_src lives) */
 } ficco_source_layout;
 
 /*
@@ -478,7 +480,10 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
  * slices in *chunks. ficco_pick_schedule_any answers for the caller's row-major A_src (what a FICCO_AUTO_ANY
  * plan uses): the step then pays for the sender-side re-layout, so column pieces are only picked where the GEMM
  * is the longer side and large enough to hide it. ficco_pick_schedule_layout takes the ficco_source_layout: for
- * a sender that holds its slices K-sliced already, column pieces are picked for every small output. */
+ * a sender that holds its slices K-sliced already, column pieces are picked for every small output; for row-major
+ * shards in pinned host memory (ROW_MAJOR_HOST) never: all their strided rectangles travel through one engine, and
+ * row pieces were ahead at every shape tried. A FICCO_AUTO_ANY plan cannot know where the shards will lie and assumes
+ * device memory (peers' memory, the paper's case): a caller with host-resident shards asks here first. */
 int ficco_pick_schedule_any(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
 int ficco_pick_schedule_layout(int64_t M, int64_t K, int64_t N, int shards, int source_layout, int *schedule, int *chunks);
 

@@ -24,7 +24,7 @@ FICCO_MODE_PAIR, FICCO_MODE_GEMM_ONLY, FICCO_MODE_COPY_ONLY, FICCO_MODE_INDEPEND
  FICCO_OPT_FLAG_WRITE, FICCO_OPT_SPIN_LIMIT_US, FICCO_OPT_LOCAL_SHARD, FICCO_OPT_HOLD_FLAGS,
  FICCO_OPT_COPY_BACKEND, FICCO_OPT_LINKS, FICCO_OPT_PACKING, FICCO_OPT_REPEAT,
  FICCO_OPT_TILE_GROUP, FICCO_OPT_TILE_COLUMN_LISTS, FICCO_OPT_SOURCE_LAYOUT) = range(16)
-FICCO_LAYOUT_ROW_MAJOR, FICCO_LAYOUT_K_SLICED = 0, 1
+FICCO_LAYOUT_ROW_MAJOR, FICCO_LAYOUT_K_SLICED, FICCO_LAYOUT_ROW_MAJOR_HOST = 0, 1, 2
 FICCO_COPY_AUTO, FICCO_COPY_STREAM, FICCO_COPY_ENGINES = 0, 1, 2
 (FICCO_TILE_AUTO, FICCO_TILE_256x256, FICCO_TILE_128x128, FICCO_TILE_256x128, FICCO_TILE_128x256,
  FICCO_TILE_64x256, FICCO_TILE_32x256, FICCO_TILE_128x128_DEEP, FICCO_TILE_128x192,

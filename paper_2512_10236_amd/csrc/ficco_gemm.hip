@@ -81,12 +81,14 @@ struct TileCfg {
     static constexpr int A_STAGE = BM * ROWB, B_STAGE = BN * ROWB;   // bytes
     static constexpr int STAGE = A_STAGE + B_STAGE;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
-    static constexpr int AB = BM / RPL / 4, BB = BN / RPL / 4; // 1 KiB blocks loaded per wavefront per stage
+    static constexpr int NW = WGM * WGN;                       // wavefronts: 4 (one per SIMD) or 8 (two per SIMD)
+    static constexpr int AB = BM / RPL / NW, BB = BN / RPL / NW; // 1 KiB blocks loaded per wavefront per stage
     static constexpr int LOADS = AB + BB;                      // load instructions per wavefront per k-tile
     static_assert(BK == 64 || BK == 32, "stages of 64 or 32 k values");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2 to 4 stages");
     static_assert(LDS_BYTES <= 160 * 1024 - 64, "LDS ring plus the kernels' few static words must fit one CU");
-    static_assert(THREADS == 256, "loaders assume 4 wavefronts");
+    static_assert(THREADS == 256 || THREADS == 512, "4 or 8 wavefronts");
+    static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "every wavefront loads the same number of blocks");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile is made of 32x32 blocks");
     static_assert(AB >= 1 && BB >= 1, "tile too small for the loader");
 };
@@ -413,7 +415,7 @@ static __device__ __forceinline__ void tile_store_rows_through(const TileAcc<T> 
 {
     constexpr int SEG = T::WTN / 8;                 // 16-byte slots per row of the wavefront's part
     constexpr int STRIDE = T::WTN * 2 + 16;         // bytes between rows in LDS
-    static_assert(4 * 32 * STRIDE <= T::LDS_BYTES, "staging area must fit the ring");
+    static_assert(T::NW * 32 * STRIDE <= T::LDS_BYTES, "staging area must fit the ring");
     static_assert((32 * SEG) % 64 == 0, "whole wavefront instructions");
     const f32x16_t (&acc)[T::FN][T::FM] = ta.acc;
     const int lane = threadIdx.x & 63;
@@ -510,7 +512,7 @@ static __device__ __forceinline__ XcdRun xcd_run(int pid, int grid, int total)
 }
 
 template <class T>
-__global__ __launch_bounds__(256) void gemm_blocks_kernel(GemmLaunch a)
+__global__ __launch_bounds__(T::THREADS) void gemm_blocks_kernel(GemmLaunch a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     if (a.n_wait > 0) {
@@ -692,7 +694,7 @@ __device__ __forceinline__ void leave_run(const RunExit &e)
 // STREAM_OUT: the GEMM -> reduce-scatter form (r.done_count set), a separate instantiation so that its
 // epilogue and bookkeeping cost the all-gather form no registers.
 template <class T, bool STREAM_OUT>
-__global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
+__global__ __launch_bounds__(T::THREADS) void gemm_resident_kernel(ResidentLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ TileWalk s_walk;
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(ResidentLaunch r)
 // M <= K): step s delivers K-slice s of every shard, and every tile of C can make progress at every
 // step. The accumulation order over k is that of the monolithic kernel, so the bits are the same.
 template <class T>
-__global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r)
+__global__ __launch_bounds__(T::THREADS) void gemm_resident2d_kernel(Resident2DLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ TileWalk s_walk;
@@ -856,7 +858,7 @@ __global__ __launch_bounds__(256) void gemm_resident2d_kernel(Resident2DLaunch r
 // expert, each multiplied by that expert's weight. Row tiles never cross a segment; the host lists
 // them in the order they become ready together with the pieces that cover them.
 template <class T>
-__global__ __launch_bounds__(256) void gemm_grouped_kernel(GroupedLaunch r)
+__global__ __launch_bounds__(T::THREADS) void gemm_grouped_kernel(GroupedLaunch r)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ TileWalk s_walk;
@@ -995,6 +997,9 @@ hipError_t launch_slice_source(const SliceLaunch &a, hipStream_t s)
 // The big tile keeps two stages of 64 k values. Four stages of 32 (TileCfg<256, 256, 2, 2, 4, 32>) take the
 // memory wait out of the loop but run 6-8 % slower: rows of 64 bytes double the cache lines each load
 // instruction touches, and every 64 k values pay two barriers instead of one.
+// Eight wavefronts (TileCfg<256, 256, 2, 4, 2> or <256, 256, 4, 2, 2>, two per SIMD, 128x64 each) give the
+// same bits 2-5 % slower: a second wavefront per SIMD hides nothing that matters here, and the smaller
+// wavefront tile reads half as much again from LDS per MFMA.
 typedef TileCfg<256, 256, 2, 2, 2> T256x256;
 typedef TileCfg<128, 128, 2, 2, 2> T128x128;       // two workgroups per CU: for launches that fill the machine
 typedef TileCfg<128, 128, 2, 2, 4> T128x128D;      // deep ring, one workgroup per CU: for launches that do not
@@ -1014,7 +1019,7 @@ typedef TileCfg<256, 192, 2, 2, 2> T256x192;
 TileShape tile_shape(int tile)
 {
     switch (tile) {
-#define X(id, T) case id: return {T::BM, T::BN, T::LDS_BYTES, 256};
+#define X(id, T) case id: return {T::BM, T::BN, T::LDS_BYTES, T::THREADS};
     FICCO_FOR_EACH_TILE(X)
 #undef X
     default: return {0, 0, 0, 0};
@@ -1046,7 +1051,7 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
         int fit = dev < 64 ? fit_of[dev] : 0;
         if (fit == 0) {
             int per_cu = 0, cus = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_blocks_kernel<T>, 256, T::LDS_BYTES) == hipSuccess &&
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_blocks_kernel<T>, T::THREADS, T::LDS_BYTES) == hipSuccess &&
                 hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu * cus >= 8)
                 fit = per_cu * cus / 8 * 8;
             else
@@ -1067,7 +1072,7 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
             if (best < 0 || c < best) { best = c; b.group_m = g; }
         }
     }
-    hipLaunchKernelGGL(gemm_blocks_kernel<T>, dim3((unsigned)grid), dim3(256), T::LDS_BYTES, s, b);
+    hipLaunchKernelGGL(gemm_blocks_kernel<T>, dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, b);
     return hipGetLastError();
 }
 
@@ -1080,9 +1085,9 @@ static hipError_t launch_resident_t(const ResidentLaunch &r, hipStream_t s)
     if (once_out != hipSuccess) return once_out;
     if (r.grid <= 0) return hipErrorInvalidValue;
     if (r.done_count)
-        hipLaunchKernelGGL((gemm_resident_kernel<T, true>), dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+        hipLaunchKernelGGL((gemm_resident_kernel<T, true>), dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     else
-        hipLaunchKernelGGL((gemm_resident_kernel<T, false>), dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+        hipLaunchKernelGGL((gemm_resident_kernel<T, false>), dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }
 
@@ -1092,7 +1097,7 @@ static hipError_t launch_resident2d_t(const Resident2DLaunch &r, hipStream_t s)
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
     if (once != hipSuccess) return once;
     if (r.grid <= 0 || !r.k0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_resident2d_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    hipLaunchKernelGGL(gemm_resident2d_kernel<T>, dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }
 
@@ -1102,7 +1107,7 @@ static int resident2d_grid_t(int device)
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
     (void)once;
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident2d_kernel<T>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident2d_kernel<T>, T::THREADS, T::LDS_BYTES) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return per_cu * cus;
 }
@@ -1113,7 +1118,7 @@ static hipError_t launch_grouped_t(const GroupedLaunch &r, hipStream_t s)
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_grouped_kernel<T>));
     if (once != hipSuccess) return once;
     if (r.grid <= 0 || r.n_row_tiles <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_grouped_kernel<T>, dim3((unsigned)r.grid), dim3(256), T::LDS_BYTES, s, r);
+    hipLaunchKernelGGL(gemm_grouped_kernel<T>, dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }
 
@@ -1123,7 +1128,7 @@ static int grouped_grid_t(int device)
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_grouped_kernel<T>));
     (void)once;
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_grouped_kernel<T>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_grouped_kernel<T>, T::THREADS, T::LDS_BYTES) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return per_cu * cus;
 }
@@ -1135,7 +1140,7 @@ static int resident_grid_t(int device)
     (void)once;
     int per_cu = 0, cus = 0;
     // (the output-streaming form may need more registers, but every tile shape is limited by LDS first)
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident_kernel<T, false>, 256, T::LDS_BYTES) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_resident_kernel<T, false>, T::THREADS, T::LDS_BYTES) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return per_cu * cus;
 }

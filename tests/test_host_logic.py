@@ -400,6 +400,22 @@ def test_pick_schedule_any_gives_valid_plans_with_its_own_cut():
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
 
 
+def test_host_resident_row_major_shards_never_get_column_pieces():
+    """Strided rectangles out of pinned host memory all go through one engine: the rule keeps row pieces, the
+    answer of ficco_pick_schedule, for every shape; a plan does not take the hint as an option (the run sees
+    where A_src lives)."""
+    for shape, _ in ROW_MAJOR_CASES + K_SLICED_CASES:
+        assert ficco.ficco_pick_schedule_layout(*shape, ficco.FICCO_LAYOUT_ROW_MAJOR_HOST) == ficco.ficco_pick_schedule(*shape)
+    plan = ficco.ficco_plan(4096, 8192, 3584, 8, 4, ficco.FICCO_FINE_2D)
+    try:
+        with pytest.raises(ficco.FiccoError):
+            ficco.ficco_plan_set(plan, ficco.FICCO_OPT_SOURCE_LAYOUT, ficco.FICCO_LAYOUT_ROW_MAJOR_HOST)
+    finally:
+        ficco.ficco_destroy(plan)
+    with pytest.raises(ficco.FiccoError):
+        ficco.ficco_pick_schedule_layout(4096, 8192, 3584, 8, 3)
+
+
 def test_source_layout_option_belongs_to_column_pieces():
     plan = ficco.ficco_plan(512, 1024, 1024, 4, 2, ficco.FICCO_FINE_2D)
     try:
