@@ -28,13 +28,28 @@ def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library. Returns its path."""
     if not force and not is_stale():
         return LIB
+    return _compile(LIB, CSRC, [], verbose)
+
+
+def build_variant(out: str, defines: list[str], verbose: bool = False) -> str:
+    """A measuring build with extra -D switches (the timing-only ablations FICCO_ABL_* and the in-kernel clock
+    probes FICCO_PROBE of ficco_gemm.hip), linked to `out`; load it with FICCO_LIBRARY=<out>. The in-tree
+    library is not touched. Example:
+        python -c "from paper_2512_10236_amd import _build; _build.build_variant('/tmp/libficco_nobar.so', ['FICCO_ABL_NOBAR'])"
+    """
+    import tempfile
+    with tempfile.TemporaryDirectory() as objdir:
+        return _compile(os.path.abspath(out), objdir, ["-D" + d for d in defines], verbose)
+
+
+def _compile(lib: str, objdir: str, extra: list[str], verbose: bool) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for cmd, pr in procs:
         out, _ = pr.communicate()
@@ -43,13 +58,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
         if verbose and out.strip():
             print(out)
-    tmp = LIB + f".tmp{os.getpid()}"
+    tmp = lib + f".tmp{os.getpid()}"
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs + ["-lhsa-runtime64"]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed: " + r.stdout)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

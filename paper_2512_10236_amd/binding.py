@@ -78,7 +78,8 @@ _lib = None
 
 
 def library_path() -> str:
-    return _build.LIB
+    """The in-tree library, or the one FICCO_LIBRARY names (a measuring build made by ``_build.build_variant``)."""
+    return os.environ.get("FICCO_LIBRARY") or _build.LIB
 
 
 def load():

@@ -61,9 +61,18 @@ static __device__ __forceinline__ void load_to_lds_16(const void *base, uint32_t
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  ::"v"(lane_off), "s"(ub), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory", "m0");
 }
+// Measuring builds (paper_2512_10236_amd/_build.py: build_variant) can take pieces out of the k loop to see what
+// each costs; their results are wrong, their timing is the point. Every access stays where it was (addresses do not
+// change) and no wait lasts longer than in the product build: FICCO_ABL_NOLOAD issues no global->LDS loads, FICCO_ABL_NOREAD no
+// LDS fragment reads, FICCO_ABL_NOBAR no k-step barrier, FICCO_ABL_LATEWAIT gives the loads one more k-step before
+// they are waited for. FICCO_PROBE adds clock reads around the waits (each costs a drain of the LDS counter).
 template <int N>
 static __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+#ifdef FICCO_ABL_NOBAR
+static __device__ __forceinline__ void wg_barrier() {}
+#else
 static __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+#endif
 
 template <int BM_, int BN_, int WGM_, int WGN_, int NSTAGE_, int BK_ = kBK>
 struct TileCfg {
@@ -216,10 +225,14 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
     // load l of the wavefront's LOADS loads of k-tile kt into `stage`: first the AB blocks of A, then the BB blocks
     // of W (k-tiles are issued in ascending order; load 0 of a k-tile comes first)
     auto issue_load = [&](int stage, int kt, int l) {
+#ifdef FICCO_ABL_NOLOAD
+        return;
+#endif
         if (l == 0) pa.seek(kt);
         if (l < T::AB) load_to_lds_16(pa.at(kt), pa.off[l], lds0 + stage * T::STAGE + (wave * T::AB + l) * 1024);
         else load_to_lds_16(wt_tile + (int64_t)kt * T::BK, offb[l - T::AB], lds0 + stage * T::STAGE + T::A_STAGE + (wave * T::BB + (l - T::AB)) * 1024);
     };
+
 
     // LDS -> fragment addresses: lane reads row (lane%32) of a 32-row block, k-slot 2*kk + lane/32,
     // un-swizzled by the row's swizzle, which only depends on the lane
@@ -230,10 +243,22 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
     const int KT = K / T::BK;
     constexpr int D = T::NSTAGE - 1;      // prefetch distance in k-tiles
     bf16x8_t fa[2][T::FM], fb[2][T::FN];
+#ifdef FICCO_ABL_NOREAD
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+#pragma unroll
+        for (int i = 0; i < T::FM; ++i) fa[n][i] = bf16x8_t{};
+#pragma unroll
+        for (int j = 0; j < T::FN; ++j) fb[n][j] = bf16x8_t{};
+    }
+#endif
     // fragment q of the FM + FN fragments of sub-step kk of the k-tile in the stage at `base`, into buffer n.
     // Order of arrival = order of first use by the MFMAs below (row block 0, then every column block, then the
     // other row blocks).
     auto read_frag = [&](const unsigned char *base, int kk, int n, int q) {
+#ifdef FICCO_ABL_NOREAD
+        return;
+#endif
         const int slot = ((2 * kk + fh) ^ fs) << 4;
         if (q == 0) fa[n][0] = *reinterpret_cast<const bf16x8_t *>(base + a_base + slot);
         else if (q <= T::FN) fb[n][q - 1] = *reinterpret_cast<const bf16x8_t *>(base + b_base + (q - 1) * 32 * T::ROWB + slot);
@@ -295,7 +320,12 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
 #endif
                 // ... and k-tile k+1 has landed: what may still be in flight are the loads issued after its own,
                 // those of the k-tiles k+2 .. k+D that exist (memory operations complete in issue order)
+#ifdef FICCO_ABL_LATEWAIT
+                // timing-only ablation (results are wrong): the loads get one more k-step to arrive
+                if constexpr (steady) wait_vmem<D * T::LOADS>();
+#else
                 if constexpr (steady) wait_vmem<(D - 1) * T::LOADS>();
+#endif
                 else if (rn) wait_issued_after<T>(min(D - 1, KT - 2 - k));
 #ifdef FICCO_PROBE
                 const long long pt2 = PROBE_T();
@@ -346,6 +376,9 @@ static __device__ __forceinline__ void tile_accumulate_from(TileAcc<T> &ta, Addr
     for (; k + 1 + D < KT; ++k) turn(k, yes, yes, yes, yes);
     for (; k < KT; ++k) turn(k, false, k + D < KT, k + 1 < KT, no);
     // (the barrier before the last sub-step was the last one: every wavefront had finished reading the ring)
+#ifdef FICCO_ABL_LATEWAIT
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
 #ifdef FICCO_PROBE
     if (lane == 0) {
         atomicAdd(&g_probe[wave][0], (unsigned long long)probe_vm);
