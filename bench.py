@@ -198,6 +198,7 @@ def main() -> int:
     ap.add_argument("--candidates", default="", help="schedule:chunks list, e.g. 3:2,4:4,5:3072+1024 (default: a small sweep)")
     ap.add_argument("--backend", default="auto", choices=["auto", "stream", "engines"],
                     help="transfer backend for every plan (default: the library's choice)")
+    ap.add_argument("--plan-opts", default="", help="measuring aid: option:value pairs (ficco_option numbers) set on every plan, e.g. 13:4,14:2")
     ap.add_argument("--roofline-plan", default="", help="schedule:chunks (or schedule:w1+w2+... for column pieces of those widths) for the roofline leg when the pair leg is not run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -325,6 +326,9 @@ def main() -> int:
             F.ficco_plan_set(plan, F.FICCO_OPT_DIRECTION, F.FICCO_DIR_GEMM_RS)
         for o, v in opts:
             F.ficco_plan_set(plan, o, v)
+        for pair in filter(None, args.plan_opts.split(",")):
+            o, v = pair.split(":")
+            F.ficco_plan_set(plan, int(o), int(v))
         if args.backend != "auto":
             F.ficco_plan_set(plan, F.FICCO_OPT_COPY_BACKEND, {"stream": F.FICCO_COPY_STREAM, "engines": F.FICCO_COPY_ENGINES}[args.backend])
         F.ficco_pack_weight(plan, W_dev, cs)
