@@ -370,8 +370,13 @@ def main() -> int:
             return (info.schedule, c, "rm")
         finally:
             F.ficco_destroy(plan)
-    pick = None if rs else library_pick()
-    pick_host = None if rs else library_pick(host_resident=True)
+    if rs:
+        s_rs, c_rs = F.ficco_pick_schedule_rs(M, K, N, G)
+        pick = (s_rs, c_rs, "rm")
+        pick_host = None           # peers in pinned host memory: no rule (everything is bound by the host link); the screen decides
+    else:
+        pick = library_pick()
+        pick_host = library_pick(host_resident=True)
     if args.candidates:
         cands = [parse_plan(t) for t in args.candidates.split(",")]
     else:
@@ -409,8 +414,7 @@ def main() -> int:
             plan = make(*sc)
             screen[sc] = timed_steps(plan, source(tag, *sc), max(5, args.steps // 5), 3, warm_seconds=0.06 if i == 0 else 0.02)
             F.ficco_destroy(plan)
-        # The schedule of this run is the library's own pick (all-gather direction; the reduce-scatter direction
-        # has no rule of its own and takes the best of the screen). It is timed in full, with a blocking query
+        # The schedule of this run is the library's own pick. It is timed in full, with a blocking query
         # after every step and - the figure that counts - with steps back to back through two chained plans.
         # The best of the screen is timed the same way beside it.
         screen_best = min(screen, key=screen.get)
@@ -455,7 +459,8 @@ def main() -> int:
             ms_het = timed_steps_chained(timed, source(tag, *timed), args.steps, args.warmup, opts=het)
         res.update(copy_backend={1: "stream", 2: "engines"}.get(info.copy_backend), links=info.links,
                    ms_per_step=ms, eff_tflops=flops / ms * 1e-9,
-                   picked_by=("the screen (no rule for this direction)" if my_pick is None else
+                   picked_by=("the screen" if my_pick is None else
+                              "the library (ficco_pick_schedule_rs)" if rs else
                               "the library (ficco_pick_schedule_layout, shards in pinned host memory)" if tag == "pcie" else
                               "the library (FICCO_AUTO_ANY)"),
                    stepping=("two plans chained behind each other take the steps in turn; the host runs one step ahead"

@@ -475,6 +475,13 @@ int ficco_profile_losses(ficco_plan_t *plan, const void *A_src, void *A_dev, con
  */
 int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
 
+/* The same rule for the GEMM -> reduce-scatter direction (FICCO_OPT_DIRECTION = FICCO_DIR_GEMM_RS; data movement,
+ * Sec. IV-E): a link carries (M/shards) x N output elements instead of (M/shards) x K of the activation. Answers
+ * the resident schedule and the pieces per output block; the caller builds the plan with them. Meant for peer
+ * buffers in device memory: towards pinned host memory every schedule is bound by the host link and the per-launch
+ * schedules on the stream backend were the fastest measured. */
+int ficco_pick_schedule_rs(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks);
+
 /* The same with column pieces allowed - the choice of communication shape of Sec. V-C, decided here by whether
  * the output is about one round of tiles over the machine: may also answer FICCO_FINE_2D, with the number of
  * slices in *chunks. ficco_pick_schedule_any answers for the caller's row-major A_src (what a FICCO_AUTO_ANY

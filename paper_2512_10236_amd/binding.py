@@ -71,7 +71,7 @@ class ficco_losses_t(C.Structure):
 
 EXPORTS = ["ficco_plan", "ficco_plan_grouped", "ficco_plan_pieces", "ficco_plan_set_slice_widths", "ficco_plan_slices", "ficco_plan_chain", "ficco_plan_set", "ficco_plan_set_arrival", "ficco_plan_info", "ficco_plan_arrival",
            "ficco_pack_weight", "ficco_run", "ficco_gemm_static", "ficco_graph_capture", "ficco_graph_launch", "ficco_rs_reduce", "ficco_query_stats", "ficco_query_spans", "ficco_profile_losses",
-           "ficco_pick_schedule", "ficco_pick_schedule_any", "ficco_pick_schedule_layout", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
+           "ficco_pick_schedule", "ficco_pick_schedule_rs", "ficco_pick_schedule_any", "ficco_pick_schedule_layout", "ficco_pick_slice_widths", "ficco_static_descriptors", "ficco_ideal_overlap_us", "ficco_destroy",
            "ficco_strerror", "ficco_last_hip_error", "ficco_version"]
 
 _lib = None
@@ -115,6 +115,7 @@ def load():
     lib.ficco_profile_losses.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(ficco_losses_t)]
     lib.ficco_pick_schedule.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_schedule_any.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.ficco_pick_schedule_rs.argtypes = [i64, i64, i64, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_schedule_layout.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.ficco_pick_slice_widths.argtypes = [i64, i64, i64, C.c_int, C.c_int, C.POINTER(i64)]
     lib.ficco_static_descriptors.argtypes = [i64, i64, i64, dp, dp]
@@ -287,6 +288,13 @@ def ficco_profile_losses(plan, A_src, A_dev, W_dev, C_dev, compute_stream, copy_
 def ficco_pick_schedule(M, K, N, shards):
     s, c = C.c_int(), C.c_int()
     _ok(load().ficco_pick_schedule(M, K, N, shards, C.byref(s), C.byref(c)), "ficco_pick_schedule")
+    return s.value, c.value
+
+
+def ficco_pick_schedule_rs(M, K, N, shards):
+    """The piece-count rule for the GEMM -> reduce-scatter direction."""
+    s, c = C.c_int(), C.c_int()
+    _ok(load().ficco_pick_schedule_rs(M, K, N, shards, C.byref(s), C.byref(c)), "ficco_pick_schedule_rs")
     return s.value, c.value
 
 

@@ -466,6 +466,37 @@ double ficco_ideal_overlap_us(double t_comm_us, double t_gemm_us, int n)
     return gemm_done;
 }
 
+// Pieces per shard (or per output block) from the overlap model, see ficco_pick_schedule. `row_bytes` = what one
+// row of a piece puts on its link: K elements of the activation (all-gather) or N of the output (reduce-scatter).
+static int pick_pieces(int64_t M, int64_t K, int64_t N, int shards, int64_t row_bytes)
+{
+    const int64_t ms = M / shards;
+    const double Tc = (double)ms * (double)row_bytes / 58.0e3;                      // us
+    const double Tg = 2.0 * (double)M * (double)N * (double)K / 1.2e9;              // us
+    int c = 1;
+    double best = -1.0;
+    for (int cc = 1; cc <= 32; cc *= 2) {
+        if (ms % cc || (cc > 1 && ms / cc < 256)) continue;
+        const double T = std::max(Tc + cc * 16.0, Tg + cc * 8.0) + std::min(Tc, Tg) / cc;
+        if (best < 0 || T < best * 0.999) { best = T; c = cc; }
+    }
+    return c;
+}
+
+int ficco_pick_schedule_rs(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
+{
+    if (M < 1 || K < 1 || N < 1 || shards < 1 || !schedule || !chunks) return FICCO_ERR_ARG;
+    if (M % shards) return FICCO_ERR_SHAPE;
+    // GEMM -> reduce-scatter, data movement (Sec. IV-E leaves the reduction out): the mirror image of the all-gather
+    // rule. Row block p of the output travels to peer p piece by piece as the GEMM completes it, so one link carries
+    // (M/shards) x N elements and what stays exposed is the last piece's transfer. Same model, same constants (they
+    // describe the engines and the kernel, not the direction); checked against the one reduce-scatter workload
+    // measured here (M 16384, K 3584, N 8192: 8 pieces per block, the best of 1-16).
+    *schedule = FICCO_FINE_PERSISTENT;
+    *chunks = pick_pieces(M, K, N, shards, N * 2);
+    return FICCO_OK;
+}
+
 int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedule, int *chunks)
 {
     if (M < 1 || K < 1 || N < 1 || shards < 1 || !schedule || !chunks) return FICCO_ERR_ARG;
@@ -481,16 +512,7 @@ int ficco_pick_schedule(int64_t M, int64_t K, int64_t N, int shards, int *schedu
     // 32 that divides the shard, keeps pieces of at least 256 rows and minimises T. Among the schedules the resident
     // kernel was the fastest at every point of the sweep, so the schedule itself needs no threshold. a, b and the
     // row limit were fitted to the 24-shape sweep and scored on 16 shapes off its grid.
-    const int64_t ms = M / shards;
-    const double Tc = (double)ms * (double)K * 2.0 / 58.0e3;                        // us
-    const double Tg = 2.0 * (double)M * (double)N * (double)K / 1.2e9;              // us
-    int c = 1;
-    double best = -1.0;
-    for (int cc = 1; cc <= 32; cc *= 2) {
-        if (ms % cc || (cc > 1 && ms / cc < 256)) continue;
-        const double T = std::max(Tc + cc * 16.0, Tg + cc * 8.0) + std::min(Tc, Tg) / cc;
-        if (best < 0 || T < best * 0.999) { best = T; c = cc; }
-    }
+    const int c = pick_pieces(M, K, N, shards, K * 2);
     const int sch = FICCO_FINE_PERSISTENT;
     *schedule = sch;
     *chunks = c;

@@ -400,6 +400,25 @@ def test_pick_schedule_any_gives_valid_plans_with_its_own_cut():
                     assert (s, c) == ficco.ficco_pick_schedule(M, K, N, 8)
 
 
+RS_PIECE_CASES = [
+    # reduce-scatter direction: a link carries (M/G) x N output elements. M 16384, K 3584, N 8192, G 8:
+    # Tc = 2048*8192*2/58e3 = 578.5 us, Tg = 2*16384*8192*3584/1.2e9 = 801.6 us;
+    # T(1) = 809.6 + 578.5 = 1388.1, T(2) = 817.6 + 289.3 = 1106.9, T(4) = 833.6 + 144.6 = 978.2,
+    # T(8) = 865.6 + 72.3 = 937.9; 16 pieces would be 128 rows each (< 256) -> 8
+    ((16384, 3584, 8192, 8), 8),
+    # M 8192, K 4096, N 768: Tc = 1024*768*2/58e3 = 27.1 us, Tg = 43.0 us;
+    # T(1) = 51.0 + 27.1 = 78.1, T(2) = max(59.1, 59.0) + 13.6 = 72.7, T(4) = max(91.1, 75.0) + 6.8 = 97.9 -> 2
+    ((8192, 4096, 768, 8), 2),
+]
+
+
+@pytest.mark.parametrize("shape,pieces", RS_PIECE_CASES)
+def test_reduce_scatter_piece_rule_hand_cases(shape, pieces):
+    assert ficco.ficco_pick_schedule_rs(*shape) == (ficco.FICCO_FINE_PERSISTENT, pieces)
+    M, K, N, G = shape
+    assert (M // G) % pieces == 0
+
+
 def test_host_resident_row_major_shards_never_get_column_pieces():
     """Strided rectangles out of pinned host memory all go through one engine: the rule keeps row pieces, the
     answer of ficco_pick_schedule, for every shape; a plan does not take the hint as an option (the run sees
