@@ -491,3 +491,17 @@ def test_grouped_plan_rules(args, status):
     with pytest.raises(ficco.FiccoError) as e:
         ficco.ficco_plan_grouped(*args)
     assert e.value.status == getattr(ficco, "FICCO_ERR_" + status)
+
+
+def test_library_path_can_be_overridden_for_measuring_builds(monkeypatch, tmp_path):
+    """FICCO_LIBRARY names a measuring build (see _build.build_variant); without it the in-tree library is used,
+    and a path that does not exist is an error, not a fallback."""
+    from paper_2512_10236_amd import _build, binding
+    monkeypatch.delenv("FICCO_LIBRARY", raising=False)
+    assert binding.library_path() == _build.LIB
+    other = str(tmp_path / "libficco_other.so")
+    monkeypatch.setenv("FICCO_LIBRARY", other)
+    assert binding.library_path() == other
+    monkeypatch.setattr(binding, "_lib", None)
+    with pytest.raises(RuntimeError):
+        binding.load()
