@@ -860,6 +860,7 @@ void ficco_destroy(ficco_plan_t *p)
     if (!p) return;
     if (p->finalized && p->run_index > 0 && p->ev_end) (void)hipEventSynchronize(p->ev_end);
     for (auto &sg : p->sig_done) hsa_signal_store_screlease(sg, 0);      // nothing may stay parked behind a piece that never completed
+    for (auto &sg : p->sig_packed) hsa_signal_store_screlease(sg, 0);    // ... or behind a re-layout that never ran
     if (p->link) {
         // plans chained behind this one keep the link alive; their transfers no longer wait for it
         p->link->alive = false;
