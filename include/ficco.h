@@ -277,7 +277,7 @@ typedef struct ficco_losses {       /* Sec. IV: measured on this GPU with this p
  * the current device; the tile is chosen and flags/events/tables are allocated on first use
  * (ficco_pack_weight or ficco_run), after which most options are frozen.
  * Shape rules (FICCO_ERR_SHAPE otherwise): M, K, N >= 1; shards >= 1; chunks >= 1;
- * M % (shards*chunks) == 0; K % 64 == 0; N % 8 == 0; chunks == 1 for SERIAL and SHARD;
+ * M % (shards*chunks) == 0; K % 64 == 0 and K <= 2^22; N % 8 == 0; chunks == 1 for SERIAL and SHARD;
  * shards*chunks <= 4096. FICCO_FINE_2D instead needs M % shards == 0 and chunks <= K/64; its
  * slices are as equal as whole k-tiles of 64 columns allow (the first (K/64) mod chunks slices
  * one k-tile wider) unless ficco_plan_set_slice_widths gives other widths.
@@ -301,7 +301,7 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
  * grouped kernel in all three; transfers on the copy engines, peer j on link j; ficco_run() as for
  * the all-gather direction (peer_out NULL). Not available: GEMM_RS, LOCAL_SHARD, PACKING, TIMING,
  * the stream backend, ficco_profile_losses, graphs.
- * Shape rules: K % 64 == 0, N % 8 == 0, peers*experts*chunks <= 4096, 1 <= M < 2^31, chunks == 1
+ * Shape rules: K % 64 == 0, K <= 2^22, N % 8 == 0, peers*experts*chunks <= 4096, 1 <= M < 2^31, chunks == 1
  * for SERIAL and SHARD.
  */
 int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64_t *rows, int chunks,
@@ -521,7 +521,7 @@ double ficco_ideal_overlap_us(double t_comm_us, double t_gemm_us, int n);
  * library runs on holds until the process ends. The call clears what must start at zero with a small
  * kernel (no memset node is recorded if the stream is being captured), packs the weight and launches
  * the GEMM, three kernels on `stream`, and returns without waiting.
- * Shape rules: M, K, N >= 1, K % 64 == 0, N % 8 == 0, each below 2^31, and K*N*2 bytes at most
+ * Shape rules: M, K, N >= 1, K % 64 == 0, N % 8 == 0, M and N below 2^31, K at most 2^22, and K*N*2 bytes at most
  * FICCO_STATIC_MAX_WEIGHT_BYTES (FICCO_ERR_SHAPE otherwise; e.g. K = 4096 with N up to 1024).
  * All calls on one GPU share that GPU's array: two calls whose kernels overlap on one GPU (different
  * streams, or the same call from two threads) race; calls on one stream are ordered and safe. The

@@ -150,7 +150,7 @@ static __device__ __forceinline__ uint32_t lane_offset(int blk, int lane, int ro
 // Where the loader finds its part of k-tile kt of A. PlainA: one row-major block [rows, K] with row stride lda:
 // a wave-uniform base that moves along k, and one per-lane byte offset per load (the tile's rows must span less
 // than 4 GiB, which the shape rules guarantee: at most 256 rows of at most 2^31 elements... of 2 bytes - the
-// launchers refuse K >= 2^23).
+// launchers refuse row strides above kMaxK).
 template <class T>
 struct PlainA {
     uint32_t off[T::AB];
@@ -1073,7 +1073,7 @@ static hipError_t launch_gemm_t(const GemmLaunch &a, hipStream_t s)
     const int tiles_n = (a.N + T::BN - 1) / T::BN;
     const int rt = (a.rows_per_block + T::BM - 1) / T::BM;
     const int64_t total = (int64_t)a.n_blocks * rt * tiles_n;
-    if (total <= 0 || total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (total <= 0 || total > 0x7FFFFFFF || a.lda > kMaxK || a.K > kMaxK) return hipErrorInvalidValue;
     // at most as many workgroups as run at once (a multiple of 8, one share per XCD); the rest of the tiles
     // are taken by the kernel's loop
     int64_t grid = total;
@@ -1116,7 +1116,7 @@ static hipError_t launch_resident_t(const ResidentLaunch &r, hipStream_t s)
     static hipError_t once_out = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident_kernel<T, true>));
     if (once != hipSuccess) return once;
     if (once_out != hipSuccess) return once_out;
-    if (r.grid <= 0) return hipErrorInvalidValue;
+    if (r.grid <= 0 || r.g.lda > kMaxK || r.g.K > kMaxK) return hipErrorInvalidValue;
     if (r.done_count)
         hipLaunchKernelGGL((gemm_resident_kernel<T, true>), dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     else
@@ -1129,7 +1129,7 @@ static hipError_t launch_resident2d_t(const Resident2DLaunch &r, hipStream_t s)
 {
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_resident2d_kernel<T>));
     if (once != hipSuccess) return once;
-    if (r.grid <= 0 || !r.k0) return hipErrorInvalidValue;
+    if (r.grid <= 0 || !r.k0 || r.g.K > kMaxK) return hipErrorInvalidValue;
     hipLaunchKernelGGL(gemm_resident2d_kernel<T>, dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }
@@ -1150,7 +1150,7 @@ static hipError_t launch_grouped_t(const GroupedLaunch &r, hipStream_t s)
 {
     static hipError_t once = set_lds_limit<T>(reinterpret_cast<const void *>(&gemm_grouped_kernel<T>));
     if (once != hipSuccess) return once;
-    if (r.grid <= 0 || r.n_row_tiles <= 0) return hipErrorInvalidValue;
+    if (r.grid <= 0 || r.n_row_tiles <= 0 || r.g.lda > kMaxK || r.g.K > kMaxK) return hipErrorInvalidValue;
     hipLaunchKernelGGL(gemm_grouped_kernel<T>, dim3((unsigned)r.grid), dim3(T::THREADS), T::LDS_BYTES, s, r);
     return hipGetLastError();
 }

@@ -16,6 +16,9 @@ TileShape tile_shape(int tile);
 
 constexpr int kFlagStrideWords = 16;      // one ready flag per 64-byte line
 constexpr int kBK = 64;                   // k extent of one LDS stage
+// Largest K (row stride of A and of the packed weight, in elements): the loaders address a tile's rows with 32-bit
+// byte offsets from a 64-bit base, and 256 rows of 2^22 elements of 2 bytes span 2 GiB.
+constexpr int64_t kMaxK = (int64_t)1 << 22;
 constexpr int kTicketLists = 8;           // one tile list per XCD (each XCD has its own L2)
 
 // Tiles of the resident kernels that list x (of kTicketLists) holds. The lists form a grid of

@@ -603,7 +603,7 @@ int ficco_plan(int64_t M, int64_t K, int64_t N, int shards, int chunks, int sche
         return FICCO_ERR_SHAPE;
     }
     if (K % 64 || N % 8) return FICCO_ERR_SHAPE;
-    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > kMaxK) return FICCO_ERR_SHAPE;
     ficco_plan_t *p = new (std::nothrow) ficco_plan_t();
     if (!p) return FICCO_ERR_ALLOC;
     p->M = M; p->K = K; p->N = N; p->G = shards; p->c = chunks; p->schedule = schedule;
@@ -630,7 +630,7 @@ int ficco_plan_grouped(int64_t K, int64_t N, int peers, int experts, const int64
     if (schedule != FICCO_SERIAL && schedule != FICCO_SHARD && schedule != FICCO_FINE_PERSISTENT) return FICCO_ERR_ARG;
     if ((schedule == FICCO_SERIAL || schedule == FICCO_SHARD) && chunks != 1) return FICCO_ERR_SHAPE;
     if ((int64_t)peers * experts * chunks > 4096) return FICCO_ERR_SHAPE;
-    if (K % 64 || N % 8 || K > 0x7FFFFFFF || N > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    if (K % 64 || N % 8 || K > kMaxK || N > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
     int64_t M = 0;
     for (int i = 0; i < peers * experts; ++i) {
         if (rows[i] < 0) return FICCO_ERR_SHAPE;

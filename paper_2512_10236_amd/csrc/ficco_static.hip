@@ -50,7 +50,7 @@ using namespace ficco;
 extern "C" int ficco_gemm_static(int64_t M, int64_t K, int64_t N, const void *A_dev, const void *W_dev, void *C_dev, void *stream)
 {
     if (!A_dev || !W_dev || !C_dev) return FICCO_ERR_ARG;
-    if (M < 1 || K < 1 || N < 1 || K % 64 || N % 8 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return FICCO_ERR_SHAPE;
+    if (M < 1 || K < 1 || N < 1 || K % 64 || N % 8 || M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > kMaxK) return FICCO_ERR_SHAPE;
     if ((uint64_t)K * (uint64_t)N * 2u > (uint64_t)FICCO_STATIC_MAX_WEIGHT_BYTES) return FICCO_ERR_SHAPE;
     bool dev_ptr = false;
     for (const void *ptr : {A_dev, W_dev, (const void *)C_dev}) {

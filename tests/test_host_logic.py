@@ -505,3 +505,13 @@ def test_library_path_can_be_overridden_for_measuring_builds(monkeypatch, tmp_pa
     monkeypatch.setattr(binding, "_lib", None)
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_row_strides_beyond_the_loaders_reach_are_refused():
+    """The kernels address a tile's rows with 32-bit byte offsets: K (the row stride of A and of the packed
+    weight) is limited to 2^22 elements, and a plan beyond that is a shape error, not a launch."""
+    K = (1 << 22) + 64
+    with pytest.raises(ficco.FiccoError):
+        ficco.ficco_plan(1024, K, 256, 8, 1, ficco.FICCO_SERIAL)
+    plan = ficco.ficco_plan(1024, 1 << 22, 256, 8, 1, ficco.FICCO_SERIAL)
+    ficco.ficco_destroy(plan)
